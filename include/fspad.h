@@ -1,0 +1,193 @@
+/*
+ * fspad.h - C ABI of the tree-verification hot path of draft-then-verify
+ * lossless speculative decoding (arXiv 2408.15562, section "Preliminaries").
+ *
+ * One verification step of the target model over a flattened draft tree:
+ *   1. tree-masked attention: every tree node attends to the whole prefix
+ *      KV cache and, among the tree tokens, only to its ancestors and itself
+ *      (Preliminaries: the draft phase ends by deriving the target's attention
+ *      mask from the token tree; the validation phase applies it);
+ *   2. lossless acceptance over the per-node logits: strict comparison of the
+ *      tree with the target's results, differing tokens and their descendants
+ *      discarded (Preliminaries, validation-phase paragraph), either greedy
+ *      (temperature 0) or by rejection sampling that leaves the target's output
+ *      distribution unchanged (Experiments, "Settings": temperature 1, and the
+ *      caption of Table 1: acceptance conditions are not relaxed).
+ *
+ * Conventions that hold for every entry point:
+ *   - "dev" pointers are device (HBM) addresses, "host" pointers are host
+ *     addresses. Every buffer is owned by the caller. The library allocates
+ *     nothing, frees nothing and never synchronises: device work is enqueued
+ *     on the caller's HIP stream (`hip_stream` is a hipStream_t, NULL = the
+ *     default stream) and the call returns at once.
+ *   - The return code covers what the host can see (null pointers, shapes,
+ *     workspace size, launch errors). Tree well-formedness of device arrays is
+ *     the caller's contract; fspad_tree_validate checks host copies.
+ *   - Results are deterministic from call to call (no floating-point atomics).
+ *   - Tree layout: nodes 0..N-1 in topological order, node 0 is the root (the
+ *     last token the target already emitted, always accepted; its K/V are not
+ *     yet in the cache). parent[0] = -1 and 0 <= parent[i] < i. Siblings are
+ *     ordered by draft rank; that order is the order of the rejection tests.
+ */
+#ifndef FSPAD_H
+#define FSPAD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define FSPAD_MAX_NODES 64 /* one 64-bit ancestor word per node */
+
+typedef enum {
+  FSPAD_OK = 0,
+  FSPAD_ERR_NULL = 1,        /* a required pointer is NULL */
+  FSPAD_ERR_SHAPE = 2,       /* B<1, N<1, N>64, D not in {64,128}, Hq%Hkv!=0, V<1, n_nodes[b] not in 1..Nmax,
+                                kv_len[b]<0, strides too small or not 16-byte multiples, row_stride<V */
+  FSPAD_ERR_TREE = 3,        /* validate(): parent[0]!=-1, parent[i] not in [0,i), token not in [0,V),
+                                two siblings with the same token */
+  FSPAD_ERR_DTYPE = 4,       /* io_dtype / out_dtype combination not supported */
+  FSPAD_ERR_WORKSPACE = 5,   /* workspace NULL or smaller than *_workspace_bytes() says */
+  FSPAD_ERR_TEMPERATURE = 6, /* temperature <= 0 or not finite */
+  FSPAD_ERR_HIP = 7          /* a HIP launch failed; hipGetLastError() has the cause */
+} fspad_status;
+
+typedef enum { FSPAD_F32 = 0, FSPAD_BF16 = 1 } fspad_dtype;
+
+/* Geometry of one attention call. All strides are in elements of io_dtype. */
+typedef struct {
+  int32_t batch;           /* B >= 1 */
+  int32_t n_nodes_max;     /* Nmax, 1..64: row pitch of every [B,Nmax,...] array */
+  int32_t n_q_heads;       /* Hq */
+  int32_t n_kv_heads;      /* Hkv, divides Hq; query head h reads kv head h / (Hq/Hkv) */
+  int32_t head_dim;        /* D: 64 or 128, contiguous in every array */
+  int32_t io_dtype;        /* fspad_dtype of q, k_tree, v_tree, k_cache, v_cache */
+  int32_t out_dtype;       /* FSPAD_F32, or the same as io_dtype */
+  float softmax_scale;     /* 0 => 1/sqrt(D) */
+  int64_t cache_stride_batch; /* k_cache/v_cache element (b,g,j,d) is at                */
+  int64_t cache_stride_head;  /*   b*stride_batch + g*stride_head + j*stride_token + d  */
+  int64_t cache_stride_token; /* >= D; all three multiples of 8 elements (16 bytes bf16) */
+} fspad_attn_desc;
+
+/*
+ * Tree-masked attention (Preliminaries, validation phase: one forward of the
+ * target over the flattened tree with the tree mask).
+ *
+ *   out[b,i,h,:] = sum_j softmax_j( scale * q[b,i,h,:] . K_j ) * V_j
+ * where j runs over the kv_len[b] prefix positions of kv head g = h/(Hq/Hkv)
+ * (all visible) followed by the tree tokens t < n_nodes[b] whose bit t is set
+ * in anc_mask[b,i] (the ancestors of i and i itself).
+ *
+ *   q        dev [B,Nmax,Hq,D]   io_dtype (already position-encoded)
+ *   k_tree   dev [B,Nmax,Hkv,D]  io_dtype, keys of the tree tokens
+ *   v_tree   dev [B,Nmax,Hkv,D]  io_dtype
+ *   k_cache  dev strided [B,Hkv,>=kv_len,D] io_dtype (may be NULL if all kv_len are 0)
+ *   v_cache  dev strided, same strides
+ *   kv_len   HOST [B] prefix lengths >= 0 (host, so that the split plan needs no device read)
+ *   n_nodes  HOST [B] 1..Nmax
+ *   anc_mask dev [B,Nmax] u64, bit t of word [b,i] set <=> t is i or an ancestor of i
+ *   out      dev [B,Nmax,Hq,D] out_dtype; rows i >= n_nodes[b] are written as zeros
+ *   workspace dev, at least fspad_tree_attn_workspace_bytes(desc, max_b kv_len[b]) bytes,
+ *            16-byte aligned; contents on entry are ignored, undefined on exit.
+ *            Two calls that may overlap in time need different workspaces.
+ * Accumulation is fp32; bf16 inputs are multiplied on the matrix cores with
+ * probabilities rounded to bf16.
+ */
+size_t fspad_tree_attn_workspace_bytes(const fspad_attn_desc* desc, int32_t max_kv_len);
+
+fspad_status fspad_tree_attn(const fspad_attn_desc* desc,
+                             const void* q, const void* k_tree, const void* v_tree,
+                             const void* k_cache, const void* v_cache,
+                             const int32_t* kv_len, const int32_t* n_nodes,
+                             const uint64_t* anc_mask, void* out,
+                             void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Greedy lossless acceptance (Preliminaries, validation phase: strict
+ * comparison, differing tokens and their descendants discarded).
+ *
+ *   a[i]   = argmax_v logits[b,i,v]   (fp32 compare; ties -> lowest v; NaN never wins)
+ *   walk   : cur = 0; while some child c of cur (lowest index first) has
+ *            draft_tokens[c] == a[cur]: cur = c
+ *   path   = root .. cur ; tokens = draft tokens of path[1..] then the bonus a[cur]
+ *
+ *   logits       dev [B,Nmax,V] fp32, row (b,i) starts at (b*Nmax+i)*row_stride
+ *   draft_tokens dev [B,Nmax] i32; [b,0] is the root's token (not compared)
+ *   parent       dev [B,Nmax] i32; [b,0] = -1, parent[i] < i
+ *   n_nodes      dev [B] i32, 1..Nmax
+ *   path         dev [B,Nmax] i32 out; path[b,0] = 0; entries >= path_len[b] are -1
+ *   path_len     dev [B] i32 out, >= 1
+ *   tokens       dev [B,Nmax] i32 out; tokens[b,0..len-2] = draft tokens of path[b,1..len-1],
+ *                tokens[b,len-1] = bonus token (the next step's root); later entries -1
+ *   n_tokens     dev [B] i32 out, = path_len[b]
+ *   workspace    dev, >= fspad_tree_accept_workspace_bytes(B,Nmax,V), 16-byte aligned
+ */
+size_t fspad_tree_accept_workspace_bytes(int32_t B, int32_t Nmax, int32_t V);
+
+fspad_status fspad_tree_accept_greedy(int32_t B, int32_t Nmax, int32_t V,
+                                      const float* logits, int64_t row_stride,
+                                      const int32_t* draft_tokens, const int32_t* parent,
+                                      const int32_t* n_nodes,
+                                      int32_t* path, int32_t* path_len,
+                                      int32_t* tokens, int32_t* n_tokens,
+                                      void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Sampling (temperature > 0) lossless acceptance: rejection sampling down the
+ * tree against the residual distribution, with caller-supplied uniforms, so
+ * that the emitted tokens are distributed exactly as the target's own samples
+ * (Experiments "Settings", temperature 1; caption of Table 1). The draft
+ * proposal at a child is a point mass (children are a deterministic top-k of
+ * the draft's output, Preliminaries, last paragraph), which reduces the
+ * accept-or-resample rule of the speculative sampling the paper builds on to:
+ *
+ *   cur = 0
+ *   loop: w[v] = exp((logits[cur,v] - max_v logits[cur,v]) / T), Z = sum_v w[v]   (fp64)
+ *         for each child c of cur, lowest index first, x = draft_tokens[c]:
+ *             if u_acc[c] * Z < w[x]: accept, cur = c, restart loop
+ *             else: Z -= w[x]; w[x] = 0         (residual: p with x removed, renormalised)
+ *         none accepted: t = u_bonus[cur] * Z;
+ *             bonus = first v in vocabulary order whose running sum of w exceeds t
+ *             (if rounding leaves none: the last v with w[v] > 0); stop.
+ *
+ * Arguments as for greedy, plus:
+ *   temperature  > 0, finite
+ *   uniforms     dev [B,2,Nmax] fp32 in [0,1): [b,0,i] = u_acc(i) tested when node i is
+ *                proposed, [b,1,i] = u_bonus(i) used if the walk stops at node i
+ * w, Z and the running sums are fp64. A result is only defined bit-for-bit when
+ * every comparison above has a relative margin well above fp64 rounding (the
+ * tests require 1e-9).
+ */
+fspad_status fspad_tree_accept_sample(int32_t B, int32_t Nmax, int32_t V,
+                                      const float* logits, int64_t row_stride,
+                                      const int32_t* draft_tokens, const int32_t* parent,
+                                      const int32_t* n_nodes,
+                                      float temperature, const float* uniforms,
+                                      int32_t* path, int32_t* path_len,
+                                      int32_t* tokens, int32_t* n_tokens,
+                                      void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Host helpers for the tree (Preliminaries: tokens organised into a tree by
+ * their dependencies, then the mask derived from the tree).
+ *
+ * fspad_tree_build_mask: mask_host[b,i] = bit i | mask_host[b,parent[b,i]] for
+ *   i < n_nodes_host[b]; words of nodes >= n_nodes_host[b] are 0. All arrays on the
+ *   host, [B,Nmax] / [B]. Returns FSPAD_ERR_TREE for an ill-formed parent array.
+ * fspad_tree_validate: checks parent order, token range (tokens_host may be
+ *   NULL to skip the token checks) and that no two siblings carry the same token.
+ */
+fspad_status fspad_tree_build_mask(int32_t B, int32_t Nmax, const int32_t* parent_host,
+                                   const int32_t* n_nodes_host, uint64_t* mask_host);
+fspad_status fspad_tree_validate(int32_t B, int32_t Nmax, int32_t V, const int32_t* parent_host,
+                                 const int32_t* tokens_host, const int32_t* n_nodes_host);
+
+/* Static, NUL-terminated description of a status code. */
+const char* fspad_status_string(fspad_status status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FSPAD_H */

@@ -1,0 +1,151 @@
+"""CPU oracle for tree verification -- TEST INFRASTRUCTURE, not product code.
+
+Thin ctypes loader around ``fspad_oracle.c`` (plain C, fp64).  Only ``tests/``,
+``__graft_entry__.smoke()`` and the ``cpu_baseline`` leg of ``bench.py`` may import
+this package; the GPU library never does and shares no code with it.
+
+All functions take and return numpy arrays.  Floating-point inputs of the
+attention oracle are converted to fp64 first (exact for fp32 and bf16 values).
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "fspad_oracle.c")
+_LIB = os.path.join(_HERE, "libfspad_oracle.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (-O2, no fast-math, OpenMP over heads only)."""
+    stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC)
+    if force or stale:
+        cmd = ["gcc", "-O2", "-std=c11", "-fno-fast-math", "-ffp-contract=off", "-fopenmp",
+               "-shared", "-fPIC", "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        _lib = ctypes.CDLL(_LIB)
+        for name in ("fspad_oracle_dense_mask", "fspad_oracle_tree_attn",
+                     "fspad_oracle_accept_greedy", "fspad_oracle_accept_sample"):
+            getattr(_lib, name).restype = ctypes.c_int
+    return _lib
+
+
+def _ptr(a):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _i32(a):
+    return np.ascontiguousarray(a, dtype=np.int32)
+
+
+def dense_mask(parent) -> np.ndarray:
+    """[N,N] uint8, M[i,t] = 1 iff t is i or an ancestor of i."""
+    parent = _i32(parent)
+    n = parent.shape[0]
+    m = np.zeros((n, n), dtype=np.uint8)
+    rc = _load().fspad_oracle_dense_mask(ctypes.c_int32(n), _ptr(parent), _ptr(m))
+    if rc != 0:
+        raise ValueError("ill-formed parent array")
+    return m
+
+
+def tree_attn(q, k_tree, v_tree, k_cache, v_cache, kv_len, n_nodes, parent,
+              packed_mask=None, scale=None, nthreads: int = 1) -> np.ndarray:
+    """fp64 tree attention by the plain definition.
+
+    q [B,Nmax,Hq,D]; k_tree,v_tree [B,Nmax,Hkv,D]; k_cache,v_cache [B,Hkv,Lcap,D]
+    (or None when every kv_len is 0); kv_len,n_nodes [B]; parent [B,Nmax];
+    packed_mask [B,Nmax] uint64 or None (checked against the tree if given).
+    Returns out [B,Nmax,Hq,D] fp64.
+    """
+    q = np.ascontiguousarray(q, dtype=np.float64)
+    k_tree = np.ascontiguousarray(k_tree, dtype=np.float64)
+    v_tree = np.ascontiguousarray(v_tree, dtype=np.float64)
+    B, Nmax, Hq, D = q.shape
+    Hkv = k_tree.shape[2]
+    assert k_tree.shape == (B, Nmax, Hkv, D) and v_tree.shape == k_tree.shape
+    if k_cache is not None:
+        k_cache = np.ascontiguousarray(k_cache, dtype=np.float64)
+        v_cache = np.ascontiguousarray(v_cache, dtype=np.float64)
+        assert k_cache.shape[:2] == (B, Hkv) and k_cache.shape[3] == D
+        assert v_cache.shape == k_cache.shape
+        Lcap = k_cache.shape[2]
+    else:
+        Lcap = 0
+    kv_len = _i32(kv_len)
+    n_nodes = _i32(n_nodes)
+    parent = _i32(parent)
+    assert parent.shape == (B, Nmax) and kv_len.shape == (B,) and n_nodes.shape == (B,)
+    if packed_mask is not None:
+        packed_mask = np.ascontiguousarray(packed_mask, dtype=np.uint64)
+        assert packed_mask.shape == (B, Nmax)
+    if scale is None:
+        scale = 1.0 / np.sqrt(D)
+    out = np.empty((B, Nmax, Hq, D), dtype=np.float64)
+    rc = _load().fspad_oracle_tree_attn(
+        ctypes.c_int32(B), ctypes.c_int32(Nmax), ctypes.c_int32(Hq), ctypes.c_int32(Hkv),
+        ctypes.c_int32(D), ctypes.c_double(float(scale)),
+        _ptr(q), _ptr(k_tree), _ptr(v_tree), _ptr(k_cache), _ptr(v_cache),
+        ctypes.c_int64(Lcap), _ptr(kv_len), _ptr(n_nodes), _ptr(parent), _ptr(packed_mask),
+        _ptr(out), ctypes.c_int32(nthreads))
+    if rc == -2:
+        raise ValueError("packed ancestor mask does not match the parent array")
+    if rc != 0:
+        raise ValueError(f"oracle tree_attn failed: {rc}")
+    return out
+
+
+def _accept_common(logits, draft_tokens, parent, n_nodes):
+    logits = np.ascontiguousarray(logits, dtype=np.float32)
+    B, Nmax, V = logits.shape
+    draft_tokens = _i32(draft_tokens)
+    parent = _i32(parent)
+    n_nodes = _i32(n_nodes)
+    assert draft_tokens.shape == (B, Nmax) and parent.shape == (B, Nmax) and n_nodes.shape == (B,)
+    path = np.empty((B, Nmax), dtype=np.int32)
+    tokens = np.empty((B, Nmax), dtype=np.int32)
+    path_len = np.empty((B,), dtype=np.int32)
+    n_tokens = np.empty((B,), dtype=np.int32)
+    return logits, B, Nmax, V, draft_tokens, parent, n_nodes, path, path_len, tokens, n_tokens
+
+
+def accept_greedy(logits, draft_tokens, parent, n_nodes):
+    """Returns (path [B,Nmax], path_len [B], tokens [B,Nmax], n_tokens [B]), int32."""
+    (logits, B, Nmax, V, draft_tokens, parent, n_nodes,
+     path, path_len, tokens, n_tokens) = _accept_common(logits, draft_tokens, parent, n_nodes)
+    rc = _load().fspad_oracle_accept_greedy(
+        ctypes.c_int32(B), ctypes.c_int32(Nmax), ctypes.c_int32(V), _ptr(logits),
+        ctypes.c_int64(V), _ptr(draft_tokens), _ptr(parent), _ptr(n_nodes),
+        _ptr(path), _ptr(path_len), _ptr(tokens), _ptr(n_tokens))
+    if rc != 0:
+        raise ValueError(f"oracle accept_greedy failed: {rc}")
+    return path, path_len, tokens, n_tokens
+
+
+def accept_sample(logits, draft_tokens, parent, n_nodes, temperature, uniforms):
+    """Returns (path, path_len, tokens, n_tokens, min_margin [B] fp64)."""
+    (logits, B, Nmax, V, draft_tokens, parent, n_nodes,
+     path, path_len, tokens, n_tokens) = _accept_common(logits, draft_tokens, parent, n_nodes)
+    uniforms = np.ascontiguousarray(uniforms, dtype=np.float32)
+    assert uniforms.shape == (B, 2, Nmax)
+    margin = np.empty((B,), dtype=np.float64)
+    rc = _load().fspad_oracle_accept_sample(
+        ctypes.c_int32(B), ctypes.c_int32(Nmax), ctypes.c_int32(V), _ptr(logits),
+        ctypes.c_int64(V), _ptr(draft_tokens), _ptr(parent), _ptr(n_nodes),
+        ctypes.c_float(float(temperature)), _ptr(uniforms),
+        _ptr(path), _ptr(path_len), _ptr(tokens), _ptr(n_tokens), _ptr(margin))
+    if rc != 0:
+        raise ValueError(f"oracle accept_sample failed: {rc}")
+    return path, path_len, tokens, n_tokens, margin

@@ -1,0 +1,156 @@
+"""Seeded input generators (numpy, CPU).  Inputs only -- no method arithmetic."""
+from __future__ import annotations
+
+import numpy as np
+
+GENERATOR_VERSION = 1
+
+
+def round_to_bf16(x: np.ndarray) -> np.ndarray:
+    """Round fp32 values to the nearest bf16 (ties to even) and return them as fp32."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    bits = x.view(np.uint32).astype(np.uint64)
+    rounded = (bits + 0x7FFF + ((bits >> 16) & 1)) & 0xFFFF0000
+    return rounded.astype(np.uint32).view(np.float32).reshape(x.shape)
+
+
+def chain_tree(n: int) -> np.ndarray:
+    """parent[i] = i-1: the tree of ordinary sequential decoding."""
+    return np.arange(-1, n - 1, dtype=np.int32)
+
+
+def gen_tree(rng: np.random.Generator, n_nodes: int, depth: int, topk: int) -> np.ndarray:
+    """Parent array of a dynamic draft tree shaped the way EAGLE-2 builds one.
+
+    Every expanded node proposes `topk` children whose conditional probabilities
+    fall off geometrically (ratio rho ~ U(0.2, 0.7) per node); a candidate's joint
+    probability is the product along its path.  At each level only the `topk`
+    candidates with the highest joint probability are expanded further; after
+    `depth` levels the n_nodes-1 candidates with the highest joint probability are
+    kept (the set is ancestor-closed since a child's joint probability is below its
+    parent's).  Nodes are renumbered breadth first, siblings by falling
+    conditional probability, so parent[i] < i and node 0 is the root.
+    """
+    if n_nodes == 1:
+        return np.array([-1], dtype=np.int32)
+    # candidate records: (joint, level, parent_candidate_id, rank)
+    joint = [1.0]
+    level = [0]
+    par = [-1]
+    rank = [0]
+    frontier = [0]
+    for lev in range(1, depth + 1):
+        new = []
+        for p in frontier:
+            rho = rng.uniform(0.2, 0.7)
+            c = rho ** np.arange(topk)
+            c = c / c.sum()
+            for j in range(topk):
+                joint.append(joint[p] * c[j])
+                level.append(lev)
+                par.append(p)
+                rank.append(j)
+                new.append(len(joint) - 1)
+        new.sort(key=lambda i: (-joint[i], i))
+        frontier = new[:topk]
+    cand = list(range(1, len(joint)))
+    cand.sort(key=lambda i: (-joint[i], i))
+    if len(cand) < n_nodes - 1:
+        raise ValueError("tree budget exceeds the number of candidates")
+    keep = set(cand[: n_nodes - 1])
+    keep.add(0)
+    # a kept node's parent has a strictly larger joint probability, so it is kept as well
+    assert all(par[i] in keep for i in keep if i != 0)
+    # breadth-first renumbering
+    children = {i: [] for i in keep}
+    for i in keep:
+        if i != 0:
+            children[par[i]].append(i)
+    order = [0]
+    head = 0
+    while head < len(order):
+        node = order[head]
+        head += 1
+        order.extend(sorted(children[node], key=lambda i: rank[i]))
+    new_id = {old: new for new, old in enumerate(order)}
+    parent = np.full(n_nodes, -1, dtype=np.int32)
+    for old in order[1:]:
+        parent[new_id[old]] = new_id[par[old]]
+    return parent
+
+
+def gen_trees(seed: int, batch: int, n_max: int, depth: int, topk: int, n_nodes=None):
+    """parent [B,Nmax] (unused slots -1) and n_nodes [B]; a different tree per sequence."""
+    rng = np.random.default_rng([seed, 0x7EE])
+    if n_nodes is None:
+        n_nodes = [n_max] * batch
+    parent = np.full((batch, n_max), -1, dtype=np.int32)
+    for b in range(batch):
+        parent[b, : n_nodes[b]] = gen_tree(rng, int(n_nodes[b]), depth, topk)
+    return parent, np.asarray(n_nodes, dtype=np.int32)
+
+
+def gen_qkv(seed: int, batch: int, n_max: int, n_q_heads: int, n_kv_heads: int, head_dim: int,
+            l_cap: int, dtype: str = "bf16"):
+    """q [B,N,Hq,D], k_tree/v_tree [B,N,Hkv,D], k_cache/v_cache [B,Hkv,Lcap,D], all N(0,1),
+    returned as fp32 arrays holding values exactly representable in `dtype`."""
+    rng = np.random.default_rng([seed, 0xA77])
+    shapes = [(batch, n_max, n_q_heads, head_dim), (batch, n_max, n_kv_heads, head_dim),
+              (batch, n_max, n_kv_heads, head_dim), (batch, n_kv_heads, l_cap, head_dim),
+              (batch, n_kv_heads, l_cap, head_dim)]
+    out = []
+    for shp in shapes:
+        x = rng.standard_normal(shp, dtype=np.float32)
+        out.append(round_to_bf16(x) if dtype == "bf16" else x)
+    return tuple(out)
+
+
+def gen_logits(seed: int, batch: int, n_max: int, vocab: int, sigma: float = 3.0,
+               peak: float = 0.0) -> np.ndarray:
+    """fp32 logits [B,N,V] ~ N(0, sigma^2).  peak > 0 lifts one random entry of every row
+    to (row max + peak) so that a single token carries most of the mass (deep accepted
+    paths and multi-rejection residuals for the tests)."""
+    rng = np.random.default_rng([seed, 0x106])
+    x = rng.standard_normal((batch, n_max, vocab), dtype=np.float32) * np.float32(sigma)
+    if peak > 0.0:
+        idx = rng.integers(0, vocab, size=(batch, n_max))
+        mx = x.max(axis=-1)
+        b, i = np.meshgrid(np.arange(batch), np.arange(n_max), indexing="ij")
+        x[b, i, idx] = mx + np.float32(peak)
+    return x
+
+
+def gen_draft_tokens(seed: int, logits: np.ndarray, parent: np.ndarray, n_nodes: np.ndarray,
+                     mode: str = "greedy", noise: float = 1.0) -> np.ndarray:
+    """Draft tokens [B,N] i32 from a perturbed copy of the target.
+
+    The children of node p get distinct tokens, in sibling order: mode "greedy" --
+    the top-m entries of logits[p] + N(0, noise^2); mode "sample" -- m draws
+    without replacement from the categorical distribution with those perturbed
+    logits (Gumbel top-m).  The root's own token is arbitrary."""
+    rng = np.random.default_rng([seed, 0xD4A])
+    batch, n_max, vocab = logits.shape
+    tok = np.zeros((batch, n_max), dtype=np.int32)
+    for b in range(batch):
+        n = int(n_nodes[b])
+        tok[b, 0] = rng.integers(0, vocab)
+        for p in range(n):
+            kids = [c for c in range(p + 1, n) if parent[b, c] == p]
+            if not kids:
+                continue
+            key = logits[b, p].astype(np.float64) + noise * rng.standard_normal(vocab)
+            if mode == "sample":
+                key = key + rng.gumbel(size=vocab)
+            elif mode != "greedy":
+                raise ValueError(mode)
+            m = len(kids)
+            top = np.argpartition(-key, m - 1)[:m] if m < vocab else np.arange(vocab)
+            top = top[np.argsort(-key[top], kind="stable")]
+            tok[b, kids] = top[:m].astype(np.int32)
+    return tok
+
+
+def gen_uniforms(seed: int, batch: int, n_max: int) -> np.ndarray:
+    """fp32 U[0,1) [B,2,N]: [:,0,:] acceptance tests, [:,1,:] bonus draws."""
+    rng = np.random.default_rng([seed, 0x0F1])
+    return rng.random((batch, 2, n_max), dtype=np.float32)
