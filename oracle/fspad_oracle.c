@@ -156,17 +156,17 @@ int fspad_oracle_tree_attn(int32_t B, int32_t Nmax, int32_t Hq, int32_t Hkv, int
 }
 
 /* ------------------------------------------------------------------ row argmax
- * fp32 comparison; ties go to the lowest index; NaN never wins; -0 == +0.
- * A row with no comparable entry (all NaN) gives 0. */
+ * fp32 comparison; ties go to the lowest index; -0 == +0. The paper assumes
+ * finite logits; the reading taken for NaN is that it ranks as -infinity, so it
+ * never beats a number (a row of only NaN / -inf gives token 0). */
 static int32_t row_argmax(const float* row, int32_t V) {
-  int32_t best = -1;
-  float bestv = 0.0f;
+  int32_t best = 0;
+  float bestv = -INFINITY;
   for (int32_t v = 0; v < V; ++v) {
-    const float x = row[v];
-    if (x != x) continue;
-    if (best < 0 || x > bestv) { best = v; bestv = x; }
+    const float x = (row[v] != row[v]) ? -INFINITY : row[v];
+    if (x > bestv) { best = v; bestv = x; }
   }
-  return best < 0 ? 0 : best;
+  return best;
 }
 
 /* ------------------------------------------------------------------ greedy acceptance

@@ -1,0 +1,24 @@
+"""MI355X-native tree verification for draft-then-verify speculative decoding.
+
+The product is libfspad.so (hand-written HIP for gfx950 behind the C ABI of
+include/fspad.h); this package is its ctypes binding.
+"""
+from .binding import (  # noqa: F401
+    EXPORTS,
+    FSPAD_BF16,
+    FSPAD_F32,
+    FSPAD_MAX_NODES,
+    FspadError,
+    fspad_attn_desc,
+    fspad_status_string,
+    fspad_tree_accept_greedy,
+    fspad_tree_accept_sample,
+    fspad_tree_accept_workspace_bytes,
+    fspad_tree_attn,
+    fspad_tree_attn_set_splits,
+    fspad_tree_attn_workspace_bytes,
+    fspad_tree_build_mask,
+    fspad_tree_validate,
+    library_path,
+    make_attn_desc,
+)

@@ -1,0 +1,273 @@
+"""ctypes binding of libfspad.so: argument marshalling only.
+
+Every step of the verification path runs in the HIP kernels behind the C ABI
+(include/fspad.h); PyTorch is used here for device memory and the current HIP
+stream, nothing else.  There is no CPU or PyTorch fallback: if the library has
+not been built, every call raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence
+
+import numpy as np
+import torch
+
+from .build import LIB_PATH
+
+FSPAD_OK = 0
+FSPAD_F32, FSPAD_BF16 = 0, 1
+FSPAD_MAX_NODES = 64
+
+_STATUS_NAMES = {0: "FSPAD_OK", 1: "FSPAD_ERR_NULL", 2: "FSPAD_ERR_SHAPE", 3: "FSPAD_ERR_TREE",
+                 4: "FSPAD_ERR_DTYPE", 5: "FSPAD_ERR_WORKSPACE", 6: "FSPAD_ERR_TEMPERATURE", 7: "FSPAD_ERR_HIP"}
+
+EXPORTS = ("fspad_tree_attn_workspace_bytes", "fspad_tree_attn_set_splits", "fspad_tree_attn",
+           "fspad_tree_accept_workspace_bytes", "fspad_tree_accept_greedy", "fspad_tree_accept_sample",
+           "fspad_tree_build_mask", "fspad_tree_validate", "fspad_status_string")
+
+
+class FspadError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        msg = _lib().fspad_status_string(status).decode() if _LIB is not None else ""
+        super().__init__(f"{where}: {_STATUS_NAMES.get(status, status)} ({msg})")
+
+
+class fspad_attn_desc(ctypes.Structure):
+    _fields_ = [("batch", ctypes.c_int32), ("n_nodes_max", ctypes.c_int32), ("n_q_heads", ctypes.c_int32),
+                ("n_kv_heads", ctypes.c_int32), ("head_dim", ctypes.c_int32), ("io_dtype", ctypes.c_int32),
+                ("out_dtype", ctypes.c_int32), ("softmax_scale", ctypes.c_float),
+                ("cache_stride_batch", ctypes.c_int64), ("cache_stride_head", ctypes.c_int64),
+                ("cache_stride_token", ctypes.c_int64)]
+
+
+_LIB = None
+
+
+def _lib():
+    global _LIB
+    if _LIB is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(
+                f"{LIB_PATH} is missing: build it first (python -m paper_2408_15562_amd.build, or "
+                "__graft_entry__.build()). There is no fallback path.")
+        lib = ctypes.CDLL(LIB_PATH)
+        vp, i32, i64, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_size_t
+        lib.fspad_status_string.restype = ctypes.c_char_p
+        lib.fspad_status_string.argtypes = [ctypes.c_int]
+        lib.fspad_tree_attn_workspace_bytes.restype = sz
+        lib.fspad_tree_attn_workspace_bytes.argtypes = [ctypes.POINTER(fspad_attn_desc), i32]
+        lib.fspad_tree_attn_set_splits.restype = None
+        lib.fspad_tree_attn_set_splits.argtypes = [i32]
+        lib.fspad_tree_attn.restype = ctypes.c_int
+        lib.fspad_tree_attn.argtypes = [ctypes.POINTER(fspad_attn_desc)] + [vp] * 9 + [vp, sz, vp]
+        lib.fspad_tree_accept_workspace_bytes.restype = sz
+        lib.fspad_tree_accept_workspace_bytes.argtypes = [i32, i32, i32]
+        lib.fspad_tree_accept_greedy.restype = ctypes.c_int
+        lib.fspad_tree_accept_greedy.argtypes = [i32, i32, i32, vp, i64, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        lib.fspad_tree_accept_sample.restype = ctypes.c_int
+        lib.fspad_tree_accept_sample.argtypes = [i32, i32, i32, vp, i64, vp, vp, vp, ctypes.c_float, vp,
+                                                 vp, vp, vp, vp, vp, sz, vp]
+        lib.fspad_tree_build_mask.restype = ctypes.c_int
+        lib.fspad_tree_build_mask.argtypes = [i32, i32, vp, vp, vp]
+        lib.fspad_tree_validate.restype = ctypes.c_int
+        lib.fspad_tree_validate.argtypes = [i32, i32, i32, vp, vp, vp]
+        _LIB = lib
+    return _LIB
+
+
+def library_path() -> str:
+    _lib()
+    return LIB_PATH
+
+
+def _check(status: int, where: str):
+    if status != FSPAD_OK:
+        raise FspadError(status, where)
+
+
+def _dev_ptr(t: Optional[torch.Tensor], name: str, dtype=None) -> Optional[int]:
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ValueError(f"{name} must be a device tensor")
+    if dtype is not None and t.dtype != dtype:
+        raise ValueError(f"{name} must be {dtype}, got {t.dtype}")
+    return t.data_ptr()
+
+
+def _host_i32(a, name: str) -> np.ndarray:
+    if isinstance(a, torch.Tensor):
+        if a.is_cuda:
+            raise ValueError(f"{name} must live on the host")
+        a = a.numpy()
+    return np.ascontiguousarray(a, dtype=np.int32)
+
+
+def _stream_ptr(stream) -> int:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
+
+
+def _dtype_code(dt: torch.dtype) -> int:
+    if dt == torch.float32:
+        return FSPAD_F32
+    if dt == torch.bfloat16:
+        return FSPAD_BF16
+    raise FspadError(4, f"dtype {dt}")
+
+
+def make_attn_desc(q: torch.Tensor, k_tree: torch.Tensor, k_cache: Optional[torch.Tensor],
+                   out_dtype: Optional[torch.dtype] = None, softmax_scale: float = 0.0) -> fspad_attn_desc:
+    """Fill the descriptor from tensor shapes; cache strides are taken from k_cache."""
+    B, Nmax, Hq, D = q.shape
+    Hkv = k_tree.shape[2]
+    d = fspad_attn_desc()
+    d.batch, d.n_nodes_max, d.n_q_heads, d.n_kv_heads, d.head_dim = B, Nmax, Hq, Hkv, D
+    d.io_dtype = _dtype_code(q.dtype)
+    d.out_dtype = _dtype_code(out_dtype if out_dtype is not None else q.dtype)
+    d.softmax_scale = float(softmax_scale)
+    if k_cache is not None:
+        if k_cache.stride(3) != 1:
+            raise ValueError("head_dim must be contiguous in the cache")
+        d.cache_stride_batch, d.cache_stride_head, d.cache_stride_token = (
+            k_cache.stride(0), k_cache.stride(1), k_cache.stride(2))
+    else:
+        d.cache_stride_batch = d.cache_stride_head = 0
+        d.cache_stride_token = D
+    return d
+
+
+def fspad_tree_attn_workspace_bytes(desc: fspad_attn_desc, max_kv_len: int) -> int:
+    return int(_lib().fspad_tree_attn_workspace_bytes(ctypes.byref(desc), int(max_kv_len)))
+
+
+def fspad_tree_attn_set_splits(splits: int) -> None:
+    _lib().fspad_tree_attn_set_splits(int(splits))
+
+
+def fspad_tree_attn(q: torch.Tensor, k_tree: torch.Tensor, v_tree: torch.Tensor,
+                    k_cache: Optional[torch.Tensor], v_cache: Optional[torch.Tensor],
+                    kv_len, n_nodes, anc_mask: torch.Tensor, out: Optional[torch.Tensor] = None,
+                    workspace: Optional[torch.Tensor] = None, softmax_scale: float = 0.0,
+                    out_dtype: Optional[torch.dtype] = None, stream=None,
+                    desc: Optional[fspad_attn_desc] = None) -> torch.Tensor:
+    """q [B,Nmax,Hq,D]; k_tree,v_tree [B,Nmax,Hkv,D]; k_cache,v_cache [B,Hkv,Lcap,D] views (any
+    batch/head/token strides); kv_len,n_nodes HOST int32 [B]; anc_mask device int64/uint64 [B,Nmax].
+    Returns out [B,Nmax,Hq,D]."""
+    for name, t in (("q", q), ("k_tree", k_tree), ("v_tree", v_tree)):
+        if not t.is_contiguous():
+            raise ValueError(f"{name} must be contiguous")
+    if k_cache is not None and (v_cache is None or v_cache.stride() != k_cache.stride()
+                                or v_cache.dtype != q.dtype or k_cache.dtype != q.dtype):
+        raise ValueError("k_cache and v_cache must share strides and the dtype of q")
+    if desc is None:
+        desc = make_attn_desc(q, k_tree, k_cache, out_dtype if out_dtype is not None else
+                              (out.dtype if out is not None else None), softmax_scale)
+    kv_len = _host_i32(kv_len, "kv_len")
+    n_nodes = _host_i32(n_nodes, "n_nodes")
+    if kv_len.shape != (desc.batch,) or n_nodes.shape != (desc.batch,):
+        raise ValueError("kv_len and n_nodes must have one entry per sequence")
+    if out is None:
+        out = torch.empty(q.shape, dtype=torch.float32 if desc.out_dtype == FSPAD_F32 else torch.bfloat16,
+                          device=q.device)
+    if anc_mask.dtype not in (torch.int64, torch.uint64) or not anc_mask.is_contiguous():
+        raise ValueError("anc_mask must be a contiguous 64-bit integer tensor")
+    if workspace is None:
+        need = fspad_tree_attn_workspace_bytes(desc, int(kv_len.max(initial=0)))
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=q.device)
+    st = _lib().fspad_tree_attn(
+        ctypes.byref(desc), _dev_ptr(q, "q"), _dev_ptr(k_tree, "k_tree"), _dev_ptr(v_tree, "v_tree"),
+        _dev_ptr(k_cache, "k_cache"), _dev_ptr(v_cache, "v_cache"),
+        kv_len.ctypes.data, n_nodes.ctypes.data, _dev_ptr(anc_mask, "anc_mask"), _dev_ptr(out, "out"),
+        _dev_ptr(workspace, "workspace"), workspace.numel() * workspace.element_size(), _stream_ptr(stream))
+    _check(st, "fspad_tree_attn")
+    return out
+
+
+def fspad_tree_accept_workspace_bytes(B: int, Nmax: int, V: int) -> int:
+    return int(_lib().fspad_tree_accept_workspace_bytes(B, Nmax, V))
+
+
+def _accept_outputs(B, Nmax, device, outputs):
+    if outputs is not None:
+        return outputs
+    return (torch.empty((B, Nmax), dtype=torch.int32, device=device), torch.empty((B,), dtype=torch.int32, device=device),
+            torch.empty((B, Nmax), dtype=torch.int32, device=device), torch.empty((B,), dtype=torch.int32, device=device))
+
+
+def _accept_common(logits, draft_tokens, parent, n_nodes, workspace):
+    if logits.dim() != 3 or logits.stride(2) != 1 or logits.stride(0) != logits.shape[1] * logits.stride(1):
+        raise ValueError("logits must be [B,Nmax,V] with a uniform row stride")
+    B, Nmax, V = logits.shape
+    if workspace is None:
+        workspace = torch.empty(fspad_tree_accept_workspace_bytes(B, Nmax, V), dtype=torch.uint8, device=logits.device)
+    for name, t in (("draft_tokens", draft_tokens), ("parent", parent), ("n_nodes", n_nodes)):
+        if t.dtype != torch.int32 or not t.is_contiguous():
+            raise ValueError(f"{name} must be a contiguous int32 device tensor")
+    return B, Nmax, V, workspace
+
+
+def fspad_tree_accept_greedy(logits: torch.Tensor, draft_tokens: torch.Tensor, parent: torch.Tensor,
+                             n_nodes: torch.Tensor, outputs=None, workspace: Optional[torch.Tensor] = None,
+                             stream=None):
+    """All tensors on the device. Returns (path [B,Nmax], path_len [B], tokens [B,Nmax], n_tokens [B])."""
+    B, Nmax, V, workspace = _accept_common(logits, draft_tokens, parent, n_nodes, workspace)
+    path, path_len, tokens, n_tokens = _accept_outputs(B, Nmax, logits.device, outputs)
+    st = _lib().fspad_tree_accept_greedy(
+        B, Nmax, V, _dev_ptr(logits, "logits", torch.float32), logits.stride(1),
+        _dev_ptr(draft_tokens, "draft_tokens"), _dev_ptr(parent, "parent"), _dev_ptr(n_nodes, "n_nodes"),
+        _dev_ptr(path, "path"), _dev_ptr(path_len, "path_len"), _dev_ptr(tokens, "tokens"),
+        _dev_ptr(n_tokens, "n_tokens"), _dev_ptr(workspace, "workspace"),
+        workspace.numel() * workspace.element_size(), _stream_ptr(stream))
+    _check(st, "fspad_tree_accept_greedy")
+    return path, path_len, tokens, n_tokens
+
+
+def fspad_tree_accept_sample(logits: torch.Tensor, draft_tokens: torch.Tensor, parent: torch.Tensor,
+                             n_nodes: torch.Tensor, temperature: float, uniforms: torch.Tensor, outputs=None,
+                             workspace: Optional[torch.Tensor] = None, stream=None):
+    """uniforms: device fp32 [B,2,Nmax] in [0,1). Returns (path, path_len, tokens, n_tokens)."""
+    B, Nmax, V, workspace = _accept_common(logits, draft_tokens, parent, n_nodes, workspace)
+    if uniforms.dtype != torch.float32 or not uniforms.is_contiguous() or tuple(uniforms.shape) != (B, 2, Nmax):
+        raise ValueError("uniforms must be a contiguous fp32 [B,2,Nmax] device tensor")
+    path, path_len, tokens, n_tokens = _accept_outputs(B, Nmax, logits.device, outputs)
+    st = _lib().fspad_tree_accept_sample(
+        B, Nmax, V, _dev_ptr(logits, "logits", torch.float32), logits.stride(1),
+        _dev_ptr(draft_tokens, "draft_tokens"), _dev_ptr(parent, "parent"), _dev_ptr(n_nodes, "n_nodes"),
+        float(temperature), _dev_ptr(uniforms, "uniforms"),
+        _dev_ptr(path, "path"), _dev_ptr(path_len, "path_len"), _dev_ptr(tokens, "tokens"),
+        _dev_ptr(n_tokens, "n_tokens"), _dev_ptr(workspace, "workspace"),
+        workspace.numel() * workspace.element_size(), _stream_ptr(stream))
+    _check(st, "fspad_tree_accept_sample")
+    return path, path_len, tokens, n_tokens
+
+
+def fspad_tree_build_mask(parent, n_nodes) -> np.ndarray:
+    """Host arrays in, host uint64 [B,Nmax] out."""
+    parent = _host_i32(parent, "parent")
+    n_nodes = _host_i32(n_nodes, "n_nodes")
+    B, Nmax = parent.shape
+    mask = np.zeros((B, Nmax), dtype=np.uint64)
+    st = _lib().fspad_tree_build_mask(B, Nmax, parent.ctypes.data, n_nodes.ctypes.data, mask.ctypes.data)
+    _check(st, "fspad_tree_build_mask")
+    return mask
+
+
+def fspad_tree_validate(parent, tokens, n_nodes, vocab: int) -> int:
+    """Returns the status code (0 = well-formed) instead of raising."""
+    parent = _host_i32(parent, "parent")
+    n_nodes = _host_i32(n_nodes, "n_nodes")
+    B, Nmax = parent.shape
+    tok_ptr = None
+    if tokens is not None:
+        tokens = _host_i32(tokens, "tokens")
+        tok_ptr = tokens.ctypes.data
+    return int(_lib().fspad_tree_validate(B, Nmax, int(vocab), parent.ctypes.data, tok_ptr, n_nodes.ctypes.data))
+
+
+def fspad_status_string(status: int) -> str:
+    return _lib().fspad_status_string(int(status)).decode()

@@ -1,0 +1,432 @@
+// Lossless acceptance over the per-node logits of a verified draft tree
+// (arXiv 2408.15562, Preliminaries, validation phase: strict comparison of the
+// tree with the target's results, a differing token dropped with all its
+// descendants; Experiments "Settings": temperature 0 and 1, acceptance not
+// relaxed). gfx950 (CDNA4) only.
+//
+// Two kernels per call. The first streams the [B*N, V] fp32 logits once, 16 bytes
+// per lane, one workgroup per (row, 8192-entry chunk), and leaves per-chunk
+// statistics: (max, first index of max) for greedy, (max, fp64 sum of
+// exp((l-max)/T)) for sampling. The second, one workgroup per sequence, merges the
+// chunk statistics of the rows it needs, walks the tree with wavefront ballots
+// and, for sampling, draws the last token by an inverse-CDF search that descends
+// chunk -> thread segment -> element.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "fspad.h"
+
+namespace {
+
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+
+constexpr int kChunk = 8192;              // logits per workgroup of the streaming kernel
+constexpr int kThreads = 256;
+constexpr int kPerThread = kChunk / kThreads;  // 32
+constexpr int kNone = 0x7fffffff;
+
+struct AcceptParams {
+  const float* logits;
+  int64_t row_stride;
+  const int32_t* draft_tokens;
+  const int32_t* parent;
+  const int32_t* n_nodes;
+  const float* uniforms;
+  int32_t* path;
+  int32_t* path_len;
+  int32_t* tokens;
+  int32_t* n_tokens;
+  float* part_max;     // [rows][chunks]
+  int32_t* part_idx;   // greedy  [rows][chunks]
+  double* part_sum;    // sampling [rows][chunks]
+  double inv_temperature;
+  int32_t B, Nmax, V, n_chunks;
+};
+
+// exp(x) for x <= 0 in fp64: x = n ln2 + r, |r| <= ln2/2, degree-11 Taylor polynomial
+// (truncation below 1e-14 relative), scaled by 2^n. Returns 0 below the denormal range.
+__device__ __forceinline__ double exp_nonpos(double x) {
+  if (!(x >= -745.2)) return 0.0;  // also catches NaN
+  const double n = rint(x * 1.4426950408889634074);
+  double r = fma(-n, 6.93147180369123816490e-01, x);
+  r = fma(-n, 1.90821492927058770002e-10, r);
+  double p = 1.0 / 39916800.0;
+  p = fma(p, r, 1.0 / 3628800.0);
+  p = fma(p, r, 1.0 / 362880.0);
+  p = fma(p, r, 1.0 / 40320.0);
+  p = fma(p, r, 1.0 / 5040.0);
+  p = fma(p, r, 1.0 / 720.0);
+  p = fma(p, r, 1.0 / 120.0);
+  p = fma(p, r, 1.0 / 24.0);
+  p = fma(p, r, 1.0 / 6.0);
+  p = fma(p, r, 0.5);
+  p = fma(p, r, 1.0);
+  p = fma(p, r, 1.0);
+  return ldexp(p, (int)n);
+}
+
+__device__ __forceinline__ float clean(float x) { return (x != x) ? -INFINITY : x; }  // NaN ranks lowest
+
+// (value, index) with "larger value, then lower index" order
+__device__ __forceinline__ void take_better(float& v, int& i, float ov, int oi) {
+  if (ov > v || (ov == v && oi < i)) { v = ov; i = oi; }
+}
+
+// ------------------------------------------------------------------------------------------------
+// Streaming pass. MODE 0: greedy (max, argmax). MODE 1: sampling (max, sum of exp).
+// VEC: rows are 16-byte aligned so that float4 loads are legal.
+template <int MODE, bool VEC>
+__global__ __launch_bounds__(kThreads) void accept_rows_kernel(const AcceptParams p) {
+  __shared__ float sh_max[4];
+  __shared__ int sh_idx[4];
+  __shared__ double sh_sum[4];
+  const int row = blockIdx.y, chunk = blockIdx.x;
+  const int b = row / p.Nmax, node = row - b * p.Nmax;
+  if (node >= p.n_nodes[b]) return;  // rows of unused tree slots are never read
+  const float* rp = p.logits + (int64_t)row * p.row_stride;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int base = chunk * kChunk;
+
+  float x[kPerThread];
+#pragma unroll
+  for (int k = 0; k < kPerThread / 4; ++k) {
+    const int e0 = base + (k * kThreads + tid) * 4;
+    if (VEC && e0 + 3 < p.V) {
+      const f32x4 v = *reinterpret_cast<const f32x4*>(rp + e0);
+      x[4 * k] = clean(v[0]); x[4 * k + 1] = clean(v[1]); x[4 * k + 2] = clean(v[2]); x[4 * k + 3] = clean(v[3]);
+    } else {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) x[4 * k + j] = (e0 + j < p.V) ? clean(rp[e0 + j]) : -INFINITY;
+    }
+  }
+
+  float best = -INFINITY;
+  int idx = kNone;
+#pragma unroll
+  for (int k = 0; k < kPerThread / 4; ++k)
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+      if (x[4 * k + j] > best) { best = x[4 * k + j]; idx = base + (k * kThreads + tid) * 4 + j; }
+
+  // workgroup (max, index): wavefront butterflies, then 4 partials through LDS
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) {
+    const float ov = __shfl_xor(best, off);
+    const int oi = __shfl_xor(idx, off);
+    take_better(best, idx, ov, oi);
+  }
+  if (lane == 0) { sh_max[wave] = best; sh_idx[wave] = idx; }
+  __syncthreads();
+  best = sh_max[0]; idx = sh_idx[0];
+#pragma unroll
+  for (int w = 1; w < 4; ++w) take_better(best, idx, sh_max[w], sh_idx[w]);
+
+  const int64_t slot = (int64_t)row * p.n_chunks + chunk;
+  if (MODE == 0) {
+    if (tid == 0) { p.part_max[slot] = best; p.part_idx[slot] = idx; }
+    return;
+  }
+  // sampling: fp64 sum of exp((x - chunk max)/T)
+  double sum = 0.0;
+  if (best > -INFINITY) {
+    const double mx = (double)best;
+#pragma unroll
+    for (int k = 0; k < kPerThread; ++k) sum += exp_nonpos(((double)x[k] - mx) * p.inv_temperature);
+  }
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) sum += __shfl_xor(sum, off);
+  if (lane == 0) sh_sum[wave] = sum;
+  __syncthreads();
+  if (tid == 0) {
+    p.part_max[slot] = best;
+    p.part_sum[slot] = (sh_sum[0] + sh_sum[1]) + (sh_sum[2] + sh_sum[3]);
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// Greedy: merge chunk argmaxes per node, then descend while a child carries the target's token.
+__global__ __launch_bounds__(64) void accept_greedy_walk_kernel(const AcceptParams p) {
+  __shared__ int amax[FSPAD_MAX_NODES];
+  const int b = blockIdx.x, lane = threadIdx.x;
+  const int n = p.n_nodes[b];
+  const int64_t o = (int64_t)b * p.Nmax;
+  int my_par = -2, my_tok = -1;
+  if (lane < n) {
+    float best = -INFINITY;
+    int idx = kNone;
+    const int64_t slot0 = (o + lane) * p.n_chunks;
+    for (int c = 0; c < p.n_chunks; ++c) take_better(best, idx, p.part_max[slot0 + c], p.part_idx[slot0 + c]);
+    amax[lane] = idx == kNone ? 0 : idx;  // a row with nothing above -inf: token 0
+    my_par = p.parent[o + lane];
+    my_tok = p.draft_tokens[o + lane];
+  }
+  __syncthreads();
+  int my_path = -1, my_out = -1;  // lane j keeps path[j] and tokens[j]
+  if (lane == 0) my_path = 0;
+  int cur = 0, len = 1;
+  for (int iter = 0; iter < p.Nmax && len < p.Nmax; ++iter) {  // bounded: a well-formed walk ends at a leaf
+    const int a = amax[cur];
+    const bool hit = lane > 0 && lane < n && my_par == cur && my_tok == a;
+    const unsigned long long bal = __ballot(hit);
+    if (bal == 0ull) break;
+    const int nxt = __ffsll(bal) - 1;  // lowest child index first
+    if (lane == len) my_path = nxt;
+    if (lane == len - 1) my_out = a;
+    cur = nxt;
+    ++len;
+  }
+  if (lane == len - 1) my_out = amax[cur];  // bonus: the target's own token after the last accepted node
+  if (lane < p.Nmax) { p.path[o + lane] = my_path; p.tokens[o + lane] = my_out; }
+  if (lane == 0) { p.path_len[b] = len; p.n_tokens[b] = len; }
+}
+
+// ------------------------------------------------------------------------------------------------
+// Sampling: wavefront 0 walks the tree (row statistics merged on demand, children tested in index
+// order against the running residual), then the whole workgroup draws the last token.
+__global__ __launch_bounds__(kThreads) void accept_sample_walk_kernel(const AcceptParams p) {
+  __shared__ int rej_tok[FSPAD_MAX_NODES];
+  __shared__ double rej_w[FSPAD_MAX_NODES];
+  __shared__ double sh_d[8];
+  __shared__ int sh_i[8];
+  __shared__ double scan_part[4];
+  const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int n = p.n_nodes[b];
+  const int64_t o = (int64_t)b * p.Nmax;
+  const float* u_acc = p.uniforms + (int64_t)b * 2 * p.Nmax;
+  const float* u_bonus = u_acc + p.Nmax;
+
+  if (wave == 0) {
+    int my_par = -2;
+    if (lane < n) my_par = p.parent[o + lane];
+    int my_path = lane == 0 ? 0 : -1, my_out = -1;
+    int cur = 0, len = 1, nrej = 0;
+    double M = 0.0, Z = 0.0;
+    for (int iter = 0; iter < p.Nmax; ++iter) {  // one level per iteration; a leaf ends the walk
+      const int64_t row = o + cur;
+      const float* pm = p.part_max + row * p.n_chunks;
+      const double* ps = p.part_sum + row * p.n_chunks;
+      float mx = -INFINITY;
+      for (int c = lane; c < p.n_chunks; c += 64) mx = fmaxf(mx, pm[c]);
+#pragma unroll
+      for (int off = 32; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off));
+      M = (double)mx;
+      double z = 0.0;
+      for (int c = lane; c < p.n_chunks; c += 64)
+        if (pm[c] > -INFINITY) z += ps[c] * exp_nonpos(((double)pm[c] - M) * p.inv_temperature);
+#pragma unroll
+      for (int off = 32; off > 0; off >>= 1) z += __shfl_xor(z, off);
+      Z = z;
+      nrej = 0;
+      unsigned long long kids = __ballot(lane > 0 && lane < n && my_par == cur);
+      int accepted = -1;
+      while (kids != 0ull && len < p.Nmax) {
+        const int c = __ffsll(kids) - 1;
+        kids &= kids - 1ull;
+        const int x = p.draft_tokens[o + c];
+        double w = 0.0;
+        if (x >= 0 && x < p.V) {
+          const float lx = p.logits[row * p.row_stride + x];
+          if (lx == lx && mx > -INFINITY) w = exp_nonpos(((double)lx - M) * p.inv_temperature);
+          for (int r = 0; r < nrej; ++r)
+            if (rej_tok[r] == x) w = 0.0;  // a token already removed from the residual
+        }
+        const double lhs = (double)u_acc[c] * Z;
+        if (lhs < w) { accepted = c; break; }
+        Z -= w;
+        if (lane == 0) { rej_tok[nrej] = x; rej_w[nrej] = w; }
+        ++nrej;
+        __builtin_amdgcn_wave_barrier();
+      }
+      if (accepted < 0) break;
+      if (lane == len) my_path = accepted;
+      if (lane == len - 1) my_out = p.draft_tokens[o + accepted];
+      cur = accepted;
+      ++len;
+    }
+    if (lane < p.Nmax) { p.path[o + lane] = my_path; if (lane != len - 1) p.tokens[o + lane] = my_out; }
+    if (lane == 0) {
+      p.path_len[b] = len; p.n_tokens[b] = len;
+      sh_i[0] = cur; sh_i[1] = len; sh_i[2] = nrej;
+      sh_d[0] = M; sh_d[1] = Z;
+    }
+
+    // bonus, stage 1: which chunk holds the running-sum crossing of t = u * Z
+    const double t = (double)u_bonus[cur] * Z;
+    const int64_t row = o + cur;
+    const float* pm = p.part_max + row * p.n_chunks;
+    const double* ps = p.part_sum + row * p.n_chunks;
+    double carry = 0.0, before = 0.0;
+    int found = -1, last_pos = -1;
+    for (int c0 = 0; c0 < p.n_chunks && found < 0; c0 += 64) {
+      const int c = c0 + lane;
+      double r = 0.0;
+      if (c < p.n_chunks && pm[c] > -INFINITY) {
+        r = ps[c] * exp_nonpos(((double)pm[c] - M) * p.inv_temperature);
+        for (int k = 0; k < nrej; ++k)
+          if (rej_tok[k] >= c * kChunk && rej_tok[k] < (c + 1) * kChunk && rej_tok[k] < p.V) r -= rej_w[k];
+      }
+      double incl = r;
+#pragma unroll
+      for (int off = 1; off < 64; off <<= 1) {
+        const double up = __shfl_up(incl, off);
+        if (lane >= off) incl += up;
+      }
+      const unsigned long long pos = __ballot(r > 0.0);
+      if (pos) last_pos = c0 + 63 - __clzll(pos);
+      const unsigned long long hit = __ballot(c < p.n_chunks && carry + incl > t);
+      if (hit) {
+        const int first = __ffsll(hit) - 1;
+        found = c0 + first;
+        before = carry + __shfl(incl - r, first);
+      } else {
+        carry += __shfl(incl, 63);
+      }
+    }
+    if (lane == 0) {
+      // rounding fallback: the last chunk that still has mass, searched to its end
+      sh_i[3] = found >= 0 ? found : last_pos;
+      sh_i[4] = found >= 0;
+      sh_d[2] = found >= 0 ? t - before : INFINITY;
+    }
+  }
+  __syncthreads();
+
+  // bonus, stage 2: inside the chunk, thread k owns 32 consecutive entries
+  const int cur = sh_i[0], len = sh_i[1], nrej = sh_i[2], chunk = sh_i[3];
+  const double M = sh_d[0], target = sh_d[2];
+  if (chunk < 0) {  // no mass anywhere (cannot happen with finite logits): token 0
+    if (tid == 0) p.tokens[o + len - 1] = 0;
+    return;
+  }
+  const float* rp = p.logits + (o + cur) * p.row_stride;
+  const int e0 = chunk * kChunk + tid * kPerThread;
+  auto weight = [&](int e) -> double {
+    if (e >= p.V) return 0.0;
+    const float lx = rp[e];
+    if (lx != lx) return 0.0;
+    for (int k = 0; k < nrej; ++k)
+      if (rej_tok[k] == e) return 0.0;
+    return exp_nonpos(((double)lx - M) * p.inv_temperature);
+  };
+  double local = 0.0;
+  int last_here = -1;
+  for (int j = 0; j < kPerThread; ++j) {
+    const double w = weight(e0 + j);
+    local += w;
+    if (w > 0.0) last_here = e0 + j;
+  }
+  double incl = local;
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const double up = __shfl_up(incl, off);
+    if (lane >= off) incl += up;
+  }
+  if (lane == 63) scan_part[wave] = incl;
+  __syncthreads();
+  double wave_base = 0.0;
+  for (int w = 0; w < wave; ++w) wave_base += scan_part[w];
+  // the owner is the first thread whose inclusive running sum exceeds the target
+  const double inclusive = wave_base + incl;
+  if (tid == 0) { sh_i[5] = kNone; sh_i[6] = -1; }
+  __syncthreads();
+  if (inclusive > target && local > 0.0) atomicMin(&sh_i[5], tid);
+  if (last_here >= 0) atomicMax(&sh_i[6], last_here);
+  __syncthreads();
+  if (sh_i[5] == kNone) {  // rounding left no crossing: the last entry with mass
+    if (tid == 0) p.tokens[o + len - 1] = sh_i[6] < 0 ? 0 : sh_i[6];
+    return;
+  }
+  if (tid == sh_i[5]) {
+    double run = inclusive - local;
+    int pick = last_here;  // if rounding hides the crossing inside the segment: its last entry with mass
+    for (int j = 0; j < kPerThread; ++j) {
+      run += weight(e0 + j);
+      if (run > target) { pick = e0 + j; break; }
+    }
+    p.tokens[o + len - 1] = pick;
+  }
+}
+
+fspad_status check_accept_args(int32_t B, int32_t Nmax, int32_t V, const float* logits, int64_t row_stride,
+                               const int32_t* draft_tokens, const int32_t* parent, const int32_t* n_nodes,
+                               int32_t* path, int32_t* path_len, int32_t* tokens, int32_t* n_tokens,
+                               void* workspace, size_t workspace_bytes) {
+  if (!logits || !draft_tokens || !parent || !n_nodes || !path || !path_len || !tokens || !n_tokens) return FSPAD_ERR_NULL;
+  if (B < 1 || Nmax < 1 || Nmax > FSPAD_MAX_NODES || V < 1 || V > (1 << 30) || row_stride < V) return FSPAD_ERR_SHAPE;
+  if ((int64_t)B * Nmax > 65535) return FSPAD_ERR_SHAPE;  // grid.y
+  if (((uintptr_t)logits) & 3) return FSPAD_ERR_SHAPE;
+  if (!workspace || ((uintptr_t)workspace & 15) || workspace_bytes < fspad_tree_accept_workspace_bytes(B, Nmax, V))
+    return FSPAD_ERR_WORKSPACE;
+  return FSPAD_OK;
+}
+
+void fill_params(AcceptParams& p, int32_t B, int32_t Nmax, int32_t V, const float* logits, int64_t row_stride,
+                 const int32_t* draft_tokens, const int32_t* parent, const int32_t* n_nodes, int32_t* path,
+                 int32_t* path_len, int32_t* tokens, int32_t* n_tokens, void* workspace) {
+  p.logits = logits; p.row_stride = row_stride; p.draft_tokens = draft_tokens; p.parent = parent;
+  p.n_nodes = n_nodes; p.path = path; p.path_len = path_len; p.tokens = tokens; p.n_tokens = n_tokens;
+  p.B = B; p.Nmax = Nmax; p.V = V; p.n_chunks = (V + kChunk - 1) / kChunk;
+  const size_t slots = (size_t)B * Nmax * p.n_chunks;
+  p.part_sum = reinterpret_cast<double*>(workspace);                 // 8-byte entries first
+  p.part_max = reinterpret_cast<float*>(p.part_sum + slots);
+  p.part_idx = reinterpret_cast<int32_t*>(p.part_max + slots);
+  p.uniforms = nullptr;
+  p.inv_temperature = 1.0;
+}
+
+bool rows_vectorisable(const float* logits, int64_t row_stride) {
+  return (((uintptr_t)logits) & 15) == 0 && (row_stride % 4) == 0;
+}
+
+}  // namespace
+
+extern "C" size_t fspad_tree_accept_workspace_bytes(int32_t B, int32_t Nmax, int32_t V) {
+  if (B < 1 || Nmax < 1 || V < 1) return 0;
+  const size_t slots = (size_t)B * Nmax * ((V + kChunk - 1) / kChunk);
+  return (slots * 16 + 255) & ~(size_t)255;
+}
+
+extern "C" fspad_status fspad_tree_accept_greedy(int32_t B, int32_t Nmax, int32_t V, const float* logits,
+                                                 int64_t row_stride, const int32_t* draft_tokens,
+                                                 const int32_t* parent, const int32_t* n_nodes, int32_t* path,
+                                                 int32_t* path_len, int32_t* tokens, int32_t* n_tokens,
+                                                 void* workspace, size_t workspace_bytes, void* hip_stream) {
+  const fspad_status st = check_accept_args(B, Nmax, V, logits, row_stride, draft_tokens, parent, n_nodes, path,
+                                            path_len, tokens, n_tokens, workspace, workspace_bytes);
+  if (st != FSPAD_OK) return st;
+  AcceptParams p{};
+  fill_params(p, B, Nmax, V, logits, row_stride, draft_tokens, parent, n_nodes, path, path_len, tokens, n_tokens, workspace);
+  hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
+  dim3 grid((unsigned)p.n_chunks, (unsigned)(B * Nmax));
+  if (rows_vectorisable(logits, row_stride)) hipLaunchKernelGGL((accept_rows_kernel<0, true>), grid, dim3(kThreads), 0, stream, p);
+  else hipLaunchKernelGGL((accept_rows_kernel<0, false>), grid, dim3(kThreads), 0, stream, p);
+  if (hipGetLastError() != hipSuccess) return FSPAD_ERR_HIP;
+  hipLaunchKernelGGL(accept_greedy_walk_kernel, dim3((unsigned)B), dim3(64), 0, stream, p);
+  if (hipGetLastError() != hipSuccess) return FSPAD_ERR_HIP;
+  return FSPAD_OK;
+}
+
+extern "C" fspad_status fspad_tree_accept_sample(int32_t B, int32_t Nmax, int32_t V, const float* logits,
+                                                 int64_t row_stride, const int32_t* draft_tokens,
+                                                 const int32_t* parent, const int32_t* n_nodes, float temperature,
+                                                 const float* uniforms, int32_t* path, int32_t* path_len,
+                                                 int32_t* tokens, int32_t* n_tokens, void* workspace,
+                                                 size_t workspace_bytes, void* hip_stream) {
+  if (!(temperature > 0.0f) || temperature > 3.0e38f) return FSPAD_ERR_TEMPERATURE;
+  if (!uniforms) return FSPAD_ERR_NULL;
+  const fspad_status st = check_accept_args(B, Nmax, V, logits, row_stride, draft_tokens, parent, n_nodes, path,
+                                            path_len, tokens, n_tokens, workspace, workspace_bytes);
+  if (st != FSPAD_OK) return st;
+  AcceptParams p{};
+  fill_params(p, B, Nmax, V, logits, row_stride, draft_tokens, parent, n_nodes, path, path_len, tokens, n_tokens, workspace);
+  p.uniforms = uniforms;
+  p.inv_temperature = 1.0 / (double)temperature;
+  hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
+  dim3 grid((unsigned)p.n_chunks, (unsigned)(B * Nmax));
+  if (rows_vectorisable(logits, row_stride)) hipLaunchKernelGGL((accept_rows_kernel<1, true>), grid, dim3(kThreads), 0, stream, p);
+  else hipLaunchKernelGGL((accept_rows_kernel<1, false>), grid, dim3(kThreads), 0, stream, p);
+  if (hipGetLastError() != hipSuccess) return FSPAD_ERR_HIP;
+  hipLaunchKernelGGL(accept_sample_walk_kernel, dim3((unsigned)B), dim3(kThreads), 0, stream, p);
+  if (hipGetLastError() != hipSuccess) return FSPAD_ERR_HIP;
+  return FSPAD_OK;
+}

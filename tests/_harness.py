@@ -1,0 +1,131 @@
+"""Test harness: feeds the same seeded inputs to the GPU library and to the CPU oracle."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+import oracle
+import paper_2408_15562_amd as fspad
+from workloads import gen_draft_tokens, gen_logits, gen_qkv, gen_trees, gen_uniforms
+
+DEV = "cuda:0"
+TOL = {"bf16": 2e-2, "f32": 1e-5}   # max-abs-error relative to the RMS of the oracle output
+MARGIN = 1e-9                        # sampling decisions closer than this to a threshold are not compared
+
+
+def to_dev(a: np.ndarray, dtype: str):
+    t = torch.from_numpy(np.ascontiguousarray(a))
+    return t.to(DEV, dtype=torch.bfloat16 if dtype == "bf16" else torch.float32)
+
+
+class AttnCase:
+    """One attention problem on both sides. Cache tensors are views into a larger allocation
+    (Lcap > max kv_len, optional interleaved K/V heads) so that the strides are exercised."""
+
+    def __init__(self, seed, B, N, Hq, Hkv, D, L, dtype="bf16", n_nodes=None, kv_len=None, depth=6, topk=10,
+                 l_cap=None, interleave=False, parent=None):
+        self.dtype, self.shape = dtype, (B, N, Hq, Hkv, D)
+        kv_len = np.full(B, L, np.int32) if kv_len is None else np.asarray(kv_len, np.int32)
+        self.kv_len = kv_len
+        lmax = int(kv_len.max())
+        l_cap = max(lmax, 1) if l_cap is None else l_cap
+        q, kt, vt, kc, vc = gen_qkv(seed, B, N, Hq, Hkv, D, l_cap, dtype)
+        if parent is None:
+            topk = min(topk, max(1, N - 1))
+            parent, n_nodes = gen_trees(seed, B, N, depth, topk, n_nodes=n_nodes)
+        else:
+            parent = np.asarray(parent, np.int32).reshape(B, N)
+            n_nodes = np.full(B, N, np.int32) if n_nodes is None else np.asarray(n_nodes, np.int32)
+        self.parent, self.n_nodes = parent, n_nodes
+        self.host = dict(q=q, k_tree=kt, v_tree=vt, k_cache=kc, v_cache=vc)
+        self.mask = fspad.fspad_tree_build_mask(parent, n_nodes)
+        self.q, self.k_tree, self.v_tree = to_dev(q, dtype), to_dev(kt, dtype), to_dev(vt, dtype)
+        if interleave:  # K and V heads interleaved in one buffer: [B, Hkv, 2, Lcap, D]
+            both = torch.stack([to_dev(kc, dtype), to_dev(vc, dtype)], dim=2).contiguous()
+            self.k_cache, self.v_cache = both[:, :, 0], both[:, :, 1]
+        else:
+            self.k_cache, self.v_cache = to_dev(kc, dtype), to_dev(vc, dtype)
+        self.mask_dev = torch.from_numpy(self.mask.view(np.int64)).to(DEV)
+
+    def run_gpu(self, out_dtype=torch.float32, scale=0.0, splits=0):
+        fspad.fspad_tree_attn_set_splits(splits)
+        try:
+            out = fspad.fspad_tree_attn(self.q, self.k_tree, self.v_tree, self.k_cache, self.v_cache, self.kv_len,
+                                        self.n_nodes, self.mask_dev, softmax_scale=scale, out_dtype=out_dtype)
+            torch.cuda.synchronize()
+        finally:
+            fspad.fspad_tree_attn_set_splits(0)
+        return out
+
+    def run_oracle(self, scale=None, heads=None, nthreads=16):
+        h = self.host
+        B, N, Hq, Hkv, D = self.shape
+        if heads is None:
+            return oracle.tree_attn(h["q"], h["k_tree"], h["v_tree"], h["k_cache"], h["v_cache"], self.kv_len,
+                                    self.n_nodes, self.parent, packed_mask=self.mask, scale=scale, nthreads=nthreads)
+        # a subset of query heads: run them as an MHA problem over their own kv heads
+        G = Hq // Hkv
+        kvh = [x // G for x in heads]
+        return oracle.tree_attn(h["q"][:, :, heads], h["k_tree"][:, :, kvh], h["v_tree"][:, :, kvh],
+                                h["k_cache"][:, kvh], h["v_cache"][:, kvh], self.kv_len, self.n_nodes, self.parent,
+                                packed_mask=self.mask, scale=scale, nthreads=nthreads)
+
+
+def rel_err(gpu: torch.Tensor, ref: np.ndarray) -> float:
+    """max |gpu - ref| / RMS(ref over its non-zero rows)."""
+    g = gpu.detach().to(torch.float64).cpu().numpy()
+    assert g.shape == ref.shape
+    assert np.all(np.isfinite(g))
+    live = ref[np.abs(ref).sum(axis=-1) > 0]
+    rms = float(np.sqrt(np.mean(live ** 2))) if live.size else 1.0
+    return float(np.abs(g - ref).max() / rms)
+
+
+class AcceptCase:
+    def __init__(self, seed, B, N, V, mode="greedy", depth=6, topk=10, peak=0.0, n_nodes=None, row_pad=0,
+                 parent=None, logits=None, tokens=None, uniforms=None):
+        if parent is None:
+            topk = min(topk, max(1, N - 1))
+            parent, n_nodes = gen_trees(seed, B, N, depth, topk, n_nodes=n_nodes)
+        else:
+            n_nodes = np.full(B, N, np.int32) if n_nodes is None else np.asarray(n_nodes, np.int32)
+        self.parent, self.n_nodes = np.ascontiguousarray(parent, np.int32), n_nodes
+        self.logits = gen_logits(seed, B, N, V, peak=peak) if logits is None else logits
+        self.tokens = gen_draft_tokens(seed, self.logits, self.parent, n_nodes, mode) if tokens is None else tokens
+        self.uniforms = gen_uniforms(seed, B, N) if uniforms is None else uniforms
+        self.B, self.N, self.V = B, N, V
+        if row_pad:  # rows that are not 16-byte aligned / padded strides
+            buf = torch.full((B, N, V + row_pad), float("nan"), dtype=torch.float32, device=DEV)
+            buf[:, :, :V] = torch.from_numpy(self.logits).to(DEV)
+            self.logits_dev = buf[:, :, :V]
+        else:
+            self.logits_dev = torch.from_numpy(self.logits).to(DEV)
+        self.tokens_dev = torch.from_numpy(self.tokens).to(DEV)
+        self.parent_dev = torch.from_numpy(self.parent).to(DEV)
+        self.n_nodes_dev = torch.from_numpy(np.asarray(n_nodes, np.int32)).to(DEV)
+        self.uniforms_dev = torch.from_numpy(self.uniforms).to(DEV)
+
+    def gpu_greedy(self):
+        out = fspad.fspad_tree_accept_greedy(self.logits_dev, self.tokens_dev, self.parent_dev, self.n_nodes_dev)
+        torch.cuda.synchronize()
+        return [t.cpu().numpy() for t in out]
+
+    def gpu_sample(self, temperature=1.0):
+        out = fspad.fspad_tree_accept_sample(self.logits_dev, self.tokens_dev, self.parent_dev, self.n_nodes_dev,
+                                             temperature, self.uniforms_dev)
+        torch.cuda.synchronize()
+        return [t.cpu().numpy() for t in out]
+
+    def cpu_greedy(self):
+        return list(oracle.accept_greedy(self.logits, self.tokens, self.parent, self.n_nodes))
+
+    def cpu_sample(self, temperature=1.0):
+        return list(oracle.accept_sample(self.logits, self.tokens, self.parent, self.n_nodes, temperature, self.uniforms))
+
+
+def assert_accept_equal(gpu, cpu, keep=None):
+    names = ("path", "path_len", "tokens", "n_tokens")
+    for name, g, c in zip(names, gpu, cpu[:4]):
+        if keep is not None:
+            g, c = g[keep], c[keep]
+        np.testing.assert_array_equal(g, c, err_msg=name)

@@ -1,0 +1,180 @@
+"""GPU parity of fspad_tree_attn against the CPU oracle, through the C ABI.
+
+Bar: max-abs-error <= 2e-2 x RMS(oracle output) for bf16 inputs, <= 1e-5 x RMS for fp32.
+"""
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+from workloads import CONFIGS, chain_tree  # noqa: E402
+
+
+@pytest.fixture(scope="module")
+def H():
+    from tests import _harness
+    return _harness
+
+
+def _check(H, case, tol, **kw):
+    out = case.run_gpu(**kw)
+    ref = case.run_oracle(scale=kw.get("scale") or None)
+    err = H.rel_err(out, ref)
+    assert err <= tol, f"rel err {err:.3e} > {tol}"
+    # rows of unused tree slots are written as zeros
+    for b, n in enumerate(case.n_nodes):
+        assert torch.all(out[b, int(n):] == 0)
+    return out, ref, err
+
+
+def test_config0_tiny_fp32(H):
+    c = CONFIGS["c0"]
+    case = H.AttnCase(100, c.batch, c.n_nodes, c.n_q_heads, c.n_kv_heads, c.head_dim, c.kv_len, "f32",
+                      depth=c.tree_depth, topk=c.tree_topk)
+    _check(H, case, H.TOL["f32"])
+
+
+@pytest.mark.parametrize("N,L,Hq,Hkv,D", [
+    (1, 0, 2, 2, 64), (2, 1, 4, 1, 64), (26, 15, 4, 4, 128), (31, 17, 8, 2, 64), (33, 255, 2, 1, 128),
+    (60, 256, 8, 8, 64), (64, 100, 4, 2, 128),
+])
+def test_fp32_sweep(H, N, L, Hq, Hkv, D):
+    case = H.AttnCase(101 + N + L, 2, N, Hq, Hkv, D, L, "f32", l_cap=L + 3)
+    _check(H, case, H.TOL["f32"])
+
+
+@pytest.mark.parametrize("N", [1, 2, 16, 17, 26, 31, 32, 33, 48, 60, 63, 64])
+@pytest.mark.parametrize("L", [0, 1, 31, 32, 33, 255, 1000])
+def test_bf16_mha_sweep_nodes_and_lengths(H, N, L):
+    case = H.AttnCase(7 * N + L, 2, N, 2, 2, 128, L, "bf16", l_cap=L + 5)
+    _check(H, case, H.TOL["bf16"])
+
+
+@pytest.mark.parametrize("Hq,Hkv", [(4, 4), (4, 1), (8, 2), (8, 1), (16, 2)])
+@pytest.mark.parametrize("D", [64, 128])
+@pytest.mark.parametrize("N", [5, 26, 60])
+def test_bf16_gqa_and_head_dim(H, Hq, Hkv, D, N):
+    case = H.AttnCase(13 * Hq + D + N, 1, N, Hq, Hkv, D, 200, "bf16")
+    _check(H, case, H.TOL["bf16"])
+
+
+@pytest.mark.parametrize("splits", [1, 2, 3, 7, 16])
+def test_bf16_split_kv_factors(H, splits):
+    case = H.AttnCase(300 + splits, 2, 26, 4, 4, 128, 777, "bf16", kv_len=[777, 40])
+    out, ref, _ = _check(H, case, H.TOL["bf16"], splits=splits)
+    # run-to-run determinism (no floating-point atomics in the merge)
+    again = case.run_gpu(splits=splits)
+    assert torch.equal(out, again)
+
+
+def test_bf16_ragged_batch_and_strided_cache(H):
+    case = H.AttnCase(400, 4, 60, 8, 2, 128, 0, "bf16", kv_len=[513, 0, 64, 1], n_nodes=[60, 1, 33, 17],
+                      l_cap=600, interleave=True)
+    _check(H, case, H.TOL["bf16"])
+    _check(H, case, H.TOL["bf16"], splits=4)
+
+
+def test_bf16_output_is_rounded_fp32_output(H):
+    case = H.AttnCase(401, 1, 26, 4, 4, 128, 300, "bf16")
+    o32 = case.run_gpu(out_dtype=torch.float32)
+    o16 = case.run_gpu(out_dtype=torch.bfloat16)
+    assert torch.equal(o16, o32.to(torch.bfloat16))
+    o16s = case.run_gpu(out_dtype=torch.bfloat16, splits=3)
+    assert torch.equal(o16s, case.run_gpu(out_dtype=torch.float32, splits=3).to(torch.bfloat16))
+
+
+def test_custom_scale(H):
+    case = H.AttnCase(402, 1, 26, 4, 2, 64, 100, "bf16")
+    _check(H, case, H.TOL["bf16"], scale=0.05)
+    case32 = H.AttnCase(403, 1, 26, 4, 2, 64, 100, "f32")
+    _check(H, case32, H.TOL["f32"], scale=0.05)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_zero_query_closed_form_on_gpu(H, dtype):
+    """Q = 0 => every row is the plain mean of the visible value rows: catches mask and stride
+    mistakes that a tolerance could hide."""
+    case = H.AttnCase(404, 1, 60, 2, 1, 128, 100, dtype)
+    case.q.zero_()
+    out = case.run_gpu().double().cpu().numpy()
+    v_pre = case.host["v_cache"][0, 0, :100].astype(np.float64)
+    v_tree = case.host["v_tree"][0, :, 0].astype(np.float64)
+    for i in range(60):
+        anc, a = [], i
+        while a >= 0:
+            anc.append(a)
+            a = int(case.parent[0, a])
+        expect = (v_pre.sum(0) + v_tree[anc].sum(0)) / (100 + len(anc))
+        tol = 2e-2 * np.sqrt(np.mean(expect ** 2)) if dtype == "bf16" else 1e-5
+        assert np.abs(out[0, i] - expect).max() <= tol
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_chain_tree_is_causal_attention_on_gpu(H, dtype):
+    import torch.nn.functional as F
+    N, L, Hh, D = 33, 70, 2, 64
+    case = H.AttnCase(405, 1, N, Hh, Hh, D, L, dtype, parent=chain_tree(N))
+    out = case.run_gpu().double().cpu()
+    h = case.host
+    k_all = torch.from_numpy(np.concatenate([h["k_cache"][0, :, :L], h["k_tree"][0].transpose(1, 0, 2)], axis=1)).double()
+    v_all = torch.from_numpy(np.concatenate([h["v_cache"][0, :, :L], h["v_tree"][0].transpose(1, 0, 2)], axis=1)).double()
+    q_full = torch.zeros(Hh, L + N, D, dtype=torch.float64)
+    q_full[:, L:] = torch.from_numpy(h["q"][0].transpose(1, 0, 2)).double()
+    ref = F.scaled_dot_product_attention(q_full[None], k_all[None], v_all[None], is_causal=True)[0, :, L:]
+    ref = ref.permute(1, 0, 2)
+    rms = ref.pow(2).mean().sqrt().item()
+    assert (out[0] - ref).abs().max().item() <= H.TOL[dtype] * rms
+
+
+def test_config1_vicuna7b_layer_full(H):
+    c = CONFIGS["c1"]
+    case = H.AttnCase(500, c.batch, c.n_nodes, c.n_q_heads, c.n_kv_heads, c.head_dim, c.kv_len, "bf16",
+                      depth=c.tree_depth, topk=c.tree_topk)
+    _check(H, case, H.TOL["bf16"])
+    out16 = case.run_gpu(out_dtype=torch.bfloat16)
+    # bf16 output: the fp32 bound plus half a bf16 ulp of the largest output
+    ref = case.run_oracle()
+    assert H.rel_err(out16.float(), ref) <= H.TOL["bf16"] + 2.0 ** -8 * np.abs(ref).max() / np.sqrt(np.mean(ref ** 2))
+
+
+def test_config2_llama3_8b_gqa_layer_full(H):
+    c = CONFIGS["c2"]
+    case = H.AttnCase(501, c.batch, c.n_nodes, c.n_q_heads, c.n_kv_heads, c.head_dim, c.kv_len, "bf16",
+                      depth=c.tree_depth, topk=c.tree_topk)
+    _check(H, case, H.TOL["bf16"])
+
+
+def test_config3_one_layer_four_sequences_sampled_heads(H):
+    """One layer of the Vicuna-33B-shaped stack at full size (B=4, 52 heads, L=4096, N=60), in the
+    launch configuration the benchmark uses; the oracle checks all rows of 6 sampled heads."""
+    c = CONFIGS["c3"]
+    case = H.AttnCase(502, c.batch, c.n_nodes, c.n_q_heads, c.n_kv_heads, c.head_dim, c.kv_len, "bf16",
+                      depth=c.tree_depth, topk=c.tree_topk)
+    out = case.run_gpu()
+    heads = [0, 7, 19, 33, 44, 51]
+    ref = case.run_oracle(heads=heads)
+    assert H.rel_err(out[:, :, heads], ref) <= H.TOL["bf16"]
+    assert torch.isfinite(out).all()
+
+
+def test_config4_one_layer_long_context_sampled_heads(H):
+    """One layer of the LLaMA3-70B-shaped stack (64/8 GQA, L=16384, N=60); oracle on 4 sampled heads."""
+    c = CONFIGS["c4"]
+    case = H.AttnCase(503, c.batch, c.n_nodes, c.n_q_heads, c.n_kv_heads, c.head_dim, c.kv_len, "bf16",
+                      depth=c.tree_depth, topk=c.tree_topk)
+    out = case.run_gpu()
+    heads = [0, 13, 38, 63]
+    ref = case.run_oracle(heads=heads)
+    assert H.rel_err(out[:, :, heads], ref) <= H.TOL["bf16"]
+    assert torch.isfinite(out).all()
+
+
+def test_missing_workspace_is_an_error_not_a_crash(H):
+    import paper_2408_15562_amd as fspad
+    case = H.AttnCase(504, 1, 26, 32, 32, 128, 2048, "bf16")
+    tiny = torch.empty(16, dtype=torch.uint8, device=H.DEV)
+    with pytest.raises(fspad.FspadError) as e:
+        fspad.fspad_tree_attn(case.q, case.k_tree, case.v_tree, case.k_cache, case.v_cache, case.kv_len,
+                              case.n_nodes, case.mask_dev, workspace=tiny)
+    assert e.value.status == 5

@@ -1,0 +1,135 @@
+"""CPU-only checks of the boundary: the library loads, exports what include/fspad.h declares,
+and the host-side logic (mask builder, validator, argument checks) behaves as documented.
+No kernel is launched here."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2408_15562_amd as fspad
+from paper_2408_15562_amd import binding
+from workloads import gen_trees
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    return ctypes.CDLL(fspad.library_path())
+
+
+def test_library_exports_every_declared_symbol(lib):
+    header = open(os.path.join(ROOT, "include", "fspad.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(fspad_[a-z_]+)\s*\(", header))
+    assert declared == set(fspad.EXPORTS)
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_status_strings():
+    seen = {fspad.fspad_status_string(i) for i in range(8)}
+    assert len(seen) == 8 and "unknown status" not in seen
+    assert fspad.fspad_status_string(99) == "unknown status"
+
+
+def _closure(parent, n):
+    words = []
+    for i in range(n):
+        w, a = 0, i
+        while a >= 0:
+            w |= 1 << a
+            a = int(parent[a])
+        words.append(w)
+    return words
+
+
+def test_build_mask_is_transitive_closure():
+    parent, n_nodes = gen_trees(21, 3, 64, 6, 10, n_nodes=[64, 26, 1])
+    mask = fspad.fspad_tree_build_mask(parent, n_nodes)
+    for b in range(3):
+        n = int(n_nodes[b])
+        assert [int(x) for x in mask[b, :n]] == _closure(parent[b], n)
+        assert np.all(mask[b, n:] == 0)
+        for i in range(n):
+            depth = len(_closure(parent[b], n)) and bin(int(mask[b, i])).count("1") - 1
+            assert (int(mask[b, i]) >> i) & 1 and int(mask[b, i]) >> (i + 1) == 0 and depth >= 0
+
+
+def test_build_mask_and_validate_reject_bad_trees():
+    good = np.array([[-1, 0, 0, 1]], np.int32)
+    tok = np.array([[5, 1, 2, 1]], np.int32)
+    assert fspad.fspad_tree_validate(good, tok, [4], 10) == 0
+    assert fspad.fspad_tree_validate(good, None, [4], 10) == 0
+    for bad in ([[0, 0, 0, 1]], [[-1, 1, 0, 1]], [[-1, 0, 3, 1]], [[-1, -1, 0, 1]]):
+        bad = np.array(bad, np.int32)
+        assert fspad.fspad_tree_validate(bad, tok, [4], 10) == 3
+        with pytest.raises(fspad.FspadError) as e:
+            fspad.fspad_tree_build_mask(bad, [4])
+        assert e.value.status == 3
+    assert fspad.fspad_tree_validate(good, np.array([[5, 1, 1, 1]], np.int32), [4], 10) == 3   # twin siblings
+    assert fspad.fspad_tree_validate(good, np.array([[5, 1, 2, 10]], np.int32), [4], 10) == 3  # token out of range
+    assert fspad.fspad_tree_validate(good, tok, [5], 10) == 2                                  # n_nodes > Nmax
+    assert fspad.fspad_tree_validate(np.zeros((1, 65), np.int32), None, [1], 10) == 2          # Nmax > 64
+
+
+def _desc(**kw):
+    d = binding.fspad_attn_desc()
+    d.batch, d.n_nodes_max, d.n_q_heads, d.n_kv_heads, d.head_dim = 1, 26, 32, 32, 128
+    d.io_dtype = d.out_dtype = binding.FSPAD_BF16
+    d.cache_stride_token, d.cache_stride_head, d.cache_stride_batch = 128, 128 * 2048, 128 * 2048 * 32
+    for k, v in kw.items():
+        setattr(d, k, v)
+    return d
+
+
+def test_attn_argument_checks_need_no_gpu(lib):
+    f = lib.fspad_tree_attn
+    f.restype = ctypes.c_int
+    kv = (ctypes.c_int32 * 1)(2048)
+    nn = (ctypes.c_int32 * 1)(26)
+    fake = ctypes.c_void_p(0x1000)  # never dereferenced: every case below fails validation first
+
+    def call(d, q=fake, kvp=kv, nnp=nn, ws=fake, wsb=1 << 30):
+        return f(ctypes.byref(d), q, fake, fake, fake, fake, kvp, nnp, fake, fake, ws, ctypes.c_size_t(wsb), None)
+
+    assert call(_desc(), q=None) == 1
+    assert call(_desc(n_nodes_max=65)) == 2
+    assert call(_desc(head_dim=96)) == 2
+    assert call(_desc(n_kv_heads=5)) == 2
+    assert call(_desc(io_dtype=3)) == 4
+    assert call(_desc(io_dtype=0, out_dtype=1)) == 4
+    assert call(_desc(cache_stride_token=100)) == 2
+    assert call(_desc(), nnp=(ctypes.c_int32 * 1)(27)) == 2
+    assert call(_desc(), kvp=(ctypes.c_int32 * 1)(-1)) == 2
+    assert call(_desc(), wsb=16) == 5
+    assert binding.fspad_tree_attn_workspace_bytes(_desc(), 2048) > 16
+    assert binding.fspad_tree_attn_workspace_bytes(_desc(head_dim=96), 2048) == 0
+
+
+def test_accept_argument_checks_need_no_gpu(lib):
+    g, s = lib.fspad_tree_accept_greedy, lib.fspad_tree_accept_sample
+    fake = ctypes.c_void_p(0x1000)
+    i32, i64, sz = ctypes.c_int32, ctypes.c_int64, ctypes.c_size_t
+    need = fspad.fspad_tree_accept_workspace_bytes(1, 26, 32000)
+    assert need >= 26 * 4 * 16
+
+    def greedy(B=1, N=26, V=32000, logits=fake, stride=32000, ws=fake, wsb=need):
+        return g(i32(B), i32(N), i32(V), logits, i64(stride), fake, fake, fake, fake, fake, fake, fake, ws, sz(wsb), None)
+
+    assert greedy(logits=None) == 1
+    assert greedy(N=65) == 2
+    assert greedy(V=0) == 2
+    assert greedy(stride=100) == 2
+    assert greedy(wsb=need - 1) == 5
+    assert greedy(ws=None) == 5
+
+    def sample(T, uni=fake):
+        return s(i32(1), i32(26), i32(32000), fake, i64(32000), fake, fake, fake, ctypes.c_float(T), uni,
+                 fake, fake, fake, fake, fake, sz(need), None)
+
+    for t in (0.0, -1.0, float("inf"), float("nan")):
+        assert sample(t) == 6
+    assert sample(1.0, uni=None) == 1
