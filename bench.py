@@ -1,0 +1,213 @@
+#!/usr/bin/env python3
+"""Benchmark of the tree-verification hot path on one MI355X.
+
+One *step* = tree-masked attention for every layer of the workload (one
+fspad_tree_attn call per layer, each over its own KV buffers) followed by one
+acceptance call over the per-node logits.  Inputs are synthetic, seeded, resident
+in HBM before the timed region; single-layer workloads rotate through enough
+independent buffer sets that they stream from HBM rather than the last-level cache.
+
+Prints ONE JSON line (see README / DESIGN for the fields).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0      # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=None)
+    ap.add_argument("--warmup", type=int, default=None)
+    ap.add_argument("--workload", default="c1", choices=["c0", "c1", "c2", "c3", "c4"])
+    ap.add_argument("--accept", default=None, choices=["greedy", "sample"], help="override the workload's acceptance mode")
+    ap.add_argument("--sets", type=int, default=None, help="independent buffer sets to rotate through")
+    ap.add_argument("--splits", type=int, default=0, help="force the split-KV factor (0 = automatic)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--seed", type=int, default=2024)
+    return ap.parse_args()
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on exactly one GPU (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2408_15562_amd as fspad
+    from workloads import CONFIGS, GENERATOR_VERSION, gen_draft_tokens, gen_logits, gen_trees, gen_uniforms
+
+    fspad.library_path()  # fail loudly if the HIP library is missing
+    if not torch.cuda.is_available():
+        raise RuntimeError("bench.py needs a GPU")
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    cfg = CONFIGS[args.workload]
+    accept = args.accept or cfg.accept
+    tdt = torch.float32 if cfg.dtype == "f32" else torch.bfloat16
+    B, N, Hq, Hkv, D, L, V = cfg.batch, cfg.n_nodes, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.kv_len, cfg.vocab
+
+    # single-layer workloads are far smaller than the 256 MB last-level cache: rotate buffer sets
+    set_bytes = cfg.step_bytes()
+    n_sets = args.sets if args.sets is not None else (1 if set_bytes > 2e9 else max(2, int(np.ceil(1.0e9 / set_bytes))))
+    steps = args.steps if args.steps is not None else (20 if set_bytes > 2e9 else 200)
+    warmup = args.warmup if args.warmup is not None else (3 if set_bytes > 2e9 else 20)
+
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(args.seed)
+    parent, n_nodes = gen_trees(args.seed, B, N, cfg.tree_depth, cfg.tree_topk)
+    mask = torch.from_numpy(fspad.fspad_tree_build_mask(parent, n_nodes).view(np.int64)).to(dev)
+    kv_len = np.full(B, L, np.int32)
+
+    sets = []
+    for s in range(n_sets):
+        layers = []
+        for _ in range(cfg.layers):
+            kc = torch.empty((B, Hkv, L, D), device=dev, dtype=tdt).normal_(generator=gen)
+            vc = torch.empty((B, Hkv, L, D), device=dev, dtype=tdt).normal_(generator=gen)
+            q = torch.empty((B, N, Hq, D), device=dev, dtype=tdt).normal_(generator=gen)
+            kt = torch.empty((B, N, Hkv, D), device=dev, dtype=tdt).normal_(generator=gen)
+            vt = torch.empty((B, N, Hkv, D), device=dev, dtype=tdt).normal_(generator=gen)
+            out = torch.empty((B, N, Hq, D), device=dev, dtype=tdt)
+            layers.append((q, kt, vt, kc, vc, out))
+        logits_h = gen_logits(args.seed + s, B, N, V)
+        tokens_h = gen_draft_tokens(args.seed + s, logits_h, parent, n_nodes, accept)
+        sets.append(dict(layers=layers, logits=torch.from_numpy(logits_h).to(dev), tokens=torch.from_numpy(tokens_h).to(dev),
+                         uniforms=torch.from_numpy(gen_uniforms(args.seed + s, B, N)).to(dev)))
+    parent_d = torch.from_numpy(parent).to(dev)
+    n_nodes_d = torch.from_numpy(n_nodes).to(dev)
+
+    fspad.fspad_tree_attn_set_splits(args.splits)
+    desc = fspad.make_attn_desc(sets[0]["layers"][0][0], sets[0]["layers"][0][1], sets[0]["layers"][0][3], tdt, 0.0)
+    ws_attn = torch.empty(max(16, fspad.fspad_tree_attn_workspace_bytes(desc, L)), dtype=torch.uint8, device=dev)
+    ws_acc = torch.empty(fspad.fspad_tree_accept_workspace_bytes(B, N, V), dtype=torch.uint8, device=dev)
+    acc_out = (torch.empty((B, N), dtype=torch.int32, device=dev), torch.empty((B,), dtype=torch.int32, device=dev),
+               torch.empty((B, N), dtype=torch.int32, device=dev), torch.empty((B,), dtype=torch.int32, device=dev))
+
+    def step(i, events=None):
+        st = sets[i % n_sets]
+        for (q, kt, vt, kc, vc, out) in st["layers"]:
+            if events is not None:
+                e0 = torch.cuda.Event(enable_timing=True); e1 = torch.cuda.Event(enable_timing=True)
+                e0.record()
+            fspad.fspad_tree_attn(q, kt, vt, kc, vc, kv_len, n_nodes, mask, out=out, workspace=ws_attn, desc=desc)
+            if events is not None:
+                e1.record()
+                events.append((e0, e1))
+        if accept == "greedy":
+            fspad.fspad_tree_accept_greedy(st["logits"], st["tokens"], parent_d, n_nodes_d, outputs=acc_out, workspace=ws_acc)
+        else:
+            fspad.fspad_tree_accept_sample(st["logits"], st["tokens"], parent_d, n_nodes_d, cfg.temperature,
+                                           st["uniforms"], outputs=acc_out, workspace=ws_acc)
+
+    for i in range(warmup):
+        step(i)
+    torch.cuda.synchronize()
+    events = []
+    t0 = time.perf_counter()
+    for i in range(steps):
+        step(warmup + i, events)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / steps
+    attn_ms = float(np.mean([a.elapsed_time(b) for a, b in events]))  # one fspad_tree_attn call (all its kernels)
+    n_tokens_mean = float(acc_out[3].float().mean().item())
+
+    attn_bytes = cfg.attn_bytes_per_layer()
+    attn_flops = cfg.attn_flops_per_layer()
+    achieved_gbs = attn_bytes / (attn_ms * 1e-3) / 1e9
+    achieved_tflops = attn_flops / (attn_ms * 1e-3) / 1e12
+    flop_per_byte = attn_flops / attn_bytes
+    mfma_bound = flop_per_byte > MFMA_BF16_PEAK_TFLOPS * 1e12 / (HBM_PEAK_GBS * 1e9) and cfg.dtype == "bf16"
+    if mfma_bound:
+        roofline = dict(bound="mfma", achieved=achieved_tflops, peak=MFMA_BF16_PEAK_TFLOPS, unit="TFLOP/s",
+                        frac=achieved_tflops / MFMA_BF16_PEAK_TFLOPS)
+    else:
+        roofline = dict(bound="hbm", achieved=achieved_gbs, peak=HBM_PEAK_GBS, unit="GB/s", frac=achieved_gbs / HBM_PEAK_GBS)
+    roofline.update(kernel="fspad_tree_attn (split-KV kernel + merge kernel)", launch_ms=attn_ms,
+                    algorithmic_bytes=attn_bytes, algorithmic_flops=attn_flops,
+                    traffic=MEASURED_TRAFFIC_BYTES.get(args.workload))
+
+    result = {
+        "metric": "tree-verify steps/s", "value": 1e3 / ms_per_step, "unit": "steps/s", "n_gpus": 1, "steps": steps,
+        "warmup": warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": cfg.name, "layers": cfg.layers, "batch": B, "n_q_heads": Hq, "n_kv_heads": Hkv,
+                   "head_dim": D, "kv_len": L, "tree_nodes": N, "vocab": V, "accept": accept, "buffer_sets": n_sets,
+                   "seed": args.seed, "generator_version": GENERATOR_VERSION, "parallelism": "single-gpu"},
+        "step_gb_per_s": cfg.step_bytes() / (ms_per_step * 1e-3) / 1e9,
+        "step_hbm_frac": cfg.step_bytes() / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "attn_tflops": achieved_tflops, "attn_gb_per_s": achieved_gbs,
+        "mean_tokens_per_step": n_tokens_mean,
+        "roofline": roofline,
+    }
+
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(cfg, accept, sets[0], parent, n_nodes, kv_len, args.seed)
+    print(json.dumps(result))
+
+
+# HBM bytes per fspad_tree_attn call measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by a
+# copy kernel of known size); filled in from the summaries under profiles/. None = not measured.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def cpu_baseline(cfg, accept, dev_set, parent, n_nodes, kv_len, seed):
+    """The CPU oracle, as it stands, on this machine's host cores, on a bounded sample of the workload."""
+    import numpy as np
+
+    import oracle
+    cores = min(os.cpu_count() or 1, int(os.environ.get("OMP_NUM_THREADS", "16")), 16)
+    B, N, Hq, Hkv = cfg.batch, cfg.n_nodes, cfg.n_q_heads, cfg.n_kv_heads
+    G = Hq // Hkv
+    # sample: all sequences, a subset of the query heads of ONE layer, sized to a few seconds of CPU work
+    work_per_head = 2.0 * N * (cfg.kv_len + N) * cfg.head_dim * 2 * B     # flops of one query head, all sequences
+    heads = int(max(1, min(Hq, 4.0e9 // work_per_head)))
+    head_ids = sorted(set(np.linspace(0, Hq - 1, heads).astype(int).tolist()))
+    kvh = [h // G for h in head_ids]
+    q, kt, vt, kc, vc, _ = dev_set["layers"][0]
+    host = [q[:, :, head_ids].float().cpu().numpy(), kt[:, :, kvh].float().cpu().numpy(), vt[:, :, kvh].float().cpu().numpy(),
+            kc[:, kvh].float().cpu().numpy(), vc[:, kvh].float().cpu().numpy()]
+    logits = dev_set["logits"].cpu().numpy()
+    tokens = dev_set["tokens"].cpu().numpy()
+    uniforms = dev_set["uniforms"].cpu().numpy()
+    t_attn, t_acc, reps = 0.0, 0.0, 0
+    t_start = time.perf_counter()
+    while reps < 1 or (time.perf_counter() - t_start < 10.0 and reps < 50):
+        t0 = time.perf_counter()
+        oracle.tree_attn(*host, kv_len, n_nodes, parent, nthreads=cores)
+        t1 = time.perf_counter()
+        if accept == "greedy":
+            oracle.accept_greedy(logits, tokens, parent, n_nodes)
+        else:
+            oracle.accept_sample(logits, tokens, parent, n_nodes, cfg.temperature, uniforms)
+        t2 = time.perf_counter()
+        t_attn += t1 - t0
+        t_acc += t2 - t1
+        reps += 1
+    # whole step = every head of every layer (attention extrapolated linearly from the sampled heads) + acceptance
+    step_s = (t_attn / reps) * (Hq / len(head_ids)) * cfg.layers + t_acc / reps
+    extrap = len(head_ids) < Hq or cfg.layers > 1
+    return {"value": 1.0 / step_s, "unit": "steps/s", "cores": cores, "kind": "oracle",
+            "sample": (f"{reps} repetitions of: attention of {len(head_ids)}/{Hq} query heads of 1/{cfg.layers} layers, all "
+                       f"{B} sequences (OpenMP over heads, {cores} threads) + full {accept} acceptance (1 thread)"
+                       + ("; step time extrapolated linearly to all heads and layers" if extrap else "")),
+            "extrapolated": extrap}
+
+
+if __name__ == "__main__":
+    main()
