@@ -33,8 +33,9 @@ def parse_args():
     ap.add_argument("--workload", default="c1", choices=["c0", "c1", "c2", "c3", "c4"])
     ap.add_argument("--accept", default=None, choices=["greedy", "sample"], help="override the workload's acceptance mode")
     ap.add_argument("--sets", type=int, default=None, help="independent buffer sets to rotate through")
-    ap.add_argument("--splits", type=int, default=0, help="force the split-KV factor (0 = automatic)")
+    ap.add_argument("--splits", type=int, default=0, help="force the number of attention workgroups (0 = automatic)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--max-qt", type=int, default=0, help=argparse.SUPPRESS)
     ap.add_argument("--seed", type=int, default=2024)
     return ap.parse_args()
 
@@ -91,7 +92,10 @@ def main():
     parent_d = torch.from_numpy(parent).to(dev)
     n_nodes_d = torch.from_numpy(n_nodes).to(dev)
 
-    fspad.fspad_tree_attn_set_splits(args.splits)
+    if args.max_qt:
+        import ctypes
+        ctypes.CDLL(fspad.library_path()).fspad_debug_set_max_qt(args.max_qt)
+    fspad.fspad_tree_attn_set_workgroups(args.splits)
     desc = fspad.make_attn_desc(sets[0]["layers"][0][0], sets[0]["layers"][0][1], sets[0]["layers"][0][3], tdt, 0.0)
     ws_attn = torch.empty(max(16, fspad.fspad_tree_attn_workspace_bytes(desc, L)), dtype=torch.uint8, device=dev)
     ws_acc = torch.empty(fspad.fspad_tree_accept_workspace_bytes(B, N, V), dtype=torch.uint8, device=dev)

@@ -97,10 +97,11 @@ typedef struct {
  */
 size_t fspad_tree_attn_workspace_bytes(const fspad_attn_desc* desc, int32_t max_kv_len);
 
-/* Tuning knob, process-wide: force the split-KV factor of the bf16 path (1..64);
- * 0 restores the built-in choice. Affects fspad_tree_attn_workspace_bytes too, so
- * set it before sizing the workspace. Not needed for correct results. */
-void fspad_tree_attn_set_splits(int32_t splits);
+/* Tuning knob, process-wide: force the number of workgroups the bf16 path spreads
+ * its key blocks over (1..4096); 0 restores the built-in choice. It changes
+ * fspad_tree_attn_workspace_bytes too, so set it before sizing the workspace.
+ * Not needed for correct results. */
+void fspad_tree_attn_set_workgroups(int32_t workgroups);
 
 fspad_status fspad_tree_attn(const fspad_attn_desc* desc,
                              const void* q, const void* k_tree, const void* v_tree,

@@ -15,7 +15,7 @@ from .binding import (  # noqa: F401
     fspad_tree_accept_sample,
     fspad_tree_accept_workspace_bytes,
     fspad_tree_attn,
-    fspad_tree_attn_set_splits,
+    fspad_tree_attn_set_workgroups,
     fspad_tree_attn_workspace_bytes,
     fspad_tree_build_mask,
     fspad_tree_validate,

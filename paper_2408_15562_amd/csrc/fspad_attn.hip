@@ -41,16 +41,18 @@ struct AttnParams {
   const void* v_cache;
   const uint64_t* anc_mask;
   void* out;
-  float* part_o;   // [S][rows][D]   un-normalised partial outputs
-  float* part_ml;  // [S][rows][2]   (running max in log2 units, running sum)
+  float* part;     // partial slots: [slot][rows_per_unit][D] un-normalised outputs, then [rows_per_unit][2] (shift, sum)
   int64_t stride_batch, stride_head, stride_token;  // cache strides, elements
   int32_t B, Nmax, Hq, Hkv, G;
-  int32_t S;        // split-KV factor (grid.x)
   int32_t WS;       // row slabs per workgroup: 1, 2 or 4 (4/WS wavefronts share a slab and split its keys)
   int32_t NS;       // row slabs per kv head
+  int32_t GY;       // slab groups per kv head: a (sequence, kv head, slab group) is one unit of work
+  int32_t n_wgs;    // workgroups of the flat decomposition
+  int64_t total_blocks;  // 32-key blocks summed over all units
   int32_t out_bf16;
   float scale;      // softmax scale
   int32_t kv_len[kMaxBatchPerLaunch];
+  int64_t bstart[kMaxBatchPerLaunch + 1];  // first flat block of each sequence; bstart[B] = total_blocks
   uint8_t n_nodes[kMaxBatchPerLaunch];
 };
 
@@ -65,42 +67,48 @@ __device__ __forceinline__ float wave_xor_sum_16_32(float v) {
   return v;
 }
 
-// One streamed block of 32 keys in registers.
-template <int D>
-struct KvBlock {
-  static constexpr int KS = D / 32;
-  static constexpr int VW = D / 32;  // 32-bit words of one lane's slice of a V row (D/16 bf16)
-  bf16x8 k[2][KS];                   // A operands: key tile kt (16 keys), k-step ks (32 dims)
-  unsigned v[8][VW];                 // 8 key rows, D/16 consecutive dims each
-};
-
 // Which key a lane's j-th V row / P element refers to inside a 32-key block:
 // the accumulator layout of two 16-key S^T tiles puts keys 4*g4+i (tile 0) and
 // 16+4*g4+i (tile 1) in lane group g4.
 __device__ __forceinline__ int key_of(int g4, int j) { return (j < 4) ? 4 * g4 + j : 16 + 4 * g4 + (j - 4); }
 
+// Where one 32-key block lives and how it is masked.
+struct BlockSrc {
+  const __bf16* k;
+  const __bf16* v;
+  int64_t stride;   // elements between consecutive keys
+  int nvalid;       // keys of the block that exist (1..32)
+  int kind;         // 0 full prefix block, 1 prefix block with a ragged tail, 2 tree block
+  int tree_key0;    // first tree node of a tree block
+};
+
+// K rows in the A-operand layout of the 16x16x32 MFMA: lane (col, g4) holds key 16*kt+col,
+// dims 32*ks + 8*g4 .. +7. Rows past the end of a ragged block are clamped (masked later).
 template <int D>
-__device__ __forceinline__ void load_block(KvBlock<D>& blk, const __bf16* kbase, const __bf16* vbase,
-                                           int64_t stride, int nvalid, int col, int g4) {
-  constexpr int KS = D / 32;
-  constexpr int DT = D / 16;
+__device__ __forceinline__ void load_k(bf16x8 (&k)[2][D / 32], const BlockSrc& src, int col, int g4) {
 #pragma unroll
   for (int kt = 0; kt < 2; ++kt) {
-    const int key = min(16 * kt + col, nvalid - 1);  // clamp: rows past the end are masked later
-    const __bf16* row = kbase + (int64_t)key * stride + 8 * g4;
+    const int key = src.kind == 0 ? 16 * kt + col : min(16 * kt + col, src.nvalid - 1);
+    const __bf16* row = src.k + (int64_t)key * src.stride + 8 * g4;
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) blk.k[kt][ks] = *reinterpret_cast<const bf16x8*>(row + 32 * ks);
+    for (int ks = 0; ks < D / 32; ++ks) k[kt][ks] = *reinterpret_cast<const bf16x8*>(row + 32 * ks);
   }
+}
+
+// V rows: lane (col, g4) holds, for its 8 keys, the D/16 consecutive dims starting at (D/16)*col,
+// i.e. 16 lanes read one whole row contiguously.
+template <int D>
+__device__ __forceinline__ void load_v(unsigned (&v)[8][D / 32], const BlockSrc& src, int col, int g4) {
 #pragma unroll
   for (int j = 0; j < 8; ++j) {
-    const int key = min(key_of(g4, j), nvalid - 1);
-    const __bf16* row = vbase + (int64_t)key * stride + DT * col;
+    const int key = src.kind == 0 ? key_of(g4, j) : min(key_of(g4, j), src.nvalid - 1);
+    const __bf16* row = src.v + (int64_t)key * src.stride + (D / 16) * col;
     if constexpr (D == 128) {
       const u32x4 w = *reinterpret_cast<const u32x4*>(row);
-      blk.v[j][0] = w[0]; blk.v[j][1] = w[1]; blk.v[j][2] = w[2]; blk.v[j][3] = w[3];
+      v[j][0] = w[0]; v[j][1] = w[1]; v[j][2] = w[2]; v[j][3] = w[3];
     } else {
       const u32x2 w = *reinterpret_cast<const u32x2*>(row);
-      blk.v[j][0] = w[0]; blk.v[j][1] = w[1];
+      v[j][0] = w[0]; v[j][1] = w[1];
     }
   }
 }
@@ -109,30 +117,40 @@ template <int QT, int D>
 struct RowState {
   static constexpr int DT = D / 16;
   f32x4 o[QT][DT];   // O^T accumulators: lane (col,g4), reg i <-> row 16t+col, dim DT*(4*g4+i)+e
-  float m[QT];       // running max (log2 units, scaled)
+  float m[QT];       // softmax shift in use (log2 units, scaled): within kLazyLog2 of the running max
   float l[QT];       // running sum, partial per lane until the final cross-lane add
 };
 
-// S^T = K Q^T for one block, mask, online softmax, O^T += V^T P^T.
-// kind: 0 full prefix block, 1 prefix block with a ragged tail, 2 tree block.
+// The shift of a row only moves when a score exceeds it by more than this (log2 units): weights
+// then stay below 2^kLazyLog2, which fp32 sums and bf16 weights hold without loss, and the
+// accumulators are rescaled (and lanes exchanged) almost never after the first blocks.
+constexpr float kLazyLog2 = 8.0f;
+
+// S^T = K Q^T for one block: s[kt][t][i] in lane (col,g4) is key 16*kt+4*g4+i against row 16*t+col.
 template <int QT, int D>
-__device__ __forceinline__ void compute_block(const KvBlock<D>& blk, const bf16x8 (&qf)[QT][D / 32],
-                                              RowState<QT, D>& st, int kind, int nvalid, int tree_key0,
-                                              const uint64_t (&mask_word)[QT], float c, int g4) {
-  constexpr int KS = D / 32;
-  constexpr int DT = D / 16;
-  f32x4 s[2][QT];
+__device__ __forceinline__ void scores(f32x4 (&s)[2][QT], const bf16x8 (&k)[2][D / 32],
+                                       const bf16x8 (&qf)[QT][D / 32]) {
 #pragma unroll
   for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
     for (int t = 0; t < QT; ++t) {
       f32x4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int ks = 0; ks < KS; ++ks)
-        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(blk.k[kt][ks], qf[t][ks], acc, 0, 0, 0);
+      for (int ks = 0; ks < D / 32; ++ks)
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k[kt][ks], qf[t][ks], acc, 0, 0, 0);
       s[kt][t] = acc;
     }
-  if (kind != 0) {
+}
+
+// Mask, online softmax: updates the row state and returns the bf16 weights as B operands.
+template <int QT, int D, typename MaskFn>
+__device__ __forceinline__ void softmax_block(f32x4 (&s)[2][QT], bf16x8 (&pf)[QT], RowState<QT, D>& st,
+                                              const BlockSrc& src, MaskFn&& mask_of_tile, float c, int g4) {
+  constexpr int DT = D / 16;
+  if (src.kind != 0) {
+    uint64_t mask_word[QT];  // fetched only here: tree blocks are a handful per call
+#pragma unroll
+    for (int t = 0; t < QT; ++t) mask_word[t] = src.kind == 2 ? mask_of_tile(t) : 0ull;
 #pragma unroll
     for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
@@ -140,55 +158,57 @@ __device__ __forceinline__ void compute_block(const KvBlock<D>& blk, const bf16x
         const int key = 16 * kt + 4 * g4 + i;
 #pragma unroll
         for (int t = 0; t < QT; ++t) {
-          bool visible = key < nvalid;
-          if (kind == 2) visible = visible && ((mask_word[t] >> (tree_key0 + key)) & 1ull);
+          bool visible = key < src.nvalid;
+          if (src.kind == 2) visible = visible && ((mask_word[t] >> (src.tree_key0 + key)) & 1ull);
           if (!visible) s[kt][t][i] = -INFINITY;
         }
       }
   }
-  // online softmax, one query row per (tile, lane column)
-  float mnew[QT];
+  float mx[QT];
   bool grow = false;
 #pragma unroll
   for (int t = 0; t < QT; ++t) {
-    float mx = fmaxf(fmaxf(fmaxf(s[0][t][0], s[0][t][1]), fmaxf(s[0][t][2], s[0][t][3])),
-                     fmaxf(fmaxf(s[1][t][0], s[1][t][1]), fmaxf(s[1][t][2], s[1][t][3])));
-    mx = wave_xor_max_16_32(mx);
-    mnew[t] = fmaxf(st.m[t], mx * c);
-    grow = grow || (mnew[t] > st.m[t]);
+    mx[t] = fmaxf(fmaxf(fmaxf(s[0][t][0], s[0][t][1]), fmaxf(s[0][t][2], s[0][t][3])),
+                  fmaxf(fmaxf(s[1][t][0], s[1][t][1]), fmaxf(s[1][t][2], s[1][t][3])));
+    grow = grow || (mx[t] * c > st.m[t] + kLazyLog2);
   }
-  if (__any(grow)) {  // wavefront-uniform: after the first blocks the maxima rarely move
+  if (__any(grow)) {  // wavefront-uniform and rare: move every row's shift to its running max
 #pragma unroll
     for (int t = 0; t < QT; ++t) {
-      const float alpha = __builtin_amdgcn_exp2f(st.m[t] - mnew[t]);
-      st.m[t] = mnew[t];
+      const float mnew = fmaxf(st.m[t], wave_xor_max_16_32(mx[t]) * c);
+      const float alpha = __builtin_amdgcn_exp2f(st.m[t] - mnew);
+      st.m[t] = mnew;
       st.l[t] *= alpha;
 #pragma unroll
       for (int e = 0; e < DT; ++e) st.o[t][e] *= alpha;
     }
   }
-  bf16x8 pf[QT];
 #pragma unroll
   for (int t = 0; t < QT; ++t) {
     float p[8];
-    float sum = 0.f;
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      p[j] = __builtin_amdgcn_exp2f(fmaf(s[j >> 2][t][j & 3], c, -st.m[t]));
-      sum += p[j];
-    }
-    st.l[t] += sum;
+    for (int j = 0; j < 8; ++j) p[j] = __builtin_amdgcn_exp2f(fmaf(s[j >> 2][t][j & 3], c, -st.m[t]));
 #pragma unroll
     for (int j = 0; j < 8; ++j) pf[t][j] = (__bf16)p[j];
-  }
-  // O^T += V^T P^T; the 8x(D/16) V slice of a lane is transposed with byte permutes
+    // the sum runs over the weights as the matrix cores see them (rounded to bf16), so that
+    // numerator and denominator carry the same weights and a dominant key is reproduced exactly
+    float sum = 0.f;
 #pragma unroll
-  for (int e = 0; e < DT; ++e) {
+    for (int j = 0; j < 8; ++j) sum += (float)pf[t][j];
+    st.l[t] += sum;
+  }
+}
+
+// O^T += V^T P^T; the 8 x (D/16) V slice of a lane is transposed with byte permutes.
+template <int QT, int D>
+__device__ __forceinline__ void weighted_values(RowState<QT, D>& st, const unsigned (&v)[8][D / 32],
+                                                const bf16x8 (&pf)[QT]) {
+#pragma unroll
+  for (int e = 0; e < D / 16; ++e) {
     const unsigned sel = (e & 1) ? 0x07060302u : 0x05040100u;
     u32x4 w;
 #pragma unroll
-    for (int m2 = 0; m2 < 4; ++m2)
-      w[m2] = __builtin_amdgcn_perm(blk.v[2 * m2 + 1][e >> 1], blk.v[2 * m2][e >> 1], sel);
+    for (int m2 = 0; m2 < 4; ++m2) w[m2] = __builtin_amdgcn_perm(v[2 * m2 + 1][e >> 1], v[2 * m2][e >> 1], sel);
     const bf16x8 va = __builtin_bit_cast(bf16x8, w);
 #pragma unroll
     for (int t = 0; t < QT; ++t)
@@ -196,8 +216,14 @@ __device__ __forceinline__ void compute_block(const KvBlock<D>& blk, const bf16x
   }
 }
 
+// The (sequence, kv head, slab group) units and their 32-key blocks form one flat list of
+// blocks; workgroup w owns the contiguous range [w*T/W, (w+1)*T/W) of it, so every workgroup
+// streams the same number of bytes whatever the head count. A workgroup therefore works on one
+// or a few *segments* (a run of blocks of one unit). A segment that is a whole unit is written
+// to `out` directly; otherwise its un-normalised (O, max, sum) goes to partial slot unit+w and the
+// merge kernel finishes the unit.
 template <int QT, int D>
-__global__ __launch_bounds__(256) void tree_attn_bf16_kernel(const AttnParams p) {
+__global__ __launch_bounds__(256, (QT <= 2 ? 2 : 1)) void tree_attn_bf16_kernel(const AttnParams p) {
   constexpr int KS = D / 32;
   constexpr int DT = D / 16;
   constexpr int ROWS = 16 * QT;
@@ -207,195 +233,252 @@ __global__ __launch_bounds__(256) void tree_attn_bf16_kernel(const AttnParams p)
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int col = lane & 15, g4 = lane >> 4;
-  const int b = blockIdx.z / p.Hkv, g = blockIdx.z % p.Hkv;
   const int slab_local = wave & (p.WS - 1);
-  const int slab = blockIdx.y * p.WS + slab_local;
-  const int KW = 4 / p.WS;           // wavefronts that split the keys of one slab
+  const int KW = 4 / p.WS;  // wavefronts that split the keys of one slab
   const int kp = wave / p.WS;
-  const int n = p.n_nodes[b];
-  const int L = p.kv_len[b];
   const float c = p.scale * kLog2e;
-  const bool slab_live = slab < p.NS;
-
-  // rows of this lane: one per tile
-  bool row_exists[QT], row_valid[QT];
-  int row_out[QT];  // index of (b, node, h) in [B*Nmax*Hq)
-  uint64_t mask_word[QT];
-  bf16x8 qf[QT][KS];
-  const uint64_t live_bits = (n >= 64) ? ~0ull : ((1ull << n) - 1ull);
-#pragma unroll
-  for (int t = 0; t < QT; ++t) {
-    const int r = slab * ROWS + 16 * t + col;
-    const int node = r / p.G, hl = r - node * p.G;
-    row_exists[t] = slab_live && r < p.Nmax * p.G;
-    row_valid[t] = row_exists[t] && node < n;
-    row_out[t] = (b * p.Nmax + node) * p.Hq + g * p.G + hl;
-    mask_word[t] = row_valid[t] ? (p.anc_mask[b * p.Nmax + node] & live_bits) : 0ull;
-    const __bf16* qrow = reinterpret_cast<const __bf16*>(p.q) + (int64_t)row_out[t] * D + 8 * g4;
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-      bf16x8 zero;
-#pragma unroll
-      for (int j = 0; j < 8; ++j) zero[j] = (__bf16)0.f;
-      qf[t][ks] = row_valid[t] ? *reinterpret_cast<const bf16x8*>(qrow + 32 * ks) : zero;
-    }
-  }
-
-  RowState<QT, D> st;
-#pragma unroll
-  for (int t = 0; t < QT; ++t) {
-    st.m[t] = kNegBig;
-    st.l[t] = 0.f;
-#pragma unroll
-    for (int e = 0; e < DT; ++e) st.o[t][e] = f32x4{0.f, 0.f, 0.f, 0.f};
-  }
-
-  // blocks of this sequence: prefix blocks first, then the tree blocks
-  const int n_prefix_blocks = (L + kBlockKeys - 1) / kBlockKeys;
-  const int n_blocks = n_prefix_blocks + (n + kBlockKeys - 1) / kBlockKeys;
-  const int key_waves = p.S * KW;
-  const int kw = blockIdx.x * KW + kp;
-  const int blk_begin = (int)(((int64_t)kw * n_blocks) / key_waves);
-  const int blk_end = (int)(((int64_t)(kw + 1) * n_blocks) / key_waves);
-
-  const __bf16* kc = reinterpret_cast<const __bf16*>(p.k_cache) + b * p.stride_batch + g * p.stride_head;
-  const __bf16* vc = reinterpret_cast<const __bf16*>(p.v_cache) + b * p.stride_batch + g * p.stride_head;
   const int64_t tree_stride = (int64_t)p.Hkv * D;
-  const __bf16* ktr = reinterpret_cast<const __bf16*>(p.k_tree) + ((int64_t)b * p.Nmax * p.Hkv + g) * D;
-  const __bf16* vtr = reinterpret_cast<const __bf16*>(p.v_tree) + ((int64_t)b * p.Nmax * p.Hkv + g) * D;
+  const int rows_per_unit = p.WS * ROWS;
 
-  auto issue = [&](KvBlock<D>& dst, int blk) {
-    if (blk < n_prefix_blocks) {
-      const int key0 = blk * kBlockKeys;
-      load_block<D>(dst, kc + (int64_t)key0 * p.stride_token, vc + (int64_t)key0 * p.stride_token,
-                    p.stride_token, min(kBlockKeys, L - key0), col, g4);
-    } else {
-      const int t0 = (blk - n_prefix_blocks) * kBlockKeys;
-      load_block<D>(dst, ktr + (int64_t)t0 * tree_stride, vtr + (int64_t)t0 * tree_stride, tree_stride,
-                    min(kBlockKeys, n - t0), col, g4);
-    }
-  };
-  auto consume = [&](const KvBlock<D>& src, int blk) {
-    if (blk < n_prefix_blocks) {
-      const int nvalid = min(kBlockKeys, L - blk * kBlockKeys);
-      compute_block<QT, D>(src, qf, st, nvalid == kBlockKeys ? 0 : 1, nvalid, 0, mask_word, c, g4);
-    } else {
-      const int t0 = (blk - n_prefix_blocks) * kBlockKeys;
-      compute_block<QT, D>(src, qf, st, 2, min(kBlockKeys, n - t0), t0, mask_word, c, g4);
-    }
-  };
+  const int w = blockIdx.x;
+  const int64_t r0 = ((int64_t)w * p.total_blocks) / p.n_wgs, r1 = ((int64_t)(w + 1) * p.total_blocks) / p.n_wgs;
+  int b = 0;
+  while (b + 1 < p.B && r0 >= p.bstart[b + 1]) ++b;
 
-  if (slab_live && blk_begin < blk_end) {
-    KvBlock<D> bufa, bufb;
-    issue(bufa, blk_begin);
-    for (int blk = blk_begin; blk < blk_end; blk += 2) {
-      const bool has_b = blk + 1 < blk_end;
-      if (has_b) issue(bufb, blk + 1);
-      consume(bufa, blk);
-      if (has_b) {
-        if (blk + 2 < blk_end) issue(bufa, blk + 2);
-        consume(bufb, blk + 1);
+  for (int64_t r = r0; r < r1;) {
+    const int n = p.n_nodes[b];
+    const int L = p.kv_len[b];
+    const int n_prefix_blocks = (L + kBlockKeys - 1) / kBlockKeys;
+    const int n_blocks = n_prefix_blocks + (n + kBlockKeys - 1) / kBlockKeys;
+    const int ub = (int)((r - p.bstart[b]) / n_blocks);          // unit within the sequence: (g, y)
+    const int seg_begin = (int)((r - p.bstart[b]) - (int64_t)ub * n_blocks);
+    const int seg_count = (int)min((int64_t)(n_blocks - seg_begin), r1 - r);
+    const int g = ub / p.GY, y = ub - g * p.GY;
+    const int unit = b * p.Hkv * p.GY + ub;
+    const bool whole_unit = seg_count == n_blocks;
+    const int slab = y * p.WS + slab_local;
+    const bool slab_live = slab < p.NS;
+
+    // row of this lane in tile t: query row rr of the kv head's N*G rows = (node, head within group)
+    struct RowInfo { bool exists, valid; int node; int64_t out; };
+    auto row_info = [&](int t) {
+      RowInfo ri;
+      const int rr = slab * ROWS + 16 * t + col;
+      ri.node = rr / p.G;
+      const int hl = rr - ri.node * p.G;
+      ri.exists = slab_live && rr < p.Nmax * p.G;
+      ri.valid = ri.exists && ri.node < n;
+      ri.out = ((int64_t)b * p.Nmax + ri.node) * p.Hq + g * p.G + hl;  // index of (b, node, h)
+      return ri;
+    };
+    auto mask_of_tile = [&](int t) -> uint64_t {
+      const RowInfo ri = row_info(t);
+      const uint64_t live_bits = (n >= 64) ? ~0ull : ((1ull << n) - 1ull);
+      return ri.valid ? (p.anc_mask[b * p.Nmax + ri.node] & live_bits) : 0ull;
+    };
+    bf16x8 qf[QT][KS];
+#pragma unroll
+    for (int t = 0; t < QT; ++t) {
+      const RowInfo ri = row_info(t);
+      const __bf16* qrow = reinterpret_cast<const __bf16*>(p.q) + ri.out * D + 8 * g4;
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        bf16x8 zero;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) zero[j] = (__bf16)0.f;
+        qf[t][ks] = ri.valid ? *reinterpret_cast<const bf16x8*>(qrow + 32 * ks) : zero;
       }
     }
-  }
-#pragma unroll
-  for (int t = 0; t < QT; ++t) st.l[t] = wave_xor_sum_16_32(st.l[t]);
 
-  // merge the key-splitting wavefronts of a slab through LDS (lane-private slots)
-  if (KW > 1) {
-    if (kp > 0) {
-      const int slot = (kp - 1) * p.WS + slab_local;
+    RowState<QT, D> st;
 #pragma unroll
-      for (int t = 0; t < QT; ++t) {
-        merge_ml[slot][t][lane] = make_float2(st.m[t], st.l[t]);
+    for (int t = 0; t < QT; ++t) {
+      st.m[t] = kNegBig;
+      st.l[t] = 0.f;
 #pragma unroll
-        for (int e = 0; e < DT; ++e) merge_o[slot][t * DT + e][lane] = st.o[t][e];
+      for (int e = 0; e < DT; ++e) st.o[t][e] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+
+    // the key-splitting wavefronts of a slab share the segment's blocks evenly
+    const int blk_begin = seg_begin + (int)(((int64_t)kp * seg_count) / KW);
+    const int blk_end = seg_begin + (int)(((int64_t)(kp + 1) * seg_count) / KW);
+
+    const __bf16* kc = reinterpret_cast<const __bf16*>(p.k_cache) + b * p.stride_batch + g * p.stride_head;
+    const __bf16* vc = reinterpret_cast<const __bf16*>(p.v_cache) + b * p.stride_batch + g * p.stride_head;
+    const __bf16* ktr = reinterpret_cast<const __bf16*>(p.k_tree) + ((int64_t)b * p.Nmax * p.Hkv + g) * D;
+    const __bf16* vtr = reinterpret_cast<const __bf16*>(p.v_tree) + ((int64_t)b * p.Nmax * p.Hkv + g) * D;
+
+    auto locate = [&](int blk) {
+      BlockSrc src;
+      if (blk < n_prefix_blocks) {
+        const int key0 = blk * kBlockKeys;
+        src.k = kc + (int64_t)key0 * p.stride_token;
+        src.v = vc + (int64_t)key0 * p.stride_token;
+        src.stride = p.stride_token;
+        src.nvalid = min(kBlockKeys, L - key0);
+        src.kind = src.nvalid == kBlockKeys ? 0 : 1;
+        src.tree_key0 = 0;
+      } else {
+        const int t0 = (blk - n_prefix_blocks) * kBlockKeys;
+        src.k = ktr + (int64_t)t0 * tree_stride;
+        src.v = vtr + (int64_t)t0 * tree_stride;
+        src.stride = tree_stride;
+        src.nvalid = min(kBlockKeys, n - t0);
+        src.kind = 2;
+        src.tree_key0 = t0;
+      }
+      return src;
+    };
+
+    // Staggered stream: V of the current block is requested before its scores are formed, K of the
+    // next block right after them, so both loads fly under the softmax / matrix work of this block
+    // while only one K and one V block are held in registers.
+    if (slab_live && blk_begin < blk_end) {
+      bf16x8 kf[2][KS];
+      unsigned vr[8][D / 32];
+      BlockSrc cur = locate(blk_begin);
+      load_k<D>(kf, cur, col, g4);
+      for (int blk = blk_begin; blk < blk_end; ++blk) {
+        load_v<D>(vr, cur, col, g4);
+        f32x4 s[2][QT];
+        scores<QT, D>(s, kf, qf);
+        BlockSrc nxt = cur;
+        if (blk + 1 < blk_end) {
+          nxt = locate(blk + 1);
+          load_k<D>(kf, nxt, col, g4);
+        }
+        bf16x8 pf[QT];
+        softmax_block<QT, D>(s, pf, st, cur, mask_of_tile, c, g4);
+        weighted_values<QT, D>(st, vr, pf);
+        cur = nxt;
       }
     }
-    __syncthreads();
-    if (kp == 0) {
-      for (int other = 1; other < KW; ++other) {
-        const int slot = (other - 1) * p.WS + slab_local;
+#pragma unroll
+    for (int t = 0; t < QT; ++t) st.l[t] = wave_xor_sum_16_32(st.l[t]);
+
+    // merge the key-splitting wavefronts of a slab through LDS (lane-private slots)
+    if (KW > 1) {
+      if (kp > 0) {
+        const int slot = (kp - 1) * p.WS + slab_local;
 #pragma unroll
         for (int t = 0; t < QT; ++t) {
-          const float2 ml = merge_ml[slot][t][lane];
-          const float mm = fmaxf(st.m[t], ml.x);
-          const float a0 = __builtin_amdgcn_exp2f(st.m[t] - mm), a1 = __builtin_amdgcn_exp2f(ml.x - mm);
-          st.m[t] = mm;
-          st.l[t] = st.l[t] * a0 + ml.y * a1;
+          merge_ml[slot][t][lane] = make_float2(st.m[t], st.l[t]);
 #pragma unroll
-          for (int e = 0; e < DT; ++e) st.o[t][e] = st.o[t][e] * a0 + merge_o[slot][t * DT + e][lane] * a1;
+          for (int e = 0; e < DT; ++e) merge_o[slot][t * DT + e][lane] = st.o[t][e];
         }
       }
-    }
-  }
-  if (kp != 0) return;
-
-  // write: final rows when there is a single split, partials otherwise
+      __syncthreads();
+      if (kp == 0) {
+        for (int other = 1; other < KW; ++other) {
+          const int slot = (other - 1) * p.WS + slab_local;
 #pragma unroll
-  for (int t = 0; t < QT; ++t) {
-    if (!row_exists[t]) continue;
-    if (p.S == 1) {
-      const float inv = row_valid[t] ? 1.0f / st.l[t] : 0.f;
+          for (int t = 0; t < QT; ++t) {
+            const float2 ml = merge_ml[slot][t][lane];
+            const float mm = fmaxf(st.m[t], ml.x);
+            const float a0 = __builtin_amdgcn_exp2f(st.m[t] - mm), a1 = __builtin_amdgcn_exp2f(ml.x - mm);
+            st.m[t] = mm;
+            st.l[t] = st.l[t] * a0 + ml.y * a1;
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int d0 = DT * (4 * g4 + i);
-        float vals[DT];
-#pragma unroll
-        for (int e = 0; e < DT; ++e) vals[e] = row_valid[t] ? st.o[t][e][i] * inv : 0.f;
-        if (p.out_bf16) {
-          __bf16* dst = reinterpret_cast<__bf16*>(p.out) + (int64_t)row_out[t] * D + d0;
-          if constexpr (DT == 8) {
-            bf16x8 pk;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) pk[e] = (__bf16)vals[e];
-            *reinterpret_cast<bf16x8*>(dst) = pk;
-          } else {
-#pragma unroll
-            for (int e = 0; e < DT; ++e) dst[e] = (__bf16)vals[e];
+            for (int e = 0; e < DT; ++e) st.o[t][e] = st.o[t][e] * a0 + merge_o[slot][t * DT + e][lane] * a1;
           }
-        } else {
-          float* dst = reinterpret_cast<float*>(p.out) + (int64_t)row_out[t] * D + d0;
-#pragma unroll
-          for (int e = 0; e < DT; e += 4) *reinterpret_cast<f32x4*>(dst + e) = f32x4{vals[e], vals[e + 1], vals[e + 2], vals[e + 3]};
         }
       }
-    } else if (row_valid[t]) {
-      const int64_t rows_total = (int64_t)p.B * p.Nmax * p.Hq;
-      const int64_t prow = (int64_t)blockIdx.x * rows_total + row_out[t];
-      if (g4 == 0) *reinterpret_cast<float2*>(p.part_ml + prow * 2) = make_float2(st.m[t], st.l[t]);
+    }
+
+    // write: final rows when the segment is the whole unit, a partial slot otherwise
+    if (kp == 0) {
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        float* dst = p.part_o + prow * D + DT * (4 * g4 + i);
+      for (int t = 0; t < QT; ++t) {
+        const RowInfo ri = row_info(t);
+        if (!ri.exists) continue;
+        if (whole_unit) {
+          const float inv = ri.valid ? 1.0f / st.l[t] : 0.f;
 #pragma unroll
-        for (int e = 0; e < DT; e += 4)
-          *reinterpret_cast<f32x4*>(dst + e) = f32x4{st.o[t][e][i], st.o[t][e + 1][i], st.o[t][e + 2][i], st.o[t][e + 3][i]};
+          for (int i = 0; i < 4; ++i) {
+            const int d0 = DT * (4 * g4 + i);
+            float vals[DT];
+#pragma unroll
+            for (int e = 0; e < DT; ++e) vals[e] = ri.valid ? st.o[t][e][i] * inv : 0.f;
+            if (p.out_bf16) {
+              __bf16* dst = reinterpret_cast<__bf16*>(p.out) + ri.out * D + d0;
+              if constexpr (DT == 8) {
+                bf16x8 pk;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) pk[e] = (__bf16)vals[e];
+                *reinterpret_cast<bf16x8*>(dst) = pk;
+              } else {
+#pragma unroll
+                for (int e = 0; e < DT; ++e) dst[e] = (__bf16)vals[e];
+              }
+            } else {
+              float* dst = reinterpret_cast<float*>(p.out) + ri.out * D + d0;
+#pragma unroll
+              for (int e = 0; e < DT; e += 4)
+                *reinterpret_cast<f32x4*>(dst + e) = f32x4{vals[e], vals[e + 1], vals[e + 2], vals[e + 3]};
+            }
+          }
+        } else if (ri.valid) {
+          float* slot = p.part + (int64_t)(unit + w) * rows_per_unit * (D + 2);
+          const int lr = slab_local * ROWS + 16 * t + col;
+          if (g4 == 0) *reinterpret_cast<float2*>(slot + (int64_t)rows_per_unit * D + 2 * lr) = make_float2(st.m[t], st.l[t]);
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            float* dst = slot + (int64_t)lr * D + DT * (4 * g4 + i);
+#pragma unroll
+            for (int e = 0; e < DT; e += 4)
+              *reinterpret_cast<f32x4*>(dst + e) = f32x4{st.o[t][e][i], st.o[t][e + 1][i], st.o[t][e + 2][i], st.o[t][e + 3][i]};
+          }
+        }
       }
     }
+    r += seg_count;
+    if (b + 1 < p.B && r >= p.bstart[b + 1]) ++b;
+    if (KW > 1 && r < r1) __syncthreads();  // the merge buffers are reused by the next segment
   }
 }
 
-// Merge of the split-KV partials: out = sum_s 2^(m_s - M) O_s / sum_s 2^(m_s - M) l_s.
+// Workgroup that owns flat block x under the even split of T blocks over W workgroups.
+__device__ __forceinline__ int owner_of(int64_t x, int64_t T, int W) {
+  int w = (int)((x * W) / T);
+  if (((int64_t)(w + 1) * T) / W <= x) ++w;
+  return w;
+}
+
+// Finishes every unit that was cut into several segments:
+// out = sum_s 2^(m_s - M) O_s / sum_s 2^(m_s - M) l_s over the unit's partial slots.
 // One thread per 4 output dims; rows of nodes past n_nodes are written as zeros.
 template <int D>
-__global__ __launch_bounds__(256) void tree_attn_combine_kernel(const AttnParams p) {
+__global__ __launch_bounds__(256) void tree_attn_combine_kernel(const AttnParams p, int rows_per_slab) {
   constexpr int TPR = D / 4;  // threads per row
-  const int64_t rows_total = (int64_t)p.B * p.Nmax * p.Hq;
-  const int64_t row = (int64_t)blockIdx.x * (256 / TPR) + threadIdx.x / TPR;
-  if (row >= rows_total) return;
+  const int unit = blockIdx.y;
+  const int units_per_seq = p.Hkv * p.GY;
+  const int b = unit / units_per_seq, ub = unit - b * units_per_seq;
+  const int g = ub / p.GY, y = ub - g * p.GY;
+  const int n_blocks = (int)((p.bstart[b + 1] - p.bstart[b]) / units_per_seq);
+  const int64_t fs = p.bstart[b] + (int64_t)ub * n_blocks;
+  const int w0 = owner_of(fs, p.total_blocks, p.n_wgs), w1 = owner_of(fs + n_blocks - 1, p.total_blocks, p.n_wgs);
+  if (w0 == w1) return;  // written directly by the one workgroup that held the whole unit
+  const int rows_per_unit = p.WS * rows_per_slab;
+  const int lr = blockIdx.x * (256 / TPR) + threadIdx.x / TPR;
+  if (lr >= rows_per_unit) return;
   const int d0 = (threadIdx.x % TPR) * 4;
-  const int b = (int)(row / ((int64_t)p.Nmax * p.Hq));
-  const int node = (int)((row / p.Hq) % p.Nmax);
+  const int slab_local = lr / rows_per_slab;
+  const int rr = (y * p.WS + slab_local) * rows_per_slab + (lr - slab_local * rows_per_slab);
+  if (rr >= p.Nmax * p.G) return;
+  const int node = rr / p.G, hl = rr - node * p.G;
+  const int64_t row = ((int64_t)b * p.Nmax + node) * p.Hq + g * p.G + hl;
   f32x4 acc = {0.f, 0.f, 0.f, 0.f};
   if (node < p.n_nodes[b]) {
+    const int64_t slot_floats = (int64_t)rows_per_unit * (D + 2);
+    const float* base = p.part + (int64_t)(unit + w0) * slot_floats;
     float M = kNegBig;
-    for (int s = 0; s < p.S; ++s) M = fmaxf(M, p.part_ml[(s * rows_total + row) * 2]);
+    for (int s = 0; s <= w1 - w0; ++s) M = fmaxf(M, base[s * slot_floats + (int64_t)rows_per_unit * D + 2 * lr]);
     float denom = 0.f;
-    for (int s = 0; s < p.S; ++s) {
-      const float2 ml = *reinterpret_cast<const float2*>(p.part_ml + (s * rows_total + row) * 2);
-      const float w = __builtin_amdgcn_exp2f(ml.x - M);
-      denom += w * ml.y;
-      acc += w * *reinterpret_cast<const f32x4*>(p.part_o + (s * rows_total + row) * D + d0);
+    for (int s = 0; s <= w1 - w0; ++s) {
+      const float2 ml = *reinterpret_cast<const float2*>(base + s * slot_floats + (int64_t)rows_per_unit * D + 2 * lr);
+      const float wgt = __builtin_amdgcn_exp2f(ml.x - M);
+      denom += wgt * ml.y;
+      acc += wgt * *reinterpret_cast<const f32x4*>(base + s * slot_floats + (int64_t)lr * D + d0);
     }
     acc *= 1.0f / denom;
   }
@@ -491,41 +574,49 @@ __global__ __launch_bounds__(256) void tree_attn_f32_kernel(const AttnParams p) 
 
 // ---------------------------------------------------------------------------------------------
 struct Plan {
-  int QT, NS, WS, grid_y, S;
+  int QT, NS, WS, GY;
+  int rows_per_unit;
+  int n_wgs;           // workgroups for the largest slice of sequences
+  int64_t total_blocks;
 };
 
-int g_forced_splits = 0;
+int g_forced_wgs = 0;
+int g_max_qt = 2;
 
-Plan make_plan(const fspad_attn_desc& d, int max_kv_len) {
-  Plan pl{};
+// Row tiling of one kv head's N*G query rows: slabs of 16*QT rows, WS slabs per workgroup.
+void plan_rows(const fspad_attn_desc& d, Plan& pl) {
   const int G = d.n_q_heads / d.n_kv_heads;
   const int rows = d.n_nodes_max * G;
   int best_cost = 1 << 30;
-  for (int qt = 4; qt >= 1; --qt) {  // ties go to the larger tile: fewer re-reads of K/V
+  for (int qt = g_max_qt; qt >= 1; --qt) {  // ties go to the larger tile: fewer re-reads of K/V
     const int ns = (rows + 16 * qt - 1) / (16 * qt);
     const int ws = ns == 1 ? 1 : (ns == 2 ? 2 : 4);
     const int gy = (ns + ws - 1) / ws;
     const int cost = gy * ws * qt;
-    if (cost < best_cost) { best_cost = cost; pl.QT = qt; pl.NS = ns; pl.WS = ws; pl.grid_y = gy; }
+    if (cost < best_cost) { best_cost = cost; pl.QT = qt; pl.NS = ns; pl.WS = ws; pl.GY = gy; }
   }
-  const int KW = 4 / pl.WS;
-  const int n_blocks = (max_kv_len + kBlockKeys - 1) / kBlockKeys + (d.n_nodes_max + kBlockKeys - 1) / kBlockKeys;
-  const int64_t wgs_per_split = (int64_t)d.batch * d.n_kv_heads * pl.grid_y;
-  // aim at two workgroups per compute unit, but leave every key-splitting wavefront >= 2 blocks
-  int64_t s = (512 + wgs_per_split - 1) / wgs_per_split;
-  const int64_t s_cap = n_blocks / (2 * KW);
-  if (s > s_cap) s = s_cap;
-  if (s < 1) s = 1;
-  if (s > 64) s = 64;
-  if (g_forced_splits > 0) s = g_forced_splits;
-  pl.S = (int)s;
-  return pl;
+  pl.rows_per_unit = pl.WS * 16 * pl.QT;
 }
 
-size_t partial_bytes(const fspad_attn_desc& d, int S) {
-  if (S <= 1) return 0;
-  const size_t rows = (size_t)d.batch * d.n_nodes_max * d.n_q_heads;
-  return (size_t)S * rows * (d.head_dim + 2) * sizeof(float);
+int blocks_of(int kv_len, int n_nodes) {
+  return (kv_len + kBlockKeys - 1) / kBlockKeys + (n_nodes + kBlockKeys - 1) / kBlockKeys;
+}
+
+// Workgroup count for `total_blocks` flat blocks: two resident workgroups per compute unit when
+// the register budget allows it, but no workgroup with fewer than 2 blocks per key-splitting wave.
+int plan_wgs(const Plan& pl, int64_t total_blocks) {
+  const int KW = 4 / pl.WS;
+  int64_t wgs = pl.QT <= 2 ? 512 : 256;
+  const int64_t cap = total_blocks / (2 * KW);
+  if (wgs > cap) wgs = cap;
+  if (g_forced_wgs > 0) wgs = g_forced_wgs;
+  if (wgs > total_blocks) wgs = total_blocks;
+  if (wgs < 1) wgs = 1;
+  return (int)wgs;
+}
+
+size_t slot_bytes(const fspad_attn_desc& d, const Plan& pl) {
+  return (size_t)pl.rows_per_unit * (d.head_dim + 2) * sizeof(float);
 }
 
 fspad_status check_desc(const fspad_attn_desc* d) {
@@ -540,7 +631,8 @@ fspad_status check_desc(const fspad_attn_desc* d) {
 }
 
 template <int D>
-void launch_bf16(const Plan& pl, const AttnParams& prm, dim3 grid, hipStream_t stream) {
+void launch_bf16(const Plan& pl, const AttnParams& prm, hipStream_t stream) {
+  const dim3 grid((unsigned)prm.n_wgs);
   switch (pl.QT) {
     case 1: hipLaunchKernelGGL((tree_attn_bf16_kernel<1, D>), grid, dim3(256), 0, stream, prm); break;
     case 2: hipLaunchKernelGGL((tree_attn_bf16_kernel<2, D>), grid, dim3(256), 0, stream, prm); break;
@@ -551,14 +643,23 @@ void launch_bf16(const Plan& pl, const AttnParams& prm, dim3 grid, hipStream_t s
 
 }  // namespace
 
-extern "C" void fspad_tree_attn_set_splits(int32_t splits) { g_forced_splits = splits > 0 ? (splits > 64 ? 64 : splits) : 0; }
+extern "C" void fspad_debug_set_max_qt(int32_t qt) { g_max_qt = qt < 1 ? 1 : (qt > 4 ? 4 : qt); }
+
+extern "C" void fspad_tree_attn_set_workgroups(int32_t workgroups) {
+  g_forced_wgs = workgroups > 0 ? (workgroups > 4096 ? 4096 : workgroups) : 0;
+}
 
 extern "C" size_t fspad_tree_attn_workspace_bytes(const fspad_attn_desc* desc, int32_t max_kv_len) {
   if (check_desc(desc) != FSPAD_OK || max_kv_len < 0) return 0;
   if (desc->io_dtype == FSPAD_F32) return 16;
-  const Plan pl = make_plan(*desc, max_kv_len);
-  const size_t need = partial_bytes(*desc, pl.S);
-  return need < 16 ? 16 : need;
+  Plan pl{};
+  plan_rows(*desc, pl);
+  // one partial slot per (unit, workgroup) boundary at most: units + workgroups of the largest slice
+  const int nb = desc->batch < kMaxBatchPerLaunch ? desc->batch : kMaxBatchPerLaunch;
+  const int64_t units = (int64_t)nb * desc->n_kv_heads * pl.GY;
+  const int64_t total = units * blocks_of(max_kv_len, desc->n_nodes_max);
+  const int64_t slots = units + plan_wgs(pl, total);
+  return (size_t)slots * slot_bytes(*desc, pl);
 }
 
 extern "C" fspad_status fspad_tree_attn(const fspad_attn_desc* desc, const void* q, const void* k_tree,
@@ -588,23 +689,19 @@ extern "C" fspad_status fspad_tree_attn(const fspad_attn_desc* desc, const void*
   hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
 
   AttnParams prm{};
-  prm.q = q; prm.k_tree = k_tree; prm.v_tree = v_tree; prm.k_cache = k_cache; prm.v_cache = v_cache;
-  prm.anc_mask = anc_mask; prm.out = out;
+  prm.anc_mask = anc_mask;
   prm.stride_batch = d.cache_stride_batch; prm.stride_head = d.cache_stride_head; prm.stride_token = d.cache_stride_token;
-  prm.B = d.batch; prm.Nmax = d.n_nodes_max; prm.Hq = d.n_q_heads; prm.Hkv = d.n_kv_heads;
+  prm.Nmax = d.n_nodes_max; prm.Hq = d.n_q_heads; prm.Hkv = d.n_kv_heads;
   prm.G = d.n_q_heads / d.n_kv_heads;
   prm.out_bf16 = d.out_dtype == FSPAD_BF16;
   prm.scale = d.softmax_scale > 0.f ? d.softmax_scale : 1.0f / sqrtf((float)d.head_dim);
+  prm.WS = 1; prm.NS = 1; prm.GY = 1;
 
   Plan pl{};
   if (d.io_dtype == FSPAD_BF16) {
-    pl = make_plan(d, max_len);
-    const size_t need = partial_bytes(d, pl.S);
-    if (need > 0 && (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 15))) return FSPAD_ERR_WORKSPACE;
-    prm.S = pl.S; prm.WS = pl.WS; prm.NS = pl.NS;
-    prm.part_o = pl.S > 1 ? reinterpret_cast<float*>(workspace) : nullptr;
-  } else {
-    prm.S = 1; prm.WS = 1; prm.NS = 1;
+    plan_rows(d, pl);
+    prm.WS = pl.WS; prm.NS = pl.NS; prm.GY = pl.GY;
+    prm.part = reinterpret_cast<float*>(workspace);
   }
 
   // sequences are independent: slices of at most kMaxBatchPerLaunch sequences per launch (the
@@ -626,18 +723,26 @@ extern "C" fspad_status fspad_tree_attn(const fspad_attn_desc* desc, const void*
     sl.out = static_cast<char*>(out) + q_rows * (d.out_dtype == FSPAD_BF16 ? 2 : 4);
     for (int i = 0; i < nb; ++i) { sl.kv_len[i] = kv_len[b0 + i]; sl.n_nodes[i] = (uint8_t)n_nodes[b0 + i]; }
     if (d.io_dtype == FSPAD_BF16) {
-      const size_t rows = (size_t)nb * d.n_nodes_max * d.n_q_heads;
-      sl.part_ml = sl.part_o ? sl.part_o + (size_t)pl.S * rows * d.head_dim : nullptr;
-      dim3 grid((unsigned)pl.S, (unsigned)pl.grid_y, (unsigned)(nb * d.n_kv_heads));
-      if (d.head_dim == 128) launch_bf16<128>(pl, sl, grid, stream); else launch_bf16<64>(pl, sl, grid, stream);
-      if (hipGetLastError() != hipSuccess) return FSPAD_ERR_HIP;
-      if (pl.S > 1) {
-        const int rpb = 256 / (d.head_dim / 4);
-        dim3 cgrid((unsigned)((rows + rpb - 1) / rpb));
-        if (d.head_dim == 128) hipLaunchKernelGGL(tree_attn_combine_kernel<128>, cgrid, dim3(256), 0, stream, sl);
-        else hipLaunchKernelGGL(tree_attn_combine_kernel<64>, cgrid, dim3(256), 0, stream, sl);
-        if (hipGetLastError() != hipSuccess) return FSPAD_ERR_HIP;
+      const int64_t units_per_seq = (int64_t)d.n_kv_heads * pl.GY;
+      int64_t total = 0;
+      for (int i = 0; i < nb; ++i) {
+        sl.bstart[i] = total;
+        total += units_per_seq * blocks_of(sl.kv_len[i], sl.n_nodes[i]);
       }
+      sl.bstart[nb] = total;
+      sl.total_blocks = total;
+      sl.n_wgs = plan_wgs(pl, total);
+      const int64_t slots = (int64_t)nb * units_per_seq + sl.n_wgs;
+      const size_t need = (size_t)slots * slot_bytes(d, pl);
+      if (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 15)) return FSPAD_ERR_WORKSPACE;
+      if (d.head_dim == 128) launch_bf16<128>(pl, sl, stream); else launch_bf16<64>(pl, sl, stream);
+      if (hipGetLastError() != hipSuccess) return FSPAD_ERR_HIP;
+      const int rows_per_slab = 16 * pl.QT;
+      const int rpb = 256 / (d.head_dim / 4);
+      dim3 cgrid((unsigned)((pl.rows_per_unit + rpb - 1) / rpb), (unsigned)(nb * units_per_seq));
+      if (d.head_dim == 128) hipLaunchKernelGGL(tree_attn_combine_kernel<128>, cgrid, dim3(256), 0, stream, sl, rows_per_slab);
+      else hipLaunchKernelGGL(tree_attn_combine_kernel<64>, cgrid, dim3(256), 0, stream, sl, rows_per_slab);
+      if (hipGetLastError() != hipSuccess) return FSPAD_ERR_HIP;
     } else {
       dim3 grid((unsigned)d.n_q_heads, (unsigned)((d.n_nodes_max + 3) / 4), (unsigned)nb);
       if (d.head_dim == 128) hipLaunchKernelGGL(tree_attn_f32_kernel<128>, grid, dim3(256), 0, stream, sl);

@@ -48,13 +48,13 @@ class AttnCase:
         self.mask_dev = torch.from_numpy(self.mask.view(np.int64)).to(DEV)
 
     def run_gpu(self, out_dtype=torch.float32, scale=0.0, splits=0):
-        fspad.fspad_tree_attn_set_splits(splits)
+        fspad.fspad_tree_attn_set_workgroups(splits)
         try:
             out = fspad.fspad_tree_attn(self.q, self.k_tree, self.v_tree, self.k_cache, self.v_cache, self.kv_len,
                                         self.n_nodes, self.mask_dev, softmax_scale=scale, out_dtype=out_dtype)
             torch.cuda.synchronize()
         finally:
-            fspad.fspad_tree_attn_set_splits(0)
+            fspad.fspad_tree_attn_set_workgroups(0)
         return out
 
     def run_oracle(self, scale=None, heads=None, nthreads=16):
@@ -72,13 +72,17 @@ class AttnCase:
 
 
 def rel_err(gpu: torch.Tensor, ref: np.ndarray) -> float:
-    """max |gpu - ref| / RMS(ref over its non-zero rows)."""
+    """max over sequences of  max |gpu - ref| / RMS(ref over the sequence's live rows)
+    (every sequence of a batch is an attention problem of its own, with its own output scale)."""
     g = gpu.detach().to(torch.float64).cpu().numpy()
     assert g.shape == ref.shape
     assert np.all(np.isfinite(g))
-    live = ref[np.abs(ref).sum(axis=-1) > 0]
-    rms = float(np.sqrt(np.mean(live ** 2))) if live.size else 1.0
-    return float(np.abs(g - ref).max() / rms)
+    worst = 0.0
+    for b in range(ref.shape[0]):
+        live = ref[b][np.abs(ref[b]).sum(axis=-1) > 0]
+        rms = float(np.sqrt(np.mean(live ** 2))) if live.size else 1.0
+        worst = max(worst, float(np.abs(g[b] - ref[b]).max() / rms))
+    return worst
 
 
 class AcceptCase:

@@ -59,8 +59,10 @@ def test_bf16_gqa_and_head_dim(H, Hq, Hkv, D, N):
     _check(H, case, H.TOL["bf16"])
 
 
-@pytest.mark.parametrize("splits", [1, 2, 3, 7, 16])
-def test_bf16_split_kv_factors(H, splits):
+@pytest.mark.parametrize("splits", [1, 2, 3, 7, 16, 50, 333, 4096])
+def test_bf16_workgroup_counts(H, splits):
+    """Any number of workgroups cuts the flat block list differently (whole units, units cut in
+    two or many segments, more workgroups than blocks); the result must not depend on it."""
     case = H.AttnCase(300 + splits, 2, 26, 4, 4, 128, 777, "bf16", kv_len=[777, 40])
     out, ref, _ = _check(H, case, H.TOL["bf16"], splits=splits)
     # run-to-run determinism (no floating-point atomics in the merge)
