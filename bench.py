@@ -36,6 +36,8 @@ def parse_args():
     ap.add_argument("--splits", type=int, default=0, help="force the number of attention workgroups (0 = automatic)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--max-qt", type=int, default=0, help=argparse.SUPPRESS)
+    ap.add_argument("--layers", type=int, default=None, help="profiling only: run fewer layers of a stack (the result line is then not the workload's)")
+    ap.add_argument("--nodes", type=int, default=None, help="experiments only: override the tree size")
     ap.add_argument("--seed", type=int, default=2024)
     return ap.parse_args()
 
@@ -58,6 +60,12 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     cfg = CONFIGS[args.workload]
+    if args.layers is not None:
+        import dataclasses
+        cfg = dataclasses.replace(cfg, layers=args.layers, name=cfg.name + f"-{args.layers}layers")
+    if args.nodes is not None:
+        import dataclasses
+        cfg = dataclasses.replace(cfg, n_nodes=args.nodes, tree_topk=min(cfg.tree_topk, 4), name=cfg.name + f"-{args.nodes}nodes")
     accept = args.accept or cfg.accept
     tdt = torch.float32 if cfg.dtype == "f32" else torch.bfloat16
     B, N, Hq, Hkv, D, L, V = cfg.batch, cfg.n_nodes, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.kv_len, cfg.vocab

@@ -113,6 +113,28 @@ __device__ __forceinline__ void load_v(unsigned (&v)[8][D / 32], const BlockSrc&
   }
 }
 
+// Full prefix blocks: scalar base + fixed per-lane byte offset, no clamping.
+template <int D>
+__device__ __forceinline__ void load_k_full(bf16x8 (&k)[2][D / 32], const char* base, const unsigned (&off)[2]) {
+#pragma unroll
+  for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+    for (int ks = 0; ks < D / 32; ++ks) k[kt][ks] = *reinterpret_cast<const bf16x8*>(base + off[kt] + 64 * ks);
+}
+template <int D>
+__device__ __forceinline__ void load_v_full(unsigned (&v)[8][D / 32], const char* base, const unsigned (&off)[8]) {
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    if constexpr (D == 128) {
+      const u32x4 w = *reinterpret_cast<const u32x4*>(base + off[j]);
+      v[j][0] = w[0]; v[j][1] = w[1]; v[j][2] = w[2]; v[j][3] = w[3];
+    } else {
+      const u32x2 w = *reinterpret_cast<const u32x2*>(base + off[j]);
+      v[j][0] = w[0]; v[j][1] = w[1];
+    }
+  }
+}
+
 template <int QT, int D>
 struct RowState {
   static constexpr int DT = D / 16;
@@ -127,27 +149,29 @@ struct RowState {
 constexpr float kLazyLog2 = 8.0f;
 
 // S^T = K Q^T for one block: s[kt][t][i] in lane (col,g4) is key 16*kt+4*g4+i against row 16*t+col.
-template <int QT, int D>
-__device__ __forceinline__ void scores(f32x4 (&s)[2][QT], const bf16x8 (&k)[2][D / 32],
-                                       const bf16x8 (&qf)[QT][D / 32]) {
+// Q fragments come from registers, or (large row tiles) from lane-private LDS slots.
+template <int QT, int D, typename QFn>
+__device__ __forceinline__ void scores(f32x4 (&s)[2][QT], const bf16x8 (&k)[2][D / 32], QFn&& q_frag) {
 #pragma unroll
-  for (int kt = 0; kt < 2; ++kt)
+  for (int t = 0; t < QT; ++t) {
+    f32x4 acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int t = 0; t < QT; ++t) {
-      f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-      for (int ks = 0; ks < D / 32; ++ks)
-        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k[kt][ks], qf[t][ks], acc, 0, 0, 0);
-      s[kt][t] = acc;
+    for (int ks = 0; ks < D / 32; ++ks) {
+      const bf16x8 q = q_frag(t, ks);
+      acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k[0][ks], q, acc0, 0, 0, 0);
+      acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k[1][ks], q, acc1, 0, 0, 0);
     }
+    s[0][t] = acc0;
+    s[1][t] = acc1;
+  }
 }
 
 // Mask, online softmax: updates the row state and returns the bf16 weights as B operands.
-template <int QT, int D, typename MaskFn>
+template <int QT, int D, bool FULL, typename MaskFn>
 __device__ __forceinline__ void softmax_block(f32x4 (&s)[2][QT], bf16x8 (&pf)[QT], RowState<QT, D>& st,
                                               const BlockSrc& src, MaskFn&& mask_of_tile, float c, int g4) {
   constexpr int DT = D / 16;
-  if (src.kind != 0) {
+  if (!FULL && src.kind != 0) {
     uint64_t mask_word[QT];  // fetched only here: tree blocks are a handful per call
 #pragma unroll
     for (int t = 0; t < QT; ++t) mask_word[t] = src.kind == 2 ? mask_of_tile(t) : 0ull;
@@ -227,12 +251,22 @@ __global__ __launch_bounds__(256, (QT <= 2 ? 2 : 1)) void tree_attn_bf16_kernel(
   constexpr int KS = D / 32;
   constexpr int DT = D / 16;
   constexpr int ROWS = 16 * QT;
-  // merge buffers: 3 wavefronts x (QT*DT accumulators + QT stats) x 64 lanes
-  __shared__ f32x4 merge_o[3][QT * DT][64];
+  // merge buffers: 3 wavefronts x (QT*DT accumulators + QT stats) x 64 lanes. With large row tiles
+  // the Q fragments of the 4 wavefronts live in lane-private LDS slots instead of registers; they are
+  // dead once a segment's stream is done, so they share the space of the merge buffers.
+  constexpr bool kQInLds = QT >= 3;
+  constexpr int kMergeBytes = 3 * QT * DT * 64 * 16;
+  constexpr int kQBytes = kQInLds ? 4 * QT * KS * 64 * 16 : 0;
+  __shared__ __attribute__((aligned(16))) char lds_raw[kMergeBytes > kQBytes ? kMergeBytes : kQBytes];
   __shared__ float2 merge_ml[3][QT][64];
+  typedef f32x4 (*MergeO)[QT * DT][64];
+  MergeO merge_o = reinterpret_cast<MergeO>(lds_raw);
 
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  // the wavefront index is the same in all 64 lanes: telling the compiler keeps everything that
+  // derives from it (key split, block counters, base addresses) in scalar registers
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int col = lane & 15, g4 = lane >> 4;
+  bf16x8* q_lds = reinterpret_cast<bf16x8*>(lds_raw) + wave * (QT * KS * 64) + lane;
   const int slab_local = wave & (p.WS - 1);
   const int KW = 4 / p.WS;  // wavefronts that split the keys of one slab
   const int kp = wave / p.WS;
@@ -276,7 +310,7 @@ __global__ __launch_bounds__(256, (QT <= 2 ? 2 : 1)) void tree_attn_bf16_kernel(
       const uint64_t live_bits = (n >= 64) ? ~0ull : ((1ull << n) - 1ull);
       return ri.valid ? (p.anc_mask[b * p.Nmax + ri.node] & live_bits) : 0ull;
     };
-    bf16x8 qf[QT][KS];
+    bf16x8 qf[kQInLds ? 1 : QT][KS];
 #pragma unroll
     for (int t = 0; t < QT; ++t) {
       const RowInfo ri = row_info(t);
@@ -286,9 +320,13 @@ __global__ __launch_bounds__(256, (QT <= 2 ? 2 : 1)) void tree_attn_bf16_kernel(
         bf16x8 zero;
 #pragma unroll
         for (int j = 0; j < 8; ++j) zero[j] = (__bf16)0.f;
-        qf[t][ks] = ri.valid ? *reinterpret_cast<const bf16x8*>(qrow + 32 * ks) : zero;
+        const bf16x8 frag = ri.valid ? *reinterpret_cast<const bf16x8*>(qrow + 32 * ks) : zero;
+        if constexpr (kQInLds) q_lds[(t * KS + ks) * 64] = frag; else qf[t][ks] = frag;
       }
     }
+    auto q_frag = [&](int t, int ks) -> bf16x8 {
+      if constexpr (kQInLds) return q_lds[(t * KS + ks) * 64]; else return qf[t][ks];
+    };
 
     RowState<QT, D> st;
 #pragma unroll
@@ -332,23 +370,53 @@ __global__ __launch_bounds__(256, (QT <= 2 ? 2 : 1)) void tree_attn_bf16_kernel(
 
     // Staggered stream: V of the current block is requested before its scores are formed, K of the
     // next block right after them, so both loads fly under the softmax / matrix work of this block
-    // while only one K and one V block are held in registers.
+    // while only one K and one V block are held in registers. Full prefix blocks (all but the last
+    // three of a sequence) take a branch-free path with scalar bases; the ragged tail and the tree
+    // blocks take the general one.
     if (slab_live && blk_begin < blk_end) {
       bf16x8 kf[2][KS];
       unsigned vr[8][D / 32];
       BlockSrc cur = locate(blk_begin);
       load_k<D>(kf, cur, col, g4);
-      for (int blk = blk_begin; blk < blk_end; ++blk) {
+      int blk = blk_begin;
+      const int full_end = min(blk_end, L / kBlockKeys);  // blocks below this index are full prefix blocks
+      if (blk + 1 < full_end) {
+        unsigned koff[2], voff[8];
+        const unsigned row_bytes = (unsigned)p.stride_token * 2u;
+#pragma unroll
+        for (int kt = 0; kt < 2; ++kt) koff[kt] = (unsigned)(16 * kt + col) * row_bytes + 16u * g4;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) voff[j] = (unsigned)key_of(g4, j) * row_bytes + (unsigned)(D / 8) * col;
+        const int64_t block_bytes = (int64_t)kBlockKeys * p.stride_token * 2;
+        const char* kb = reinterpret_cast<const char*>(kc) + (int64_t)blk * block_bytes;
+        const char* vb = reinterpret_cast<const char*>(vc) + (int64_t)blk * block_bytes;
+        BlockSrc full{};  // kind 0
+        for (; blk + 1 < full_end; ++blk) {
+          if constexpr (kQInLds) asm volatile("" ::: "memory");  // keep the Q reads inside the loop (they are the point)
+          load_v_full<D>(vr, vb, voff);
+          f32x4 s[2][QT];
+          scores<QT, D>(s, kf, q_frag);
+          kb += block_bytes;
+          vb += block_bytes;
+          load_k_full<D>(kf, kb, koff);
+          bf16x8 pf[QT];
+          softmax_block<QT, D, true>(s, pf, st, full, mask_of_tile, c, g4);
+          weighted_values<QT, D>(st, vr, pf);
+        }
+        cur = locate(blk);
+      }
+      for (; blk < blk_end; ++blk) {
+        if constexpr (kQInLds) asm volatile("" ::: "memory");
         load_v<D>(vr, cur, col, g4);
         f32x4 s[2][QT];
-        scores<QT, D>(s, kf, qf);
+        scores<QT, D>(s, kf, q_frag);
         BlockSrc nxt = cur;
         if (blk + 1 < blk_end) {
           nxt = locate(blk + 1);
           load_k<D>(kf, nxt, col, g4);
         }
         bf16x8 pf[QT];
-        softmax_block<QT, D>(s, pf, st, cur, mask_of_tile, c, g4);
+        softmax_block<QT, D, false>(s, pf, st, cur, mask_of_tile, c, g4);
         weighted_values<QT, D>(st, vr, pf);
         cur = nxt;
       }
@@ -358,6 +426,7 @@ __global__ __launch_bounds__(256, (QT <= 2 ? 2 : 1)) void tree_attn_bf16_kernel(
 
     // merge the key-splitting wavefronts of a slab through LDS (lane-private slots)
     if (KW > 1) {
+      if (kQInLds) __syncthreads();  // every wavefront is done with its Q slots before they are overwritten
       if (kp > 0) {
         const int slot = (kp - 1) * p.WS + slab_local;
 #pragma unroll
@@ -433,7 +502,7 @@ __global__ __launch_bounds__(256, (QT <= 2 ? 2 : 1)) void tree_attn_bf16_kernel(
     }
     r += seg_count;
     if (b + 1 < p.B && r >= p.bstart[b + 1]) ++b;
-    if (KW > 1 && r < r1) __syncthreads();  // the merge buffers are reused by the next segment
+    if ((KW > 1 || kQInLds) && r < r1) __syncthreads();  // the LDS buffers are reused by the next segment
   }
 }
 
@@ -581,7 +650,7 @@ struct Plan {
 };
 
 int g_forced_wgs = 0;
-int g_max_qt = 2;
+int g_max_qt = 4;
 
 // Row tiling of one kv head's N*G query rows: slabs of 16*QT rows, WS slabs per workgroup.
 void plan_rows(const fspad_attn_desc& d, Plan& pl) {
