@@ -338,8 +338,10 @@ __global__ __launch_bounds__(256, (QT <= 2 ? 2 : 1)) void tree_attn_bf16_kernel(
     }
 
     // the key-splitting wavefronts of a slab share the segment's blocks evenly
-    const int blk_begin = seg_begin + (int)(((int64_t)kp * seg_count) / KW);
-    const int blk_end = seg_begin + (int)(((int64_t)(kp + 1) * seg_count) / KW);
+    // interleaved: wavefront kp takes blocks kp, kp+KW, ... so that the workgroup as a whole walks
+    // one contiguous stretch of K and of V (neighbouring DRAM pages stay open)
+    const int blk_begin = seg_begin + kp;
+    const int blk_end = seg_begin + seg_count;
 
     const __bf16* kc = reinterpret_cast<const __bf16*>(p.k_cache) + b * p.stride_batch + g * p.stride_head;
     const __bf16* vc = reinterpret_cast<const __bf16*>(p.v_cache) + b * p.stride_batch + g * p.stride_head;
@@ -380,7 +382,7 @@ __global__ __launch_bounds__(256, (QT <= 2 ? 2 : 1)) void tree_attn_bf16_kernel(
       load_k<D>(kf, cur, col, g4);
       int blk = blk_begin;
       const int full_end = min(blk_end, L / kBlockKeys);  // blocks below this index are full prefix blocks
-      if (blk + 1 < full_end) {
+      if (blk + KW < full_end) {
         unsigned koff[2], voff[8];
         const unsigned row_bytes = (unsigned)p.stride_token * 2u;
 #pragma unroll
@@ -391,13 +393,13 @@ __global__ __launch_bounds__(256, (QT <= 2 ? 2 : 1)) void tree_attn_bf16_kernel(
         const char* kb = reinterpret_cast<const char*>(kc) + (int64_t)blk * block_bytes;
         const char* vb = reinterpret_cast<const char*>(vc) + (int64_t)blk * block_bytes;
         BlockSrc full{};  // kind 0
-        for (; blk + 1 < full_end; ++blk) {
+        for (; blk + KW < full_end; blk += KW) {
           if constexpr (kQInLds) asm volatile("" ::: "memory");  // keep the Q reads inside the loop (they are the point)
           load_v_full<D>(vr, vb, voff);
           f32x4 s[2][QT];
           scores<QT, D>(s, kf, q_frag);
-          kb += block_bytes;
-          vb += block_bytes;
+          kb += block_bytes * KW;
+          vb += block_bytes * KW;
           load_k_full<D>(kf, kb, koff);
           bf16x8 pf[QT];
           softmax_block<QT, D, true>(s, pf, st, full, mask_of_tile, c, g4);
@@ -405,14 +407,14 @@ __global__ __launch_bounds__(256, (QT <= 2 ? 2 : 1)) void tree_attn_bf16_kernel(
         }
         cur = locate(blk);
       }
-      for (; blk < blk_end; ++blk) {
+      for (; blk < blk_end; blk += KW) {
         if constexpr (kQInLds) asm volatile("" ::: "memory");
         load_v<D>(vr, cur, col, g4);
         f32x4 s[2][QT];
         scores<QT, D>(s, kf, q_frag);
         BlockSrc nxt = cur;
-        if (blk + 1 < blk_end) {
-          nxt = locate(blk + 1);
+        if (blk + KW < blk_end) {
+          nxt = locate(blk + KW);
           load_k<D>(kf, nxt, col, g4);
         }
         bf16x8 pf[QT];
