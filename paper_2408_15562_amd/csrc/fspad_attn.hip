@@ -140,7 +140,7 @@ struct RowState {
   static constexpr int DT = D / 16;
   f32x4 o[QT][DT];   // O^T accumulators: lane (col,g4), reg i <-> row 16t+col, dim DT*(4*g4+i)+e
   float m[QT];       // softmax shift in use (log2 units, scaled): within kLazyLog2 of the running max
-  float l[QT];       // running sum, partial per lane until the final cross-lane add
+  f32x4 l[QT];       // running sum of the weights, formed on the matrix cores (all 4 entries equal)
 };
 
 // The shift of a row only moves when a score exceeds it by more than this (log2 units): weights
@@ -148,95 +148,121 @@ struct RowState {
 // accumulators are rescaled (and lanes exchanged) almost never after the first blocks.
 constexpr float kLazyLog2 = 8.0f;
 
-// S^T = K Q^T for one block: s[kt][t][i] in lane (col,g4) is key 16*kt+4*g4+i against row 16*t+col.
+// One 32-key block against the wavefront's 16*QT query rows, two row tiles at a time so that only
+// 16 score and 8 weight registers are live and the matrix work of one tile pair can run under the
+// vector work of the other:
+//   S^T = K Q^T          s[kt][i] of tile t in lane (col,g4) is key 16*kt+4*g4+i against row 16*t+col
+//   mask (ragged / tree blocks), lazy shift update, weights p = 2^(s*c - m) rounded to bf16
+//   O^T += V^T P^T       V slice of a lane transposed once per block with byte permutes
+//   l   += 1^T P^T       row sums on the matrix cores: sums of the bf16 weights actually used, so
+//                        numerator and denominator agree (a dominant key is reproduced exactly),
+//                        with no vector-ALU adds and no lane exchange.
 // Q fragments come from registers, or (large row tiles) from lane-private LDS slots.
-template <int QT, int D, typename QFn>
-__device__ __forceinline__ void scores(f32x4 (&s)[2][QT], const bf16x8 (&k)[2][D / 32], QFn&& q_frag) {
-#pragma unroll
-  for (int t = 0; t < QT; ++t) {
-    f32x4 acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int ks = 0; ks < D / 32; ++ks) {
-      const bf16x8 q = q_frag(t, ks);
-      acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k[0][ks], q, acc0, 0, 0, 0);
-      acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k[1][ks], q, acc1, 0, 0, 0);
-    }
-    s[0][t] = acc0;
-    s[1][t] = acc1;
-  }
-}
-
-// Mask, online softmax: updates the row state and returns the bf16 weights as B operands.
-template <int QT, int D, bool FULL, typename MaskFn>
-__device__ __forceinline__ void softmax_block(f32x4 (&s)[2][QT], bf16x8 (&pf)[QT], RowState<QT, D>& st,
-                                              const BlockSrc& src, MaskFn&& mask_of_tile, float c, int g4) {
+// `after_scores()` runs once the last product that reads k has been issued (the caller requests
+// the next block's K there when it keeps a single K buffer). `after_transpose()` runs, for tiles
+// done in several passes, once v has been transposed and is dead (the caller requests the next
+// block's V into the same registers there: a whole block of lead time at no register cost).
+template <int QT, int D, bool FULL, typename QFn, typename MaskFn, typename AfterFn, typename AfterVFn>
+__device__ __forceinline__ void process_block(RowState<QT, D>& st, const bf16x8 (&k)[2][D / 32],
+                                              const unsigned (&v)[8][D / 32], QFn&& q_frag, const BlockSrc& src,
+                                              MaskFn&& mask_of_tile, float c, int g4, AfterFn&& after_scores,
+                                              AfterVFn&& after_transpose) {
   constexpr int DT = D / 16;
-  if (!FULL && src.kind != 0) {
-    uint64_t mask_word[QT];  // fetched only here: tree blocks are a handful per call
+  constexpr int TP = QT >= 2 ? 2 : 1;  // tiles per pass
+  bf16x8 ones;
 #pragma unroll
-    for (int t = 0; t < QT; ++t) mask_word[t] = src.kind == 2 ? mask_of_tile(t) : 0ull;
+  for (int j = 0; j < 8; ++j) ones[j] = (__bf16)1.0f;
+  bf16x8 vt[DT];  // transposed V: A operand of d-tile e holds dims DT*col+e of the lane group's 8 keys
 #pragma unroll
-    for (int kt = 0; kt < 2; ++kt)
+  for (int t0 = 0; t0 < QT; t0 += TP) {
+    f32x4 s[TP][2];
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int key = 16 * kt + 4 * g4 + i;
+    for (int tt = 0; tt < TP; ++tt) {
+      if (t0 + tt >= QT) continue;
+      f32x4 acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int t = 0; t < QT; ++t) {
-          bool visible = key < src.nvalid;
-          if (src.kind == 2) visible = visible && ((mask_word[t] >> (src.tree_key0 + key)) & 1ull);
-          if (!visible) s[kt][t][i] = -INFINITY;
-        }
+      for (int ks = 0; ks < D / 32; ++ks) {
+        const bf16x8 q = q_frag(t0 + tt, ks);
+        acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k[0][ks], q, acc0, 0, 0, 0);
+        acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k[1][ks], q, acc1, 0, 0, 0);
       }
-  }
-  float mx[QT];
-  bool grow = false;
-#pragma unroll
-  for (int t = 0; t < QT; ++t) {
-    mx[t] = fmaxf(fmaxf(fmaxf(s[0][t][0], s[0][t][1]), fmaxf(s[0][t][2], s[0][t][3])),
-                  fmaxf(fmaxf(s[1][t][0], s[1][t][1]), fmaxf(s[1][t][2], s[1][t][3])));
-    grow = grow || (mx[t] * c > st.m[t] + kLazyLog2);
-  }
-  if (__any(grow)) {  // wavefront-uniform and rare: move every row's shift to its running max
-#pragma unroll
-    for (int t = 0; t < QT; ++t) {
-      const float mnew = fmaxf(st.m[t], wave_xor_max_16_32(mx[t]) * c);
-      const float alpha = __builtin_amdgcn_exp2f(st.m[t] - mnew);
-      st.m[t] = mnew;
-      st.l[t] *= alpha;
-#pragma unroll
-      for (int e = 0; e < DT; ++e) st.o[t][e] *= alpha;
+      s[tt][0] = acc0;
+      s[tt][1] = acc1;
     }
-  }
+    if (t0 + TP >= QT) after_scores();
+    if (!FULL && src.kind != 0) {
 #pragma unroll
-  for (int t = 0; t < QT; ++t) {
-    float p[8];
+      for (int tt = 0; tt < TP; ++tt) {
+        if (t0 + tt >= QT) continue;
+        const uint64_t word = src.kind == 2 ? mask_of_tile(t0 + tt) : 0ull;  // fetched only in the few tree blocks
 #pragma unroll
-    for (int j = 0; j < 8; ++j) p[j] = __builtin_amdgcn_exp2f(fmaf(s[j >> 2][t][j & 3], c, -st.m[t]));
+        for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
-    for (int j = 0; j < 8; ++j) pf[t][j] = (__bf16)p[j];
-    // the sum runs over the weights as the matrix cores see them (rounded to bf16), so that
-    // numerator and denominator carry the same weights and a dominant key is reproduced exactly
-    float sum = 0.f;
+          for (int i = 0; i < 4; ++i) {
+            const int key = 16 * kt + 4 * g4 + i;
+            bool visible = key < src.nvalid;
+            if (src.kind == 2) visible = visible && ((word >> (src.tree_key0 + key)) & 1ull);
+            if (!visible) s[tt][kt][i] = -INFINITY;
+          }
+      }
+    }
+    float mx[TP];
+    bool grow = false;
 #pragma unroll
-    for (int j = 0; j < 8; ++j) sum += (float)pf[t][j];
-    st.l[t] += sum;
-  }
-}
-
-// O^T += V^T P^T; the 8 x (D/16) V slice of a lane is transposed with byte permutes.
-template <int QT, int D>
-__device__ __forceinline__ void weighted_values(RowState<QT, D>& st, const unsigned (&v)[8][D / 32],
-                                                const bf16x8 (&pf)[QT]) {
+    for (int tt = 0; tt < TP; ++tt) {
+      if (t0 + tt >= QT) continue;
+      mx[tt] = fmaxf(fmaxf(fmaxf(s[tt][0][0], s[tt][0][1]), fmaxf(s[tt][0][2], s[tt][0][3])),
+                     fmaxf(fmaxf(s[tt][1][0], s[tt][1][1]), fmaxf(s[tt][1][2], s[tt][1][3])));
+      grow = grow || (mx[tt] * c > st.m[t0 + tt] + kLazyLog2);
+    }
+    if (__any(grow)) {  // wavefront-uniform and rare: move these rows' shifts to their running maxima
 #pragma unroll
-  for (int e = 0; e < D / 16; ++e) {
-    const unsigned sel = (e & 1) ? 0x07060302u : 0x05040100u;
-    u32x4 w;
+      for (int tt = 0; tt < TP; ++tt) {
+        if (t0 + tt >= QT) continue;
+        const int t = t0 + tt;
+        const float mnew = fmaxf(st.m[t], wave_xor_max_16_32(mx[tt]) * c);
+        const float alpha = __builtin_amdgcn_exp2f(st.m[t] - mnew);
+        st.m[t] = mnew;
+        st.l[t] *= alpha;
 #pragma unroll
-    for (int m2 = 0; m2 < 4; ++m2) w[m2] = __builtin_amdgcn_perm(v[2 * m2 + 1][e >> 1], v[2 * m2][e >> 1], sel);
-    const bf16x8 va = __builtin_bit_cast(bf16x8, w);
+        for (int e = 0; e < DT; ++e) st.o[t][e] *= alpha;
+      }
+    }
+    bf16x8 pf[TP];
 #pragma unroll
-    for (int t = 0; t < QT; ++t)
-      st.o[t][e] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, pf[t], st.o[t][e], 0, 0, 0);
+    for (int tt = 0; tt < TP; ++tt) {
+      if (t0 + tt >= QT) continue;
+      const float m = st.m[t0 + tt];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) pf[tt][j] = (__bf16)__builtin_amdgcn_exp2f(fmaf(s[tt][j >> 2][j & 3], c, -m));
+    }
+    auto transposed = [&](int e) {  // A operand of d-tile e from the lane's 8 x DT slice of V
+      const unsigned sel = (e & 1) ? 0x07060302u : 0x05040100u;
+      u32x4 w;
+#pragma unroll
+      for (int m2 = 0; m2 < 4; ++m2) w[m2] = __builtin_amdgcn_perm(v[2 * m2 + 1][e >> 1], v[2 * m2][e >> 1], sel);
+      return __builtin_bit_cast(bf16x8, w);
+    };
+    constexpr bool kSinglePass = QT <= TP;  // one pass: transpose on the fly, nothing to keep
+    if (!kSinglePass && t0 == 0) {
+#pragma unroll
+      for (int e = 0; e < DT; ++e) vt[e] = transposed(e);
+      after_transpose();
+    }
+#pragma unroll
+    for (int tt = 0; tt < TP; ++tt) {
+      if (t0 + tt >= QT) continue;
+      st.l[t0 + tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, pf[tt], st.l[t0 + tt], 0, 0, 0);
+    }
+#pragma unroll
+    for (int e = 0; e < DT; ++e) {
+      const bf16x8 va = kSinglePass ? transposed(e) : vt[e];
+#pragma unroll
+      for (int tt = 0; tt < TP; ++tt) {
+        if (t0 + tt >= QT) continue;
+        st.o[t0 + tt][e] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, pf[tt], st.o[t0 + tt][e], 0, 0, 0);
+      }
+    }
   }
 }
 
@@ -255,6 +281,9 @@ __global__ __launch_bounds__(256, (QT <= 2 ? 2 : 1)) void tree_attn_bf16_kernel(
   // the Q fragments of the 4 wavefronts live in lane-private LDS slots instead of registers; they are
   // dead once a segment's stream is done, so they share the space of the merge buffers.
   constexpr bool kQInLds = QT >= 3;
+  // Tiles done in several passes run one wavefront per SIMD: they hide the memory latency by
+  // themselves, keeping K and V of the next block in flight for a whole block
+  constexpr bool kDeep = QT >= 3;
   constexpr int kMergeBytes = 3 * QT * DT * 64 * 16;
   constexpr int kQBytes = kQInLds ? 4 * QT * KS * 64 * 16 : 0;
   __shared__ __attribute__((aligned(16))) char lds_raw[kMergeBytes > kQBytes ? kMergeBytes : kQBytes];
@@ -332,7 +361,7 @@ __global__ __launch_bounds__(256, (QT <= 2 ? 2 : 1)) void tree_attn_bf16_kernel(
 #pragma unroll
     for (int t = 0; t < QT; ++t) {
       st.m[t] = kNegBig;
-      st.l[t] = 0.f;
+      st.l[t] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int e = 0; e < DT; ++e) st.o[t][e] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
@@ -370,16 +399,20 @@ __global__ __launch_bounds__(256, (QT <= 2 ? 2 : 1)) void tree_attn_bf16_kernel(
       return src;
     };
 
-    // Staggered stream: V of the current block is requested before its scores are formed, K of the
-    // next block right after them, so both loads fly under the softmax / matrix work of this block
-    // while only one K and one V block are held in registers. Full prefix blocks (all but the last
-    // three of a sequence) take a branch-free path with scalar bases; the ragged tail and the tree
-    // blocks take the general one.
+    // The stream. Small tiles (two wavefronts per SIMD): V of the current block is requested before
+    // its scores are formed, K of the next block right after them; one K and one V block in registers.
+    // Large tiles (one wavefront per SIMD): K of the next block is requested at the top of this one
+    // into a second buffer, V of the next block as soon as this block's V has been transposed, into
+    // the registers that frees. Full prefix blocks (all but the last three of a sequence) take a
+    // branch-free path with scalar bases; the ragged tail and the tree blocks take the general one.
     if (slab_live && blk_begin < blk_end) {
-      bf16x8 kf[2][KS];
+      // large row tiles run one wavefront per SIMD and have the registers to hold the next block's K
+      // while this block's is in use (requested a whole block ahead); small tiles reuse one buffer
+      bf16x8 kf[2][KS], kfn[kDeep ? 2 : 1][KS];
       unsigned vr[8][D / 32];
       BlockSrc cur = locate(blk_begin);
       load_k<D>(kf, cur, col, g4);
+      if constexpr (kDeep) load_v<D>(vr, cur, col, g4);
       int blk = blk_begin;
       const int full_end = min(blk_end, L / kBlockKeys);  // blocks below this index are full prefix blocks
       if (blk + KW < full_end) {
@@ -395,36 +428,52 @@ __global__ __launch_bounds__(256, (QT <= 2 ? 2 : 1)) void tree_attn_bf16_kernel(
         BlockSrc full{};  // kind 0
         for (; blk + KW < full_end; blk += KW) {
           if constexpr (kQInLds) asm volatile("" ::: "memory");  // keep the Q reads inside the loop (they are the point)
-          load_v_full<D>(vr, vb, voff);
-          f32x4 s[2][QT];
-          scores<QT, D>(s, kf, q_frag);
-          kb += block_bytes * KW;
-          vb += block_bytes * KW;
-          load_k_full<D>(kf, kb, koff);
-          bf16x8 pf[QT];
-          softmax_block<QT, D, true>(s, pf, st, full, mask_of_tile, c, g4);
-          weighted_values<QT, D>(st, vr, pf);
+          if constexpr (kDeep) {
+            kb += block_bytes * KW;
+            vb += block_bytes * KW;
+            load_k_full<D>(kfn, kb, koff);
+            process_block<QT, D, true>(st, kf, vr, q_frag, full, mask_of_tile, c, g4, [] {},
+                                       [&] { load_v_full<D>(vr, vb, voff); });
+#pragma unroll
+            for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+              for (int ks = 0; ks < KS; ++ks) kf[kt][ks] = kfn[kt][ks];
+          } else {
+            load_v_full<D>(vr, vb, voff);
+            kb += block_bytes * KW;
+            vb += block_bytes * KW;
+            process_block<QT, D, true>(st, kf, vr, q_frag, full, mask_of_tile, c, g4,
+                                       [&] { load_k_full<D>(kf, kb, koff); }, [] {});
+          }
         }
         cur = locate(blk);
       }
       for (; blk < blk_end; blk += KW) {
         if constexpr (kQInLds) asm volatile("" ::: "memory");
-        load_v<D>(vr, cur, col, g4);
-        f32x4 s[2][QT];
-        scores<QT, D>(s, kf, q_frag);
         BlockSrc nxt = cur;
-        if (blk + KW < blk_end) {
-          nxt = locate(blk + KW);
-          load_k<D>(kf, nxt, col, g4);
+        const bool more = blk + KW < blk_end;
+        if (more) nxt = locate(blk + KW);
+        if constexpr (kDeep) {
+          if (more) load_k<D>(kfn, nxt, col, g4);
+          process_block<QT, D, false>(st, kf, vr, q_frag, cur, mask_of_tile, c, g4, [] {},
+                                     [&] { if (more) load_v<D>(vr, nxt, col, g4); });
+          if (more) {
+#pragma unroll
+            for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+              for (int ks = 0; ks < KS; ++ks) kf[kt][ks] = kfn[kt][ks];
+          }
+        } else {
+          load_v<D>(vr, cur, col, g4);
+          process_block<QT, D, false>(st, kf, vr, q_frag, cur, mask_of_tile, c, g4,
+                                     [&] { if (more) load_k<D>(kf, nxt, col, g4); }, [] {});
         }
-        bf16x8 pf[QT];
-        softmax_block<QT, D, false>(s, pf, st, cur, mask_of_tile, c, g4);
-        weighted_values<QT, D>(st, vr, pf);
         cur = nxt;
       }
     }
+    float lsum[QT];  // the matrix-core row sums already cover every key of the wavefront's blocks
 #pragma unroll
-    for (int t = 0; t < QT; ++t) st.l[t] = wave_xor_sum_16_32(st.l[t]);
+    for (int t = 0; t < QT; ++t) lsum[t] = st.l[t][0];
 
     // merge the key-splitting wavefronts of a slab through LDS (lane-private slots)
     if (KW > 1) {
@@ -433,7 +482,7 @@ __global__ __launch_bounds__(256, (QT <= 2 ? 2 : 1)) void tree_attn_bf16_kernel(
         const int slot = (kp - 1) * p.WS + slab_local;
 #pragma unroll
         for (int t = 0; t < QT; ++t) {
-          merge_ml[slot][t][lane] = make_float2(st.m[t], st.l[t]);
+          merge_ml[slot][t][lane] = make_float2(st.m[t], lsum[t]);
 #pragma unroll
           for (int e = 0; e < DT; ++e) merge_o[slot][t * DT + e][lane] = st.o[t][e];
         }
@@ -448,7 +497,7 @@ __global__ __launch_bounds__(256, (QT <= 2 ? 2 : 1)) void tree_attn_bf16_kernel(
             const float mm = fmaxf(st.m[t], ml.x);
             const float a0 = __builtin_amdgcn_exp2f(st.m[t] - mm), a1 = __builtin_amdgcn_exp2f(ml.x - mm);
             st.m[t] = mm;
-            st.l[t] = st.l[t] * a0 + ml.y * a1;
+            lsum[t] = lsum[t] * a0 + ml.y * a1;
 #pragma unroll
             for (int e = 0; e < DT; ++e) st.o[t][e] = st.o[t][e] * a0 + merge_o[slot][t * DT + e][lane] * a1;
           }
@@ -463,7 +512,7 @@ __global__ __launch_bounds__(256, (QT <= 2 ? 2 : 1)) void tree_attn_bf16_kernel(
         const RowInfo ri = row_info(t);
         if (!ri.exists) continue;
         if (whole_unit) {
-          const float inv = ri.valid ? 1.0f / st.l[t] : 0.f;
+          const float inv = ri.valid ? 1.0f / lsum[t] : 0.f;
 #pragma unroll
           for (int i = 0; i < 4; ++i) {
             const int d0 = DT * (4 * g4 + i);
@@ -491,7 +540,7 @@ __global__ __launch_bounds__(256, (QT <= 2 ? 2 : 1)) void tree_attn_bf16_kernel(
         } else if (ri.valid) {
           float* slot = p.part + (int64_t)(unit + w) * rows_per_unit * (D + 2);
           const int lr = slab_local * ROWS + 16 * t + col;
-          if (g4 == 0) *reinterpret_cast<float2*>(slot + (int64_t)rows_per_unit * D + 2 * lr) = make_float2(st.m[t], st.l[t]);
+          if (g4 == 0) *reinterpret_cast<float2*>(slot + (int64_t)rows_per_unit * D + 2 * lr) = make_float2(st.m[t], lsum[t]);
 #pragma unroll
           for (int i = 0; i < 4; ++i) {
             float* dst = slot + (int64_t)lr * D + DT * (4 * g4 + i);
