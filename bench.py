@@ -36,6 +36,7 @@ def parse_args():
     ap.add_argument("--splits", type=int, default=0, help="force the number of attention workgroups (0 = automatic)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--max-qt", type=int, default=0, help=argparse.SUPPRESS)
+    ap.add_argument("--accept-target", type=int, default=0, help=argparse.SUPPRESS)
     ap.add_argument("--layers", type=int, default=None, help="profiling only: run fewer layers of a stack (the result line is then not the workload's)")
     ap.add_argument("--nodes", type=int, default=None, help="experiments only: override the tree size")
     ap.add_argument("--heads", type=int, default=None, help="experiments only: override the head count (MHA)")
@@ -104,6 +105,9 @@ def main():
     parent_d = torch.from_numpy(parent).to(dev)
     n_nodes_d = torch.from_numpy(n_nodes).to(dev)
 
+    if args.accept_target:
+        import ctypes
+        ctypes.CDLL(fspad.library_path()).fspad_debug_set_accept_target(args.accept_target)
     if args.max_qt:
         import ctypes
         ctypes.CDLL(fspad.library_path()).fspad_debug_set_max_qt(args.max_qt)

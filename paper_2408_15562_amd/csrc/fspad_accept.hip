@@ -5,7 +5,7 @@
 // relaxed). gfx950 (CDNA4) only.
 //
 // Two kernels per call. The first streams the [B*N, V] fp32 logits once, 16 bytes
-// per lane, one workgroup per (row, 8192-entry chunk), and leaves per-chunk
+// per lane, one workgroup per (row, chunk of 1024..8192 entries), and leaves per-chunk
 // statistics: (max, first index of max) for greedy, (max, fp64 sum of
 // exp((l-max)/T)) for sampling. The second, one workgroup per sequence, merges the
 // chunk statistics of the rows it needs, walks the tree with wavefront ballots
@@ -20,9 +20,10 @@ namespace {
 
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 
-constexpr int kChunk = 8192;              // logits per workgroup of the streaming kernel
 constexpr int kThreads = 256;
-constexpr int kPerThread = kChunk / kThreads;  // 32
+constexpr int kMinChunk = 1024;           // logits per workgroup of the streaming kernel: 1024 .. 8192,
+constexpr int kMaxChunk = 8192;           // chosen per call so that small problems still fill the chip
+constexpr int kMaxPerThread = kMaxChunk / kThreads;  // 32
 constexpr int kNone = 0x7fffffff;
 
 struct AcceptParams {
@@ -41,6 +42,7 @@ struct AcceptParams {
   double* part_sum;    // sampling [rows][chunks]
   double inv_temperature;
   int32_t B, Nmax, V, n_chunks;
+  int32_t chunk;       // logits per (row, chunk) workgroup: 256 * PT
 };
 
 // exp(x) for x <= 0 in fp64: x = n ln2 + r, |r| <= ln2/2, degree-11 Taylor polynomial
@@ -75,8 +77,10 @@ __device__ __forceinline__ void take_better(float& v, int& i, float ov, int oi) 
 // ------------------------------------------------------------------------------------------------
 // Streaming pass. MODE 0: greedy (max, argmax). MODE 1: sampling (max, sum of exp).
 // VEC: rows are 16-byte aligned so that float4 loads are legal.
-template <int MODE, bool VEC>
+template <int MODE, bool VEC, int PT>
 __global__ __launch_bounds__(kThreads) void accept_rows_kernel(const AcceptParams p) {
+  constexpr int kChunk = kThreads * PT;
+  constexpr int kPerThread = PT;
   __shared__ float sh_max[4];
   __shared__ int sh_idx[4];
   __shared__ double sh_sum[4];
@@ -144,23 +148,53 @@ __global__ __launch_bounds__(kThreads) void accept_rows_kernel(const AcceptParam
 }
 
 // ------------------------------------------------------------------------------------------------
-// Greedy: merge chunk argmaxes per node, then descend while a child carries the target's token.
-__global__ __launch_bounds__(64) void accept_greedy_walk_kernel(const AcceptParams p) {
+// Greedy: merge chunk argmaxes per node, then wavefront 0 descends while a child carries the
+// target's token.
+__global__ __launch_bounds__(kThreads) void accept_greedy_walk_kernel(const AcceptParams p) {
   __shared__ int amax[FSPAD_MAX_NODES];
-  const int b = blockIdx.x, lane = threadIdx.x;
+  const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n = p.n_nodes[b];
   const int64_t o = (int64_t)b * p.Nmax;
-  int my_par = -2, my_tok = -1;
-  if (lane < n) {
+  // thread (node = lane, quarter = wave) scans every 4th chunk entry of its node, eight loads in
+  // flight at a time; the four quarters of a node meet in LDS (no lane exchange needed)
+  __shared__ float q_best[4][FSPAD_MAX_NODES];
+  __shared__ int q_idx[4][FSPAD_MAX_NODES];
+  {
     float best = -INFINITY;
     int idx = kNone;
-    const int64_t slot0 = (o + lane) * p.n_chunks;
-    for (int c = 0; c < p.n_chunks; ++c) take_better(best, idx, p.part_max[slot0 + c], p.part_idx[slot0 + c]);
+    if (lane < n) {
+      const int64_t slot0 = (o + lane) * p.n_chunks;
+      for (int c0 = wave; c0 < p.n_chunks; c0 += 32) {
+        float v[8];
+        int ix[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+          const int c = c0 + 4 * k;
+          v[k] = c < p.n_chunks ? p.part_max[slot0 + c] : -INFINITY;
+          ix[k] = c < p.n_chunks ? p.part_idx[slot0 + c] : kNone;
+        }
+#pragma unroll
+        for (int k = 0; k < 8; ++k) take_better(best, idx, v[k], ix[k]);
+      }
+    }
+    q_best[wave][lane] = best;
+    q_idx[wave][lane] = idx;
+  }
+  __syncthreads();
+  if (wave == 0 && lane < n) {
+    float best = q_best[0][lane];
+    int idx = q_idx[0][lane];
+#pragma unroll
+    for (int w = 1; w < 4; ++w) take_better(best, idx, q_best[w][lane], q_idx[w][lane]);
     amax[lane] = idx == kNone ? 0 : idx;  // a row with nothing above -inf: token 0
+  }
+  __syncthreads();
+  if (wave != 0) return;
+  int my_par = -2, my_tok = -1;
+  if (lane < n) {
     my_par = p.parent[o + lane];
     my_tok = p.draft_tokens[o + lane];
   }
-  __syncthreads();
   int my_path = -1, my_out = -1;  // lane j keeps path[j] and tokens[j]
   if (lane == 0) my_path = 0;
   int cur = 0, len = 1;
@@ -196,8 +230,9 @@ __global__ __launch_bounds__(kThreads) void accept_sample_walk_kernel(const Acce
   const float* u_bonus = u_acc + p.Nmax;
 
   if (wave == 0) {
-    int my_par = -2;
-    if (lane < n) my_par = p.parent[o + lane];
+    int my_par = -2, my_tok = -1;
+    float my_u = 0.f;
+    if (lane < n) { my_par = p.parent[o + lane]; my_tok = p.draft_tokens[o + lane]; my_u = u_acc[lane]; }
     int my_path = lane == 0 ? 0 : -1, my_out = -1;
     int cur = 0, len = 1, nrej = 0;
     double M = 0.0, Z = 0.0;
@@ -217,29 +252,37 @@ __global__ __launch_bounds__(kThreads) void accept_sample_walk_kernel(const Acce
       for (int off = 32; off > 0; off >>= 1) z += __shfl_xor(z, off);
       Z = z;
       nrej = 0;
-      unsigned long long kids = __ballot(lane > 0 && lane < n && my_par == cur);
+      // every child (lane = node) fetches its own token's weight at once; a token that an earlier
+      // sibling already proposed has been removed from the residual by then and weighs nothing
+      const bool is_kid = lane > 0 && lane < n && my_par == cur;
+      unsigned long long kids = __ballot(is_kid);
+      double my_w = 0.0;
+      if (is_kid && my_tok >= 0 && my_tok < p.V && mx > -INFINITY) {
+        const float lx = p.logits[row * p.row_stride + my_tok];
+        if (lx == lx) my_w = exp_nonpos(((double)lx - M) * p.inv_temperature);
+      }
+      for (unsigned long long rest = kids; rest != 0ull; rest &= rest - 1ull) {
+        const int c = __ffsll(rest) - 1;
+        const int tc = __shfl(my_tok, c);
+        if (is_kid && lane > c && my_tok == tc) my_w = 0.0;
+      }
       int accepted = -1;
       while (kids != 0ull && len < p.Nmax) {
         const int c = __ffsll(kids) - 1;
         kids &= kids - 1ull;
-        const int x = p.draft_tokens[o + c];
-        double w = 0.0;
-        if (x >= 0 && x < p.V) {
-          const float lx = p.logits[row * p.row_stride + x];
-          if (lx == lx && mx > -INFINITY) w = exp_nonpos(((double)lx - M) * p.inv_temperature);
-          for (int r = 0; r < nrej; ++r)
-            if (rej_tok[r] == x) w = 0.0;  // a token already removed from the residual
-        }
-        const double lhs = (double)u_acc[c] * Z;
+        const int x = __shfl(my_tok, c);
+        const double w = __shfl(my_w, c);
+        const double lhs = (double)__shfl(my_u, c) * Z;
         if (lhs < w) { accepted = c; break; }
         Z -= w;
         if (lane == 0) { rej_tok[nrej] = x; rej_w[nrej] = w; }
         ++nrej;
-        __builtin_amdgcn_wave_barrier();
       }
+      __builtin_amdgcn_wave_barrier();
       if (accepted < 0) break;
       if (lane == len) my_path = accepted;
-      if (lane == len - 1) my_out = p.draft_tokens[o + accepted];
+      const int accepted_tok = __shfl(my_tok, accepted);  // all lanes take part in the exchange
+      if (lane == len - 1) my_out = accepted_tok;
       cur = accepted;
       ++len;
     }
@@ -263,7 +306,7 @@ __global__ __launch_bounds__(kThreads) void accept_sample_walk_kernel(const Acce
       if (c < p.n_chunks && pm[c] > -INFINITY) {
         r = ps[c] * exp_nonpos(((double)pm[c] - M) * p.inv_temperature);
         for (int k = 0; k < nrej; ++k)
-          if (rej_tok[k] >= c * kChunk && rej_tok[k] < (c + 1) * kChunk && rej_tok[k] < p.V) r -= rej_w[k];
+          if (rej_tok[k] >= c * p.chunk && rej_tok[k] < (c + 1) * p.chunk && rej_tok[k] < p.V) r -= rej_w[k];
       }
       double incl = r;
 #pragma unroll
@@ -291,7 +334,7 @@ __global__ __launch_bounds__(kThreads) void accept_sample_walk_kernel(const Acce
   }
   __syncthreads();
 
-  // bonus, stage 2: inside the chunk, thread k owns 32 consecutive entries
+  // bonus, stage 2: inside the chunk, thread k owns chunk/256 consecutive entries
   const int cur = sh_i[0], len = sh_i[1], nrej = sh_i[2], chunk = sh_i[3];
   const double M = sh_d[0], target = sh_d[2];
   if (chunk < 0) {  // no mass anywhere (cannot happen with finite logits): token 0
@@ -299,7 +342,8 @@ __global__ __launch_bounds__(kThreads) void accept_sample_walk_kernel(const Acce
     return;
   }
   const float* rp = p.logits + (o + cur) * p.row_stride;
-  const int e0 = chunk * kChunk + tid * kPerThread;
+  const int per_thread = p.chunk / kThreads;
+  const int e0 = chunk * p.chunk + tid * per_thread;
   auto weight = [&](int e) -> double {
     if (e >= p.V) return 0.0;
     const float lx = rp[e];
@@ -310,7 +354,7 @@ __global__ __launch_bounds__(kThreads) void accept_sample_walk_kernel(const Acce
   };
   double local = 0.0;
   int last_here = -1;
-  for (int j = 0; j < kPerThread; ++j) {
+  for (int j = 0; j < per_thread; ++j) {
     const double w = weight(e0 + j);
     local += w;
     if (w > 0.0) last_here = e0 + j;
@@ -339,12 +383,21 @@ __global__ __launch_bounds__(kThreads) void accept_sample_walk_kernel(const Acce
   if (tid == sh_i[5]) {
     double run = inclusive - local;
     int pick = last_here;  // if rounding hides the crossing inside the segment: its last entry with mass
-    for (int j = 0; j < kPerThread; ++j) {
+    for (int j = 0; j < per_thread; ++j) {
       run += weight(e0 + j);
       if (run > target) { pick = e0 + j; break; }
     }
     p.tokens[o + len - 1] = pick;
   }
+}
+
+// Largest chunk that still gives about a thousand workgroups (rows x chunks), so that a few rows of
+// a small vocabulary are spread over the whole chip.
+int g_target_wgs = 1024;
+int pick_chunk(int32_t B, int32_t Nmax, int32_t V) {
+  int chunk = kMaxChunk;
+  while (chunk > kMinChunk && (int64_t)B * Nmax * ((V + chunk - 1) / chunk) < g_target_wgs) chunk >>= 1;
+  return chunk;
 }
 
 fspad_status check_accept_args(int32_t B, int32_t Nmax, int32_t V, const float* logits, int64_t row_stride,
@@ -365,7 +418,9 @@ void fill_params(AcceptParams& p, int32_t B, int32_t Nmax, int32_t V, const floa
                  int32_t* path_len, int32_t* tokens, int32_t* n_tokens, void* workspace) {
   p.logits = logits; p.row_stride = row_stride; p.draft_tokens = draft_tokens; p.parent = parent;
   p.n_nodes = n_nodes; p.path = path; p.path_len = path_len; p.tokens = tokens; p.n_tokens = n_tokens;
-  p.B = B; p.Nmax = Nmax; p.V = V; p.n_chunks = (V + kChunk - 1) / kChunk;
+  p.B = B; p.Nmax = Nmax; p.V = V;
+  p.chunk = pick_chunk(B, Nmax, V);
+  p.n_chunks = (V + p.chunk - 1) / p.chunk;
   const size_t slots = (size_t)B * Nmax * p.n_chunks;
   p.part_sum = reinterpret_cast<double*>(workspace);                 // 8-byte entries first
   p.part_max = reinterpret_cast<float*>(p.part_sum + slots);
@@ -378,11 +433,30 @@ bool rows_vectorisable(const float* logits, int64_t row_stride) {
   return (((uintptr_t)logits) & 15) == 0 && (row_stride % 4) == 0;
 }
 
+template <int MODE>
+void launch_rows(const AcceptParams& p, bool vec, hipStream_t stream) {
+  const dim3 grid((unsigned)p.n_chunks, (unsigned)(p.B * p.Nmax));
+#define FSPAD_ROWS(PT)                                                                                         \
+  do {                                                                                                           \
+    if (vec) hipLaunchKernelGGL((accept_rows_kernel<MODE, true, PT>), grid, dim3(kThreads), 0, stream, p);      \
+    else hipLaunchKernelGGL((accept_rows_kernel<MODE, false, PT>), grid, dim3(kThreads), 0, stream, p);         \
+  } while (0)
+  switch (p.chunk / kThreads) {
+    case 4: FSPAD_ROWS(4); break;
+    case 8: FSPAD_ROWS(8); break;
+    case 16: FSPAD_ROWS(16); break;
+    default: FSPAD_ROWS(32); break;
+  }
+#undef FSPAD_ROWS
+}
+
 }  // namespace
+
+extern "C" void fspad_debug_set_accept_target(int32_t wgs) { g_target_wgs = wgs; }
 
 extern "C" size_t fspad_tree_accept_workspace_bytes(int32_t B, int32_t Nmax, int32_t V) {
   if (B < 1 || Nmax < 1 || V < 1) return 0;
-  const size_t slots = (size_t)B * Nmax * ((V + kChunk - 1) / kChunk);
+  const size_t slots = (size_t)B * Nmax * ((V + kMinChunk - 1) / kMinChunk);  // room for the finest split
   return (slots * 16 + 255) & ~(size_t)255;
 }
 
@@ -397,11 +471,9 @@ extern "C" fspad_status fspad_tree_accept_greedy(int32_t B, int32_t Nmax, int32_
   AcceptParams p{};
   fill_params(p, B, Nmax, V, logits, row_stride, draft_tokens, parent, n_nodes, path, path_len, tokens, n_tokens, workspace);
   hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
-  dim3 grid((unsigned)p.n_chunks, (unsigned)(B * Nmax));
-  if (rows_vectorisable(logits, row_stride)) hipLaunchKernelGGL((accept_rows_kernel<0, true>), grid, dim3(kThreads), 0, stream, p);
-  else hipLaunchKernelGGL((accept_rows_kernel<0, false>), grid, dim3(kThreads), 0, stream, p);
+  launch_rows<0>(p, rows_vectorisable(logits, row_stride), stream);
   if (hipGetLastError() != hipSuccess) return FSPAD_ERR_HIP;
-  hipLaunchKernelGGL(accept_greedy_walk_kernel, dim3((unsigned)B), dim3(64), 0, stream, p);
+  hipLaunchKernelGGL(accept_greedy_walk_kernel, dim3((unsigned)B), dim3(kThreads), 0, stream, p);
   if (hipGetLastError() != hipSuccess) return FSPAD_ERR_HIP;
   return FSPAD_OK;
 }
@@ -422,9 +494,7 @@ extern "C" fspad_status fspad_tree_accept_sample(int32_t B, int32_t Nmax, int32_
   p.uniforms = uniforms;
   p.inv_temperature = 1.0 / (double)temperature;
   hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
-  dim3 grid((unsigned)p.n_chunks, (unsigned)(B * Nmax));
-  if (rows_vectorisable(logits, row_stride)) hipLaunchKernelGGL((accept_rows_kernel<1, true>), grid, dim3(kThreads), 0, stream, p);
-  else hipLaunchKernelGGL((accept_rows_kernel<1, false>), grid, dim3(kThreads), 0, stream, p);
+  launch_rows<1>(p, rows_vectorisable(logits, row_stride), stream);
   if (hipGetLastError() != hipSuccess) return FSPAD_ERR_HIP;
   hipLaunchKernelGGL(accept_sample_walk_kernel, dim3((unsigned)B), dim3(kThreads), 0, stream, p);
   if (hipGetLastError() != hipSuccess) return FSPAD_ERR_HIP;

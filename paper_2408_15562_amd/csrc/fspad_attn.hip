@@ -590,15 +590,33 @@ __global__ __launch_bounds__(256) void tree_attn_combine_kernel(const AttnParams
   f32x4 acc = {0.f, 0.f, 0.f, 0.f};
   if (node < p.n_nodes[b]) {
     const int64_t slot_floats = (int64_t)rows_per_unit * (D + 2);
-    const float* base = p.part + (int64_t)(unit + w0) * slot_floats;
-    float M = kNegBig;
-    for (int s = 0; s <= w1 - w0; ++s) M = fmaxf(M, base[s * slot_floats + (int64_t)rows_per_unit * D + 2 * lr]);
-    float denom = 0.f;
-    for (int s = 0; s <= w1 - w0; ++s) {
-      const float2 ml = *reinterpret_cast<const float2*>(base + s * slot_floats + (int64_t)rows_per_unit * D + 2 * lr);
-      const float wgt = __builtin_amdgcn_exp2f(ml.x - M);
-      denom += wgt * ml.y;
-      acc += wgt * *reinterpret_cast<const f32x4*>(base + s * slot_floats + (int64_t)lr * D + d0);
+    const float* o_base = p.part + (int64_t)(unit + w0) * slot_floats + (int64_t)lr * D + d0;
+    const float* ml_base = p.part + (int64_t)(unit + w0) * slot_floats + (int64_t)rows_per_unit * D + 2 * lr;
+    // slots in index order (deterministic), eight at a time so that their loads are in flight together
+    float M = kNegBig, denom = 0.f;
+    const int n_seg = w1 - w0 + 1;
+    for (int s0 = 0; s0 < n_seg; s0 += 8) {
+      float2 ml[8];
+      f32x4 o[8];
+#pragma unroll
+      for (int k = 0; k < 8; ++k) {
+        const int sidx = min(s0 + k, n_seg - 1);  // clamped duplicates get zero weight below
+        ml[k] = *reinterpret_cast<const float2*>(ml_base + sidx * slot_floats);
+        o[k] = *reinterpret_cast<const f32x4*>(o_base + sidx * slot_floats);
+      }
+      float mx = M;
+#pragma unroll
+      for (int k = 0; k < 8; ++k) mx = fmaxf(mx, ml[k].x);
+      const float a = __builtin_amdgcn_exp2f(M - mx);
+      acc *= a;
+      denom *= a;
+      M = mx;
+#pragma unroll
+      for (int k = 0; k < 8; ++k) {
+        const float wgt = (s0 + k < n_seg) ? __builtin_amdgcn_exp2f(ml[k].x - M) : 0.f;
+        denom += wgt * ml[k].y;
+        acc += wgt * o[k];
+      }
     }
     acc *= 1.0f / denom;
   }
@@ -722,17 +740,31 @@ int blocks_of(int kv_len, int n_nodes) {
   return (kv_len + kBlockKeys - 1) / kBlockKeys + (n_nodes + kBlockKeys - 1) / kBlockKeys;
 }
 
-// Workgroup count for `total_blocks` flat blocks: two resident workgroups per compute unit when
-// the register budget allows it, but no workgroup with fewer than 2 blocks per key-splitting wave.
-int plan_wgs(const Plan& pl, int64_t total_blocks) {
+// Workgroup count for `total_blocks` flat blocks in `units` units: two resident workgroups per
+// compute unit when the register budget allows it (one otherwise), but no workgroup with fewer
+// than 2 blocks per key-splitting wave. When all units are equally long and fill at least three
+// quarters of the resident slots by themselves, one workgroup per unit: nothing is cut, nothing
+// is merged, and that beats the better balance of a cut.
+int plan_wgs(const Plan& pl, int64_t total_blocks, int64_t units, bool uniform) {
   const int KW = 4 / pl.WS;
-  int64_t wgs = pl.QT <= 2 ? 512 : 256;
+  const int64_t resident = pl.QT <= 2 ? 512 : 256;
+  int64_t wgs = resident;
   const int64_t cap = total_blocks / (2 * KW);
   if (wgs > cap) wgs = cap;
+  if (uniform && units <= total_blocks) {
+    const int64_t rounds = (units + resident - 1) / resident;
+    if (4 * units >= 3 * rounds * resident) wgs = units;
+  }
   if (g_forced_wgs > 0) wgs = g_forced_wgs;
   if (wgs > total_blocks) wgs = total_blocks;
   if (wgs < 1) wgs = 1;
   return (int)wgs;
+}
+
+int host_owner_of(int64_t x, int64_t T, int W) {
+  int w = (int)((x * W) / T);
+  if (((int64_t)(w + 1) * T) / W <= x) ++w;
+  return w;
 }
 
 size_t slot_bytes(const fspad_attn_desc& d, const Plan& pl) {
@@ -778,7 +810,10 @@ extern "C" size_t fspad_tree_attn_workspace_bytes(const fspad_attn_desc* desc, i
   const int nb = desc->batch < kMaxBatchPerLaunch ? desc->batch : kMaxBatchPerLaunch;
   const int64_t units = (int64_t)nb * desc->n_kv_heads * pl.GY;
   const int64_t total = units * blocks_of(max_kv_len, desc->n_nodes_max);
-  const int64_t slots = units + plan_wgs(pl, total);
+  int64_t wgs = plan_wgs(pl, total, units, true);
+  const int64_t wgs_cut = plan_wgs(pl, total, units, false);  // a ragged batch of the same size
+  if (wgs_cut > wgs) wgs = wgs_cut;
+  const int64_t slots = units + wgs;
   return (size_t)slots * slot_bytes(*desc, pl);
 }
 
@@ -851,18 +886,33 @@ extern "C" fspad_status fspad_tree_attn(const fspad_attn_desc* desc, const void*
       }
       sl.bstart[nb] = total;
       sl.total_blocks = total;
-      sl.n_wgs = plan_wgs(pl, total);
-      const int64_t slots = (int64_t)nb * units_per_seq + sl.n_wgs;
+      bool uniform = true;
+      for (int i = 1; i < nb; ++i)
+        uniform = uniform && blocks_of(sl.kv_len[i], sl.n_nodes[i]) == blocks_of(sl.kv_len[0], sl.n_nodes[0]);
+      const int64_t units = (int64_t)nb * units_per_seq;
+      sl.n_wgs = plan_wgs(pl, total, units, uniform);
+      const int64_t slots = units + sl.n_wgs;
       const size_t need = (size_t)slots * slot_bytes(d, pl);
       if (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 15)) return FSPAD_ERR_WORKSPACE;
       if (d.head_dim == 128) launch_bf16<128>(pl, sl, stream); else launch_bf16<64>(pl, sl, stream);
       if (hipGetLastError() != hipSuccess) return FSPAD_ERR_HIP;
-      const int rows_per_slab = 16 * pl.QT;
-      const int rpb = 256 / (d.head_dim / 4);
-      dim3 cgrid((unsigned)((pl.rows_per_unit + rpb - 1) / rpb), (unsigned)(nb * units_per_seq));
-      if (d.head_dim == 128) hipLaunchKernelGGL(tree_attn_combine_kernel<128>, cgrid, dim3(256), 0, stream, sl, rows_per_slab);
-      else hipLaunchKernelGGL(tree_attn_combine_kernel<64>, cgrid, dim3(256), 0, stream, sl, rows_per_slab);
-      if (hipGetLastError() != hipSuccess) return FSPAD_ERR_HIP;
+      // the merge pass runs only if some unit was cut across workgroups
+      bool any_cut = false;
+      for (int i = 0; i < nb && !any_cut; ++i) {
+        const int64_t nblk = blocks_of(sl.kv_len[i], sl.n_nodes[i]);
+        for (int64_t ub = 0; ub < units_per_seq && !any_cut; ++ub) {
+          const int64_t fs = sl.bstart[i] + ub * nblk;
+          any_cut = host_owner_of(fs, total, sl.n_wgs) != host_owner_of(fs + nblk - 1, total, sl.n_wgs);
+        }
+      }
+      if (any_cut) {
+        const int rows_per_slab = 16 * pl.QT;
+        const int rpb = 256 / (d.head_dim / 4);
+        dim3 cgrid((unsigned)((pl.rows_per_unit + rpb - 1) / rpb), (unsigned)units);
+        if (d.head_dim == 128) hipLaunchKernelGGL(tree_attn_combine_kernel<128>, cgrid, dim3(256), 0, stream, sl, rows_per_slab);
+        else hipLaunchKernelGGL(tree_attn_combine_kernel<64>, cgrid, dim3(256), 0, stream, sl, rows_per_slab);
+        if (hipGetLastError() != hipSuccess) return FSPAD_ERR_HIP;
+      }
     } else {
       dim3 grid((unsigned)d.n_q_heads, (unsigned)((d.n_nodes_max + 3) / 4), (unsigned)nb);
       if (d.head_dim == 128) hipLaunchKernelGGL(tree_attn_f32_kernel<128>, grid, dim3(256), 0, stream, sl);
