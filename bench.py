@@ -40,6 +40,7 @@ def parse_args():
     ap.add_argument("--layers", type=int, default=None, help="profiling only: run fewer layers of a stack (the result line is then not the workload's)")
     ap.add_argument("--nodes", type=int, default=None, help="experiments only: override the tree size")
     ap.add_argument("--heads", type=int, default=None, help="experiments only: override the head count (MHA)")
+    ap.add_argument("--kv-len", type=int, default=None, help="experiments only: override the prefix length")
     ap.add_argument("--seed", type=int, default=2024)
     return ap.parse_args()
 
@@ -71,6 +72,9 @@ def main():
     if args.heads is not None:
         import dataclasses
         cfg = dataclasses.replace(cfg, n_q_heads=args.heads, n_kv_heads=args.heads, name=cfg.name + f"-{args.heads}heads")
+    if args.kv_len is not None:
+        import dataclasses
+        cfg = dataclasses.replace(cfg, kv_len=args.kv_len, name=cfg.name + f"-{args.kv_len}prefix")
     accept = args.accept or cfg.accept
     tdt = torch.float32 if cfg.dtype == "f32" else torch.bfloat16
     B, N, Hq, Hkv, D, L, V = cfg.batch, cfg.n_nodes, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.kv_len, cfg.vocab

@@ -59,15 +59,36 @@ def test_bf16_gqa_and_head_dim(H, Hq, Hkv, D, N):
     _check(H, case, H.TOL["bf16"])
 
 
+@pytest.mark.parametrize("mode", [0, 1])
 @pytest.mark.parametrize("splits", [1, 2, 3, 7, 16, 50, 333, 4096])
-def test_bf16_workgroup_counts(H, splits):
-    """Any number of workgroups cuts the flat block list differently (whole units, units cut in
-    two or many segments, more workgroups than blocks); the result must not depend on it."""
+def test_bf16_workgroup_counts(H, splits, mode):
+    """Any number of workgroups cuts the key blocks differently, in either split mode (whole units,
+    units cut in two or many segments, more workgroups than blocks); the result must not depend
+    on it, nor on which workgroup happens to finish a unit last."""
     case = H.AttnCase(300 + splits, 2, 26, 4, 4, 128, 777, "bf16", kv_len=[777, 40])
-    out, ref, _ = _check(H, case, H.TOL["bf16"], splits=splits)
-    # run-to-run determinism (no floating-point atomics in the merge)
-    again = case.run_gpu(splits=splits)
-    assert torch.equal(out, again)
+    out, ref, _ = _check(H, case, H.TOL["bf16"], splits=splits, mode=mode)
+    # run-to-run determinism (no floating-point atomics, fixed merge order)
+    for _ in range(3):
+        again = case.run_gpu(splits=splits, mode=mode)
+        assert torch.equal(out, again)
+
+
+def test_bf16_shared_workspace_sees_no_stale_partials(H):
+    """Two different problems of one shape alternate on one workspace, launched back to back: a
+    merge that picked up the other problem's leftovers would not reproduce the result obtained
+    on a private workspace."""
+    import paper_2408_15562_amd as fspad
+    cases = [H.AttnCase(340 + i, 1, 26, 8, 8, 128, 1500, "bf16") for i in range(2)]
+    desc = fspad.make_attn_desc(cases[0].q, cases[0].k_tree, cases[0].k_cache, torch.float32, 0.0)
+    shared = torch.empty(fspad.fspad_tree_attn_workspace_bytes(desc, 1500), dtype=torch.uint8, device=H.DEV)
+    private = [c.run_gpu() for c in cases]
+    for i, c in enumerate(cases):
+        assert H.rel_err(private[i], c.run_oracle()) <= H.TOL["bf16"]
+    for rep in range(6):
+        for i, c in enumerate(cases):   # no host synchronisation in between: back-to-back launches
+            out = fspad.fspad_tree_attn(c.q, c.k_tree, c.v_tree, c.k_cache, c.v_cache, c.kv_len, c.n_nodes,
+                                        c.mask_dev, workspace=shared, out_dtype=torch.float32)
+            assert torch.equal(out, private[i]), f"repetition {rep}, problem {i}"
 
 
 def test_bf16_ragged_batch_and_strided_cache(H):
@@ -75,6 +96,9 @@ def test_bf16_ragged_batch_and_strided_cache(H):
                       l_cap=600, interleave=True)
     _check(H, case, H.TOL["bf16"])
     _check(H, case, H.TOL["bf16"], splits=4)
+    _check(H, case, H.TOL["bf16"], splits=40, mode=1)
+    _check(H, case, H.TOL["bf16"], mode=0)
+    _check(H, case, H.TOL["bf16"], mode=1)
 
 
 def test_bf16_output_is_rounded_fp32_output(H):
