@@ -90,24 +90,18 @@ typedef struct {
  *   anc_mask dev [B,Nmax] u64, bit t of word [b,i] set <=> t is i or an ancestor of i
  *   out      dev [B,Nmax,Hq,D] out_dtype; rows i >= n_nodes[b] are written as zeros
  *   workspace dev, at least fspad_tree_attn_workspace_bytes(desc, max_b kv_len[b]) bytes,
- *            16-byte aligned; contents on entry are ignored, undefined on exit (it holds the
- *            partial results of (sequence, kv head) pairs whose keys are split across workgroups).
+ *            16-byte aligned; contents on entry are ignored, undefined on exit.
  *            Two calls that may overlap in time need different workspaces.
  * Accumulation is fp32; bf16 inputs are multiplied on the matrix cores with
  * probabilities rounded to bf16.
  */
 size_t fspad_tree_attn_workspace_bytes(const fspad_attn_desc* desc, int32_t max_kv_len);
 
-/* Tuning knobs, process-wide, not needed for correct results. Both change
- * fspad_tree_attn_workspace_bytes too, so set them before sizing the workspace.
- * fspad_tree_attn_set_workgroups: number of workgroups the bf16 path aims to spread
- *   its key blocks over (1..4096); 0 restores the built-in choice.
- * fspad_tree_attn_set_split_mode: how key blocks are dealt to workgroups. 0: the blocks
- *   of all (sequence, kv head) pairs form one list cut into equal contiguous ranges (a
- *   workgroup may hold the end of one pair and the start of the next); 1: every pair is
- *   cut into equal chunks, one workgroup per chunk; -1 restores the built-in choice. */
+/* Tuning knob, process-wide: force the number of workgroups the bf16 path spreads
+ * its key blocks over (1..4096); 0 restores the built-in choice. It changes
+ * fspad_tree_attn_workspace_bytes too, so set it before sizing the workspace.
+ * Not needed for correct results. */
 void fspad_tree_attn_set_workgroups(int32_t workgroups);
-void fspad_tree_attn_set_split_mode(int32_t mode);
 
 fspad_status fspad_tree_attn(const fspad_attn_desc* desc,
                              const void* q, const void* k_tree, const void* v_tree,

@@ -15,7 +15,6 @@ from .binding import (  # noqa: F401
     fspad_tree_accept_sample,
     fspad_tree_accept_workspace_bytes,
     fspad_tree_attn,
-    fspad_tree_attn_set_split_mode,
     fspad_tree_attn_set_workgroups,
     fspad_tree_attn_workspace_bytes,
     fspad_tree_build_mask,

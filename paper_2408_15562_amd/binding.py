@@ -23,8 +23,7 @@ FSPAD_MAX_NODES = 64
 _STATUS_NAMES = {0: "FSPAD_OK", 1: "FSPAD_ERR_NULL", 2: "FSPAD_ERR_SHAPE", 3: "FSPAD_ERR_TREE",
                  4: "FSPAD_ERR_DTYPE", 5: "FSPAD_ERR_WORKSPACE", 6: "FSPAD_ERR_TEMPERATURE", 7: "FSPAD_ERR_HIP"}
 
-EXPORTS = ("fspad_tree_attn_workspace_bytes", "fspad_tree_attn_set_workgroups", "fspad_tree_attn_set_split_mode",
-           "fspad_tree_attn",
+EXPORTS = ("fspad_tree_attn_workspace_bytes", "fspad_tree_attn_set_workgroups", "fspad_tree_attn",
            "fspad_tree_accept_workspace_bytes", "fspad_tree_accept_greedy", "fspad_tree_accept_sample",
            "fspad_tree_build_mask", "fspad_tree_validate", "fspad_status_string")
 
@@ -62,8 +61,6 @@ def _lib():
         lib.fspad_tree_attn_workspace_bytes.argtypes = [ctypes.POINTER(fspad_attn_desc), i32]
         lib.fspad_tree_attn_set_workgroups.restype = None
         lib.fspad_tree_attn_set_workgroups.argtypes = [i32]
-        lib.fspad_tree_attn_set_split_mode.restype = None
-        lib.fspad_tree_attn_set_split_mode.argtypes = [i32]
         lib.fspad_tree_attn.restype = ctypes.c_int
         lib.fspad_tree_attn.argtypes = [ctypes.POINTER(fspad_attn_desc)] + [vp] * 9 + [vp, sz, vp]
         lib.fspad_tree_accept_workspace_bytes.restype = sz
@@ -150,10 +147,6 @@ def fspad_tree_attn_workspace_bytes(desc: fspad_attn_desc, max_kv_len: int) -> i
 
 def fspad_tree_attn_set_workgroups(splits: int) -> None:
     _lib().fspad_tree_attn_set_workgroups(int(splits))
-
-
-def fspad_tree_attn_set_split_mode(mode: int) -> None:
-    _lib().fspad_tree_attn_set_split_mode(int(mode))
 
 
 def fspad_tree_attn(q: torch.Tensor, k_tree: torch.Tensor, v_tree: torch.Tensor,

@@ -12,14 +12,12 @@
 // 16 bytes per lane (a whole 256-byte row per 16 lanes) and transposed in
 // registers with byte permutes. Wavefronts of a workgroup either split the keys
 // (few rows: MHA) and merge through LDS, or take different row slabs of the same
-// keys (GQA). A second, tiny kernel merges the partials of (sequence, kv head)
-// pairs whose keys were cut across workgroups (fixed order, no atomics).
+// keys (GQA). A second, tiny kernel merges the split-KV partials.
 //
 // fp32 path: plain VALU kernel, one wavefront per query row, used for the small
 // fp32 parity configuration.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
-
 
 #include "fspad.h"
 
@@ -35,18 +33,6 @@ constexpr int kBlockKeys = 32;          // keys per streamed block
 constexpr float kNegBig = -1.0e30f;     // finite stand-in for "no key seen yet"
 constexpr float kLog2e = 1.4426950408889634f;
 
-// What the kernels need to know about one sequence of the launch: one 16-byte record, fetched
-// with a single scalar load.
-struct SeqInfo {
-  int32_t kv_len;    // prefix length
-  int32_t bstart;    // first flat block of the sequence
-  int32_t wg0;       // aligned mode: first partial slot (= first workgroup) of the sequence
-  uint16_t cpu;      // aligned mode: chunks (workgroups) per unit
-  uint8_t n_nodes;   // tree size
-  uint8_t pad;
-};
-
-// Kernel arguments: a compact header, then the per-sequence records.
 struct AttnParams {
   const void* q;
   const void* k_tree;
@@ -61,37 +47,14 @@ struct AttnParams {
   int32_t WS;       // row slabs per workgroup: 1, 2 or 4 (4/WS wavefronts share a slab and split its keys)
   int32_t NS;       // row slabs per kv head
   int32_t GY;       // slab groups per kv head: a (sequence, kv head, slab group) is one unit of work
-  int32_t mode;     // kFlat or kAligned (how blocks are dealt to workgroups)
-  int32_t n_wgs;    // flat mode: workgroups of the launch
-  int32_t flat_q, flat_rem;  // flat mode: total_blocks = n_wgs * flat_q + flat_rem; the first flat_rem workgroups take flat_q + 1 blocks
-  int32_t total_blocks;      // 32-key blocks summed over all units
+  int32_t n_wgs;    // workgroups of the flat decomposition
+  int64_t total_blocks;  // 32-key blocks summed over all units
   int32_t out_bf16;
   float scale;      // softmax scale
-  int32_t pad;
-  SeqInfo seq[kMaxBatchPerLaunch + 1];  // seq[B].bstart = total_blocks
+  int32_t kv_len[kMaxBatchPerLaunch];
+  int64_t bstart[kMaxBatchPerLaunch + 1];  // first flat block of each sequence; bstart[B] = total_blocks
+  uint8_t n_nodes[kMaxBatchPerLaunch];
 };
-
-// How the 32-key blocks of all units are dealt to workgroups.
-//   kFlat:    the units' blocks form one flat list cut into W contiguous ranges of equal length
-//             (the first T mod W one block longer): equal bytes per workgroup whatever the head
-//             count, but a workgroup may hold the tail of one unit and the head of the next (two
-//             segments, one after the other). Grid (W, 1).
-//   kAligned: every unit of sequence b is cut into cpu[b] chunks of (nearly) equal length, one
-//             workgroup per chunk: a workgroup holds exactly one segment, which matters when the
-//             whole call is only a few memory round trips long. Grid (max_b units*cpu[b], B): the
-//             sequence is blockIdx.y, so everything a workgroup needs arrives with its first
-//             round of scalar loads.
-enum { kFlat = 0, kAligned = 1 };
-
-#ifdef FSPAD_TIMELINE
-// Debug build only: per-wavefront cycle stamps of the first segment of every workgroup.
-__device__ unsigned long long* g_timeline;
-#define FSPAD_STAMP(e) do { if (tl_on && lane == 0) g_timeline[((blockIdx.y * gridDim.x + blockIdx.x) * 4 + wave) * 16 + (e)] = ((e) == 6 || (e) == 7 ? __builtin_amdgcn_s_memrealtime() : __builtin_amdgcn_s_memtime()); } while (0)
-#define FSPAD_STAMP_IN(st, e) do { if ((st).tl_first && (threadIdx.x & 63) == 0) g_timeline[((blockIdx.y * gridDim.x + blockIdx.x) * 4 + (threadIdx.x >> 6)) * 16 + (e)] = __builtin_amdgcn_s_memtime(); } while (0)
-#else
-#define FSPAD_STAMP(e) do { } while (0)
-#define FSPAD_STAMP_IN(st, e) do { } while (0)
-#endif
 
 __device__ __forceinline__ float wave_xor_max_16_32(float v) {
   v = fmaxf(v, __shfl_xor(v, 16));
@@ -178,9 +141,6 @@ struct RowState {
   f32x4 o[QT][DT];   // O^T accumulators: lane (col,g4), reg i <-> row 16t+col, dim DT*(4*g4+i)+e
   float m[QT];       // softmax shift in use (log2 units, scaled): within kLazyLog2 of the running max
   f32x4 l[QT];       // running sum of the weights, formed on the matrix cores (all 4 entries equal)
-#ifdef FSPAD_TIMELINE
-  bool tl_first;
-#endif
 };
 
 // The shift of a row only moves when a score exceeds it by more than this (log2 units): weights
@@ -230,7 +190,6 @@ __device__ __forceinline__ void process_block(RowState<QT, D>& st, const bf16x8 
       s[tt][1] = acc1;
     }
     if (t0 + TP >= QT) after_scores();
-    if (t0 == 0) FSPAD_STAMP_IN(st, 8);
     if (!FULL && src.kind != 0) {
 #pragma unroll
       for (int tt = 0; tt < TP; ++tt) {
@@ -277,7 +236,6 @@ __device__ __forceinline__ void process_block(RowState<QT, D>& st, const bf16x8 
 #pragma unroll
       for (int j = 0; j < 8; ++j) pf[tt][j] = (__bf16)__builtin_amdgcn_exp2f(fmaf(s[tt][j >> 2][j & 3], c, -m));
     }
-    if (t0 == 0) FSPAD_STAMP_IN(st, 9);
     auto transposed = [&](int e) {  // A operand of d-tile e from the lane's 8 x DT slice of V
       const unsigned sel = (e & 1) ? 0x07060302u : 0x05040100u;
       u32x4 w;
@@ -305,23 +263,15 @@ __device__ __forceinline__ void process_block(RowState<QT, D>& st, const bf16x8 
         st.o[t0 + tt][e] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, pf[tt], st.o[t0 + tt][e], 0, 0, 0);
       }
     }
-    if (t0 == 0) FSPAD_STAMP_IN(st, 10);
   }
-#ifdef FSPAD_TIMELINE
-  st.tl_first = false;
-#endif
 }
 
-// Flat split: first block of workgroup w, and the workgroup that owns flat block x.
-__device__ __forceinline__ int flat_first(const AttnParams& p, int w) { return w * p.flat_q + min(w, p.flat_rem); }
-__device__ __forceinline__ int flat_owner(const AttnParams& p, int x) {
-  const int head = p.flat_rem * (p.flat_q + 1);  // blocks held by the longer ranges
-  return x < head ? x / (p.flat_q + 1) : p.flat_rem + (x - head) / p.flat_q;
-}
-
-// One workgroup works on one or a few *segments* (a run of blocks of one unit = (sequence, kv head,
-// slab group)). A segment that is a whole unit is written to `out` directly; otherwise its
-// un-normalised (O, shift, sum) goes to a partial slot and the merge kernel finishes the unit.
+// The (sequence, kv head, slab group) units and their 32-key blocks form one flat list of
+// blocks; workgroup w owns the contiguous range [w*T/W, (w+1)*T/W) of it, so every workgroup
+// streams the same number of bytes whatever the head count. A workgroup therefore works on one
+// or a few *segments* (a run of blocks of one unit). A segment that is a whole unit is written
+// to `out` directly; otherwise its un-normalised (O, max, sum) goes to partial slot unit+w and the
+// merge kernel finishes the unit.
 template <int QT, int D>
 __global__ __launch_bounds__(256, (QT <= 2 ? 2 : 1)) void tree_attn_bf16_kernel(const AttnParams p) {
   constexpr int KS = D / 32;
@@ -330,7 +280,7 @@ __global__ __launch_bounds__(256, (QT <= 2 ? 2 : 1)) void tree_attn_bf16_kernel(
   // merge buffers: 3 wavefronts x (QT*DT accumulators + QT stats) x 64 lanes. With large row tiles
   // the Q fragments of the 4 wavefronts live in lane-private LDS slots instead of registers; they are
   // dead once a segment's stream is done, so they share the space of the merge buffers.
-  constexpr bool kQInLds = QT >= 2;
+  constexpr bool kQInLds = QT >= 3;
   // Tiles done in several passes run one wavefront per SIMD: they hide the memory latency by
   // themselves, keeping K and V of the next block in flight for a whole block
   constexpr bool kDeep = QT >= 3;
@@ -341,68 +291,33 @@ __global__ __launch_bounds__(256, (QT <= 2 ? 2 : 1)) void tree_attn_bf16_kernel(
   typedef f32x4 (*MergeO)[QT * DT][64];
   MergeO merge_o = reinterpret_cast<MergeO>(lds_raw);
 
-  // Touch every cache line of the argument block that this workgroup reads, in one round of scalar
-  // loads: fetched one by one as the code reaches them, each cold line costs a memory round trip.
-  asm volatile("" ::"s"(p.q), "s"(p.part), "s"(p.stride_token), "s"(p.B), "s"(p.scale), "s"(p.seq[blockIdx.y].kv_len),
-               "s"(p.seq[blockIdx.y].wg0));
-
   // the wavefront index is the same in all 64 lanes: telling the compiler keeps everything that
   // derives from it (key split, block counters, base addresses) in scalar registers
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int col = lane & 15, g4 = lane >> 4;
-#ifdef FSPAD_TIMELINE
-  bool tl_on = g_timeline != nullptr;
-#endif
-  FSPAD_STAMP(0);
-  FSPAD_STAMP(7);
-  bf16x8* q_lds_wave = reinterpret_cast<bf16x8*>(lds_raw) + wave * (QT * KS * 64);
-  bf16x8* q_lds = q_lds_wave + lane;
+  bf16x8* q_lds = reinterpret_cast<bf16x8*>(lds_raw) + wave * (QT * KS * 64) + lane;
   const int slab_local = wave & (p.WS - 1);
   const int KW = 4 / p.WS;  // wavefronts that split the keys of one slab
   const int kp = wave / p.WS;
   const float c = p.scale * kLog2e;
   const int64_t tree_stride = (int64_t)p.Hkv * D;
   const int rows_per_unit = p.WS * ROWS;
-  const int units_per_seq = p.Hkv * p.GY;
 
-  // the workgroup's range [r0, r1) of the flat block list, and the sequence it starts in
   const int w = blockIdx.x;
-  int b = blockIdx.y;   // aligned mode: the sequence; flat mode: grid.y is 1
-  SeqInfo si = p.seq[b];
-  int r0, r1;
-  if (p.mode == kAligned) {
-    const int nb = (si.kv_len + kBlockKeys - 1) / kBlockKeys + (si.n_nodes + kBlockKeys - 1) / kBlockKeys;
-    const int chunks = si.cpu;
-    if (w >= units_per_seq * chunks) return;   // a shorter sequence of a ragged batch has fewer workgroups
-    const int ub = w / chunks, ch = w - ub * chunks;
-    const int base = si.bstart + ub * nb;
-    r0 = base + (ch * nb) / chunks;
-    r1 = base + ((ch + 1) * nb) / chunks;
-  } else {
-    r0 = flat_first(p, w);
-    r1 = flat_first(p, w + 1);
-    if (p.B > 1) {  // last sequence whose first block is <= r0
-      int lo = 0, hi = p.B - 1;
-      while (lo < hi) {
-        const int mid = (lo + hi + 1) >> 1;
-        if (p.seq[mid].bstart <= r0) lo = mid; else hi = mid - 1;
-      }
-      b = lo;
-      si = p.seq[b];
-    }
-  }
+  const int64_t r0 = ((int64_t)w * p.total_blocks) / p.n_wgs, r1 = ((int64_t)(w + 1) * p.total_blocks) / p.n_wgs;
+  int b = 0;
+  while (b + 1 < p.B && r0 >= p.bstart[b + 1]) ++b;
 
-  for (int r = r0; r < r1;) {
-    const int n = si.n_nodes;
-    const int L = si.kv_len;
-    const int seq_first = si.bstart;
+  for (int64_t r = r0; r < r1;) {
+    const int n = p.n_nodes[b];
+    const int L = p.kv_len[b];
     const int n_prefix_blocks = (L + kBlockKeys - 1) / kBlockKeys;
     const int n_blocks = n_prefix_blocks + (n + kBlockKeys - 1) / kBlockKeys;
-    const int ub = (r - seq_first) / n_blocks;          // unit within the sequence: (g, y)
-    const int seg_begin = (r - seq_first) - ub * n_blocks;
-    const int seg_count = min(n_blocks - seg_begin, r1 - r);
+    const int ub = (int)((r - p.bstart[b]) / n_blocks);          // unit within the sequence: (g, y)
+    const int seg_begin = (int)((r - p.bstart[b]) - (int64_t)ub * n_blocks);
+    const int seg_count = (int)min((int64_t)(n_blocks - seg_begin), r1 - r);
     const int g = ub / p.GY, y = ub - g * p.GY;
-    const int unit = b * units_per_seq + ub;
+    const int unit = b * p.Hkv * p.GY + ub;
     const bool whole_unit = seg_count == n_blocks;
     const int slab = y * p.WS + slab_local;
     const bool slab_live = slab < p.NS;
@@ -419,46 +334,30 @@ __global__ __launch_bounds__(256, (QT <= 2 ? 2 : 1)) void tree_attn_bf16_kernel(
       ri.out = ((int64_t)b * p.Nmax + ri.node) * p.Hq + g * p.G + hl;  // index of (b, node, h)
       return ri;
     };
-    // Ancestor words, requested up front and without conditions: lane i holds the word of node i,
-    // and a row's word is fetched from the lane of its node when a tree block is reached (a load
-    // waiting in the path of the tree blocks would cost a whole memory round trip).
-    const uint64_t node_word = p.anc_mask[b * p.Nmax + min(lane, p.Nmax - 1)];
-    const uint64_t live_bits = (n >= 64) ? ~0ull : ((1ull << n) - 1ull);
-    // Q rows, from a clamped (always valid) address: a row that does not exist computes with the
-    // first row's values, which is harmless because its results are never stored. Small tiles keep
-    // the fragments in registers; larger ones have them written straight into the wavefront's
-    // lane-private LDS slots by the load itself (16 bytes per lane, lane i at slot base + 16 i), so
-    // they never occupy registers. The first K and V blocks are requested right behind them.
+    auto mask_of_tile = [&](int t) -> uint64_t {
+      const RowInfo ri = row_info(t);
+      const uint64_t live_bits = (n >= 64) ? ~0ull : ((1ull << n) - 1ull);
+      return ri.valid ? (p.anc_mask[b * p.Nmax + ri.node] & live_bits) : 0ull;
+    };
     bf16x8 qf[kQInLds ? 1 : QT][KS];
 #pragma unroll
     for (int t = 0; t < QT; ++t) {
       const RowInfo ri = row_info(t);
-      const int64_t safe_row = ri.valid ? ri.out : ((int64_t)b * p.Nmax) * p.Hq + g * p.G;
-      const __bf16* qrow = reinterpret_cast<const __bf16*>(p.q) + safe_row * D + 8 * g4;
+      const __bf16* qrow = reinterpret_cast<const __bf16*>(p.q) + ri.out * D + 8 * g4;
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) {
-        if constexpr (kQInLds) {
-          __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(qrow + 32 * ks),
-                                           (__attribute__((address_space(3))) void*)(q_lds_wave + (t * KS + ks) * 64), 16, 0, 0);
-        } else {
-          qf[t][ks] = *reinterpret_cast<const bf16x8*>(qrow + 32 * ks);
-        }
+        bf16x8 zero;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) zero[j] = (__bf16)0.f;
+        const bf16x8 frag = ri.valid ? *reinterpret_cast<const bf16x8*>(qrow + 32 * ks) : zero;
+        if constexpr (kQInLds) q_lds[(t * KS + ks) * 64] = frag; else qf[t][ks] = frag;
       }
     }
-    auto mask_of_tile = [&](int t) -> uint64_t {
-      const RowInfo ri = row_info(t);
-      const int src_lane = ri.valid ? ri.node : 0;
-      const unsigned lo = __shfl((unsigned)node_word, src_lane), hi = __shfl((unsigned)(node_word >> 32), src_lane);
-      return ri.valid ? ((((uint64_t)hi << 32) | lo) & live_bits) : 0ull;
-    };
     auto q_frag = [&](int t, int ks) -> bf16x8 {
       if constexpr (kQInLds) return q_lds[(t * KS + ks) * 64]; else return qf[t][ks];
     };
 
     RowState<QT, D> st;
-#ifdef FSPAD_TIMELINE
-    st.tl_first = tl_on;
-#endif
 #pragma unroll
     for (int t = 0; t < QT; ++t) {
       st.m[t] = kNegBig;
@@ -500,30 +399,21 @@ __global__ __launch_bounds__(256, (QT <= 2 ? 2 : 1)) void tree_attn_bf16_kernel(
       return src;
     };
 
-    // The stream. K and V of the first block are requested together with Q. Small tiles (two
-    // wavefronts per SIMD): K of the next block is requested right after this block's scores, V of
-    // the next block as soon as this block's has been consumed; one K and one V block in registers.
+    // The stream. Small tiles (two wavefronts per SIMD): V of the current block is requested before
+    // its scores are formed, K of the next block right after them; one K and one V block in registers.
     // Large tiles (one wavefront per SIMD): K of the next block is requested at the top of this one
     // into a second buffer, V of the next block as soon as this block's V has been transposed, into
     // the registers that frees. Full prefix blocks (all but the last three of a sequence) take a
     // branch-free path with scalar bases; the ragged tail and the tree blocks take the general one.
-    const bool active = slab_live && blk_begin < blk_end;
-    // large row tiles run one wavefront per SIMD and have the registers to hold the next block's K
-    // while this block's is in use (requested a whole block ahead); small tiles reuse one buffer
-    bf16x8 kf[2][KS], kfn[kDeep ? 2 : 1][KS];
-    unsigned vr[8][D / 32];
-    BlockSrc cur{};
-    if (active) {
-      cur = locate(blk_begin);
+    if (slab_live && blk_begin < blk_end) {
+      // large row tiles run one wavefront per SIMD and have the registers to hold the next block's K
+      // while this block's is in use (requested a whole block ahead); small tiles reuse one buffer
+      bf16x8 kf[2][KS], kfn[kDeep ? 2 : 1][KS];
+      unsigned vr[8][D / 32];
+      BlockSrc cur = locate(blk_begin);
       load_k<D>(kf, cur, col, g4);
-      load_v<D>(vr, cur, col, g4);
-    }
-    // the loads that fill the Q slots are not tracked by the compiler: wait for them by hand (the
-    // first K and V blocks, requested after them, are needed at the same moment anyway)
-    if constexpr (kQInLds) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    if (active) {
+      if constexpr (kDeep) load_v<D>(vr, cur, col, g4);
       int blk = blk_begin;
-      FSPAD_STAMP(1);
       const int full_end = min(blk_end, L / kBlockKeys);  // blocks below this index are full prefix blocks
       if (blk + KW < full_end) {
         unsigned koff[2], voff[8];
@@ -549,15 +439,12 @@ __global__ __launch_bounds__(256, (QT <= 2 ? 2 : 1)) void tree_attn_bf16_kernel(
 #pragma unroll
               for (int ks = 0; ks < KS; ++ks) kf[kt][ks] = kfn[kt][ks];
           } else {
+            load_v_full<D>(vr, vb, voff);
             kb += block_bytes * KW;
             vb += block_bytes * KW;
             process_block<QT, D, true>(st, kf, vr, q_frag, full, mask_of_tile, c, g4,
                                        [&] { load_k_full<D>(kf, kb, koff); }, [] {});
-            load_v_full<D>(vr, vb, voff);
           }
-#ifdef FSPAD_TIMELINE
-          if (blk == blk_begin) FSPAD_STAMP(2);
-#endif
         }
         cur = locate(blk);
       }
@@ -577,14 +464,13 @@ __global__ __launch_bounds__(256, (QT <= 2 ? 2 : 1)) void tree_attn_bf16_kernel(
               for (int ks = 0; ks < KS; ++ks) kf[kt][ks] = kfn[kt][ks];
           }
         } else {
+          load_v<D>(vr, cur, col, g4);
           process_block<QT, D, false>(st, kf, vr, q_frag, cur, mask_of_tile, c, g4,
                                      [&] { if (more) load_k<D>(kf, nxt, col, g4); }, [] {});
-          if (more) load_v<D>(vr, nxt, col, g4);
         }
         cur = nxt;
       }
     }
-    FSPAD_STAMP(3);
     float lsum[QT];  // the matrix-core row sums already cover every key of the wavefront's blocks
 #pragma unroll
     for (int t = 0; t < QT; ++t) lsum[t] = st.l[t][0];
@@ -618,11 +504,6 @@ __global__ __launch_bounds__(256, (QT <= 2 ? 2 : 1)) void tree_attn_bf16_kernel(
         }
       }
     }
-    FSPAD_STAMP(4);
-
-    // partial slot of (unit, workgroup): the workgroup index when every workgroup holds one chunk,
-    // unit + workgroup under the flat split (no two pairs share one)
-    const int my_slot = p.mode == kAligned ? si.wg0 + w : unit + w;
 
     // write: final rows when the segment is the whole unit, a partial slot otherwise
     if (kp == 0) {
@@ -657,7 +538,7 @@ __global__ __launch_bounds__(256, (QT <= 2 ? 2 : 1)) void tree_attn_bf16_kernel(
             }
           }
         } else if (ri.valid) {
-          float* slot = p.part + (int64_t)my_slot * rows_per_unit * (D + 2);
+          float* slot = p.part + (int64_t)(unit + w) * rows_per_unit * (D + 2);
           const int lr = slab_local * ROWS + 16 * t + col;
           if (g4 == 0) *reinterpret_cast<float2*>(slot + (int64_t)rows_per_unit * D + 2 * lr) = make_float2(st.m[t], lsum[t]);
 #pragma unroll
@@ -670,21 +551,22 @@ __global__ __launch_bounds__(256, (QT <= 2 ? 2 : 1)) void tree_attn_bf16_kernel(
         }
       }
     }
-    FSPAD_STAMP(5);
-
-#ifdef FSPAD_TIMELINE
-    FSPAD_STAMP(6);
-    tl_on = false;
-#endif
     r += seg_count;
-    if (r < r1 && r >= p.seq[b + 1].bstart) si = p.seq[++b];   // flat mode: the range runs into the next sequence
+    if (b + 1 < p.B && r >= p.bstart[b + 1]) ++b;
     if ((KW > 1 || kQInLds) && r < r1) __syncthreads();  // the LDS buffers are reused by the next segment
   }
 }
 
+// Workgroup that owns flat block x under the even split of T blocks over W workgroups.
+__device__ __forceinline__ int owner_of(int64_t x, int64_t T, int W) {
+  int w = (int)((x * W) / T);
+  if (((int64_t)(w + 1) * T) / W <= x) ++w;
+  return w;
+}
+
 // Finishes every unit that was cut into several segments:
-//   out = sum_s 2^(m_s - M) O_s / sum_s 2^(m_s - M) l_s   over the unit's partial slots, in slot order.
-// One thread per 4 output dims of a row; rows of nodes past n_nodes are written as zeros.
+// out = sum_s 2^(m_s - M) O_s / sum_s 2^(m_s - M) l_s over the unit's partial slots.
+// One thread per 4 output dims; rows of nodes past n_nodes are written as zeros.
 template <int D>
 __global__ __launch_bounds__(256) void tree_attn_combine_kernel(const AttnParams p, int rows_per_slab) {
   constexpr int TPR = D / 4;  // threads per row
@@ -692,19 +574,10 @@ __global__ __launch_bounds__(256) void tree_attn_combine_kernel(const AttnParams
   const int units_per_seq = p.Hkv * p.GY;
   const int b = unit / units_per_seq, ub = unit - b * units_per_seq;
   const int g = ub / p.GY, y = ub - g * p.GY;
-  int first_slot, n_seg;
-  const SeqInfo si = p.seq[b];
-  if (p.mode == kAligned) {
-    n_seg = si.cpu;
-    first_slot = si.wg0 + ub * n_seg;
-  } else {
-    const int n_blocks = (p.seq[b + 1].bstart - si.bstart) / units_per_seq;
-    const int fs = si.bstart + ub * n_blocks;
-    const int w0 = flat_owner(p, fs), w1 = flat_owner(p, fs + n_blocks - 1);
-    n_seg = w1 - w0 + 1;
-    first_slot = unit + w0;
-  }
-  if (n_seg == 1) return;  // written directly by the one workgroup that held the whole unit
+  const int n_blocks = (int)((p.bstart[b + 1] - p.bstart[b]) / units_per_seq);
+  const int64_t fs = p.bstart[b] + (int64_t)ub * n_blocks;
+  const int w0 = owner_of(fs, p.total_blocks, p.n_wgs), w1 = owner_of(fs + n_blocks - 1, p.total_blocks, p.n_wgs);
+  if (w0 == w1) return;  // written directly by the one workgroup that held the whole unit
   const int rows_per_unit = p.WS * rows_per_slab;
   const int lr = blockIdx.x * (256 / TPR) + threadIdx.x / TPR;
   if (lr >= rows_per_unit) return;
@@ -715,12 +588,13 @@ __global__ __launch_bounds__(256) void tree_attn_combine_kernel(const AttnParams
   const int node = rr / p.G, hl = rr - node * p.G;
   const int64_t row = ((int64_t)b * p.Nmax + node) * p.Hq + g * p.G + hl;
   f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-  if (node < si.n_nodes) {
+  if (node < p.n_nodes[b]) {
     const int64_t slot_floats = (int64_t)rows_per_unit * (D + 2);
-    const float* o_base = p.part + (int64_t)first_slot * slot_floats + (int64_t)lr * D + d0;
-    const float* ml_base = p.part + (int64_t)first_slot * slot_floats + (int64_t)rows_per_unit * D + 2 * lr;
+    const float* o_base = p.part + (int64_t)(unit + w0) * slot_floats + (int64_t)lr * D + d0;
+    const float* ml_base = p.part + (int64_t)(unit + w0) * slot_floats + (int64_t)rows_per_unit * D + 2 * lr;
     // slots in index order (deterministic), eight at a time so that their loads are in flight together
     float M = kNegBig, denom = 0.f;
+    const int n_seg = w1 - w0 + 1;
     for (int s0 = 0; s0 < n_seg; s0 += 8) {
       float2 ml[8];
       f32x4 o[8];
@@ -768,7 +642,7 @@ __global__ __launch_bounds__(256) void tree_attn_f32_kernel(const AttnParams p) 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int h = blockIdx.x, b = blockIdx.z;
   const int g = h / p.G;
-  const int n = p.seq[b].n_nodes, L = p.seq[b].kv_len;
+  const int n = p.n_nodes[b], L = p.kv_len[b];
   const float* kc = reinterpret_cast<const float*>(p.k_cache) + b * p.stride_batch + g * p.stride_head;
   const float* vc = reinterpret_cast<const float*>(p.v_cache) + b * p.stride_batch + g * p.stride_head;
   const int64_t tree_stride = (int64_t)p.Hkv * D;
@@ -840,10 +714,11 @@ __global__ __launch_bounds__(256) void tree_attn_f32_kernel(const AttnParams p) 
 struct Plan {
   int QT, NS, WS, GY;
   int rows_per_unit;
+  int n_wgs;           // workgroups for the largest slice of sequences
+  int64_t total_blocks;
 };
 
 int g_forced_wgs = 0;
-int g_forced_mode = -1;
 int g_max_qt = 4;
 
 // Row tiling of one kv head's N*G query rows: slabs of 16*QT rows, WS slabs per workgroup.
@@ -865,97 +740,31 @@ int blocks_of(int kv_len, int n_nodes) {
   return (kv_len + kBlockKeys - 1) / kBlockKeys + (n_nodes + kBlockKeys - 1) / kBlockKeys;
 }
 
-// Resident workgroup slots of the chip for a tile size: 256 compute units, two workgroups each
-// when the register budget allows it.
-int resident_slots(const Plan& pl) { return pl.QT <= 2 ? 512 : 256; }
-
-// The split of one slice of sequences over workgroups.
-struct Split {
-  int mode, n_wgs, grid_x;
-  int64_t total_blocks, units, slots;
-  bool any_cut;
-};
-
-// Decides mode, workgroup count and (aligned mode) chunks per unit; fills the tables of `sl`.
-//  * enough equally long units to fill the chip by themselves: one workgroup per unit, nothing cut;
-//  * few units (a single sequence, few kv heads): every unit cut into equal chunks, one workgroup
-//    per chunk, about one chunk per resident slot but no chunk shorter than one block per
-//    key-splitting wavefront (two when that still fills the chip);
-//  * otherwise the flat split, which balances bytes for any head count and any mix of lengths.
-Split plan_split(const Plan& pl, int nb, const int32_t* kv_len, const int32_t* n_nodes, int units_per_seq,
-                 AttnParams* sl) {
+// Workgroup count for `total_blocks` flat blocks in `units` units: two resident workgroups per
+// compute unit when the register budget allows it (one otherwise), but no workgroup with fewer
+// than 2 blocks per key-splitting wave. When all units are equally long and fill at least three
+// quarters of the resident slots by themselves, one workgroup per unit: nothing is cut, nothing
+// is merged, and that beats the better balance of a cut.
+int plan_wgs(const Plan& pl, int64_t total_blocks, int64_t units, bool uniform) {
   const int KW = 4 / pl.WS;
-  Split sp{};
-  int64_t total = 0;
-  bool uniform = true;
-  int min_blocks = 1 << 30;
-  for (int i = 0; i < nb; ++i) {
-    const int blocks = blocks_of(kv_len[i], n_nodes[i]);
-    if (sl) sl->seq[i].bstart = (int32_t)total;
-    total += (int64_t)units_per_seq * blocks;
-    uniform = uniform && blocks == blocks_of(kv_len[0], n_nodes[0]);
-    if (blocks < min_blocks) min_blocks = blocks;
+  const int64_t resident = pl.QT <= 2 ? 512 : 256;
+  int64_t wgs = resident;
+  const int64_t cap = total_blocks / (2 * KW);
+  if (wgs > cap) wgs = cap;
+  if (uniform && units <= total_blocks) {
+    const int64_t rounds = (units + resident - 1) / resident;
+    if (4 * units >= 3 * rounds * resident) wgs = units;
   }
-  if (sl) { sl->seq[nb].bstart = (int32_t)total; sl->total_blocks = (int32_t)total; }
-  sp.total_blocks = total;
-  sp.units = (int64_t)nb * units_per_seq;
-  const int64_t resident = resident_slots(pl);
-  const int64_t target = g_forced_wgs > 0 ? g_forced_wgs : resident;
+  if (g_forced_wgs > 0) wgs = g_forced_wgs;
+  if (wgs > total_blocks) wgs = total_blocks;
+  if (wgs < 1) wgs = 1;
+  return (int)wgs;
+}
 
-  int mode;
-  const int64_t rounds = (sp.units + resident - 1) / resident;
-  const bool fills = uniform && 4 * sp.units >= 3 * rounds * resident;
-  if (g_forced_mode >= 0) mode = g_forced_mode;
-  else if (g_forced_wgs > 0) mode = kFlat;
-  else if (fills) mode = kAligned;
-  else if (2 * sp.units <= target) mode = kAligned;
-  else mode = kFlat;
-
-  if (mode == kAligned) {
-    int64_t wgs = 0;
-    for (int i = 0; i < nb; ++i) {
-      const int blocks = blocks_of(kv_len[i], n_nodes[i]);
-      int64_t chunks = 1;
-      if (!(fills && g_forced_wgs == 0 && g_forced_mode < 0)) {
-        chunks = (target * blocks) / total;             // this sequence's share of the slots, per unit
-        const int64_t longest = blocks / KW;            // at least one block per key-splitting wavefront
-        if (chunks > longest) chunks = longest;
-        if (chunks > 4096) chunks = 4096;
-        if (chunks < 1) chunks = 1;
-      }
-      if (sl) { sl->seq[i].wg0 = (int32_t)wgs; sl->seq[i].cpu = (uint16_t)chunks; }
-      if (chunks > 1) sp.any_cut = true;
-      if (chunks * units_per_seq > sp.grid_x) sp.grid_x = (int)(chunks * units_per_seq);
-      wgs += chunks * units_per_seq;
-    }
-    sp.n_wgs = (int)wgs;
-    sp.slots = wgs;
-  } else {
-    int64_t wgs = target;
-    if (g_forced_wgs == 0) {  // no workgroup with fewer than 2 blocks per key-splitting wavefront
-      const int64_t cap = total / (2 * KW);
-      if (wgs > cap) wgs = cap;
-    }
-    if (wgs > total) wgs = total;
-    if (wgs < 1) wgs = 1;
-    sp.n_wgs = (int)wgs;
-    sp.grid_x = (int)wgs;
-    if (sl) { sl->n_wgs = (int)wgs; sl->flat_q = (int32_t)(total / wgs); sl->flat_rem = (int32_t)(total % wgs); }
-    sp.slots = sp.units + wgs;
-    // some unit is cut unless every unit boundary is a workgroup boundary
-    const int64_t fq = total / wgs, frem = total % wgs;
-    auto first_of = [&](int64_t w) { return w * fq + (w < frem ? w : frem); };
-    int64_t fs = 0, w = 0;
-    for (int i = 0; i < nb && !sp.any_cut; ++i) {
-      const int64_t blocks = blocks_of(kv_len[i], n_nodes[i]);
-      for (int u = 0; u < units_per_seq && !sp.any_cut; ++u, fs += blocks) {
-        while (first_of(w + 1) <= fs) ++w;           // workgroup that owns block fs
-        sp.any_cut = first_of(w + 1) < fs + blocks;  // ... does not reach the unit's end
-      }
-    }
-  }
-  sp.mode = mode;
-  return sp;
+int host_owner_of(int64_t x, int64_t T, int W) {
+  int w = (int)((x * W) / T);
+  if (((int64_t)(w + 1) * T) / W <= x) ++w;
+  return w;
 }
 
 size_t slot_bytes(const fspad_attn_desc& d, const Plan& pl) {
@@ -974,7 +783,8 @@ fspad_status check_desc(const fspad_attn_desc* d) {
 }
 
 template <int D>
-void launch_bf16(const Plan& pl, const AttnParams& prm, dim3 grid, hipStream_t stream) {
+void launch_bf16(const Plan& pl, const AttnParams& prm, hipStream_t stream) {
+  const dim3 grid((unsigned)prm.n_wgs);
   switch (pl.QT) {
     case 1: hipLaunchKernelGGL((tree_attn_bf16_kernel<1, D>), grid, dim3(256), 0, stream, prm); break;
     case 2: hipLaunchKernelGGL((tree_attn_bf16_kernel<2, D>), grid, dim3(256), 0, stream, prm); break;
@@ -986,10 +796,6 @@ void launch_bf16(const Plan& pl, const AttnParams& prm, dim3 grid, hipStream_t s
 }  // namespace
 
 extern "C" void fspad_debug_set_max_qt(int32_t qt) { g_max_qt = qt < 1 ? 1 : (qt > 4 ? 4 : qt); }
-extern "C" void fspad_tree_attn_set_split_mode(int32_t mode) { g_forced_mode = mode < 0 ? -1 : (mode ? kAligned : kFlat); }
-#ifdef FSPAD_TIMELINE
-extern "C" void fspad_debug_set_timeline(void* dev_buffer) { (void)hipMemcpyToSymbol(HIP_SYMBOL(g_timeline), &dev_buffer, sizeof(dev_buffer)); }
-#endif
 
 extern "C" void fspad_tree_attn_set_workgroups(int32_t workgroups) {
   g_forced_wgs = workgroups > 0 ? (workgroups > 4096 ? 4096 : workgroups) : 0;
@@ -1000,16 +806,14 @@ extern "C" size_t fspad_tree_attn_workspace_bytes(const fspad_attn_desc* desc, i
   if (desc->io_dtype == FSPAD_F32) return 16;
   Plan pl{};
   plan_rows(*desc, pl);
-  // the largest slice of sequences, all at the maximum length; a ragged batch of the same size may
-  // take the flat split instead, which needs one slot per (unit, workgroup) boundary
+  // one partial slot per (unit, workgroup) boundary at most: units + workgroups of the largest slice
   const int nb = desc->batch < kMaxBatchPerLaunch ? desc->batch : kMaxBatchPerLaunch;
-  const int units_per_seq = desc->n_kv_heads * pl.GY;
-  int32_t lens[kMaxBatchPerLaunch], nodes[kMaxBatchPerLaunch];
-  for (int i = 0; i < nb; ++i) { lens[i] = max_kv_len; nodes[i] = desc->n_nodes_max; }
-  const Split sp = plan_split(pl, nb, lens, nodes, units_per_seq, nullptr);
-  const int64_t target = g_forced_wgs > 0 ? g_forced_wgs : resident_slots(pl);
-  int64_t slots = sp.slots;
-  if (slots < sp.units + target) slots = sp.units + target;
+  const int64_t units = (int64_t)nb * desc->n_kv_heads * pl.GY;
+  const int64_t total = units * blocks_of(max_kv_len, desc->n_nodes_max);
+  int64_t wgs = plan_wgs(pl, total, units, true);
+  const int64_t wgs_cut = plan_wgs(pl, total, units, false);  // a ragged batch of the same size
+  if (wgs_cut > wgs) wgs = wgs_cut;
+  const int64_t slots = units + wgs;
   return (size_t)slots * slot_bytes(*desc, pl);
 }
 
@@ -1052,6 +856,7 @@ extern "C" fspad_status fspad_tree_attn(const fspad_attn_desc* desc, const void*
   if (d.io_dtype == FSPAD_BF16) {
     plan_rows(d, pl);
     prm.WS = pl.WS; prm.NS = pl.NS; prm.GY = pl.GY;
+    prm.part = reinterpret_cast<float*>(workspace);
   }
 
   // sequences are independent: slices of at most kMaxBatchPerLaunch sequences per launch (the
@@ -1071,26 +876,39 @@ extern "C" fspad_status fspad_tree_attn(const fspad_attn_desc* desc, const void*
     }
     sl.anc_mask = anc_mask + (size_t)b0 * d.n_nodes_max;
     sl.out = static_cast<char*>(out) + q_rows * (d.out_dtype == FSPAD_BF16 ? 2 : 4);
-    for (int i = 0; i < nb; ++i) { sl.seq[i].kv_len = kv_len[b0 + i]; sl.seq[i].n_nodes = (uint8_t)n_nodes[b0 + i]; }
+    for (int i = 0; i < nb; ++i) { sl.kv_len[i] = kv_len[b0 + i]; sl.n_nodes[i] = (uint8_t)n_nodes[b0 + i]; }
     if (d.io_dtype == FSPAD_BF16) {
-      const int units_per_seq = d.n_kv_heads * pl.GY;
+      const int64_t units_per_seq = (int64_t)d.n_kv_heads * pl.GY;
       int64_t total = 0;
-      for (int i = 0; i < nb; ++i) total += (int64_t)units_per_seq * blocks_of(kv_len[b0 + i], n_nodes[b0 + i]);
-      if (total >= (int64_t)1 << 30) return FSPAD_ERR_SHAPE;  // block indices are 32-bit in the kernel
-      const Split sp = plan_split(pl, nb, kv_len + b0, n_nodes + b0, units_per_seq, &sl);
-      sl.mode = sp.mode;
-      const dim3 grid((unsigned)sp.grid_x, sp.mode == kAligned ? (unsigned)nb : 1u);
-      if (sp.any_cut) {
-        const size_t need = (size_t)sp.slots * slot_bytes(d, pl);
-        if (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 15)) return FSPAD_ERR_WORKSPACE;
-        sl.part = reinterpret_cast<float*>(workspace);
+      for (int i = 0; i < nb; ++i) {
+        sl.bstart[i] = total;
+        total += units_per_seq * blocks_of(sl.kv_len[i], sl.n_nodes[i]);
       }
-      if (d.head_dim == 128) launch_bf16<128>(pl, sl, grid, stream); else launch_bf16<64>(pl, sl, grid, stream);
+      sl.bstart[nb] = total;
+      sl.total_blocks = total;
+      bool uniform = true;
+      for (int i = 1; i < nb; ++i)
+        uniform = uniform && blocks_of(sl.kv_len[i], sl.n_nodes[i]) == blocks_of(sl.kv_len[0], sl.n_nodes[0]);
+      const int64_t units = (int64_t)nb * units_per_seq;
+      sl.n_wgs = plan_wgs(pl, total, units, uniform);
+      const int64_t slots = units + sl.n_wgs;
+      const size_t need = (size_t)slots * slot_bytes(d, pl);
+      if (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 15)) return FSPAD_ERR_WORKSPACE;
+      if (d.head_dim == 128) launch_bf16<128>(pl, sl, stream); else launch_bf16<64>(pl, sl, stream);
       if (hipGetLastError() != hipSuccess) return FSPAD_ERR_HIP;
-      if (sp.any_cut) {  // the merge pass runs only if some unit was cut across workgroups
+      // the merge pass runs only if some unit was cut across workgroups
+      bool any_cut = false;
+      for (int i = 0; i < nb && !any_cut; ++i) {
+        const int64_t nblk = blocks_of(sl.kv_len[i], sl.n_nodes[i]);
+        for (int64_t ub = 0; ub < units_per_seq && !any_cut; ++ub) {
+          const int64_t fs = sl.bstart[i] + ub * nblk;
+          any_cut = host_owner_of(fs, total, sl.n_wgs) != host_owner_of(fs + nblk - 1, total, sl.n_wgs);
+        }
+      }
+      if (any_cut) {
         const int rows_per_slab = 16 * pl.QT;
         const int rpb = 256 / (d.head_dim / 4);
-        dim3 cgrid((unsigned)((pl.rows_per_unit + rpb - 1) / rpb), (unsigned)sp.units);
+        dim3 cgrid((unsigned)((pl.rows_per_unit + rpb - 1) / rpb), (unsigned)units);
         if (d.head_dim == 128) hipLaunchKernelGGL(tree_attn_combine_kernel<128>, cgrid, dim3(256), 0, stream, sl, rows_per_slab);
         else hipLaunchKernelGGL(tree_attn_combine_kernel<64>, cgrid, dim3(256), 0, stream, sl, rows_per_slab);
         if (hipGetLastError() != hipSuccess) return FSPAD_ERR_HIP;

@@ -47,16 +47,14 @@ class AttnCase:
             self.k_cache, self.v_cache = to_dev(kc, dtype), to_dev(vc, dtype)
         self.mask_dev = torch.from_numpy(self.mask.view(np.int64)).to(DEV)
 
-    def run_gpu(self, out_dtype=torch.float32, scale=0.0, splits=0, mode=-1):
+    def run_gpu(self, out_dtype=torch.float32, scale=0.0, splits=0):
         fspad.fspad_tree_attn_set_workgroups(splits)
-        fspad.fspad_tree_attn_set_split_mode(mode)
         try:
             out = fspad.fspad_tree_attn(self.q, self.k_tree, self.v_tree, self.k_cache, self.v_cache, self.kv_len,
                                         self.n_nodes, self.mask_dev, softmax_scale=scale, out_dtype=out_dtype)
             torch.cuda.synchronize()
         finally:
             fspad.fspad_tree_attn_set_workgroups(0)
-            fspad.fspad_tree_attn_set_split_mode(-1)
         return out
 
     def run_oracle(self, scale=None, heads=None, nthreads=16):
