@@ -8,9 +8,9 @@
 // per lane, one workgroup per (row, chunk of 1024..8192 entries), and leaves per-chunk
 // statistics: (max, first index of max) for greedy, (max, fp64 sum of
 // exp((l-max)/T)) for sampling. The second, one workgroup per sequence, merges the
-// chunk statistics of the rows it needs, walks the tree with wavefront ballots
-// and, for sampling, draws the last token by an inverse-CDF search that descends
-// chunk -> thread segment -> element.
+// chunk statistics of every row at once, walks the tree with wavefront ballots
+// out of LDS and, for sampling, draws the last token by an inverse-CDF search that
+// descends chunk -> thread segment -> element.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -215,77 +215,217 @@ __global__ __launch_bounds__(kThreads) void accept_greedy_walk_kernel(const Acce
 }
 
 // ------------------------------------------------------------------------------------------------
-// Sampling: wavefront 0 walks the tree (row statistics merged on demand, children tested in index
-// order against the running residual), then the whole workgroup draws the last token.
+// Last step of the sampling pass: the workgroup draws the token at which the running sum of the
+// residual weights of one chunk crosses `target`. Thread k owns PT consecutive entries; their
+// weights are formed once and stay in registers, so the thread that owns the crossing finds it
+// without touching memory again. If rounding leaves no crossing, the last entry with mass is taken.
+struct DrawArgs {
+  const float* rp;          // the row
+  int first, V;             // first entry of the chunk, vocabulary size
+  double M, target, inv_temperature;
+  const int* rej_tok;       // tokens rejected at this node: zero weight
+  int nrej;
+  double* scan_part;        // LDS scratch: 4 doubles
+  int* sh_i;                // LDS scratch: entries 5 and 6 are used
+  int32_t* out;
+  bool vec;                 // rows are 16-byte aligned
+};
+
+template <int PT>
+__device__ __forceinline__ void draw_in_chunk(const DrawArgs& a) {
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int e0 = a.first + tid * PT;
+  float lx[PT];
+#pragma unroll
+  for (int k = 0; k < PT / 4; ++k) {
+    const int e = e0 + 4 * k;
+    if (a.vec && e + 3 < a.V) {
+      const f32x4 v = *reinterpret_cast<const f32x4*>(a.rp + e);
+      lx[4 * k] = v[0]; lx[4 * k + 1] = v[1]; lx[4 * k + 2] = v[2]; lx[4 * k + 3] = v[3];
+    } else {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) lx[4 * k + j] = (e + j < a.V) ? a.rp[e + j] : NAN;
+    }
+  }
+  unsigned gone = 0u;   // bit j: entry e0 + j was rejected at this node and has left the residual
+  for (int k = 0; k < a.nrej; ++k) {
+    const unsigned r = (unsigned)(a.rej_tok[k] - e0);
+    if (r < (unsigned)PT) gone |= 1u << r;
+  }
+  double w[PT];
+  double local = 0.0;
+  int last_here = -1;
+#pragma unroll
+  for (int j = 0; j < PT; ++j) {
+    double wj = 0.0;
+    if (lx[j] == lx[j] && !((gone >> j) & 1u))   // not NaN (entries past the vocabulary were loaded as NaN)
+      wj = exp_nonpos(((double)lx[j] - a.M) * a.inv_temperature);
+    w[j] = wj;
+    local += wj;
+    if (wj > 0.0) last_here = e0 + j;
+  }
+  double incl = local;
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const double up = __shfl_up(incl, off);
+    if (lane >= off) incl += up;
+  }
+  if (lane == 63) a.scan_part[wave] = incl;
+  if (tid == 0) { a.sh_i[5] = kNone; a.sh_i[6] = -1; }
+  __syncthreads();
+  double wave_base = 0.0;
+  for (int v = 0; v < wave; ++v) wave_base += a.scan_part[v];
+  // the owner is the first thread whose inclusive running sum exceeds the target
+  const double inclusive = wave_base + incl;
+  if (inclusive > a.target && local > 0.0) atomicMin(&a.sh_i[5], tid);
+  if (last_here >= 0) atomicMax(&a.sh_i[6], last_here);
+  __syncthreads();
+  if (a.sh_i[5] == kNone) {  // rounding left no crossing: the last entry with mass
+    if (tid == 0) *a.out = a.sh_i[6] < 0 ? 0 : a.sh_i[6];
+    return;
+  }
+  if (tid == a.sh_i[5]) {
+    double run = inclusive - local;
+    int pick = last_here;  // if rounding hides the crossing inside the segment: its last entry with mass
+    bool done = false;
+#pragma unroll
+    for (int j = 0; j < PT; ++j) {
+      run += w[j];
+      if (!done && run > a.target) { pick = e0 + j; done = true; }
+    }
+    *a.out = pick;
+  }
+}
+
+// Sampling. Everything the walk can need is fetched up front, in parallel, so that the walk itself
+// touches no memory: (1) the chunk statistics of every row are merged into the row's max M and
+// normaliser Z (four threads per row); (2) every node fetches the weight of its own draft token
+// under its parent's distribution (one gather for the whole tree; a token that an earlier sibling
+// already proposed weighs nothing, because it has left the residual by the time it is tested);
+// (3) wavefront 0 walks the tree out of LDS, testing the children of the current node in index
+// order against the running residual; (4) the workgroup draws the last token.
 __global__ __launch_bounds__(kThreads) void accept_sample_walk_kernel(const AcceptParams p) {
   __shared__ int rej_tok[FSPAD_MAX_NODES];
   __shared__ double rej_w[FSPAD_MAX_NODES];
   __shared__ double sh_d[8];
   __shared__ int sh_i[8];
   __shared__ double scan_part[4];
+  __shared__ double row_M[FSPAD_MAX_NODES], row_Z[FSPAD_MAX_NODES], node_w[FSPAD_MAX_NODES];
+  __shared__ int node_par[FSPAD_MAX_NODES], node_tok[FSPAD_MAX_NODES];
+  __shared__ float node_u[2][FSPAD_MAX_NODES];
   const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int n = p.n_nodes[b];
   const int64_t o = (int64_t)b * p.Nmax;
   const float* u_acc = p.uniforms + (int64_t)b * 2 * p.Nmax;
-  const float* u_bonus = u_acc + p.Nmax;
+
+  // (1) row statistics: thread (row = tid / 4, quarter = tid % 4) scans every 4th chunk of its row,
+  // eight chunks in flight at a time, keeping a running (max, sum); the four quarters of a row are
+  // then merged. Nothing here waits for the tree size: rows past it hold unused numbers.
+  const int n_raw = p.n_nodes[b];
+  {
+    const int row = tid >> 2, q = tid & 3;
+    const bool in_range = row < p.Nmax;
+    const float* pm = p.part_max + (o + (in_range ? row : 0)) * p.n_chunks;
+    const double* ps = p.part_sum + (o + (in_range ? row : 0)) * p.n_chunks;
+    float m_run = -INFINITY;
+    double z_run = 0.0;
+    for (int c0 = q; c0 < p.n_chunks; c0 += 32) {
+      float m_c[8];
+      double s_c[8];
+#pragma unroll
+      for (int k = 0; k < 8; ++k) {
+        const int c = c0 + 4 * k;
+        const bool ok = in_range && c < p.n_chunks;
+        m_c[k] = ok ? pm[c] : -INFINITY;
+        s_c[k] = ok ? ps[c] : 0.0;
+      }
+      float m_new = m_run;
+#pragma unroll
+      for (int k = 0; k < 8; ++k) m_new = fmaxf(m_new, m_c[k]);
+      if (m_new > -INFINITY) {
+        double z = m_run > -INFINITY ? z_run * exp_nonpos(((double)m_run - (double)m_new) * p.inv_temperature) : 0.0;
+#pragma unroll
+        for (int k = 0; k < 8; ++k)
+          if (m_c[k] > -INFINITY) z += s_c[k] * exp_nonpos(((double)m_c[k] - (double)m_new) * p.inv_temperature);
+        z_run = z;
+        m_run = m_new;
+      }
+    }
+    float mx = fmaxf(m_run, __shfl_xor(m_run, 1));
+    mx = fmaxf(mx, __shfl_xor(mx, 2));
+    double z = m_run > -INFINITY ? z_run * exp_nonpos(((double)m_run - (double)mx) * p.inv_temperature) : 0.0;
+    z += __shfl_xor(z, 1);
+    z += __shfl_xor(z, 2);
+    if (in_range && q == 0) { row_M[row] = (double)mx; row_Z[row] = z; }
+    if (tid < FSPAD_MAX_NODES) {
+      const bool ok = tid < p.Nmax;
+      node_par[tid] = ok ? p.parent[o + tid] : -2;
+      node_tok[tid] = ok ? p.draft_tokens[o + tid] : -1;
+      node_u[0][tid] = ok ? u_acc[tid] : 0.f;
+      node_u[1][tid] = ok ? u_acc[p.Nmax + tid] : 0.f;
+    }
+  }
+  const int n = n_raw;
+  __syncthreads();
+  // (2) weight of every node's draft token under its parent's row
+  if (tid < FSPAD_MAX_NODES) {
+    double w = 0.0;
+    const int par = node_par[tid], tok = node_tok[tid];
+    if (tid > 0 && tid < n && par >= 0 && par < tid && tok >= 0 && tok < p.V) {
+      const double M = row_M[par];
+      if (M > -INFINITY) {
+        const float lx = p.logits[(o + par) * p.row_stride + tok];
+        if (lx == lx) w = exp_nonpos(((double)lx - M) * p.inv_temperature);
+      }
+    }
+    node_w[tid] = w;
+  }
+  __syncthreads();
 
   if (wave == 0) {
-    int my_par = -2, my_tok = -1;
-    float my_u = 0.f;
-    if (lane < n) { my_par = p.parent[o + lane]; my_tok = p.draft_tokens[o + lane]; my_u = u_acc[lane]; }
+    const int my_par = node_par[lane], my_tok = node_tok[lane];
+    const double my_w = node_w[lane];
+    const float my_u = node_u[0][lane];
     int my_path = lane == 0 ? 0 : -1, my_out = -1;
     int cur = 0, len = 1, nrej = 0;
+    int my_rej = -1;       // lane k keeps the k-th token rejected at the current node, and its weight
+    double my_rej_w = 0.0;
     double M = 0.0, Z = 0.0;
+    auto lane_value = [](double v, int src) {   // src is the same in every lane: scalar reads, no LDS exchange
+      const unsigned long long bits = __builtin_bit_cast(unsigned long long, v);
+      const unsigned lo = __builtin_amdgcn_readlane((unsigned)bits, src);
+      const unsigned hi = __builtin_amdgcn_readlane((unsigned)(bits >> 32), src);
+      return __builtin_bit_cast(double, ((unsigned long long)hi << 32) | lo);
+    };
     for (int iter = 0; iter < p.Nmax; ++iter) {  // one level per iteration; a leaf ends the walk
-      const int64_t row = o + cur;
-      const float* pm = p.part_max + row * p.n_chunks;
-      const double* ps = p.part_sum + row * p.n_chunks;
-      float mx = -INFINITY;
-      for (int c = lane; c < p.n_chunks; c += 64) mx = fmaxf(mx, pm[c]);
-#pragma unroll
-      for (int off = 32; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off));
-      M = (double)mx;
-      double z = 0.0;
-      for (int c = lane; c < p.n_chunks; c += 64)
-        if (pm[c] > -INFINITY) z += ps[c] * exp_nonpos(((double)pm[c] - M) * p.inv_temperature);
-#pragma unroll
-      for (int off = 32; off > 0; off >>= 1) z += __shfl_xor(z, off);
-      Z = z;
+      M = row_M[cur];
+      Z = row_Z[cur];
       nrej = 0;
-      // every child (lane = node) fetches its own token's weight at once; a token that an earlier
-      // sibling already proposed has been removed from the residual by then and weighs nothing
+      my_rej = -1;
       const bool is_kid = lane > 0 && lane < n && my_par == cur;
       unsigned long long kids = __ballot(is_kid);
-      double my_w = 0.0;
-      if (is_kid && my_tok >= 0 && my_tok < p.V && mx > -INFINITY) {
-        const float lx = p.logits[row * p.row_stride + my_tok];
-        if (lx == lx) my_w = exp_nonpos(((double)lx - M) * p.inv_temperature);
-      }
-      for (unsigned long long rest = kids; rest != 0ull; rest &= rest - 1ull) {
-        const int c = __ffsll(rest) - 1;
-        const int tc = __shfl(my_tok, c);
-        if (is_kid && lane > c && my_tok == tc) my_w = 0.0;
-      }
       int accepted = -1;
       while (kids != 0ull && len < p.Nmax) {
-        const int c = __ffsll(kids) - 1;
+        const int c = __builtin_amdgcn_readfirstlane(__ffsll(kids) - 1);
         kids &= kids - 1ull;
-        const int x = __shfl(my_tok, c);
-        const double w = __shfl(my_w, c);
-        const double lhs = (double)__shfl(my_u, c) * Z;
+        const int x = __builtin_amdgcn_readlane(my_tok, c);
+        // a token that an earlier sibling proposed has left the residual: it weighs nothing now
+        const bool gone = __ballot(lane < nrej && my_rej == x) != 0ull;
+        const double w = gone ? 0.0 : lane_value(my_w, c);
+        const double lhs = (double)__builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, my_u), c)) * Z;
         if (lhs < w) { accepted = c; break; }
         Z -= w;
-        if (lane == 0) { rej_tok[nrej] = x; rej_w[nrej] = w; }
+        if (lane == nrej) { my_rej = x; my_rej_w = w; }
         ++nrej;
       }
-      __builtin_amdgcn_wave_barrier();
       if (accepted < 0) break;
       if (lane == len) my_path = accepted;
-      const int accepted_tok = __shfl(my_tok, accepted);  // all lanes take part in the exchange
+      const int accepted_tok = __builtin_amdgcn_readlane(my_tok, accepted);
       if (lane == len - 1) my_out = accepted_tok;
       cur = accepted;
       ++len;
     }
+    if (lane < nrej) { rej_tok[lane] = my_rej; rej_w[lane] = my_rej_w; }
+    __builtin_amdgcn_wave_barrier();
     if (lane < p.Nmax) { p.path[o + lane] = my_path; if (lane != len - 1) p.tokens[o + lane] = my_out; }
     if (lane == 0) {
       p.path_len[b] = len; p.n_tokens[b] = len;
@@ -294,7 +434,7 @@ __global__ __launch_bounds__(kThreads) void accept_sample_walk_kernel(const Acce
     }
 
     // bonus, stage 1: which chunk holds the running-sum crossing of t = u * Z
-    const double t = (double)u_bonus[cur] * Z;
+    const double t = (double)node_u[1][cur] * Z;
     const int64_t row = o + cur;
     const float* pm = p.part_max + row * p.n_chunks;
     const double* ps = p.part_sum + row * p.n_chunks;
@@ -336,58 +476,28 @@ __global__ __launch_bounds__(kThreads) void accept_sample_walk_kernel(const Acce
 
   // bonus, stage 2: inside the chunk, thread k owns chunk/256 consecutive entries
   const int cur = sh_i[0], len = sh_i[1], nrej = sh_i[2], chunk = sh_i[3];
-  const double M = sh_d[0], target = sh_d[2];
   if (chunk < 0) {  // no mass anywhere (cannot happen with finite logits): token 0
     if (tid == 0) p.tokens[o + len - 1] = 0;
     return;
   }
-  const float* rp = p.logits + (o + cur) * p.row_stride;
-  const int per_thread = p.chunk / kThreads;
-  const int e0 = chunk * p.chunk + tid * per_thread;
-  auto weight = [&](int e) -> double {
-    if (e >= p.V) return 0.0;
-    const float lx = rp[e];
-    if (lx != lx) return 0.0;
-    for (int k = 0; k < nrej; ++k)
-      if (rej_tok[k] == e) return 0.0;
-    return exp_nonpos(((double)lx - M) * p.inv_temperature);
-  };
-  double local = 0.0;
-  int last_here = -1;
-  for (int j = 0; j < per_thread; ++j) {
-    const double w = weight(e0 + j);
-    local += w;
-    if (w > 0.0) last_here = e0 + j;
-  }
-  double incl = local;
-#pragma unroll
-  for (int off = 1; off < 64; off <<= 1) {
-    const double up = __shfl_up(incl, off);
-    if (lane >= off) incl += up;
-  }
-  if (lane == 63) scan_part[wave] = incl;
-  __syncthreads();
-  double wave_base = 0.0;
-  for (int w = 0; w < wave; ++w) wave_base += scan_part[w];
-  // the owner is the first thread whose inclusive running sum exceeds the target
-  const double inclusive = wave_base + incl;
-  if (tid == 0) { sh_i[5] = kNone; sh_i[6] = -1; }
-  __syncthreads();
-  if (inclusive > target && local > 0.0) atomicMin(&sh_i[5], tid);
-  if (last_here >= 0) atomicMax(&sh_i[6], last_here);
-  __syncthreads();
-  if (sh_i[5] == kNone) {  // rounding left no crossing: the last entry with mass
-    if (tid == 0) p.tokens[o + len - 1] = sh_i[6] < 0 ? 0 : sh_i[6];
-    return;
-  }
-  if (tid == sh_i[5]) {
-    double run = inclusive - local;
-    int pick = last_here;  // if rounding hides the crossing inside the segment: its last entry with mass
-    for (int j = 0; j < per_thread; ++j) {
-      run += weight(e0 + j);
-      if (run > target) { pick = e0 + j; break; }
-    }
-    p.tokens[o + len - 1] = pick;
+  DrawArgs a;
+  a.rp = p.logits + (o + cur) * p.row_stride;
+  a.first = chunk * p.chunk;
+  a.V = p.V;
+  a.M = sh_d[0];
+  a.target = sh_d[2];
+  a.inv_temperature = p.inv_temperature;
+  a.rej_tok = rej_tok;
+  a.nrej = nrej;
+  a.scan_part = scan_part;
+  a.sh_i = sh_i;
+  a.out = p.tokens + o + len - 1;
+  a.vec = (((uintptr_t)p.logits) & 15) == 0 && (p.row_stride % 4) == 0;
+  switch (p.chunk / kThreads) {
+    case 4: draw_in_chunk<4>(a); break;
+    case 8: draw_in_chunk<8>(a); break;
+    case 16: draw_in_chunk<16>(a); break;
+    default: draw_in_chunk<32>(a); break;
   }
 }
 
