@@ -46,10 +46,16 @@ struct AcceptParams {
 };
 
 // exp(x) for x <= 0 in fp64: x = n ln2 + r, |r| <= ln2/2, degree-11 Taylor polynomial
-// (truncation below 1e-14 relative), scaled by 2^n. Returns 0 below the denormal range.
+// (truncation below 1e-14 relative), scaled by 2^n. n is rounded with the 1.5*2^52 shift (its
+// integer value then sits in the low word of the shifted number) and 2^n is assembled from its
+// exponent bits, which keeps the whole routine on full-rate multiply-adds. Returns 0 below
+// -708 (where the true value is under 1e-307: its absence moves no sum by a representable amount).
 __device__ __forceinline__ double exp_nonpos(double x) {
-  if (!(x >= -745.2)) return 0.0;  // also catches NaN
-  const double n = rint(x * 1.4426950408889634074);
+  if (!(x >= -708.0)) return 0.0;  // also catches NaN
+  const double shift = 6755399441055744.0;  // 1.5 * 2^52
+  const double t = fma(x, 1.4426950408889634074, shift);
+  const double n = t - shift;
+  const int ni = (int)__double2loint(t);   // low word of the shifted value: n as a 32-bit integer (n in [-1022, 0])
   double r = fma(-n, 6.93147180369123816490e-01, x);
   r = fma(-n, 1.90821492927058770002e-10, r);
   double p = 1.0 / 39916800.0;
@@ -64,7 +70,8 @@ __device__ __forceinline__ double exp_nonpos(double x) {
   p = fma(p, r, 0.5);
   p = fma(p, r, 1.0);
   p = fma(p, r, 1.0);
-  return ldexp(p, (int)n);
+  const double scale = __hiloint2double((ni + 1023) << 20, 0);   // 2^n
+  return p * scale;
 }
 
 __device__ __forceinline__ float clean(float x) { return (x != x) ? -INFINITY : x; }  // NaN ranks lowest
@@ -104,6 +111,38 @@ __global__ __launch_bounds__(kThreads) void accept_rows_kernel(const AcceptParam
     }
   }
 
+  const int64_t slot = (int64_t)row * p.n_chunks + chunk;
+  if (MODE == 1) {
+    // sampling: each thread sums exp((x - its own max)/T) over its entries as soon as they arrive
+    // (fp64, no waiting for the rest of the workgroup); the threads' (max, sum) pairs are then merged
+    // into the chunk's: sum_c = sum_t sum_t * exp((max_t - max_c)/T).
+    float mt = x[0];
+#pragma unroll
+    for (int k = 1; k < kPerThread; ++k) mt = fmaxf(mt, x[k]);
+    double st = 0.0;
+    if (mt > -INFINITY) {
+      const double mtd = (double)mt;
+#pragma unroll
+      for (int k = 0; k < kPerThread; ++k) st += exp_nonpos(((double)x[k] - mtd) * p.inv_temperature);
+    }
+    float mw = mt;
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) mw = fmaxf(mw, __shfl_xor(mw, off));
+    if (lane == 0) sh_max[wave] = mw;
+    __syncthreads();
+    const float mc = fmaxf(fmaxf(sh_max[0], sh_max[1]), fmaxf(sh_max[2], sh_max[3]));
+    double sum = mt > -INFINITY ? st * exp_nonpos(((double)mt - (double)mc) * p.inv_temperature) : 0.0;
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) sum += __shfl_xor(sum, off);
+    if (lane == 0) sh_sum[wave] = sum;
+    __syncthreads();
+    if (tid == 0) {
+      p.part_max[slot] = mc;
+      p.part_sum[slot] = (sh_sum[0] + sh_sum[1]) + (sh_sum[2] + sh_sum[3]);
+    }
+    return;
+  }
+
   float best = -INFINITY;
   int idx = kNone;
 #pragma unroll
@@ -124,27 +163,7 @@ __global__ __launch_bounds__(kThreads) void accept_rows_kernel(const AcceptParam
   best = sh_max[0]; idx = sh_idx[0];
 #pragma unroll
   for (int w = 1; w < 4; ++w) take_better(best, idx, sh_max[w], sh_idx[w]);
-
-  const int64_t slot = (int64_t)row * p.n_chunks + chunk;
-  if (MODE == 0) {
-    if (tid == 0) { p.part_max[slot] = best; p.part_idx[slot] = idx; }
-    return;
-  }
-  // sampling: fp64 sum of exp((x - chunk max)/T)
-  double sum = 0.0;
-  if (best > -INFINITY) {
-    const double mx = (double)best;
-#pragma unroll
-    for (int k = 0; k < kPerThread; ++k) sum += exp_nonpos(((double)x[k] - mx) * p.inv_temperature);
-  }
-#pragma unroll
-  for (int off = 32; off > 0; off >>= 1) sum += __shfl_xor(sum, off);
-  if (lane == 0) sh_sum[wave] = sum;
-  __syncthreads();
-  if (tid == 0) {
-    p.part_max[slot] = best;
-    p.part_sum[slot] = (sh_sum[0] + sh_sum[1]) + (sh_sum[2] + sh_sum[3]);
-  }
+  if (tid == 0) { p.part_max[slot] = best; p.part_idx[slot] = idx; }
 }
 
 // ------------------------------------------------------------------------------------------------
