@@ -41,6 +41,12 @@ def parse_args():
     ap.add_argument("--nodes", type=int, default=None, help="experiments only: override the tree size")
     ap.add_argument("--heads", type=int, default=None, help="experiments only: override the head count (MHA)")
     ap.add_argument("--kv-len", type=int, default=None, help="experiments only: override the prefix length")
+    ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
+                    help="profiling only: before the timed region, copy a buffer of this many MiB three times "
+                         "(a kernel of known HBM traffic next to which rocprofv3 byte counters can be scaled)")
+    ap.add_argument("--commit", action="store_true",
+                    help="also append the accepted path's keys/values to every layer's cache after the acceptance "
+                         "(fspad_kv_commit; the caches then carry room for one more tree)")
     ap.add_argument("--seed", type=int, default=2024)
     return ap.parse_args()
 
@@ -95,8 +101,9 @@ def main():
     for s in range(n_sets):
         layers = []
         for _ in range(cfg.layers):
-            kc = torch.empty((B, Hkv, L, D), device=dev, dtype=tdt).normal_(generator=gen)
-            vc = torch.empty((B, Hkv, L, D), device=dev, dtype=tdt).normal_(generator=gen)
+            cap = L + N if args.commit else L
+            kc = torch.empty((B, Hkv, cap, D), device=dev, dtype=tdt).normal_(generator=gen)
+            vc = torch.empty((B, Hkv, cap, D), device=dev, dtype=tdt).normal_(generator=gen)
             q = torch.empty((B, N, Hq, D), device=dev, dtype=tdt).normal_(generator=gen)
             kt = torch.empty((B, N, Hkv, D), device=dev, dtype=tdt).normal_(generator=gen)
             vt = torch.empty((B, N, Hkv, D), device=dev, dtype=tdt).normal_(generator=gen)
@@ -137,6 +144,17 @@ def main():
         else:
             fspad.fspad_tree_accept_sample(st["logits"], st["tokens"], parent_d, n_nodes_d, cfg.temperature,
                                            st["uniforms"], outputs=acc_out, workspace=ws_acc)
+        if args.commit:   # the prefix length stays L from step to step: every step rewrites the same tail
+            for (q, kt, vt, kc, vc, out) in st["layers"]:
+                fspad.fspad_kv_commit(kt, vt, kc, vc, kv_len, acc_out[0], acc_out[1])
+
+    if args.copy_calibration:
+        src = torch.empty(args.copy_calibration << 20, dtype=torch.uint8, device=dev).random_(generator=gen)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     for i in range(warmup):
         step(i)
@@ -172,6 +190,7 @@ def main():
         "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": cfg.name, "layers": cfg.layers, "batch": B, "n_q_heads": Hq, "n_kv_heads": Hkv,
                    "head_dim": D, "kv_len": L, "tree_nodes": N, "vocab": V, "accept": accept, "buffer_sets": n_sets,
+                   "kv_commit": bool(args.commit),
                    "seed": args.seed, "generator_version": GENERATOR_VERSION, "parallelism": "single-gpu"},
         "step_gb_per_s": cfg.step_bytes() / (ms_per_step * 1e-3) / 1e9,
         "step_hbm_frac": cfg.step_bytes() / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,

@@ -176,6 +176,34 @@ fspad_status fspad_tree_accept_sample(int32_t B, int32_t Nmax, int32_t V,
                                       void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * Commit of the accepted path to the KV cache. The paper leaves this step implied
+ * (Preliminaries: the tokens that pass validation extend the sequence from which the
+ * next draft phase starts): the keys and values the verification forward computed for
+ * the accepted nodes are appended to the cache in path order, so that the next
+ * cycle's prefix holds them and its root is the bonus token.
+ *
+ *   for j < path_len[b], every kv head g:
+ *       k_cache[b,g,kv_len[b]+j,:] = k_tree[b,path[b,j],g,:]      (v likewise)
+ *   kv_len_out[b] = kv_len[b] + path_len[b]
+ *
+ *   desc     batch, n_nodes_max, n_kv_heads, head_dim, io_dtype and the cache strides are
+ *            read; the other fields are ignored
+ *   k_tree, v_tree   dev [B,Nmax,Hkv,D] io_dtype (this layer's tree keys / values)
+ *   k_cache, v_cache dev strided, written; every (b,g) row must hold cache_capacity tokens
+ *   cache_capacity   tokens per (b,g) row; kv_len[b] + Nmax <= cache_capacity is required
+ *            (FSPAD_ERR_SHAPE otherwise: the path length is only known on the device)
+ *   kv_len   HOST [B] prefix lengths before the commit (the ones the attention call took)
+ *   path, path_len   dev [B,Nmax], [B]: outputs of an acceptance call. Entries outside
+ *            [0,Nmax) and lengths outside [0,Nmax] are not followed (nothing is moved for them)
+ *   kv_len_out       dev [B] i32 out, may be NULL
+ * Cache positions other than kv_len[b] .. kv_len[b]+path_len[b]-1 are left untouched.
+ */
+fspad_status fspad_kv_commit(const fspad_attn_desc* desc, const void* k_tree, const void* v_tree,
+                             void* k_cache, void* v_cache, int32_t cache_capacity,
+                             const int32_t* kv_len, const int32_t* path, const int32_t* path_len,
+                             int32_t* kv_len_out, void* hip_stream);
+
+/*
  * Host helpers for the tree (Preliminaries: tokens organised into a tree by
  * their dependencies, then the mask derived from the tree).
  *

@@ -149,3 +149,24 @@ def accept_sample(logits, draft_tokens, parent, n_nodes, temperature, uniforms):
     if rc != 0:
         raise ValueError(f"oracle accept_sample failed: {rc}")
     return path, path_len, tokens, n_tokens, margin
+
+
+def kv_commit(k_tree, v_tree, k_cache, v_cache, kv_len, path, path_len):
+    """Cache update after acceptance (Preliminaries: the validated tokens extend the prefix of
+    the next cycle; the paper does not spell the update out). Position kv_len[b]+j of every kv
+    head's cache row receives the key/value of tree node path[b,j], for j < path_len[b].
+
+    k_tree,v_tree [B,Nmax,Hkv,D]; k_cache,v_cache [B,Hkv,Lcap,D] (any numpy dtype; values are
+    moved, not converted). Returns (k_cache', v_cache', kv_len') as new arrays."""
+    k_new, v_new = np.array(k_cache, copy=True), np.array(v_cache, copy=True)
+    kv_len = _i32(kv_len)
+    new_len = kv_len.copy()
+    B, Nmax, Hkv, _ = k_tree.shape
+    for b in range(B):
+        for j in range(int(path_len[b])):
+            node = int(path[b, j])
+            for g in range(Hkv):
+                k_new[b, g, kv_len[b] + j, :] = k_tree[b, node, g, :]
+                v_new[b, g, kv_len[b] + j, :] = v_tree[b, node, g, :]
+        new_len[b] = kv_len[b] + int(path_len[b])
+    return k_new, v_new, new_len

@@ -10,6 +10,7 @@ from .binding import (  # noqa: F401
     FSPAD_MAX_NODES,
     FspadError,
     fspad_attn_desc,
+    fspad_kv_commit,
     fspad_status_string,
     fspad_tree_accept_greedy,
     fspad_tree_accept_sample,

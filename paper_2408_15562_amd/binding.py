@@ -25,7 +25,7 @@ _STATUS_NAMES = {0: "FSPAD_OK", 1: "FSPAD_ERR_NULL", 2: "FSPAD_ERR_SHAPE", 3: "F
 
 EXPORTS = ("fspad_tree_attn_workspace_bytes", "fspad_tree_attn_set_workgroups", "fspad_tree_attn",
            "fspad_tree_accept_workspace_bytes", "fspad_tree_accept_greedy", "fspad_tree_accept_sample",
-           "fspad_tree_build_mask", "fspad_tree_validate", "fspad_status_string")
+           "fspad_kv_commit", "fspad_tree_build_mask", "fspad_tree_validate", "fspad_status_string")
 
 
 class FspadError(RuntimeError):
@@ -70,6 +70,8 @@ def _lib():
         lib.fspad_tree_accept_sample.restype = ctypes.c_int
         lib.fspad_tree_accept_sample.argtypes = [i32, i32, i32, vp, i64, vp, vp, vp, ctypes.c_float, vp,
                                                  vp, vp, vp, vp, vp, sz, vp]
+        lib.fspad_kv_commit.restype = ctypes.c_int
+        lib.fspad_kv_commit.argtypes = [ctypes.POINTER(fspad_attn_desc), vp, vp, vp, vp, i32, vp, vp, vp, vp, vp]
         lib.fspad_tree_build_mask.restype = ctypes.c_int
         lib.fspad_tree_build_mask.argtypes = [i32, i32, vp, vp, vp]
         lib.fspad_tree_validate.restype = ctypes.c_int
@@ -244,6 +246,38 @@ def fspad_tree_accept_sample(logits: torch.Tensor, draft_tokens: torch.Tensor, p
         workspace.numel() * workspace.element_size(), _stream_ptr(stream))
     _check(st, "fspad_tree_accept_sample")
     return path, path_len, tokens, n_tokens
+
+
+def fspad_kv_commit(k_tree: torch.Tensor, v_tree: torch.Tensor, k_cache: torch.Tensor, v_cache: torch.Tensor,
+                    kv_len, path: torch.Tensor, path_len: torch.Tensor,
+                    kv_len_out: Optional[torch.Tensor] = None, stream=None) -> Optional[torch.Tensor]:
+    """Appends the accepted nodes' keys/values to the cache in place. k_tree,v_tree [B,Nmax,Hkv,D];
+    k_cache,v_cache [B,Hkv,Lcap,D] views; kv_len HOST int32 [B]; path [B,Nmax], path_len [B] device
+    int32 (from an acceptance call). Returns kv_len_out."""
+    for name, t in (("k_tree", k_tree), ("v_tree", v_tree)):
+        if not t.is_contiguous():
+            raise ValueError(f"{name} must be contiguous")
+    if (v_cache.stride() != k_cache.stride() or v_cache.shape != k_cache.shape or k_cache.stride(3) != 1
+            or k_cache.dtype != k_tree.dtype or v_cache.dtype != k_tree.dtype):
+        raise ValueError("k_cache and v_cache must share shape, strides and the dtype of k_tree")
+    B, Nmax, Hkv, D = k_tree.shape
+    d = fspad_attn_desc()
+    d.batch, d.n_nodes_max, d.n_q_heads, d.n_kv_heads, d.head_dim = B, Nmax, Hkv, Hkv, D
+    d.io_dtype = d.out_dtype = _dtype_code(k_tree.dtype)
+    d.cache_stride_batch, d.cache_stride_head, d.cache_stride_token = (
+        k_cache.stride(0), k_cache.stride(1), k_cache.stride(2))
+    kv_len = _host_i32(kv_len, "kv_len")
+    if kv_len.shape != (B,):
+        raise ValueError("kv_len must have one entry per sequence")
+    if path.shape != (B, Nmax) or path_len.shape != (B,) or not path.is_contiguous():
+        raise ValueError("path must be [B,Nmax] and path_len [B]")
+    st = _lib().fspad_kv_commit(
+        ctypes.byref(d), _dev_ptr(k_tree, "k_tree"), _dev_ptr(v_tree, "v_tree"),
+        _dev_ptr(k_cache, "k_cache"), _dev_ptr(v_cache, "v_cache"), int(k_cache.shape[2]),
+        kv_len.ctypes.data, _dev_ptr(path, "path", torch.int32), _dev_ptr(path_len, "path_len", torch.int32),
+        _dev_ptr(kv_len_out, "kv_len_out", torch.int32), _stream_ptr(stream))
+    _check(st, "fspad_kv_commit")
+    return kv_len_out
 
 
 def fspad_tree_build_mask(parent, n_nodes) -> np.ndarray:

@@ -133,3 +133,23 @@ def test_accept_argument_checks_need_no_gpu(lib):
     for t in (0.0, -1.0, float("inf"), float("nan")):
         assert sample(t) == 6
     assert sample(1.0, uni=None) == 1
+
+
+def test_commit_argument_checks_need_no_gpu(lib):
+    f = lib.fspad_kv_commit
+    f.restype = ctypes.c_int
+    fake = ctypes.c_void_p(0x1000)   # never dereferenced: every case below fails validation first
+
+    def call(d, kt=fake, cap=4096, kv=2048, path=fake):
+        return f(ctypes.byref(d), kt, fake, fake, fake, ctypes.c_int32(cap), (ctypes.c_int32 * 1)(kv), path, fake,
+                 None, None)
+
+    assert call(_desc(), kt=None) == 1
+    assert call(_desc(), path=None) == 1
+    assert call(_desc(n_nodes_max=65)) == 2
+    assert call(_desc(head_dim=96)) == 2
+    assert call(_desc(io_dtype=2)) == 4
+    assert call(_desc(cache_stride_token=100)) == 2
+    assert call(_desc(), kv=-1) == 2
+    assert call(_desc(), cap=2048 + 25) == 2        # no room for the longest possible path
+    assert call(_desc(), kt=ctypes.c_void_p(0x1004)) == 2
