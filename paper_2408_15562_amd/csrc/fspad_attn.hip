@@ -29,6 +29,7 @@ typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
 typedef __attribute__((ext_vector_type(2))) unsigned u32x2;
 
 constexpr int kMaxBatchPerLaunch = 128;
+constexpr int64_t kMaxFlatBlocks = 1ll << 30;  // 32-key blocks of one launch, summed over its units
 constexpr int kBlockKeys = 32;          // keys per streamed block
 constexpr float kNegBig = -1.0e30f;     // finite stand-in for "no key seen yet"
 constexpr float kLog2e = 1.4426950408889634f;
@@ -48,13 +49,26 @@ struct AttnParams {
   int32_t NS;       // row slabs per kv head
   int32_t GY;       // slab groups per kv head: a (sequence, kv head, slab group) is one unit of work
   int32_t n_wgs;    // workgroups of the flat decomposition
-  int64_t total_blocks;  // 32-key blocks summed over all units
+  int32_t total_blocks;  // 32-key blocks summed over all units (T)
+  int32_t wg_quot, wg_rem;  // T = wg_quot * n_wgs + wg_rem: workgroup w starts at w*wg_quot + w*wg_rem/n_wgs
+  uint32_t g_magic, gy_magic;  // ceil(2^32 / G), ceil(2^32 / GY): division by multiplication (unused when the divisor is 1)
   int32_t out_bf16;
   float scale;      // softmax scale
   int32_t kv_len[kMaxBatchPerLaunch];
-  int64_t bstart[kMaxBatchPerLaunch + 1];  // first flat block of each sequence; bstart[B] = total_blocks
+  int32_t bstart[kMaxBatchPerLaunch + 1];  // first flat block of each sequence; bstart[B] = total_blocks
   uint8_t n_nodes[kMaxBatchPerLaunch];
 };
+
+// x / d for x*d < 2^32, with magic = ceil(2^32 / d) (d >= 2) from the host
+__device__ __forceinline__ unsigned div_magic(unsigned x, int d, unsigned magic) {
+  return d == 1 ? x : __umulhi(x, magic);
+}
+
+// First flat block of workgroup w under the even split: floor(w * T / W), in 32-bit arithmetic
+// (w * wg_rem < 2^24 because both stay below the 4096 workgroups a launch may have).
+__device__ __forceinline__ unsigned wg_first_block(const AttnParams& p, unsigned w) {
+  return w * (unsigned)p.wg_quot + (w * (unsigned)p.wg_rem) / (unsigned)p.n_wgs;
+}
 
 __device__ __forceinline__ float wave_xor_max_16_32(float v) {
   v = fmaxf(v, __shfl_xor(v, 16));
@@ -74,55 +88,41 @@ __device__ __forceinline__ int key_of(int g4, int j) { return (j < 4) ? 4 * g4 +
 
 // Where one 32-key block lives and how it is masked.
 struct BlockSrc {
-  const __bf16* k;
-  const __bf16* v;
-  int64_t stride;   // elements between consecutive keys
-  int nvalid;       // keys of the block that exist (1..32)
-  int kind;         // 0 full prefix block, 1 prefix block with a ragged tail, 2 tree block
-  int tree_key0;    // first tree node of a tree block
+  const char* k;       // first key row of the block
+  const char* v;
+  unsigned row_bytes;  // bytes between consecutive keys
+  int nvalid;          // keys of the block that exist (1..32)
+  int kind;            // 0 full prefix block, 1 prefix block with a ragged tail, 2 tree block
+  int tree_key0;       // first tree node of a tree block
 };
 
-// K rows in the A-operand layout of the 16x16x32 MFMA: lane (col, g4) holds key 16*kt+col,
-// dims 32*ks + 8*g4 .. +7. Rows past the end of a ragged block are clamped (masked later).
-template <int D>
-__device__ __forceinline__ void load_k(bf16x8 (&k)[2][D / 32], const BlockSrc& src, int col, int g4) {
+// Per-lane byte offsets of a block's rows from its first row. They depend only on the row pitch
+// and on how many rows exist (rows past the end of a ragged block are clamped and masked later),
+// so they are recomputed only where a stream changes from full blocks to its tail or to the tree.
+// K rows arrive in the A-operand layout of the 16x16x32 MFMA: lane (col, g4) holds key 16*kt+col,
+// dims 32*ks + 8*g4 .. +7.
+__device__ __forceinline__ void k_offsets(unsigned (&off)[2], unsigned row_bytes, int nvalid, int col, int g4) {
 #pragma unroll
-  for (int kt = 0; kt < 2; ++kt) {
-    const int key = src.kind == 0 ? 16 * kt + col : min(16 * kt + col, src.nvalid - 1);
-    const __bf16* row = src.k + (int64_t)key * src.stride + 8 * g4;
-#pragma unroll
-    for (int ks = 0; ks < D / 32; ++ks) k[kt][ks] = *reinterpret_cast<const bf16x8*>(row + 32 * ks);
-  }
+  for (int kt = 0; kt < 2; ++kt) off[kt] = (unsigned)min(16 * kt + col, nvalid - 1) * row_bytes + 16u * g4;
 }
-
 // V rows: lane (col, g4) holds, for its 8 keys, the D/16 consecutive dims starting at (D/16)*col,
 // i.e. 16 lanes read one whole row contiguously.
 template <int D>
-__device__ __forceinline__ void load_v(unsigned (&v)[8][D / 32], const BlockSrc& src, int col, int g4) {
+__device__ __forceinline__ void v_offsets(unsigned (&off)[8], unsigned row_bytes, int nvalid, int col, int g4) {
 #pragma unroll
-  for (int j = 0; j < 8; ++j) {
-    const int key = src.kind == 0 ? key_of(g4, j) : min(key_of(g4, j), src.nvalid - 1);
-    const __bf16* row = src.v + (int64_t)key * src.stride + (D / 16) * col;
-    if constexpr (D == 128) {
-      const u32x4 w = *reinterpret_cast<const u32x4*>(row);
-      v[j][0] = w[0]; v[j][1] = w[1]; v[j][2] = w[2]; v[j][3] = w[3];
-    } else {
-      const u32x2 w = *reinterpret_cast<const u32x2*>(row);
-      v[j][0] = w[0]; v[j][1] = w[1];
-    }
-  }
+  for (int j = 0; j < 8; ++j) off[j] = (unsigned)min(key_of(g4, j), nvalid - 1) * row_bytes + (unsigned)(D / 8) * col;
 }
 
-// Full prefix blocks: scalar base + fixed per-lane byte offset, no clamping.
+// Scalar base + per-lane byte offset.
 template <int D>
-__device__ __forceinline__ void load_k_full(bf16x8 (&k)[2][D / 32], const char* base, const unsigned (&off)[2]) {
+__device__ __forceinline__ void load_k(bf16x8 (&k)[2][D / 32], const char* base, const unsigned (&off)[2]) {
 #pragma unroll
   for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
     for (int ks = 0; ks < D / 32; ++ks) k[kt][ks] = *reinterpret_cast<const bf16x8*>(base + off[kt] + 64 * ks);
 }
 template <int D>
-__device__ __forceinline__ void load_v_full(unsigned (&v)[8][D / 32], const char* base, const unsigned (&off)[8]) {
+__device__ __forceinline__ void load_v(unsigned (&v)[8][D / 32], const char* base, const unsigned (&off)[8]) {
 #pragma unroll
   for (int j = 0; j < 8; ++j) {
     if constexpr (D == 128) {
@@ -162,7 +162,7 @@ constexpr float kLazyLog2 = 8.0f;
 // the next block's K there when it keeps a single K buffer). `after_transpose()` runs, for tiles
 // done in several passes, once v has been transposed and is dead (the caller requests the next
 // block's V into the same registers there: a whole block of lead time at no register cost).
-template <int QT, int D, bool FULL, typename QFn, typename MaskFn, typename AfterFn, typename AfterVFn>
+template <int QT, int D, typename QFn, typename MaskFn, typename AfterFn, typename AfterVFn>
 __device__ __forceinline__ void process_block(RowState<QT, D>& st, const bf16x8 (&k)[2][D / 32],
                                               const unsigned (&v)[8][D / 32], QFn&& q_frag, const BlockSrc& src,
                                               MaskFn&& mask_of_tile, float c, int g4, AfterFn&& after_scores,
@@ -190,20 +190,18 @@ __device__ __forceinline__ void process_block(RowState<QT, D>& st, const bf16x8 
       s[tt][1] = acc1;
     }
     if (t0 + TP >= QT) after_scores();
-    if (!FULL && src.kind != 0) {
+    if (src.kind != 0) {  // wavefront-uniform: ragged tail and tree blocks only
 #pragma unroll
       for (int tt = 0; tt < TP; ++tt) {
         if (t0 + tt >= QT) continue;
-        const uint64_t word = src.kind == 2 ? mask_of_tile(t0 + tt) : 0ull;  // fetched only in the few tree blocks
+        // visibility of the block's 32 keys for this lane's row, then shifted to the lane's own keys
+        unsigned vis = src.nvalid >= kBlockKeys ? ~0u : ((1u << src.nvalid) - 1u);
+        if (src.kind == 2) vis &= (unsigned)(mask_of_tile(t0 + tt) >> src.tree_key0);
+        vis >>= 4 * g4;
 #pragma unroll
         for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
-          for (int i = 0; i < 4; ++i) {
-            const int key = 16 * kt + 4 * g4 + i;
-            bool visible = key < src.nvalid;
-            if (src.kind == 2) visible = visible && ((word >> (src.tree_key0 + key)) & 1ull);
-            if (!visible) s[tt][kt][i] = -INFINITY;
-          }
+          for (int i = 0; i < 4; ++i) s[tt][kt][i] = ((vis >> (16 * kt + i)) & 1u) ? s[tt][kt][i] : -INFINITY;
       }
     }
     float mx[TP];
@@ -300,50 +298,120 @@ __global__ __launch_bounds__(256, (QT <= 2 ? 2 : 1)) void tree_attn_bf16_kernel(
   const int KW = 4 / p.WS;  // wavefronts that split the keys of one slab
   const int kp = wave / p.WS;
   const float c = p.scale * kLog2e;
-  const int64_t tree_stride = (int64_t)p.Hkv * D;
+  const unsigned tree_row_bytes = (unsigned)p.Hkv * D * 2u;
+  const unsigned cache_row_bytes = (unsigned)p.stride_token * 2u;
   const int rows_per_unit = p.WS * ROWS;
 
-  const int w = blockIdx.x;
-  const int64_t r0 = ((int64_t)w * p.total_blocks) / p.n_wgs, r1 = ((int64_t)(w + 1) * p.total_blocks) / p.n_wgs;
+  // A kernel this short-lived spends much of its time fetching instructions it runs once: all
+  // index arithmetic up to the first loads is 32-bit, and divisions by the launch's constants
+  // are multiplications.
+  const unsigned w = blockIdx.x;
+  const unsigned r0 = wg_first_block(p, w), r1 = wg_first_block(p, w + 1);
   int b = 0;
-  while (b + 1 < p.B && r0 >= p.bstart[b + 1]) ++b;
+  while (b + 1 < p.B && r0 >= (unsigned)p.bstart[b + 1]) ++b;
 
-  for (int64_t r = r0; r < r1;) {
+  for (unsigned r = r0; r < r1;) {
     const int n = p.n_nodes[b];
     const int L = p.kv_len[b];
     const int n_prefix_blocks = (L + kBlockKeys - 1) / kBlockKeys;
     const int n_blocks = n_prefix_blocks + (n + kBlockKeys - 1) / kBlockKeys;
-    const int ub = (int)((r - p.bstart[b]) / n_blocks);          // unit within the sequence: (g, y)
-    const int seg_begin = (int)((r - p.bstart[b]) - (int64_t)ub * n_blocks);
-    const int seg_count = (int)min((int64_t)(n_blocks - seg_begin), r1 - r);
-    const int g = ub / p.GY, y = ub - g * p.GY;
+    const unsigned rel = r - (unsigned)p.bstart[b];
+    const int ub = (int)(rel / (unsigned)n_blocks);              // unit within the sequence: (g, y)
+    const int seg_begin = (int)(rel - (unsigned)ub * (unsigned)n_blocks);
+    const int seg_count = min(n_blocks - seg_begin, (int)(r1 - r));
+    const int g = (int)div_magic((unsigned)ub, p.GY, p.gy_magic), y = ub - g * p.GY;
     const int unit = b * p.Hkv * p.GY + ub;
     const bool whole_unit = seg_count == n_blocks;
     const int slab = y * p.WS + slab_local;
     const bool slab_live = slab < p.NS;
+
+    // the key-splitting wavefronts of a slab share the segment's blocks evenly
+    // interleaved: wavefront kp takes blocks kp, kp+KW, ... so that the workgroup as a whole walks
+    // one contiguous stretch of K and of V (neighbouring DRAM pages stay open)
+    const int blk_begin = seg_begin + kp;
+    const int blk_end = seg_begin + seg_count;
+    const bool active = slab_live && blk_begin < blk_end;
+
+    const char* kc = reinterpret_cast<const char*>(p.k_cache) + (b * p.stride_batch + g * p.stride_head) * 2;
+    const char* vc = reinterpret_cast<const char*>(p.v_cache) + (b * p.stride_batch + g * p.stride_head) * 2;
+    const char* ktr = reinterpret_cast<const char*>(p.k_tree) + ((int64_t)b * p.Nmax * p.Hkv + g) * (D * 2);
+    const char* vtr = reinterpret_cast<const char*>(p.v_tree) + ((int64_t)b * p.Nmax * p.Hkv + g) * (D * 2);
+
+    auto locate = [&](int blk) {
+      BlockSrc src;
+      if (blk < n_prefix_blocks) {
+        const int key0 = blk * kBlockKeys;
+        const int64_t byte0 = (int64_t)key0 * cache_row_bytes;
+        src.k = kc + byte0;
+        src.v = vc + byte0;
+        src.row_bytes = cache_row_bytes;
+        src.nvalid = min(kBlockKeys, L - key0);
+        src.kind = src.nvalid == kBlockKeys ? 0 : 1;
+        src.tree_key0 = 0;
+      } else {
+        const int t0 = (blk - n_prefix_blocks) * kBlockKeys;
+        src.k = ktr + t0 * tree_row_bytes;
+        src.v = vtr + t0 * tree_row_bytes;
+        src.row_bytes = tree_row_bytes;
+        src.nvalid = min(kBlockKeys, n - t0);
+        src.kind = 2;
+        src.tree_key0 = t0;
+      }
+      return src;
+    };
+
+    // The stream's first block is requested before anything else is set up. Small tiles (two
+    // wavefronts per SIMD) keep one K and one V block in registers: K of the next block is requested
+    // right after the scores of this one, V of the next block once this block's products are issued.
+    // Large tiles (one wavefront per SIMD) request K of the next block at the top of this one into a
+    // second buffer and V of the next block as soon as this block's V has been transposed, into the
+    // registers that frees.
+    bf16x8 kf[2][KS], kfn[kDeep ? 2 : 1][KS];
+    unsigned vr[8][D / 32];
+    unsigned koff[2], voff[8];
+    unsigned k_rb = 0, v_rb = 0;   // row pitch and row count the offsets were last computed for
+    int k_nv = 0, v_nv = 0;
+    auto set_k = [&](const BlockSrc& s) {
+      if (s.row_bytes != k_rb || s.nvalid != k_nv) {
+        k_offsets(koff, s.row_bytes, s.nvalid, col, g4);
+        k_rb = s.row_bytes; k_nv = s.nvalid;
+      }
+    };
+    auto set_v = [&](const BlockSrc& s) {
+      if (s.row_bytes != v_rb || s.nvalid != v_nv) {
+        v_offsets<D>(voff, s.row_bytes, s.nvalid, col, g4);
+        v_rb = s.row_bytes; v_nv = s.nvalid;
+      }
+    };
+    BlockSrc cur{};
+    if (active) {
+      cur = locate(blk_begin);
+      set_k(cur);
+      load_k<D>(kf, cur.k, koff);
+      set_v(cur);
+      load_v<D>(vr, cur.v, voff);
+    }
 
     // row of this lane in tile t: query row rr of the kv head's N*G rows = (node, head within group)
     struct RowInfo { bool exists, valid; int node; int64_t out; };
     auto row_info = [&](int t) {
       RowInfo ri;
       const int rr = slab * ROWS + 16 * t + col;
-      ri.node = rr / p.G;
+      ri.node = (int)div_magic((unsigned)rr, p.G, p.g_magic);
       const int hl = rr - ri.node * p.G;
       ri.exists = slab_live && rr < p.Nmax * p.G;
       ri.valid = ri.exists && ri.node < n;
       ri.out = ((int64_t)b * p.Nmax + ri.node) * p.Hq + g * p.G + hl;  // index of (b, node, h)
       return ri;
     };
-    auto mask_of_tile = [&](int t) -> uint64_t {
-      const RowInfo ri = row_info(t);
-      const uint64_t live_bits = (n >= 64) ? ~0ull : ((1ull << n) - 1ull);
-      return ri.valid ? (p.anc_mask[b * p.Nmax + ri.node] & live_bits) : 0ull;
-    };
     bf16x8 qf[kQInLds ? 1 : QT][KS];
+    uint64_t tree_mask[QT];  // ancestor words of the lane's rows, fetched up front (used by the tree blocks only)
 #pragma unroll
     for (int t = 0; t < QT; ++t) {
       const RowInfo ri = row_info(t);
       const __bf16* qrow = reinterpret_cast<const __bf16*>(p.q) + ri.out * D + 8 * g4;
+      const uint64_t live_bits = (n >= 64) ? ~0ull : ((1ull << n) - 1ull);
+      tree_mask[t] = ri.valid ? (p.anc_mask[b * p.Nmax + ri.node] & live_bits) : 0ull;
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) {
         bf16x8 zero;
@@ -356,6 +424,7 @@ __global__ __launch_bounds__(256, (QT <= 2 ? 2 : 1)) void tree_attn_bf16_kernel(
     auto q_frag = [&](int t, int ks) -> bf16x8 {
       if constexpr (kQInLds) return q_lds[(t * KS + ks) * 64]; else return qf[t][ks];
     };
+    auto mask_of_tile = [&](int t) -> uint64_t { return tree_mask[t]; };
 
     RowState<QT, D> st;
 #pragma unroll
@@ -366,97 +435,42 @@ __global__ __launch_bounds__(256, (QT <= 2 ? 2 : 1)) void tree_attn_bf16_kernel(
       for (int e = 0; e < DT; ++e) st.o[t][e] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
 
-    // the key-splitting wavefronts of a slab share the segment's blocks evenly
-    // interleaved: wavefront kp takes blocks kp, kp+KW, ... so that the workgroup as a whole walks
-    // one contiguous stretch of K and of V (neighbouring DRAM pages stay open)
-    const int blk_begin = seg_begin + kp;
-    const int blk_end = seg_begin + seg_count;
-
-    const __bf16* kc = reinterpret_cast<const __bf16*>(p.k_cache) + b * p.stride_batch + g * p.stride_head;
-    const __bf16* vc = reinterpret_cast<const __bf16*>(p.v_cache) + b * p.stride_batch + g * p.stride_head;
-    const __bf16* ktr = reinterpret_cast<const __bf16*>(p.k_tree) + ((int64_t)b * p.Nmax * p.Hkv + g) * D;
-    const __bf16* vtr = reinterpret_cast<const __bf16*>(p.v_tree) + ((int64_t)b * p.Nmax * p.Hkv + g) * D;
-
-    auto locate = [&](int blk) {
-      BlockSrc src;
-      if (blk < n_prefix_blocks) {
-        const int key0 = blk * kBlockKeys;
-        src.k = kc + (int64_t)key0 * p.stride_token;
-        src.v = vc + (int64_t)key0 * p.stride_token;
-        src.stride = p.stride_token;
-        src.nvalid = min(kBlockKeys, L - key0);
-        src.kind = src.nvalid == kBlockKeys ? 0 : 1;
-        src.tree_key0 = 0;
-      } else {
-        const int t0 = (blk - n_prefix_blocks) * kBlockKeys;
-        src.k = ktr + (int64_t)t0 * tree_stride;
-        src.v = vtr + (int64_t)t0 * tree_stride;
-        src.stride = tree_stride;
-        src.nvalid = min(kBlockKeys, n - t0);
-        src.kind = 2;
-        src.tree_key0 = t0;
-      }
-      return src;
-    };
-
-    // The stream. Small tiles (two wavefronts per SIMD): V of the current block is requested before
-    // its scores are formed, K of the next block right after them; one K and one V block in registers.
-    // Large tiles (one wavefront per SIMD): K of the next block is requested at the top of this one
-    // into a second buffer, V of the next block as soon as this block's V has been transposed, into
-    // the registers that frees. Full prefix blocks (all but the last three of a sequence) take a
-    // branch-free path with scalar bases; the ragged tail and the tree blocks take the general one.
-    if (slab_live && blk_begin < blk_end) {
-      // large row tiles run one wavefront per SIMD and have the registers to hold the next block's K
-      // while this block's is in use (requested a whole block ahead); small tiles reuse one buffer
-      bf16x8 kf[2][KS], kfn[kDeep ? 2 : 1][KS];
-      unsigned vr[8][D / 32];
-      BlockSrc cur = locate(blk_begin);
-      load_k<D>(kf, cur, col, g4);
-      if constexpr (kDeep) load_v<D>(vr, cur, col, g4);
+    if (active) {
       int blk = blk_begin;
-      const int full_end = min(blk_end, L / kBlockKeys);  // blocks below this index are full prefix blocks
-      if (blk + KW < full_end) {
-        unsigned koff[2], voff[8];
-        const unsigned row_bytes = (unsigned)p.stride_token * 2u;
-#pragma unroll
-        for (int kt = 0; kt < 2; ++kt) koff[kt] = (unsigned)(16 * kt + col) * row_bytes + 16u * g4;
-#pragma unroll
-        for (int j = 0; j < 8; ++j) voff[j] = (unsigned)key_of(g4, j) * row_bytes + (unsigned)(D / 8) * col;
-        const int64_t block_bytes = (int64_t)kBlockKeys * p.stride_token * 2;
-        const char* kb = reinterpret_cast<const char*>(kc) + (int64_t)blk * block_bytes;
-        const char* vb = reinterpret_cast<const char*>(vc) + (int64_t)blk * block_bytes;
-        BlockSrc full{};  // kind 0
-        for (; blk + KW < full_end; blk += KW) {
-          if constexpr (kQInLds) asm volatile("" ::: "memory");  // keep the Q reads inside the loop (they are the point)
-          if constexpr (kDeep) {
-            kb += block_bytes * KW;
-            vb += block_bytes * KW;
-            load_k_full<D>(kfn, kb, koff);
-            process_block<QT, D, true>(st, kf, vr, q_frag, full, mask_of_tile, c, g4, [] {},
-                                       [&] { load_v_full<D>(vr, vb, voff); });
+      if constexpr (kDeep) {
+        // long streams of full prefix blocks: a loop of its own with nothing in it but the steady state
+        // (the next block is a full block too, so bases advance by a constant and the offsets stay)
+        const int full_end = min(blk_end, L / kBlockKeys);
+        if (blk + KW < full_end) {
+          const int64_t step = (int64_t)kBlockKeys * cache_row_bytes * KW;
+          const char* kb = cur.k;
+          const char* vb = cur.v;
+          BlockSrc full{};  // kind 0
+          full.nvalid = kBlockKeys;
+          for (; blk + KW < full_end; blk += KW) {
+            asm volatile("" ::: "memory");  // keep the Q reads inside the loop (they are the point)
+            kb += step;
+            vb += step;
+            load_k<D>(kfn, kb, koff);
+            process_block<QT, D>(st, kf, vr, q_frag, full, mask_of_tile, c, g4, [] {},
+                                 [&] { load_v<D>(vr, vb, voff); });
 #pragma unroll
             for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
               for (int ks = 0; ks < KS; ++ks) kf[kt][ks] = kfn[kt][ks];
-          } else {
-            load_v_full<D>(vr, vb, voff);
-            kb += block_bytes * KW;
-            vb += block_bytes * KW;
-            process_block<QT, D, true>(st, kf, vr, q_frag, full, mask_of_tile, c, g4,
-                                       [&] { load_k_full<D>(kf, kb, koff); }, [] {});
           }
+          cur = locate(blk);
         }
-        cur = locate(blk);
       }
-      for (; blk < blk_end; blk += KW) {
-        if constexpr (kQInLds) asm volatile("" ::: "memory");
-        BlockSrc nxt = cur;
+      for (;; blk += KW) {
+        if constexpr (kQInLds) asm volatile("" ::: "memory");  // keep the Q reads inside the loop (they are the point)
         const bool more = blk + KW < blk_end;
+        BlockSrc nxt = cur;
         if (more) nxt = locate(blk + KW);
         if constexpr (kDeep) {
-          if (more) load_k<D>(kfn, nxt, col, g4);
-          process_block<QT, D, false>(st, kf, vr, q_frag, cur, mask_of_tile, c, g4, [] {},
-                                     [&] { if (more) load_v<D>(vr, nxt, col, g4); });
+          if (more) { set_k(nxt); load_k<D>(kfn, nxt.k, koff); }
+          process_block<QT, D>(st, kf, vr, q_frag, cur, mask_of_tile, c, g4, [] {},
+                               [&] { if (more) { set_v(nxt); load_v<D>(vr, nxt.v, voff); } });
           if (more) {
 #pragma unroll
             for (int kt = 0; kt < 2; ++kt)
@@ -464,10 +478,11 @@ __global__ __launch_bounds__(256, (QT <= 2 ? 2 : 1)) void tree_attn_bf16_kernel(
               for (int ks = 0; ks < KS; ++ks) kf[kt][ks] = kfn[kt][ks];
           }
         } else {
-          load_v<D>(vr, cur, col, g4);
-          process_block<QT, D, false>(st, kf, vr, q_frag, cur, mask_of_tile, c, g4,
-                                     [&] { if (more) load_k<D>(kf, nxt, col, g4); }, [] {});
+          process_block<QT, D>(st, kf, vr, q_frag, cur, mask_of_tile, c, g4,
+                               [&] { if (more) { set_k(nxt); load_k<D>(kf, nxt.k, koff); } }, [] {});
+          if (more) { set_v(nxt); load_v<D>(vr, nxt.v, voff); }
         }
+        if (!more) break;
         cur = nxt;
       }
     }
@@ -551,16 +566,19 @@ __global__ __launch_bounds__(256, (QT <= 2 ? 2 : 1)) void tree_attn_bf16_kernel(
         }
       }
     }
-    r += seg_count;
-    if (b + 1 < p.B && r >= p.bstart[b + 1]) ++b;
+    r += (unsigned)seg_count;
+    if (b + 1 < p.B && r >= (unsigned)p.bstart[b + 1]) ++b;
     if ((KW > 1 || kQInLds) && r < r1) __syncthreads();  // the LDS buffers are reused by the next segment
   }
 }
 
-// Workgroup that owns flat block x under the even split of T blocks over W workgroups.
-__device__ __forceinline__ int owner_of(int64_t x, int64_t T, int W) {
-  int w = (int)((x * W) / T);
-  if (((int64_t)(w + 1) * T) / W <= x) ++w;
+// Workgroup that owns flat block x under the even split: the w with first(w) <= x < first(w+1).
+// A float estimate (off by one at most for the sizes a launch can have) and a correction.
+__device__ __forceinline__ int owner_of(const AttnParams& p, unsigned x) {
+  int w = (int)((float)x * ((float)p.n_wgs / (float)p.total_blocks));
+  w = min(w, p.n_wgs - 1);
+  while (w > 0 && wg_first_block(p, (unsigned)w) > x) --w;
+  while (w + 1 < p.n_wgs && wg_first_block(p, (unsigned)w + 1u) <= x) ++w;
   return w;
 }
 
@@ -573,10 +591,10 @@ __global__ __launch_bounds__(256) void tree_attn_combine_kernel(const AttnParams
   const int unit = blockIdx.y;
   const int units_per_seq = p.Hkv * p.GY;
   const int b = unit / units_per_seq, ub = unit - b * units_per_seq;
-  const int g = ub / p.GY, y = ub - g * p.GY;
-  const int n_blocks = (int)((p.bstart[b + 1] - p.bstart[b]) / units_per_seq);
-  const int64_t fs = p.bstart[b] + (int64_t)ub * n_blocks;
-  const int w0 = owner_of(fs, p.total_blocks, p.n_wgs), w1 = owner_of(fs + n_blocks - 1, p.total_blocks, p.n_wgs);
+  const int g = (int)div_magic((unsigned)ub, p.GY, p.gy_magic), y = ub - g * p.GY;
+  const int n_blocks = (p.kv_len[b] + kBlockKeys - 1) / kBlockKeys + (p.n_nodes[b] + kBlockKeys - 1) / kBlockKeys;
+  const unsigned fs = (unsigned)p.bstart[b] + (unsigned)ub * (unsigned)n_blocks;
+  const int w0 = owner_of(p, fs), w1 = owner_of(p, fs + (unsigned)n_blocks - 1u);
   if (w0 == w1) return;  // written directly by the one workgroup that held the whole unit
   const int rows_per_unit = p.WS * rows_per_slab;
   const int lr = blockIdx.x * (256 / TPR) + threadIdx.x / TPR;
@@ -585,7 +603,7 @@ __global__ __launch_bounds__(256) void tree_attn_combine_kernel(const AttnParams
   const int slab_local = lr / rows_per_slab;
   const int rr = (y * p.WS + slab_local) * rows_per_slab + (lr - slab_local * rows_per_slab);
   if (rr >= p.Nmax * p.G) return;
-  const int node = rr / p.G, hl = rr - node * p.G;
+  const int node = (int)div_magic((unsigned)rr, p.G, p.g_magic), hl = rr - node * p.G;
   const int64_t row = ((int64_t)b * p.Nmax + node) * p.Hq + g * p.G + hl;
   f32x4 acc = {0.f, 0.f, 0.f, 0.f};
   if (node < p.n_nodes[b]) {
@@ -742,9 +760,11 @@ int blocks_of(int kv_len, int n_nodes) {
 
 // Workgroup count for `total_blocks` flat blocks in `units` units: two resident workgroups per
 // compute unit when the register budget allows it (one otherwise), but no workgroup with fewer
-// than 2 blocks per key-splitting wave. When all units are equally long and fill at least three
-// quarters of the resident slots by themselves, one workgroup per unit: nothing is cut, nothing
-// is merged, and that beats the better balance of a cut.
+// than 2 blocks per key-splitting wave. When all units are equally long, the count is a multiple
+// of the unit count whenever that still fills three quarters of the slots: every unit is then cut
+// into the same number of pieces and no workgroup straddles two units (a second segment costs a
+// short-lived workgroup as much as its blocks do). With one piece per unit nothing is cut and
+// nothing is merged.
 int plan_wgs(const Plan& pl, int64_t total_blocks, int64_t units, bool uniform) {
   const int KW = 4 / pl.WS;
   const int64_t resident = pl.QT <= 2 ? 512 : 256;
@@ -753,7 +773,14 @@ int plan_wgs(const Plan& pl, int64_t total_blocks, int64_t units, bool uniform) 
   if (wgs > cap) wgs = cap;
   if (uniform && units <= total_blocks) {
     const int64_t rounds = (units + resident - 1) / resident;
-    if (4 * units >= 3 * rounds * resident) wgs = units;
+    if (4 * units >= 3 * rounds * resident) {
+      wgs = units;
+    } else if (units <= resident) {
+      const int64_t blocks_per_unit = total_blocks / units;
+      int64_t pieces = (blocks_per_unit + 2 * KW - 1) / (2 * KW);
+      if (pieces > resident / units) pieces = resident / units;
+      if (pieces >= 1 && 4 * units * pieces >= 3 * wgs) wgs = units * pieces;
+    }
   }
   if (g_forced_wgs > 0) wgs = g_forced_wgs;
   if (wgs > total_blocks) wgs = total_blocks;
@@ -835,7 +862,7 @@ extern "C" fspad_status fspad_tree_attn(const fspad_attn_desc* desc, const void*
   if (max_len > 0) {
     if (!k_cache || !v_cache) return FSPAD_ERR_NULL;
     const int64_t align = 16 / esz;
-    if (d.cache_stride_token < d.head_dim || d.cache_stride_token % align || d.cache_stride_head % align ||
+    if (d.cache_stride_token < d.head_dim || d.cache_stride_token > (1ll << 26) || d.cache_stride_token % align || d.cache_stride_head % align ||
         d.cache_stride_batch % align || d.cache_stride_head < 0 || d.cache_stride_batch < 0)
       return FSPAD_ERR_SHAPE;
     if (((uintptr_t)k_cache | (uintptr_t)v_cache) & 15) return FSPAD_ERR_SHAPE;
@@ -851,11 +878,13 @@ extern "C" fspad_status fspad_tree_attn(const fspad_attn_desc* desc, const void*
   prm.out_bf16 = d.out_dtype == FSPAD_BF16;
   prm.scale = d.softmax_scale > 0.f ? d.softmax_scale : 1.0f / sqrtf((float)d.head_dim);
   prm.WS = 1; prm.NS = 1; prm.GY = 1;
+  prm.g_magic = prm.G > 1 ? (uint32_t)(((1ull << 32) + prm.G - 1) / prm.G) : 0u;
 
   Plan pl{};
   if (d.io_dtype == FSPAD_BF16) {
     plan_rows(d, pl);
     prm.WS = pl.WS; prm.NS = pl.NS; prm.GY = pl.GY;
+    prm.gy_magic = pl.GY > 1 ? (uint32_t)(((1ull << 32) + pl.GY - 1) / pl.GY) : 0u;
     prm.part = reinterpret_cast<float*>(workspace);
   }
 
@@ -881,16 +910,19 @@ extern "C" fspad_status fspad_tree_attn(const fspad_attn_desc* desc, const void*
       const int64_t units_per_seq = (int64_t)d.n_kv_heads * pl.GY;
       int64_t total = 0;
       for (int i = 0; i < nb; ++i) {
-        sl.bstart[i] = total;
+        sl.bstart[i] = (int32_t)total;
         total += units_per_seq * blocks_of(sl.kv_len[i], sl.n_nodes[i]);
+        if (total > kMaxFlatBlocks) return FSPAD_ERR_SHAPE;  // the kernels index blocks with 32 bits
       }
-      sl.bstart[nb] = total;
-      sl.total_blocks = total;
+      sl.bstart[nb] = (int32_t)total;
+      sl.total_blocks = (int32_t)total;
       bool uniform = true;
       for (int i = 1; i < nb; ++i)
         uniform = uniform && blocks_of(sl.kv_len[i], sl.n_nodes[i]) == blocks_of(sl.kv_len[0], sl.n_nodes[0]);
       const int64_t units = (int64_t)nb * units_per_seq;
       sl.n_wgs = plan_wgs(pl, total, units, uniform);
+      sl.wg_quot = (int32_t)(total / sl.n_wgs);
+      sl.wg_rem = (int32_t)(total % sl.n_wgs);
       const int64_t slots = units + sl.n_wgs;
       const size_t need = (size_t)slots * slot_bytes(d, pl);
       if (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 15)) return FSPAD_ERR_WORKSPACE;
