@@ -404,21 +404,34 @@ __global__ __launch_bounds__(256, (QT <= 2 ? 2 : 1)) void tree_attn_bf16_kernel(
       ri.out = ((int64_t)b * p.Nmax + ri.node) * p.Hq + g * p.G + hl;  // index of (b, node, h)
       return ri;
     };
+    // every load of the set-up is issued before the first value of any of them is needed (memory
+    // returns in order, so a wait for one is a wait for everything requested before it)
     bf16x8 qf[kQInLds ? 1 : QT][KS];
-    uint64_t tree_mask[QT];  // ancestor words of the lane's rows, fetched up front (used by the tree blocks only)
+    uint64_t tree_mask[QT];  // ancestor words of the lane's rows (used by the tree blocks only)
+    bf16x8 qtmp[kQInLds ? QT : 1][KS];
 #pragma unroll
     for (int t = 0; t < QT; ++t) {
       const RowInfo ri = row_info(t);
       const __bf16* qrow = reinterpret_cast<const __bf16*>(p.q) + ri.out * D + 8 * g4;
-      const uint64_t live_bits = (n >= 64) ? ~0ull : ((1ull << n) - 1ull);
-      tree_mask[t] = ri.valid ? (p.anc_mask[b * p.Nmax + ri.node] & live_bits) : 0ull;
+      tree_mask[t] = ri.valid ? p.anc_mask[b * p.Nmax + ri.node] : 0ull;
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) {
         bf16x8 zero;
 #pragma unroll
         for (int j = 0; j < 8; ++j) zero[j] = (__bf16)0.f;
         const bf16x8 frag = ri.valid ? *reinterpret_cast<const bf16x8*>(qrow + 32 * ks) : zero;
-        if constexpr (kQInLds) q_lds[(t * KS + ks) * 64] = frag; else qf[t][ks] = frag;
+        if constexpr (kQInLds) qtmp[t][ks] = frag; else qf[t][ks] = frag;
+      }
+    }
+    {
+      const uint64_t live_bits = (n >= 64) ? ~0ull : ((1ull << n) - 1ull);
+#pragma unroll
+      for (int t = 0; t < QT; ++t) {
+        tree_mask[t] &= live_bits;
+        if constexpr (kQInLds) {
+#pragma unroll
+          for (int ks = 0; ks < KS; ++ks) q_lds[(t * KS + ks) * 64] = qtmp[t][ks];
+        }
       }
     }
     auto q_frag = [&](int t, int ks) -> bf16x8 {
@@ -736,6 +749,7 @@ struct Plan {
   int64_t total_blocks;
 };
 
+constexpr int64_t kComputeUnits = 256;
 int g_forced_wgs = 0;
 int g_max_qt = 4;
 
@@ -760,11 +774,11 @@ int blocks_of(int kv_len, int n_nodes) {
 
 // Workgroup count for `total_blocks` flat blocks in `units` units: two resident workgroups per
 // compute unit when the register budget allows it (one otherwise), but no workgroup with fewer
-// than 2 blocks per key-splitting wave. When all units are equally long, the count is a multiple
-// of the unit count whenever that still fills three quarters of the slots: every unit is then cut
-// into the same number of pieces and no workgroup straddles two units (a second segment costs a
-// short-lived workgroup as much as its blocks do). With one piece per unit nothing is cut and
-// nothing is merged.
+// than 2 blocks per key-splitting wave. When all units are equally long and short (a few blocks
+// per wave), the count is a multiple of the unit count whenever that still fills three quarters of
+// the compute units: every unit is then cut into the same number of pieces and no workgroup
+// straddles two units (a second segment costs a short-lived workgroup as much as its blocks do).
+// With one piece per unit nothing is cut and nothing is merged.
 int plan_wgs(const Plan& pl, int64_t total_blocks, int64_t units, bool uniform) {
   const int KW = 4 / pl.WS;
   const int64_t resident = pl.QT <= 2 ? 512 : 256;
@@ -775,11 +789,14 @@ int plan_wgs(const Plan& pl, int64_t total_blocks, int64_t units, bool uniform) 
     const int64_t rounds = (units + resident - 1) / resident;
     if (4 * units >= 3 * rounds * resident) {
       wgs = units;
-    } else if (units <= resident) {
+    } else if (units <= kComputeUnits) {
+      // short units: one workgroup per compute unit at most, since a second one on the same unit
+      // shares its instruction issue and finishes last
       const int64_t blocks_per_unit = total_blocks / units;
       int64_t pieces = (blocks_per_unit + 2 * KW - 1) / (2 * KW);
-      if (pieces > resident / units) pieces = resident / units;
-      if (pieces >= 1 && 4 * units * pieces >= 3 * wgs) wgs = units * pieces;
+      if (pieces > kComputeUnits / units) pieces = kComputeUnits / units;
+      const bool short_pieces = pieces >= 1 && blocks_per_unit <= 4 * KW * pieces;  // at most 4 blocks per wave
+      if (short_pieces && 4 * units * pieces >= 3 * (wgs < kComputeUnits ? wgs : kComputeUnits)) wgs = units * pieces;
     }
   }
   if (g_forced_wgs > 0) wgs = g_forced_wgs;
