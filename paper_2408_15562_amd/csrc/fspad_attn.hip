@@ -46,6 +46,7 @@ struct AttnParams {
   int64_t stride_batch, stride_head, stride_token;  // cache strides, elements
   int32_t B, Nmax, Hq, Hkv, G;
   int32_t WS;       // row slabs per workgroup: 1, 2 or 4 (4/WS wavefronts share a slab and split its keys)
+  int32_t ws_shift; // log2(WS)
   int32_t NS;       // row slabs per kv head
   int32_t GY;       // slab groups per kv head: a (sequence, kv head, slab group) is one unit of work
   int32_t n_wgs;    // workgroups of the flat decomposition
@@ -56,7 +57,7 @@ struct AttnParams {
   float scale;      // softmax scale
   int32_t kv_len[kMaxBatchPerLaunch];
   int32_t bstart[kMaxBatchPerLaunch + 1];  // first flat block of each sequence; bstart[B] = total_blocks
-  uint8_t n_nodes[kMaxBatchPerLaunch];
+  int32_t n_nodes[kMaxBatchPerLaunch];
 };
 
 // x / d for x*d < 2^32, with magic = ceil(2^32 / d) (d >= 2) from the host
@@ -275,17 +276,17 @@ __global__ __launch_bounds__(256, (QT <= 2 ? 2 : 1)) void tree_attn_bf16_kernel(
   constexpr int KS = D / 32;
   constexpr int DT = D / 16;
   constexpr int ROWS = 16 * QT;
-  // merge buffers: 3 wavefronts x (QT*DT accumulators + QT stats) x 64 lanes. With large row tiles
+  // merge buffers: 4 wavefronts x (QT*DT accumulators + QT stats) x 64 lanes. With large row tiles
   // the Q fragments of the 4 wavefronts live in lane-private LDS slots instead of registers; they are
   // dead once a segment's stream is done, so they share the space of the merge buffers.
   constexpr bool kQInLds = QT >= 3;
   // Tiles done in several passes run one wavefront per SIMD: they hide the memory latency by
   // themselves, keeping K and V of the next block in flight for a whole block
   constexpr bool kDeep = QT >= 3;
-  constexpr int kMergeBytes = 3 * QT * DT * 64 * 16;
+  constexpr int kMergeBytes = 4 * QT * DT * 64 * 16;
   constexpr int kQBytes = kQInLds ? 4 * QT * KS * 64 * 16 : 0;
   __shared__ __attribute__((aligned(16))) char lds_raw[kMergeBytes > kQBytes ? kMergeBytes : kQBytes];
-  __shared__ float2 merge_ml[3][QT][64];
+  __shared__ float2 merge_ml[4][QT][64];
   typedef f32x4 (*MergeO)[QT * DT][64];
   MergeO merge_o = reinterpret_cast<MergeO>(lds_raw);
 
@@ -295,8 +296,8 @@ __global__ __launch_bounds__(256, (QT <= 2 ? 2 : 1)) void tree_attn_bf16_kernel(
   const int col = lane & 15, g4 = lane >> 4;
   bf16x8* q_lds = reinterpret_cast<bf16x8*>(lds_raw) + wave * (QT * KS * 64) + lane;
   const int slab_local = wave & (p.WS - 1);
-  const int KW = 4 / p.WS;  // wavefronts that split the keys of one slab
-  const int kp = wave / p.WS;
+  const int KW = 4 >> p.ws_shift;  // wavefronts that split the keys of one slab
+  const int kp = wave >> p.ws_shift;
   const float c = p.scale * kLog2e;
   const unsigned tree_row_bytes = (unsigned)p.Hkv * D * 2u;
   const unsigned cache_row_bytes = (unsigned)p.stride_token * 2u;
@@ -306,7 +307,10 @@ __global__ __launch_bounds__(256, (QT <= 2 ? 2 : 1)) void tree_attn_bf16_kernel(
   // index arithmetic up to the first loads is 32-bit, and divisions by the launch's constants
   // are multiplications.
   const unsigned w = blockIdx.x;
-  const unsigned r0 = wg_first_block(p, w), r1 = wg_first_block(p, w + 1);
+  // [r0, r1) = [floor(w*T/W), floor((w+1)*T/W)) with T = wg_quot*W + wg_rem, from one division
+  const unsigned wr = w * (unsigned)p.wg_rem, wq = wr / (unsigned)p.n_wgs;
+  const unsigned r0 = w * (unsigned)p.wg_quot + wq;
+  const unsigned r1 = r0 + (unsigned)p.wg_quot + ((wr - wq * (unsigned)p.n_wgs) + (unsigned)p.wg_rem >= (unsigned)p.n_wgs ? 1u : 0u);
   int b = 0;
   while (b + 1 < p.B && r0 >= (unsigned)p.bstart[b + 1]) ++b;
 
@@ -503,81 +507,80 @@ __global__ __launch_bounds__(256, (QT <= 2 ? 2 : 1)) void tree_attn_bf16_kernel(
 #pragma unroll
     for (int t = 0; t < QT; ++t) lsum[t] = st.l[t][0];
 
-    // merge the key-splitting wavefronts of a slab through LDS (lane-private slots)
-    if (KW > 1) {
-      if (kQInLds) __syncthreads();  // every wavefront is done with its Q slots before they are overwritten
-      if (kp > 0) {
-        const int slot = (kp - 1) * p.WS + slab_local;
+    // Writes 4 consecutive d-tiles (e0..e0+3) of row tile t: final rows when the segment is the whole
+    // unit, a partial slot otherwise. o4[j][i] belongs to dim DT*(4*g4+i)+e0+j of row 16*t+col.
+    auto write_quad = [&](int t, int e0, const f32x4 (&o4)[4], float m_row, float l_row) {
+      const RowInfo ri = row_info(t);
+      if (!ri.exists) return;
+      if (whole_unit) {
+        const float inv = ri.valid ? 1.0f / l_row : 0.f;
 #pragma unroll
-        for (int t = 0; t < QT; ++t) {
-          merge_ml[slot][t][lane] = make_float2(st.m[t], lsum[t]);
+        for (int i = 0; i < 4; ++i) {
+          const int d0 = DT * (4 * g4 + i) + e0;
+          float vals[4];
 #pragma unroll
-          for (int e = 0; e < DT; ++e) merge_o[slot][t * DT + e][lane] = st.o[t][e];
-        }
-      }
-      __syncthreads();
-      if (kp == 0) {
-        for (int other = 1; other < KW; ++other) {
-          const int slot = (other - 1) * p.WS + slab_local;
+          for (int j = 0; j < 4; ++j) vals[j] = ri.valid ? o4[j][i] * inv : 0.f;
+          if (p.out_bf16) {
+            typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+            bf16x4 pk;
 #pragma unroll
-          for (int t = 0; t < QT; ++t) {
-            const float2 ml = merge_ml[slot][t][lane];
-            const float mm = fmaxf(st.m[t], ml.x);
-            const float a0 = __builtin_amdgcn_exp2f(st.m[t] - mm), a1 = __builtin_amdgcn_exp2f(ml.x - mm);
-            st.m[t] = mm;
-            lsum[t] = lsum[t] * a0 + ml.y * a1;
-#pragma unroll
-            for (int e = 0; e < DT; ++e) st.o[t][e] = st.o[t][e] * a0 + merge_o[slot][t * DT + e][lane] * a1;
+            for (int j = 0; j < 4; ++j) pk[j] = (__bf16)vals[j];
+            *reinterpret_cast<bf16x4*>(reinterpret_cast<__bf16*>(p.out) + ri.out * D + d0) = pk;
+          } else {
+            *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(p.out) + ri.out * D + d0) =
+                f32x4{vals[0], vals[1], vals[2], vals[3]};
           }
         }
+      } else if (ri.valid) {
+        float* slot = p.part + (int64_t)(unit + w) * rows_per_unit * (D + 2);
+        const int lr = slab_local * ROWS + 16 * t + col;
+        if (g4 == 0 && e0 == 0) *reinterpret_cast<float2*>(slot + (int64_t)rows_per_unit * D + 2 * lr) = make_float2(m_row, l_row);
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          *reinterpret_cast<f32x4*>(slot + (int64_t)lr * D + DT * (4 * g4 + i) + e0) =
+              f32x4{o4[0][i], o4[1][i], o4[2][i], o4[3][i]};
       }
-    }
+    };
 
-    // write: final rows when the segment is the whole unit, a partial slot otherwise
-    if (kp == 0) {
+    if (KW > 1) {
+      // The key-splitting wavefronts of a slab leave their states in lane-private LDS slots; after one
+      // barrier each of them reduces and writes its own share of the (row tile, 4 d-tiles) quads, so
+      // the tail of a short-lived workgroup is spread over all its wavefronts.
+      if (kQInLds) __syncthreads();  // every wavefront is done with its Q slots before they are overwritten
 #pragma unroll
       for (int t = 0; t < QT; ++t) {
-        const RowInfo ri = row_info(t);
-        if (!ri.exists) continue;
-        if (whole_unit) {
-          const float inv = ri.valid ? 1.0f / lsum[t] : 0.f;
+        merge_ml[wave][t][lane] = make_float2(st.m[t], lsum[t]);
 #pragma unroll
-          for (int i = 0; i < 4; ++i) {
-            const int d0 = DT * (4 * g4 + i);
-            float vals[DT];
-#pragma unroll
-            for (int e = 0; e < DT; ++e) vals[e] = ri.valid ? st.o[t][e][i] * inv : 0.f;
-            if (p.out_bf16) {
-              __bf16* dst = reinterpret_cast<__bf16*>(p.out) + ri.out * D + d0;
-              if constexpr (DT == 8) {
-                bf16x8 pk;
-#pragma unroll
-                for (int e = 0; e < 8; ++e) pk[e] = (__bf16)vals[e];
-                *reinterpret_cast<bf16x8*>(dst) = pk;
-              } else {
-#pragma unroll
-                for (int e = 0; e < DT; ++e) dst[e] = (__bf16)vals[e];
-              }
-            } else {
-              float* dst = reinterpret_cast<float*>(p.out) + ri.out * D + d0;
-#pragma unroll
-              for (int e = 0; e < DT; e += 4)
-                *reinterpret_cast<f32x4*>(dst + e) = f32x4{vals[e], vals[e + 1], vals[e + 2], vals[e + 3]};
-            }
-          }
-        } else if (ri.valid) {
-          float* slot = p.part + (int64_t)(unit + w) * rows_per_unit * (D + 2);
-          const int lr = slab_local * ROWS + 16 * t + col;
-          if (g4 == 0) *reinterpret_cast<float2*>(slot + (int64_t)rows_per_unit * D + 2 * lr) = make_float2(st.m[t], lsum[t]);
-#pragma unroll
-          for (int i = 0; i < 4; ++i) {
-            float* dst = slot + (int64_t)lr * D + DT * (4 * g4 + i);
-#pragma unroll
-            for (int e = 0; e < DT; e += 4)
-              *reinterpret_cast<f32x4*>(dst + e) = f32x4{st.o[t][e][i], st.o[t][e + 1][i], st.o[t][e + 2][i], st.o[t][e + 3][i]};
-          }
-        }
+        for (int e = 0; e < DT; ++e) merge_o[wave][t * DT + e][lane] = st.o[t][e];
       }
+      __syncthreads();
+      constexpr int kQuadsPerTile = DT / 4;
+      for (int q = kp; q < QT * kQuadsPerTile; q += KW) {
+        const int t = q / kQuadsPerTile, e0 = 4 * (q - t * kQuadsPerTile);
+        float mm = kNegBig;
+        for (int k = 0; k < KW; ++k) mm = fmaxf(mm, merge_ml[slab_local + k * p.WS][t][lane].x);
+        float l_row = 0.f;
+        f32x4 o4[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) o4[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int k = 0; k < KW; ++k) {  // in wavefront order: deterministic
+          const int peer = slab_local + k * p.WS;
+          const float2 ml = merge_ml[peer][t][lane];
+          const float a = __builtin_amdgcn_exp2f(ml.x - mm);
+          l_row += ml.y * a;
+#pragma unroll
+          for (int j = 0; j < 4; ++j) o4[j] += merge_o[peer][t * DT + e0 + j][lane] * a;
+        }
+        write_quad(t, e0, o4, mm, l_row);
+      }
+    } else {
+#pragma unroll
+      for (int t = 0; t < QT; ++t)
+#pragma unroll
+        for (int e0 = 0; e0 < DT; e0 += 4) {
+          const f32x4 o4[4] = {st.o[t][e0], st.o[t][e0 + 1], st.o[t][e0 + 2], st.o[t][e0 + 3]};
+          write_quad(t, e0, o4, st.m[t], lsum[t]);
+        }
     }
     r += (unsigned)seg_count;
     if (b + 1 < p.B && r >= (unsigned)p.bstart[b + 1]) ++b;
@@ -901,6 +904,7 @@ extern "C" fspad_status fspad_tree_attn(const fspad_attn_desc* desc, const void*
   if (d.io_dtype == FSPAD_BF16) {
     plan_rows(d, pl);
     prm.WS = pl.WS; prm.NS = pl.NS; prm.GY = pl.GY;
+    prm.ws_shift = pl.WS == 4 ? 2 : (pl.WS == 2 ? 1 : 0);
     prm.gy_magic = pl.GY > 1 ? (uint32_t)(((1ull << 32) + pl.GY - 1) / pl.GY) : 0u;
     prm.part = reinterpret_cast<float*>(workspace);
   }
@@ -922,7 +926,7 @@ extern "C" fspad_status fspad_tree_attn(const fspad_attn_desc* desc, const void*
     }
     sl.anc_mask = anc_mask + (size_t)b0 * d.n_nodes_max;
     sl.out = static_cast<char*>(out) + q_rows * (d.out_dtype == FSPAD_BF16 ? 2 : 4);
-    for (int i = 0; i < nb; ++i) { sl.kv_len[i] = kv_len[b0 + i]; sl.n_nodes[i] = (uint8_t)n_nodes[b0 + i]; }
+    for (int i = 0; i < nb; ++i) { sl.kv_len[i] = kv_len[b0 + i]; sl.n_nodes[i] = n_nodes[b0 + i]; }
     if (d.io_dtype == FSPAD_BF16) {
       const int64_t units_per_seq = (int64_t)d.n_kv_heads * pl.GY;
       int64_t total = 0;
