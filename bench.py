@@ -36,6 +36,7 @@ def parse_args():
     ap.add_argument("--splits", type=int, default=0, help="force the number of attention workgroups (0 = automatic)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--max-qt", type=int, default=0, help=argparse.SUPPRESS)
+    ap.add_argument("--max-ws", type=int, default=0, help=argparse.SUPPRESS)
     ap.add_argument("--accept-target", type=int, default=0, help=argparse.SUPPRESS)
     ap.add_argument("--layers", type=int, default=None, help="profiling only: run fewer layers of a stack (the result line is then not the workload's)")
     ap.add_argument("--nodes", type=int, default=None, help="experiments only: override the tree size")
@@ -119,6 +120,9 @@ def main():
     if args.accept_target:
         import ctypes
         ctypes.CDLL(fspad.library_path()).fspad_debug_set_accept_target(args.accept_target)
+    if args.max_ws:
+        import ctypes
+        ctypes.CDLL(fspad.library_path()).fspad_debug_set_max_ws(args.max_ws)
     if args.max_qt:
         import ctypes
         ctypes.CDLL(fspad.library_path()).fspad_debug_set_max_qt(args.max_qt)

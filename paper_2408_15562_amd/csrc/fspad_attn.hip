@@ -753,17 +753,21 @@ struct Plan {
 };
 
 constexpr int64_t kComputeUnits = 256;
+constexpr int64_t kShortStreamBlocks = 16;  // blocks per workgroup below which a stream counts as short
 int g_forced_wgs = 0;
 int g_max_qt = 4;
+int g_max_ws = 4;
 
 // Row tiling of one kv head's N*G query rows: slabs of 16*QT rows, WS slabs per workgroup.
-void plan_rows(const fspad_attn_desc& d, Plan& pl) {
+void plan_rows(const fspad_attn_desc& d, Plan& pl, int max_ws = 4) {
   const int G = d.n_q_heads / d.n_kv_heads;
   const int rows = d.n_nodes_max * G;
   int best_cost = 1 << 30;
   for (int qt = g_max_qt; qt >= 1; --qt) {  // ties go to the larger tile: fewer re-reads of K/V
     const int ns = (rows + 16 * qt - 1) / (16 * qt);
-    const int ws = ns == 1 ? 1 : (ns == 2 ? 2 : 4);
+    int ws = ns == 1 ? 1 : (ns == 2 ? 2 : 4);
+    if (ws > g_max_ws) ws = g_max_ws;
+    if (ws > max_ws) ws = max_ws;
     const int gy = (ns + ws - 1) / ws;
     const int cost = gy * ws * qt;
     if (cost < best_cost) { best_cost = cost; pl.QT = qt; pl.NS = ns; pl.WS = ws; pl.GY = gy; }
@@ -842,6 +846,7 @@ void launch_bf16(const Plan& pl, const AttnParams& prm, hipStream_t stream) {
 
 }  // namespace
 
+extern "C" void fspad_debug_set_max_ws(int32_t ws) { g_max_ws = ws >= 4 ? 4 : (ws >= 2 ? 2 : 1); }
 extern "C" void fspad_debug_set_max_qt(int32_t qt) { g_max_qt = qt < 1 ? 1 : (qt > 4 ? 4 : qt); }
 
 extern "C" void fspad_tree_attn_set_workgroups(int32_t workgroups) {
@@ -851,17 +856,23 @@ extern "C" void fspad_tree_attn_set_workgroups(int32_t workgroups) {
 extern "C" size_t fspad_tree_attn_workspace_bytes(const fspad_attn_desc* desc, int32_t max_kv_len) {
   if (check_desc(desc) != FSPAD_OK || max_kv_len < 0) return 0;
   if (desc->io_dtype == FSPAD_F32) return 16;
-  Plan pl{};
-  plan_rows(*desc, pl);
-  // one partial slot per (unit, workgroup) boundary at most: units + workgroups of the largest slice
-  const int nb = desc->batch < kMaxBatchPerLaunch ? desc->batch : kMaxBatchPerLaunch;
-  const int64_t units = (int64_t)nb * desc->n_kv_heads * pl.GY;
-  const int64_t total = units * blocks_of(max_kv_len, desc->n_nodes_max);
-  int64_t wgs = plan_wgs(pl, total, units, true);
-  const int64_t wgs_cut = plan_wgs(pl, total, units, false);  // a ragged batch of the same size
-  if (wgs_cut > wgs) wgs = wgs_cut;
-  const int64_t slots = units + wgs;
-  return (size_t)slots * slot_bytes(*desc, pl);
+  // one partial slot per (unit, workgroup) boundary at most: units + workgroups of the largest slice;
+  // the call may settle on either slab count (see kShortStreamBlocks), so both are sized
+  size_t need = 0;
+  for (int max_ws = 4; max_ws >= 2; max_ws -= 2) {
+    Plan pl{};
+    plan_rows(*desc, pl, max_ws);
+    const int nb = desc->batch < kMaxBatchPerLaunch ? desc->batch : kMaxBatchPerLaunch;
+    const int64_t units = (int64_t)nb * desc->n_kv_heads * pl.GY;
+    const int64_t total = units * blocks_of(max_kv_len, desc->n_nodes_max);
+    int64_t wgs = plan_wgs(pl, total, units, true);
+    const int64_t wgs_cut = plan_wgs(pl, total, units, false);  // a ragged batch of the same size
+    if (wgs_cut > wgs) wgs = wgs_cut;
+    const int64_t slots = units + wgs;
+    const size_t bytes = (size_t)slots * slot_bytes(*desc, pl);
+    if (bytes > need) need = bytes;
+  }
+  return need;
 }
 
 extern "C" fspad_status fspad_tree_attn(const fspad_attn_desc* desc, const void* q, const void* k_tree,
@@ -900,14 +911,7 @@ extern "C" fspad_status fspad_tree_attn(const fspad_attn_desc* desc, const void*
   prm.WS = 1; prm.NS = 1; prm.GY = 1;
   prm.g_magic = prm.G > 1 ? (uint32_t)(((1ull << 32) + prm.G - 1) / prm.G) : 0u;
 
-  Plan pl{};
-  if (d.io_dtype == FSPAD_BF16) {
-    plan_rows(d, pl);
-    prm.WS = pl.WS; prm.NS = pl.NS; prm.GY = pl.GY;
-    prm.ws_shift = pl.WS == 4 ? 2 : (pl.WS == 2 ? 1 : 0);
-    prm.gy_magic = pl.GY > 1 ? (uint32_t)(((1ull << 32) + pl.GY - 1) / pl.GY) : 0u;
-    prm.part = reinterpret_cast<float*>(workspace);
-  }
+  if (d.io_dtype == FSPAD_BF16) prm.part = reinterpret_cast<float*>(workspace);
 
   // sequences are independent: slices of at most kMaxBatchPerLaunch sequences per launch (the
   // per-sequence lengths travel as kernel arguments), each slice reusing the workspace in stream order
@@ -928,6 +932,25 @@ extern "C" fspad_status fspad_tree_attn(const fspad_attn_desc* desc, const void*
     sl.out = static_cast<char*>(out) + q_rows * (d.out_dtype == FSPAD_BF16 ? 2 : 4);
     for (int i = 0; i < nb; ++i) { sl.kv_len[i] = kv_len[b0 + i]; sl.n_nodes[i] = n_nodes[b0 + i]; }
     if (d.io_dtype == FSPAD_BF16) {
+      bool uniform = true;
+      int64_t seq_blocks = 0;
+      for (int i = 0; i < nb; ++i) {
+        uniform = uniform && blocks_of(sl.kv_len[i], sl.n_nodes[i]) == blocks_of(sl.kv_len[0], sl.n_nodes[0]);
+        seq_blocks += blocks_of(sl.kv_len[i], sl.n_nodes[i]);
+      }
+      // Four row slabs per workgroup share every K/V block between its four wavefronts, but the
+      // partial results of a cut unit grow with the rows a workgroup holds. With short streams
+      // (few blocks per workgroup) those partials outweigh the K/V bytes: two slabs then.
+      Plan pl{};
+      plan_rows(d, pl);
+      if (pl.WS == 4) {
+        const int64_t units4 = (int64_t)nb * d.n_kv_heads * pl.GY;
+        const int64_t total4 = (int64_t)d.n_kv_heads * pl.GY * seq_blocks;
+        if (total4 < kShortStreamBlocks * plan_wgs(pl, total4, units4, uniform)) plan_rows(d, pl, 2);
+      }
+      sl.WS = pl.WS; sl.NS = pl.NS; sl.GY = pl.GY;
+      sl.ws_shift = pl.WS == 4 ? 2 : (pl.WS == 2 ? 1 : 0);
+      sl.gy_magic = pl.GY > 1 ? (uint32_t)(((1ull << 32) + pl.GY - 1) / pl.GY) : 0u;
       const int64_t units_per_seq = (int64_t)d.n_kv_heads * pl.GY;
       int64_t total = 0;
       for (int i = 0; i < nb; ++i) {
@@ -937,9 +960,6 @@ extern "C" fspad_status fspad_tree_attn(const fspad_attn_desc* desc, const void*
       }
       sl.bstart[nb] = (int32_t)total;
       sl.total_blocks = (int32_t)total;
-      bool uniform = true;
-      for (int i = 1; i < nb; ++i)
-        uniform = uniform && blocks_of(sl.kv_len[i], sl.n_nodes[i]) == blocks_of(sl.kv_len[0], sl.n_nodes[0]);
       const int64_t units = (int64_t)nb * units_per_seq;
       sl.n_wgs = plan_wgs(pl, total, units, uniform);
       sl.wg_quot = (int32_t)(total / sl.n_wgs);
