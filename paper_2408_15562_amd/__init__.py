@@ -9,6 +9,7 @@ from .binding import (  # noqa: F401
     FSPAD_F32,
     FSPAD_MAX_NODES,
     FspadError,
+    PreparedCall,
     fspad_attn_desc,
     fspad_kv_commit,
     fspad_status_string,

@@ -90,6 +90,28 @@ def _check(status: int, where: str):
         raise FspadError(status, where)
 
 
+class PreparedCall:
+    """One library call with its arguments already marshalled: calling it issues exactly that call
+    again (same buffers, same stream). For loops that repeat a call, so that Python's argument
+    checks are paid once. Holds references to every tensor and host array it points into."""
+
+    __slots__ = ("_fn", "_where", "_args", "_keep", "result")
+
+    def __init__(self, fn, where, args, keep, result):
+        self._fn, self._where, self._args, self._keep, self.result = fn, where, args, keep, result
+
+    def __call__(self):
+        st = self._fn(*self._args)
+        if st != FSPAD_OK:
+            raise FspadError(st, self._where)
+        return self.result
+
+
+def _issue(fn, where, args, keep, result, prepare):
+    call = PreparedCall(fn, where, args, keep, result)
+    return call if prepare else call()
+
+
 def _dev_ptr(t: Optional[torch.Tensor], name: str, dtype=None) -> Optional[int]:
     if t is None:
         return None
@@ -156,10 +178,10 @@ def fspad_tree_attn(q: torch.Tensor, k_tree: torch.Tensor, v_tree: torch.Tensor,
                     kv_len, n_nodes, anc_mask: torch.Tensor, out: Optional[torch.Tensor] = None,
                     workspace: Optional[torch.Tensor] = None, softmax_scale: float = 0.0,
                     out_dtype: Optional[torch.dtype] = None, stream=None,
-                    desc: Optional[fspad_attn_desc] = None) -> torch.Tensor:
+                    desc: Optional[fspad_attn_desc] = None, prepare: bool = False):
     """q [B,Nmax,Hq,D]; k_tree,v_tree [B,Nmax,Hkv,D]; k_cache,v_cache [B,Hkv,Lcap,D] views (any
     batch/head/token strides); kv_len,n_nodes HOST int32 [B]; anc_mask device int64/uint64 [B,Nmax].
-    Returns out [B,Nmax,Hq,D]."""
+    Returns out [B,Nmax,Hq,D]; with prepare=True a PreparedCall that issues the call each time it is called."""
     for name, t in (("q", q), ("k_tree", k_tree), ("v_tree", v_tree)):
         if not t.is_contiguous():
             raise ValueError(f"{name} must be contiguous")
@@ -181,13 +203,12 @@ def fspad_tree_attn(q: torch.Tensor, k_tree: torch.Tensor, v_tree: torch.Tensor,
     if workspace is None:
         need = fspad_tree_attn_workspace_bytes(desc, int(kv_len.max(initial=0)))
         workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=q.device)
-    st = _lib().fspad_tree_attn(
-        ctypes.byref(desc), _dev_ptr(q, "q"), _dev_ptr(k_tree, "k_tree"), _dev_ptr(v_tree, "v_tree"),
-        _dev_ptr(k_cache, "k_cache"), _dev_ptr(v_cache, "v_cache"),
-        kv_len.ctypes.data, n_nodes.ctypes.data, _dev_ptr(anc_mask, "anc_mask"), _dev_ptr(out, "out"),
-        _dev_ptr(workspace, "workspace"), workspace.numel() * workspace.element_size(), _stream_ptr(stream))
-    _check(st, "fspad_tree_attn")
-    return out
+    args = (ctypes.byref(desc), _dev_ptr(q, "q"), _dev_ptr(k_tree, "k_tree"), _dev_ptr(v_tree, "v_tree"),
+            _dev_ptr(k_cache, "k_cache"), _dev_ptr(v_cache, "v_cache"),
+            kv_len.ctypes.data, n_nodes.ctypes.data, _dev_ptr(anc_mask, "anc_mask"), _dev_ptr(out, "out"),
+            _dev_ptr(workspace, "workspace"), workspace.numel() * workspace.element_size(), _stream_ptr(stream))
+    keep = (desc, q, k_tree, v_tree, k_cache, v_cache, kv_len, n_nodes, anc_mask, out, workspace)
+    return _issue(_lib().fspad_tree_attn, "fspad_tree_attn", args, keep, out, prepare)
 
 
 def fspad_tree_accept_workspace_bytes(B: int, Nmax: int, V: int) -> int:
@@ -215,42 +236,44 @@ def _accept_common(logits, draft_tokens, parent, n_nodes, workspace):
 
 def fspad_tree_accept_greedy(logits: torch.Tensor, draft_tokens: torch.Tensor, parent: torch.Tensor,
                              n_nodes: torch.Tensor, outputs=None, workspace: Optional[torch.Tensor] = None,
-                             stream=None):
-    """All tensors on the device. Returns (path [B,Nmax], path_len [B], tokens [B,Nmax], n_tokens [B])."""
+                             stream=None, prepare: bool = False):
+    """All tensors on the device. Returns (path [B,Nmax], path_len [B], tokens [B,Nmax], n_tokens [B]);
+    with prepare=True a PreparedCall."""
     B, Nmax, V, workspace = _accept_common(logits, draft_tokens, parent, n_nodes, workspace)
     path, path_len, tokens, n_tokens = _accept_outputs(B, Nmax, logits.device, outputs)
-    st = _lib().fspad_tree_accept_greedy(
-        B, Nmax, V, _dev_ptr(logits, "logits", torch.float32), logits.stride(1),
-        _dev_ptr(draft_tokens, "draft_tokens"), _dev_ptr(parent, "parent"), _dev_ptr(n_nodes, "n_nodes"),
-        _dev_ptr(path, "path"), _dev_ptr(path_len, "path_len"), _dev_ptr(tokens, "tokens"),
-        _dev_ptr(n_tokens, "n_tokens"), _dev_ptr(workspace, "workspace"),
-        workspace.numel() * workspace.element_size(), _stream_ptr(stream))
-    _check(st, "fspad_tree_accept_greedy")
-    return path, path_len, tokens, n_tokens
+    args = (B, Nmax, V, _dev_ptr(logits, "logits", torch.float32), logits.stride(1),
+            _dev_ptr(draft_tokens, "draft_tokens"), _dev_ptr(parent, "parent"), _dev_ptr(n_nodes, "n_nodes"),
+            _dev_ptr(path, "path"), _dev_ptr(path_len, "path_len"), _dev_ptr(tokens, "tokens"),
+            _dev_ptr(n_tokens, "n_tokens"), _dev_ptr(workspace, "workspace"),
+            workspace.numel() * workspace.element_size(), _stream_ptr(stream))
+    keep = (logits, draft_tokens, parent, n_nodes, workspace)
+    return _issue(_lib().fspad_tree_accept_greedy, "fspad_tree_accept_greedy", args, keep,
+                  (path, path_len, tokens, n_tokens), prepare)
 
 
 def fspad_tree_accept_sample(logits: torch.Tensor, draft_tokens: torch.Tensor, parent: torch.Tensor,
                              n_nodes: torch.Tensor, temperature: float, uniforms: torch.Tensor, outputs=None,
-                             workspace: Optional[torch.Tensor] = None, stream=None):
-    """uniforms: device fp32 [B,2,Nmax] in [0,1). Returns (path, path_len, tokens, n_tokens)."""
+                             workspace: Optional[torch.Tensor] = None, stream=None, prepare: bool = False):
+    """uniforms: device fp32 [B,2,Nmax] in [0,1). Returns (path, path_len, tokens, n_tokens); with
+    prepare=True a PreparedCall."""
     B, Nmax, V, workspace = _accept_common(logits, draft_tokens, parent, n_nodes, workspace)
     if uniforms.dtype != torch.float32 or not uniforms.is_contiguous() or tuple(uniforms.shape) != (B, 2, Nmax):
         raise ValueError("uniforms must be a contiguous fp32 [B,2,Nmax] device tensor")
     path, path_len, tokens, n_tokens = _accept_outputs(B, Nmax, logits.device, outputs)
-    st = _lib().fspad_tree_accept_sample(
-        B, Nmax, V, _dev_ptr(logits, "logits", torch.float32), logits.stride(1),
-        _dev_ptr(draft_tokens, "draft_tokens"), _dev_ptr(parent, "parent"), _dev_ptr(n_nodes, "n_nodes"),
-        float(temperature), _dev_ptr(uniforms, "uniforms"),
-        _dev_ptr(path, "path"), _dev_ptr(path_len, "path_len"), _dev_ptr(tokens, "tokens"),
-        _dev_ptr(n_tokens, "n_tokens"), _dev_ptr(workspace, "workspace"),
-        workspace.numel() * workspace.element_size(), _stream_ptr(stream))
-    _check(st, "fspad_tree_accept_sample")
-    return path, path_len, tokens, n_tokens
+    args = (B, Nmax, V, _dev_ptr(logits, "logits", torch.float32), logits.stride(1),
+            _dev_ptr(draft_tokens, "draft_tokens"), _dev_ptr(parent, "parent"), _dev_ptr(n_nodes, "n_nodes"),
+            float(temperature), _dev_ptr(uniforms, "uniforms"),
+            _dev_ptr(path, "path"), _dev_ptr(path_len, "path_len"), _dev_ptr(tokens, "tokens"),
+            _dev_ptr(n_tokens, "n_tokens"), _dev_ptr(workspace, "workspace"),
+            workspace.numel() * workspace.element_size(), _stream_ptr(stream))
+    keep = (logits, draft_tokens, parent, n_nodes, uniforms, workspace)
+    return _issue(_lib().fspad_tree_accept_sample, "fspad_tree_accept_sample", args, keep,
+                  (path, path_len, tokens, n_tokens), prepare)
 
 
 def fspad_kv_commit(k_tree: torch.Tensor, v_tree: torch.Tensor, k_cache: torch.Tensor, v_cache: torch.Tensor,
                     kv_len, path: torch.Tensor, path_len: torch.Tensor,
-                    kv_len_out: Optional[torch.Tensor] = None, stream=None) -> Optional[torch.Tensor]:
+                    kv_len_out: Optional[torch.Tensor] = None, stream=None, prepare: bool = False):
     """Appends the accepted nodes' keys/values to the cache in place. k_tree,v_tree [B,Nmax,Hkv,D];
     k_cache,v_cache [B,Hkv,Lcap,D] views; kv_len HOST int32 [B]; path [B,Nmax], path_len [B] device
     int32 (from an acceptance call). Returns kv_len_out."""
@@ -271,13 +294,12 @@ def fspad_kv_commit(k_tree: torch.Tensor, v_tree: torch.Tensor, k_cache: torch.T
         raise ValueError("kv_len must have one entry per sequence")
     if path.shape != (B, Nmax) or path_len.shape != (B,) or not path.is_contiguous():
         raise ValueError("path must be [B,Nmax] and path_len [B]")
-    st = _lib().fspad_kv_commit(
-        ctypes.byref(d), _dev_ptr(k_tree, "k_tree"), _dev_ptr(v_tree, "v_tree"),
-        _dev_ptr(k_cache, "k_cache"), _dev_ptr(v_cache, "v_cache"), int(k_cache.shape[2]),
-        kv_len.ctypes.data, _dev_ptr(path, "path", torch.int32), _dev_ptr(path_len, "path_len", torch.int32),
-        _dev_ptr(kv_len_out, "kv_len_out", torch.int32), _stream_ptr(stream))
-    _check(st, "fspad_kv_commit")
-    return kv_len_out
+    args = (ctypes.byref(d), _dev_ptr(k_tree, "k_tree"), _dev_ptr(v_tree, "v_tree"),
+            _dev_ptr(k_cache, "k_cache"), _dev_ptr(v_cache, "v_cache"), int(k_cache.shape[2]),
+            kv_len.ctypes.data, _dev_ptr(path, "path", torch.int32), _dev_ptr(path_len, "path_len", torch.int32),
+            _dev_ptr(kv_len_out, "kv_len_out", torch.int32), _stream_ptr(stream))
+    keep = (d, k_tree, v_tree, k_cache, v_cache, kv_len, path, path_len, kv_len_out)
+    return _issue(_lib().fspad_kv_commit, "fspad_kv_commit", args, keep, kv_len_out, prepare)
 
 
 def fspad_tree_build_mask(parent, n_nodes) -> np.ndarray:
