@@ -84,6 +84,7 @@ def main():
     if args.kv_len is not None:
         import dataclasses
         cfg = dataclasses.replace(cfg, kv_len=args.kv_len, name=cfg.name + f"-{args.kv_len}prefix")
+    default_shape = args.layers is None and args.nodes is None and args.heads is None and args.kv_len is None
     accept = args.accept or cfg.accept
     tdt = torch.float32 if cfg.dtype == "f32" else torch.bfloat16
     B, N, Hq, Hkv, D, L, V = cfg.batch, cfg.n_nodes, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.kv_len, cfg.vocab
@@ -205,7 +206,7 @@ def main():
         roofline = dict(bound="hbm", achieved=achieved_gbs, peak=HBM_PEAK_GBS, unit="GB/s", frac=achieved_gbs / HBM_PEAK_GBS)
     roofline.update(kernel="fspad_tree_attn (split-KV kernel + merge kernel)", launch_ms=attn_ms,
                     algorithmic_bytes=attn_bytes, algorithmic_flops=attn_flops,
-                    traffic=MEASURED_TRAFFIC_BYTES.get(args.workload))
+                    traffic=MEASURED_TRAFFIC_BYTES.get(args.workload) if default_shape else None)
 
     result = {
         "metric": "tree-verify steps/s", "value": 1e3 / ms_per_step, "unit": "steps/s", "n_gpus": 1, "steps": steps,
@@ -262,9 +263,12 @@ class TimingEvent:
             TimingEvent._hip.hipEventDestroy(self._ev)
 
 
-# HBM bytes per fspad_tree_attn call measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by a
-# copy kernel of known size); filled in from the summaries under profiles/. None = not measured.
-MEASURED_TRAFFIC_BYTES = {}
+# HBM bytes moved by one fspad_tree_attn call (its kernels together, read + written) at the default shape of
+# each workload, from two rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE), each scaled by what the same counter
+# reads for a 512 MiB copy (2048 B per FETCH count, 1024 B per WRITE count on this machine); figures and
+# commands in profiles/tree_verify_traffic.txt. Above the algorithmic bytes by the partial results of units
+# that are cut across workgroups (c2, c4: 256 rows per workgroup) and by the second slab group's K/V reads.
+MEASURED_TRAFFIC_BYTES = {"c1": 45764349, "c2": 62505560, "c3": 456205523, "c4": 151583929}
 
 
 def cpu_baseline(cfg, accept, dev_set, parent, n_nodes, kv_len, seed):
