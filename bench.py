@@ -190,8 +190,20 @@ def main():
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / steps
-    attn_ms = float(np.mean([a.elapsed_time(b) for a, b in events]))  # one fspad_tree_attn call (all its kernels)
+    call_ms = np.array([a.elapsed_time(b) for a, b in events])  # one fspad_tree_attn call (all its kernels) each
+    attn_ms = float(call_ms.mean())
     n_tokens_mean = float(acc_out[3].float().mean().item())
+
+    # After the timed region: the same steps when the host reads the emitted-token counts back after
+    # every step, as a decoding loop must (one device-to-host copy and synchronisation per step).
+    sync_steps = max(1, steps // 4)
+    torch.cuda.synchronize()
+    t2 = time.perf_counter()
+    for i in range(sync_steps):
+        step(warmup + steps + i)
+        acc_out[3].cpu()
+    t3 = time.perf_counter()
+    ms_per_step_sync = (t3 - t2) * 1e3 / sync_steps
 
     attn_bytes = cfg.attn_bytes_per_layer()
     attn_flops = cfg.attn_flops_per_layer()
@@ -219,6 +231,10 @@ def main():
         "step_gb_per_s": cfg.step_bytes() / (ms_per_step * 1e-3) / 1e9,
         "step_hbm_frac": cfg.step_bytes() / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "attn_tflops": achieved_tflops, "attn_gb_per_s": achieved_gbs,
+        "attn_call_us": {"mean": attn_ms * 1e3, "p10": float(np.percentile(call_ms, 10)) * 1e3,
+                         "p50": float(np.percentile(call_ms, 50)) * 1e3, "p90": float(np.percentile(call_ms, 90)) * 1e3,
+                         "samples": int(call_ms.size)},
+        "steps_per_s_with_host_readback": 1e3 / ms_per_step_sync,
         "mean_tokens_per_step": n_tokens_mean,
         "roofline": roofline,
     }
