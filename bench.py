@@ -50,6 +50,9 @@ def parse_args():
     ap.add_argument("--commit", action="store_true",
                     help="also append the accepted path's keys/values to every layer's cache after the acceptance "
                          "(fspad_kv_commit; the caches then carry room for one more tree)")
+    ap.add_argument("--tree-build", action="store_true",
+                    help="also select a tree from depth x top-k draft candidates at the top of every step "
+                         "(fspad_tree_build; timing only: the step's other calls keep their pre-built tree)")
     ap.add_argument("--seed", type=int, default=2024)
     return ap.parse_args()
 
@@ -64,7 +67,7 @@ def main():
     import torch
 
     import paper_2408_15562_amd as fspad
-    from workloads import CONFIGS, GENERATOR_VERSION, gen_draft_tokens, gen_logits, gen_trees, gen_uniforms
+    from workloads import CONFIGS, GENERATOR_VERSION, gen_candidates, gen_draft_tokens, gen_logits, gen_trees, gen_uniforms
 
     fspad.library_path()  # fail loudly if the HIP library is missing
     if not torch.cuda.is_available():
@@ -150,11 +153,17 @@ def main():
             st["accept"] = fspad.fspad_tree_accept_sample(st["logits"], st["tokens"], parent_d, n_nodes_d, cfg.temperature,
                                                           st["uniforms"], outputs=acc_out, workspace=ws_acc, prepare=True)
         # the prefix length stays L from step to step: every step rewrites the same tail
+        st["build"] = None
+        if args.tree_build:
+            cands = gen_candidates(args.seed, B, cfg.tree_depth, cfg.tree_topk, V)
+            st["build"] = fspad.fspad_tree_build(*[torch.from_numpy(a).to(dev) for a in cands], N, N, prepare=True)
         st["commit"] = [fspad.fspad_kv_commit(kt, vt, kc, vc, kv_len, acc_out[0], acc_out[1], prepare=True)
                         for (q, kt, vt, kc, vc, out) in st["layers"]] if args.commit else []
 
     def step(i, timed=None):
         st = sets[i % n_sets]
+        if st["build"] is not None:
+            st["build"]()
         if timed is None:
             for call in st["attn"]:
                 call()
@@ -226,7 +235,7 @@ def main():
         "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": cfg.name, "layers": cfg.layers, "batch": B, "n_q_heads": Hq, "n_kv_heads": Hkv,
                    "head_dim": D, "kv_len": L, "tree_nodes": N, "vocab": V, "accept": accept, "buffer_sets": n_sets,
-                   "kv_commit": bool(args.commit),
+                   "kv_commit": bool(args.commit), "tree_build": bool(args.tree_build),
                    "seed": args.seed, "generator_version": GENERATOR_VERSION, "parallelism": "single-gpu"},
         "step_gb_per_s": cfg.step_bytes() / (ms_per_step * 1e-3) / 1e9,
         "step_hbm_frac": cfg.step_bytes() / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,

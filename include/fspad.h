@@ -204,6 +204,38 @@ fspad_status fspad_kv_commit(const fspad_attn_desc* desc, const void* k_tree, co
                              int32_t* kv_len_out, void* hip_stream);
 
 /*
+ * Dynamic draft tree from its candidates (Preliminaries, last paragraph: the output of every
+ * draft step is cut to its top-k, joint probabilities follow from the dependencies between the
+ * tokens, and one more top-k over all tokens yields a valid tree of bounded size; the
+ * paragraph before it: the tokens are then organised into a tree and the attention mask is
+ * derived from it). This call covers everything after the per-step top-k: it accumulates the
+ * joint scores, picks the tree, flattens it and emits the arrays the verification calls consume.
+ *
+ *   joint[0] = 0;  joint[c] = joint[cand_parent[c]] + cand_logp[c]    (one fp32 addition per edge)
+ *   kept = root + the n_keep-1 non-root candidates with the highest joint (ties: lower index);
+ *          a kept candidate whose parent is not kept is dropped with its descendants (cannot
+ *          happen when all cand_logp <= 0)
+ *   nodes = kept candidates in candidate order (parents precede children, siblings keep their
+ *          order); parent / draft_tokens / anc_mask as every other call here expects them
+ *
+ *   cand_parent dev [B,M] i32: candidate index of the parent, < own index; [b,0] = -1 (root)
+ *   cand_token  dev [B,M] i32
+ *   cand_logp   dev [B,M] f32: conditional log-probability given the parent's path; [b,0] is
+ *               ignored; NaN counts as -infinity
+ *   n_cand      dev [B] i32, 1..M;  M <= FSPAD_MAX_CANDIDATES
+ *   n_keep      nodes to keep, root included, 1..Nmax (Nmax <= 64)
+ *   parent, draft_tokens, node_cand dev [B,Nmax] i32 out (-1 in unused slots); node_cand[b,i] is
+ *               the candidate node i came from; n_nodes dev [B] i32 out; anc_mask dev [B,Nmax] u64 out
+ * A parent index outside [0, own index) makes that candidate (and its descendants) unreachable:
+ * it is never kept. No workspace.
+ */
+#define FSPAD_MAX_CANDIDATES 1024
+fspad_status fspad_tree_build(int32_t B, int32_t M, int32_t Nmax, const int32_t* cand_parent,
+                              const int32_t* cand_token, const float* cand_logp, const int32_t* n_cand,
+                              int32_t n_keep, int32_t* parent, int32_t* draft_tokens, int32_t* n_nodes,
+                              uint64_t* anc_mask, int32_t* node_cand, void* hip_stream);
+
+/*
  * Host helpers for the tree (Preliminaries: tokens organised into a tree by
  * their dependencies, then the mask derived from the tree).
  *

@@ -170,3 +170,51 @@ def kv_commit(k_tree, v_tree, k_cache, v_cache, kv_len, path, path_len):
                 v_new[b, g, kv_len[b] + j, :] = v_tree[b, node, g, :]
         new_len[b] = kv_len[b] + int(path_len[b])
     return k_new, v_new, new_len
+
+
+def tree_build(cand_parent, cand_token, cand_logp, n_cand, n_keep, n_max):
+    """Dynamic draft tree from its candidates (Preliminaries, last paragraph: each draft step's
+    output is cut to its top-k, joint probabilities follow from the dependencies, and one more
+    top-k over all tokens bounds the tree): joint[c] = joint[parent] + logp[c] accumulated in
+    float32 down every path (joint[root] = 0); the n_keep-1 non-root candidates with the highest
+    joint score are kept (ties: lower candidate index), a kept candidate whose parent is not
+    kept is dropped with its descendants; kept candidates become the nodes in candidate order.
+
+    Returns (parent [B,n_max], tokens [B,n_max], n_nodes [B], anc_mask [B,n_max] uint64,
+    node_cand [B,n_max]); unused slots hold -1 (mask 0). NaN scores count as -infinity."""
+    cand_parent, cand_token, n_cand = _i32(cand_parent), _i32(cand_token), _i32(n_cand)
+    cand_logp = np.ascontiguousarray(cand_logp, dtype=np.float32)
+    B = cand_parent.shape[0]
+    parent = np.full((B, n_max), -1, np.int32)
+    tokens = np.full((B, n_max), -1, np.int32)
+    node_cand = np.full((B, n_max), -1, np.int32)
+    mask = np.zeros((B, n_max), np.uint64)
+    n_nodes = np.zeros(B, np.int32)
+    for b in range(B):
+        m = int(n_cand[b])
+        joint = np.zeros(m, np.float32)
+        for c in range(1, m):
+            lp = cand_logp[b, c]
+            lp = np.float32(-np.inf) if np.isnan(lp) else lp
+            joint[c] = np.float32(joint[cand_parent[b, c]] + lp)      # one float32 addition per edge
+        order = sorted(range(1, m), key=lambda c: (-float(joint[c]), c))
+        kept = np.zeros(m, bool)
+        kept[0] = True
+        kept[order[: max(0, n_keep - 1)]] = True
+        for c in range(1, m):                                          # parents come first
+            kept[c] = kept[c] and kept[cand_parent[b, c]]
+        new_id = {}
+        for c in range(m):
+            if not kept[c]:
+                continue
+            i = len(new_id)
+            new_id[c] = i
+            node_cand[b, i] = c
+            tokens[b, i] = cand_token[b, c]
+            if c == 0:
+                mask[b, i] = np.uint64(1)
+            else:
+                parent[b, i] = new_id[int(cand_parent[b, c])]
+                mask[b, i] = mask[b, parent[b, i]] | (np.uint64(1) << np.uint64(i))
+        n_nodes[b] = len(new_id)
+    return parent, tokens, n_nodes, mask, node_cand

@@ -19,6 +19,7 @@ from .binding import (  # noqa: F401
     fspad_tree_attn,
     fspad_tree_attn_set_workgroups,
     fspad_tree_attn_workspace_bytes,
+    fspad_tree_build,
     fspad_tree_build_mask,
     fspad_tree_validate,
     library_path,

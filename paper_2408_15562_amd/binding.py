@@ -25,7 +25,7 @@ _STATUS_NAMES = {0: "FSPAD_OK", 1: "FSPAD_ERR_NULL", 2: "FSPAD_ERR_SHAPE", 3: "F
 
 EXPORTS = ("fspad_tree_attn_workspace_bytes", "fspad_tree_attn_set_workgroups", "fspad_tree_attn",
            "fspad_tree_accept_workspace_bytes", "fspad_tree_accept_greedy", "fspad_tree_accept_sample",
-           "fspad_kv_commit", "fspad_tree_build_mask", "fspad_tree_validate", "fspad_status_string")
+           "fspad_kv_commit", "fspad_tree_build", "fspad_tree_build_mask", "fspad_tree_validate", "fspad_status_string")
 
 
 class FspadError(RuntimeError):
@@ -72,6 +72,8 @@ def _lib():
                                                  vp, vp, vp, vp, vp, sz, vp]
         lib.fspad_kv_commit.restype = ctypes.c_int
         lib.fspad_kv_commit.argtypes = [ctypes.POINTER(fspad_attn_desc), vp, vp, vp, vp, i32, vp, vp, vp, vp, vp]
+        lib.fspad_tree_build.restype = ctypes.c_int
+        lib.fspad_tree_build.argtypes = [i32, i32, i32, vp, vp, vp, vp, i32, vp, vp, vp, vp, vp, vp]
         lib.fspad_tree_build_mask.restype = ctypes.c_int
         lib.fspad_tree_build_mask.argtypes = [i32, i32, vp, vp, vp]
         lib.fspad_tree_validate.restype = ctypes.c_int
@@ -300,6 +302,33 @@ def fspad_kv_commit(k_tree: torch.Tensor, v_tree: torch.Tensor, k_cache: torch.T
             _dev_ptr(kv_len_out, "kv_len_out", torch.int32), _stream_ptr(stream))
     keep = (d, k_tree, v_tree, k_cache, v_cache, kv_len, path, path_len, kv_len_out)
     return _issue(_lib().fspad_kv_commit, "fspad_kv_commit", args, keep, kv_len_out, prepare)
+
+
+def fspad_tree_build(cand_parent: torch.Tensor, cand_token: torch.Tensor, cand_logp: torch.Tensor,
+                     n_cand: torch.Tensor, n_keep: int, n_max: int, stream=None, prepare: bool = False):
+    """Device tensors: cand_parent, cand_token int32 [B,M], cand_logp fp32 [B,M], n_cand int32 [B].
+    Returns (parent [B,n_max], draft_tokens [B,n_max], n_nodes [B], anc_mask [B,n_max] int64 bit
+    pattern of the u64 words, node_cand [B,n_max])."""
+    B, M = cand_parent.shape
+    for name, t, dt in (("cand_parent", cand_parent, torch.int32), ("cand_token", cand_token, torch.int32),
+                        ("cand_logp", cand_logp, torch.float32)):
+        if t.dtype != dt or not t.is_contiguous() or tuple(t.shape) != (B, M):
+            raise ValueError(f"{name} must be a contiguous {dt} [B,M] device tensor")
+    if n_cand.dtype != torch.int32 or tuple(n_cand.shape) != (B,):
+        raise ValueError("n_cand must be an int32 [B] device tensor")
+    dev = cand_parent.device
+    parent = torch.empty((B, n_max), dtype=torch.int32, device=dev)
+    tokens = torch.empty((B, n_max), dtype=torch.int32, device=dev)
+    node_cand = torch.empty((B, n_max), dtype=torch.int32, device=dev)
+    n_nodes = torch.empty((B,), dtype=torch.int32, device=dev)
+    mask = torch.empty((B, n_max), dtype=torch.int64, device=dev)
+    args = (B, M, int(n_max), _dev_ptr(cand_parent, "cand_parent"), _dev_ptr(cand_token, "cand_token"),
+            _dev_ptr(cand_logp, "cand_logp"), _dev_ptr(n_cand, "n_cand"), int(n_keep), _dev_ptr(parent, "parent"),
+            _dev_ptr(tokens, "draft_tokens"), _dev_ptr(n_nodes, "n_nodes"), _dev_ptr(mask, "anc_mask"),
+            _dev_ptr(node_cand, "node_cand"), _stream_ptr(stream))
+    keep = (cand_parent, cand_token, cand_logp, n_cand)
+    return _issue(_lib().fspad_tree_build, "fspad_tree_build", args, keep,
+                  (parent, tokens, n_nodes, mask, node_cand), prepare)
 
 
 def fspad_tree_build_mask(parent, n_nodes) -> np.ndarray:

@@ -153,3 +153,20 @@ def test_commit_argument_checks_need_no_gpu(lib):
     assert call(_desc(), kv=-1) == 2
     assert call(_desc(), cap=2048 + 25) == 2        # no room for the longest possible path
     assert call(_desc(), kt=ctypes.c_void_p(0x1004)) == 2
+
+
+def test_tree_build_argument_checks_need_no_gpu(lib):
+    f = lib.fspad_tree_build
+    f.restype = ctypes.c_int
+    fake = ctypes.c_void_p(0x1000)   # never dereferenced: every case below fails validation first
+
+    def call(B=1, M=511, N=60, keep=60, first=fake):
+        return f(ctypes.c_int32(B), ctypes.c_int32(M), ctypes.c_int32(N), first, fake, fake, fake, ctypes.c_int32(keep),
+                 fake, fake, fake, fake, fake, None)
+
+    assert call(first=None) == 1
+    assert call(M=1025) == 2
+    assert call(N=65, keep=65) == 2
+    assert call(keep=61) == 2
+    assert call(keep=0) == 2
+    assert call(B=0) == 2

@@ -19,6 +19,7 @@ from .generators import (  # noqa: F401
     gen_logits,
     gen_draft_tokens,
     gen_uniforms,
+    gen_candidates,
     round_to_bf16,
     chain_tree,
 )

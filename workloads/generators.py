@@ -154,3 +154,42 @@ def gen_uniforms(seed: int, batch: int, n_max: int) -> np.ndarray:
     """fp32 U[0,1) [B,2,N]: [:,0,:] acceptance tests, [:,1,:] bonus draws."""
     rng = np.random.default_rng([seed, 0x0F1])
     return rng.random((batch, 2, n_max), dtype=np.float32)
+
+
+def gen_candidates(seed: int, batch: int, depth: int, topk: int, vocab: int, m_max: int = 0,
+                   ties: bool = False):
+    """Draft-tree candidates before selection, shaped like the output of `depth` draft steps that each
+    keep `topk` continuations of `topk` expanded nodes: candidate 0 is the root; level 1 holds topk
+    children of the root; every later level holds topk children of each of topk nodes of the level
+    before (which ones are expanded is drawn at random here: no selection rule lives in this module).
+    Returns cand_parent [B,M] int32 (-1 for the root, always < own index), cand_token [B,M] int32
+    (distinct among siblings), cand_logp [B,M] float32 (conditional log-probabilities, <= 0; with
+    `ties` drawn from a few values so that equal joint scores occur) and n_cand [B]."""
+    rng = np.random.default_rng([seed, 0xCA9D])
+    m = 1 + topk + (depth - 1) * topk * topk
+    m_max = max(m_max, m)
+    par = np.full((batch, m_max), -1, dtype=np.int32)
+    tok = np.full((batch, m_max), -1, dtype=np.int32)
+    logp = np.zeros((batch, m_max), dtype=np.float32)
+    n_cand = np.zeros(batch, dtype=np.int32)
+    for b in range(batch):
+        d_b = int(rng.integers(1, depth + 1)) if b % 3 == 2 else depth   # some sequences stop early
+        tok[b, 0] = rng.integers(0, vocab)
+        count, frontier = 1, [0]
+        for lev in range(1, d_b + 1):
+            new = []
+            for p in frontier:
+                if ties:
+                    c = np.log(rng.choice([0.5, 0.25, 0.125], size=topk)).astype(np.float32)
+                else:
+                    rho = rng.uniform(0.2, 0.7)
+                    c = rho ** np.arange(topk)
+                    c = np.log(c / c.sum() * rng.uniform(0.6, 1.0)).astype(np.float32)
+                toks = rng.choice(vocab, size=topk, replace=False)
+                for j in range(topk):
+                    par[b, count], tok[b, count], logp[b, count] = p, toks[j], c[j]
+                    new.append(count)
+                    count += 1
+            frontier = sorted(rng.choice(new, size=min(topk, len(new)), replace=False).tolist())
+        n_cand[b] = count
+    return par, tok, logp, n_cand
