@@ -66,7 +66,7 @@ __device__ __forceinline__ unsigned div_magic(unsigned x, int d, unsigned magic)
 }
 
 // First flat block of workgroup w under the even split: floor(w * T / W), in 32-bit arithmetic
-// (w * wg_rem < 2^24 because both stay below the 4096 workgroups a launch may have).
+// (w * wg_rem < 2^30 because both stay below the 32768 workgroups a launch may have).
 __device__ __forceinline__ unsigned wg_first_block(const AttnParams& p, unsigned w) {
   return w * (unsigned)p.wg_quot + (w * (unsigned)p.wg_rem) / (unsigned)p.n_wgs;
 }
@@ -753,6 +753,7 @@ struct Plan {
 };
 
 constexpr int64_t kComputeUnits = 256;
+constexpr int64_t kMaxWorkgroups = 32768;
 constexpr int64_t kShortStreamBlocks = 16;  // blocks per workgroup below which a stream counts as short
 int g_forced_wgs = 0;
 int g_max_qt = 4;
@@ -807,6 +808,7 @@ int plan_wgs(const Plan& pl, int64_t total_blocks, int64_t units, bool uniform) 
     }
   }
   if (g_forced_wgs > 0) wgs = g_forced_wgs;
+  if (wgs > kMaxWorkgroups) wgs = kMaxWorkgroups;  // the kernels form w * (T mod W) in 32 bits
   if (wgs > total_blocks) wgs = total_blocks;
   if (wgs < 1) wgs = 1;
   return (int)wgs;
@@ -827,6 +829,7 @@ fspad_status check_desc(const fspad_attn_desc* d) {
   if (d->batch < 1 || d->n_nodes_max < 1 || d->n_nodes_max > FSPAD_MAX_NODES) return FSPAD_ERR_SHAPE;
   if (d->n_q_heads < 1 || d->n_kv_heads < 1 || d->n_q_heads % d->n_kv_heads != 0) return FSPAD_ERR_SHAPE;
   if (d->head_dim != 64 && d->head_dim != 128) return FSPAD_ERR_SHAPE;
+  if ((int64_t)d->n_kv_heads * d->head_dim > (1ll << 26)) return FSPAD_ERR_SHAPE;  // 32-bit byte offsets inside a block
   if (d->io_dtype != FSPAD_F32 && d->io_dtype != FSPAD_BF16) return FSPAD_ERR_DTYPE;
   if (d->out_dtype != FSPAD_F32 && d->out_dtype != d->io_dtype) return FSPAD_ERR_DTYPE;
   if (!(d->softmax_scale >= 0.f) || d->softmax_scale > 3.0e38f) return FSPAD_ERR_SHAPE;

@@ -71,6 +71,14 @@ def test_bf16_workgroup_counts(H, splits):
         assert torch.equal(out, again)
 
 
+@pytest.mark.parametrize("N,splits", [(26, 0), (26, 300), (26, 511), (17, 400), (26, 256)])
+def test_bf16_small_tiles_above_and_below_one_workgroup_per_cu(H, N, splits):
+    """32-row tiles with one workgroup per compute unit at most, and with two (more than 256
+    workgroups), on a problem long enough for either: streams of 4 to 30 blocks per wave."""
+    case = H.AttnCase(500 + N + splits, 2, N, 8, 8, 128, 2100, "bf16", kv_len=[2100, 1500])
+    _check(H, case, H.TOL["bf16"], splits=splits)
+
+
 def test_bf16_shared_workspace_sees_no_stale_partials(H):
     """Two different problems of one shape alternate on one workspace, launched back to back: a
     merge that picked up the other problem's leftovers would not reproduce the result obtained
