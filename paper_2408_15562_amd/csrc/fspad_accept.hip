@@ -51,7 +51,10 @@ struct AcceptParams {
 // exponent bits, which keeps the whole routine on full-rate multiply-adds. Returns 0 below
 // -708 (where the true value is under 1e-307: its absence moves no sum by a representable amount).
 __device__ __forceinline__ double exp_nonpos(double x) {
-  if (!(x >= -708.0)) return 0.0;  // also catches NaN
+  // Branch-free on purpose: with an early return every call becomes a block of its own and the
+  // compiler rebuilds the 64-bit constants in each (more moves than arithmetic).
+  const bool vanishes = !(x >= -708.0);  // also catches NaN
+  x = fmax(x, -708.0);                   // NaN -> -708: the arithmetic below stays in range
   const double shift = 6755399441055744.0;  // 1.5 * 2^52
   const double t = fma(x, 1.4426950408889634074, shift);
   const double n = t - shift;
@@ -71,7 +74,7 @@ __device__ __forceinline__ double exp_nonpos(double x) {
   p = fma(p, r, 1.0);
   p = fma(p, r, 1.0);
   const double scale = __hiloint2double((ni + 1023) << 20, 0);   // 2^n
-  return p * scale;
+  return vanishes ? 0.0 : p * scale;
 }
 
 __device__ __forceinline__ float clean(float x) { return (x != x) ? -INFINITY : x; }  // NaN ranks lowest
