@@ -584,6 +584,7 @@ void launch_rows(const AcceptParams& p, bool vec, hipStream_t stream) {
 
 }  // namespace
 
+// Experiment knob (not part of the declared interface): workgroups the row pass aims for.
 extern "C" void fspad_debug_set_accept_target(int32_t wgs) { g_target_wgs = wgs; }
 
 extern "C" size_t fspad_tree_accept_workspace_bytes(int32_t B, int32_t Nmax, int32_t V) {

@@ -76,11 +76,6 @@ __device__ __forceinline__ float wave_xor_max_16_32(float v) {
   v = fmaxf(v, __shfl_xor(v, 32));
   return v;
 }
-__device__ __forceinline__ float wave_xor_sum_16_32(float v) {
-  v += __shfl_xor(v, 16);
-  v += __shfl_xor(v, 32);
-  return v;
-}
 
 // Which key a lane's j-th V row / P element refers to inside a 32-key block:
 // the accumulator layout of two 16-key S^T tiles puts keys 4*g4+i (tile 0) and
@@ -849,6 +844,8 @@ void launch_bf16(const Plan& pl, const AttnParams& prm, hipStream_t stream) {
 
 }  // namespace
 
+// Experiment knobs (not part of the declared interface; the benchmark's hidden flags use them):
+// upper limits for the row slabs per workgroup and the 16-row tiles per wavefront.
 extern "C" void fspad_debug_set_max_ws(int32_t ws) { g_max_ws = ws >= 4 ? 4 : (ws >= 2 ? 2 : 1); }
 extern "C" void fspad_debug_set_max_qt(int32_t qt) { g_max_qt = qt < 1 ? 1 : (qt > 4 ? 4 : qt); }
 
