@@ -79,6 +79,18 @@ def test_bf16_small_tiles_above_and_below_one_workgroup_per_cu(H, N, splits):
     _check(H, case, H.TOL["bf16"], splits=splits)
 
 
+@pytest.mark.parametrize("dtype,N,Hq,Hkv", [("bf16", 9, 2, 2), ("bf16", 40, 4, 1), ("f32", 9, 2, 2)])
+def test_more_sequences_than_one_launch_takes(H, dtype, N, Hq, Hkv):
+    """Sequences go to the kernels in slices of 128 (their lengths travel as kernel arguments): 130
+    ragged sequences take two launches that reuse one workspace in stream order."""
+    B = 130
+    rng = np.random.default_rng(130 + N)
+    kv_len = rng.integers(0, 90, B).astype(np.int32)
+    n_nodes = rng.integers(1, N + 1, B).astype(np.int32)
+    case = H.AttnCase(1300 + N, B, N, Hq, Hkv, 64, 90, dtype, kv_len=kv_len, n_nodes=n_nodes, topk=4)
+    _check(H, case, H.TOL[dtype])
+
+
 def test_bf16_shared_workspace_sees_no_stale_partials(H):
     """Two different problems of one shape alternate on one workspace, launched back to back: a
     merge that picked up the other problem's leftovers would not reproduce the result obtained
