@@ -37,6 +37,7 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--max-qt", type=int, default=0, help=argparse.SUPPRESS)
     ap.add_argument("--max-ws", type=int, default=0, help=argparse.SUPPRESS)
+    ap.add_argument("--gqa-waves", type=int, default=0, help=argparse.SUPPRESS)
     ap.add_argument("--event-every", type=int, default=0,
                     help="bracket the attention calls of every n-th timed step with timing events (0 = every max(4, steps/12)-th)")
     ap.add_argument("--accept-target", type=int, default=0, help=argparse.SUPPRESS)
@@ -126,6 +127,9 @@ def main():
     if args.accept_target:
         import ctypes
         ctypes.CDLL(fspad.library_path()).fspad_debug_set_accept_target(args.accept_target)
+    if args.gqa_waves:
+        import ctypes
+        ctypes.CDLL(fspad.library_path()).fspad_debug_set_gqa_waves(args.gqa_waves)
     if args.max_ws:
         import ctypes
         ctypes.CDLL(fspad.library_path()).fspad_debug_set_max_ws(args.max_ws)
