@@ -592,7 +592,8 @@ __global__ __launch_bounds__(256, (QT <= 2 ? 2 : 1)) void tree_attn_bf16_kernel(
 // stage with the global-to-LDS load (row-contiguous requests, no registers), and all of them pick
 // their operands out of the stage. K is kept swizzled (16-byte chunk c of row r at slot c ^ f(r))
 // so that a fragment read, 16 rows by one chunk, touches 16 different bank groups; V is kept
-// row-major, which is how it is read. Three stages: block i is read while i+1 and i+2 are in flight.
+// row-major, which is how it is read. Three stages of one block each (two blocks each in the
+// eight-wavefront form, which halves the barriers): stage i is read while i+1 and i+2 are in flight.
 template <int D, int WAVES>
 struct Stage {
   static constexpr int kChunks = D / 8;                      // 16-byte chunks per row
@@ -610,7 +611,11 @@ template <int D, int WAVES>
 __global__ __launch_bounds__(64 * WAVES, (WAVES == 4 ? 2 : 1)) void tree_attn_gqa_kernel(const AttnParams p) {
   typedef Stage<D, WAVES> S;
   constexpr int QT = 2, KS = D / 32, DT = D / 16, ROWS = 32, kWaves = WAVES, kStages = 3;
-  __shared__ __attribute__((aligned(16))) char stages[kStages * S::kBytes];
+  // blocks per stage, one barrier per kGroup blocks: two where one workgroup fills the CU, one
+  // where two four-wavefront workgroups have to share its LDS
+  constexpr int kGroup = WAVES == 8 ? 2 : 1;
+  constexpr int kStageBytes = kGroup * S::kBytes;
+  __shared__ __attribute__((aligned(16))) char stages[kStages * kStageBytes];
 
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int col = lane & 15, g4 = lane >> 4;
@@ -687,19 +692,26 @@ __global__ __launch_bounds__(64 * WAVES, (WAVES == 4 ? 2 : 1)) void tree_attn_gq
       }
       return src;
     };
-    // request this wavefront's share of a block into a stage (rows past the end are clamped; masked later)
-    auto request = [&](const BlockSrc& s, int stage) {
+    // request this wavefront's share of a block into slot u of a stage (rows past the end are clamped; masked later)
+    auto request_block = [&](const BlockSrc& s, int stage, int u) {
 #pragma unroll
       for (int i = 0; i < S::kPerWave; ++i) {
         const unsigned off = (unsigned)min(dma_row[i], s.nvalid - 1) * s.row_bytes + 16u * dma_chunk[i];
         const char* src = (dma_tensor[i] == 0 ? s.k : s.v) + off;
-        __builtin_amdgcn_global_load_lds((GlobalPtr)src, (LdsPtr)(stages + stage * S::kBytes + dma_dst[i]), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds((GlobalPtr)src, (LdsPtr)(stages + stage * kStageBytes + u * S::kBytes + dma_dst[i]), 16, 0, 0);
       }
     };
-
     const int blk_begin = seg_begin, blk_end = seg_begin + seg_count;
-    request(locate(blk_begin), 0);
-    if (blk_begin + 1 < blk_end) request(locate(blk_begin + 1), 1);
+    // a group = kGroup consecutive blocks (the last one may be short); returns how many blocks it requested
+    auto request_group = [&](int first, int stage) {
+#pragma unroll
+      for (int u = 0; u < kGroup; ++u)
+        if (first + u < blk_end) request_block(locate(first + u), stage, u);
+    };
+    auto group_size = [&](int first) { return max(0, min(kGroup, blk_end - first)); };
+
+    request_group(blk_begin, 0);
+    request_group(blk_begin + kGroup, 1);
 
     struct RowInfo { bool exists, valid; int node; int64_t out; };
     auto row_info = [&](int t) {
@@ -745,35 +757,41 @@ __global__ __launch_bounds__(64 * WAVES, (WAVES == 4 ? 2 : 1)) void tree_attn_gq
     }
 
     int stage = 0;
-    for (int blk = blk_begin; blk < blk_end; ++blk) {
-      const BlockSrc cur = locate(blk);
-      // this block's copies have landed (the next block's, requested after them, may still be in
+    for (int first = blk_begin; first < blk_end; first += kGroup) {
+      // this group's copies have landed (the next group's, requested after them, may still be in
       // flight); the barrier makes every wavefront's share visible and retires the stage that the
-      // block after the next is about to overwrite
-      if (blk + 1 < blk_end) asm volatile("s_waitcnt vmcnt(%0)" : : "n"(S::kPerWave) : "memory");
+      // group after the next is about to overwrite
+      const int next_size = group_size(first + kGroup);
+      if (next_size == kGroup) asm volatile("s_waitcnt vmcnt(%0)" : : "n"(kGroup * S::kPerWave) : "memory");
+      else if (next_size == 1) asm volatile("s_waitcnt vmcnt(%0)" : : "n"(S::kPerWave) : "memory");
       else asm volatile("s_waitcnt vmcnt(0)" : : : "memory");
       __syncthreads();
-      if (blk + 2 < blk_end) request(locate(blk + 2), stage == 0 ? 2 : stage - 1);
+      request_group(first + 2 * kGroup, stage == 0 ? 2 : stage - 1);
       if (slab_live) {
-        const char* sbase = stages + stage * S::kBytes;
-        bf16x8 kf[2][KS];
-        unsigned vr[8][D / 32];
 #pragma unroll
-        for (int kt = 0; kt < 2; ++kt)
+        for (int u = 0; u < kGroup; ++u) {
+          if (first + u >= blk_end) break;
+          const BlockSrc cur = locate(first + u);
+          const char* sbase = stages + stage * kStageBytes + u * S::kBytes;
+          bf16x8 kf[2][KS];
+          unsigned vr[8][D / 32];
 #pragma unroll
-          for (int ks = 0; ks < KS; ++ks)
-            kf[kt][ks] = *reinterpret_cast<const bf16x8*>(sbase + kt * 16 * (D * 2) + kfrag[ks]);
+          for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-          if constexpr (D == 128) {
-            const u32x4 x = *reinterpret_cast<const u32x4*>(sbase + vrow[j]);
-            vr[j][0] = x[0]; vr[j][1] = x[1]; vr[j][2] = x[2]; vr[j][3] = x[3];
-          } else {
-            const u32x2 x = *reinterpret_cast<const u32x2*>(sbase + vrow[j]);
-            vr[j][0] = x[0]; vr[j][1] = x[1];
+            for (int ks = 0; ks < KS; ++ks)
+              kf[kt][ks] = *reinterpret_cast<const bf16x8*>(sbase + kt * 16 * (D * 2) + kfrag[ks]);
+#pragma unroll
+          for (int j = 0; j < 8; ++j) {
+            if constexpr (D == 128) {
+              const u32x4 x = *reinterpret_cast<const u32x4*>(sbase + vrow[j]);
+              vr[j][0] = x[0]; vr[j][1] = x[1]; vr[j][2] = x[2]; vr[j][3] = x[3];
+            } else {
+              const u32x2 x = *reinterpret_cast<const u32x2*>(sbase + vrow[j]);
+              vr[j][0] = x[0]; vr[j][1] = x[1];
+            }
           }
+          process_block<QT, D>(st, kf, vr, q_frag, cur, mask_of_tile, c, g4, [] {}, [] {});
         }
-        process_block<QT, D>(st, kf, vr, q_frag, cur, mask_of_tile, c, g4, [] {}, [] {});
       }
       stage = stage == 2 ? 0 : stage + 1;
     }
