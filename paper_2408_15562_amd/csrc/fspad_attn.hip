@@ -1032,7 +1032,7 @@ void plan_rows(const fspad_attn_desc& d, Plan& pl, int max_ws = 4) {
   pl.rows_per_unit = pl.WS * 16 * pl.QT;
 }
 
-// The eight-wavefront kernel's plan: 32-row slabs, eight per workgroup (256 rows per unit).
+// The shared-stage kernel's plan: 32-row slabs, one per wavefront, four or eight per workgroup.
 bool gqa_plan_applies(const fspad_attn_desc& d) {
   return g_max_ws >= 8 && d.n_nodes_max * (d.n_q_heads / d.n_kv_heads) > 4 * 32;
 }
@@ -1135,7 +1135,7 @@ extern "C" size_t fspad_tree_attn_workspace_bytes(const fspad_attn_desc* desc, i
   // one partial slot per (unit, workgroup) boundary at most: units + workgroups of the largest slice;
   // the call may settle on either slab count (see kShortStreamBlocks), so both are sized
   size_t need = 0;
-  for (int variant = 0; variant < 3; ++variant) {   // four slabs, two slabs, the eight-wavefront plan
+  for (int variant = 0; variant < 3; ++variant) {   // four slabs, two slabs, the shared-stage plan
     Plan pl{};
     if (variant < 2) plan_rows(*desc, pl, variant == 0 ? 4 : 2);
     else if (gqa_plan_applies(*desc)) plan_rows_gqa(*desc, pl);
@@ -1227,7 +1227,7 @@ extern "C" fspad_status fspad_tree_attn(const fspad_attn_desc* desc, const void*
         if (total4 < kShortStreamBlocks * plan_wgs(pl, total4, units4, uniform)) {
           plan_rows(d, pl, 2);
         } else if (gqa_plan_applies(d)) {
-          // long streams and more than four 32-row slabs per kv head: eight wavefronts of 32 rows that
+          // long streams and more than four 32-row slabs per kv head: wavefronts of 32 rows that
           // share every K/V block through LDS
           plan_rows_gqa(d, pl);
         }
