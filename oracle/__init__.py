@@ -218,3 +218,57 @@ def tree_build(cand_parent, cand_token, cand_logp, n_cand, n_keep, n_max):
                 mask[b, i] = mask[b, parent[b, i]] | (np.uint64(1) << np.uint64(i))
         n_nodes[b] = len(new_id)
     return parent, tokens, n_nodes, mask, node_cand
+
+
+def lm_head_greedy(hidden, lm_head, draft_tokens, parent, n_nodes):
+    """Greedy validation straight from the target's last hidden states (Methodology, "LM Head":
+    the final linear map from features to the vocabulary; Preliminaries, validation phase: the
+    tree is compared strictly with the target's own choices and a differing token is dropped
+    with its descendants; Experiments "Settings": temperature 0).
+
+        logits[b,i,v] = sum_k hidden[b,i,k] * lm_head[v,k]        (fp64; the inputs are bf16 values)
+        target[b,i]   = the v with the largest logit, lowest v among equals
+        walk: cur = root; while some child c of cur (lowest index first) carries
+              draft_tokens[c] == target[cur]: emit target[cur], cur = c;  finally emit target[cur].
+
+    hidden [B,Nmax,Hd], lm_head [V,Hd] (any float dtype holding the values), draft_tokens/parent
+    [B,Nmax], n_nodes [B].  Returns (path [B,Nmax], path_len [B], tokens [B,Nmax], n_tokens [B],
+    target [B,Nmax] i32, top [B,Nmax] f64, margin [B,Nmax] f64): unused slots hold -1 (target -1,
+    top/margin nan); margin = top logit minus the runner-up (inf when V == 1) -- what a test
+    needs to tell a decided argmax from one that fp32 accumulation order may flip."""
+    hidden = np.asarray(hidden, dtype=np.float64)
+    lm_head = np.asarray(lm_head, dtype=np.float64)
+    draft_tokens, parent, n_nodes = _i32(draft_tokens), _i32(parent), _i32(n_nodes)
+    B, Nmax, Hd = hidden.shape
+    V = lm_head.shape[0]
+    assert lm_head.shape == (V, Hd) and draft_tokens.shape == (B, Nmax) and parent.shape == (B, Nmax)
+    path = np.full((B, Nmax), -1, np.int32)
+    tokens = np.full((B, Nmax), -1, np.int32)
+    path_len = np.zeros(B, np.int32)
+    n_tokens = np.zeros(B, np.int32)
+    target = np.full((B, Nmax), -1, np.int32)
+    top = np.full((B, Nmax), np.nan)
+    margin = np.full((B, Nmax), np.nan)
+    for b in range(B):
+        n = int(n_nodes[b])
+        logits = hidden[b, :n] @ lm_head.T                         # [n, V] fp64
+        for i in range(n):
+            row = logits[i]
+            t = int(np.argmax(row))                                # first index of the maximum
+            target[b, i] = t
+            top[b, i] = row[t]
+            margin[b, i] = row[t] - np.max(np.delete(row, t)) if V > 1 else np.inf
+        cur, length = 0, 1
+        path[b, 0] = 0
+        while True:
+            t = int(target[b, cur])
+            tokens[b, length - 1] = t
+            nxt = next((c for c in range(cur + 1, n) if parent[b, c] == cur and draft_tokens[b, c] == t), None)
+            if nxt is None:
+                break
+            path[b, length] = nxt
+            cur = nxt
+            length += 1
+        path_len[b] = length
+        n_tokens[b] = length
+    return path, path_len, tokens, n_tokens, target, top, margin

@@ -20,6 +20,7 @@ from .generators import (  # noqa: F401
     gen_draft_tokens,
     gen_uniforms,
     gen_candidates,
+    gen_lm_head,
     round_to_bf16,
     chain_tree,
 )

@@ -193,3 +193,14 @@ def gen_candidates(seed: int, batch: int, depth: int, topk: int, vocab: int, m_m
             frontier = sorted(rng.choice(new, size=min(topk, len(new)), replace=False).tolist())
         n_cand[b] = count
     return par, tok, logp, n_cand
+
+
+def gen_lm_head(seed: int, batch: int, n_max: int, hidden_dim: int, vocab: int, sigma: float = 3.0):
+    """Last hidden states [B,N,Hd] ~ N(0,1) and LM-head weights [V,Hd] ~ N(0, sigma^2/Hd), both
+    rounded to bf16 and returned as fp32: the logits they produce are ~ N(0, sigma^2), like the
+    ones gen_logits draws."""
+    rng = np.random.default_rng([seed, 0x1A4D])
+    hidden = round_to_bf16(rng.standard_normal((batch, n_max, hidden_dim), dtype=np.float32))
+    w = rng.standard_normal((vocab, hidden_dim), dtype=np.float32)
+    w *= np.float32(sigma / np.sqrt(hidden_dim))
+    return hidden, round_to_bf16(w)
