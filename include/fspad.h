@@ -176,6 +176,42 @@ fspad_status fspad_tree_accept_sample(int32_t B, int32_t Nmax, int32_t V,
                                       void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * Greedy acceptance straight from the target's last hidden states, fused with the LM head
+ * (Methodology, "LM Head": the final linear map from features to the vocabulary distribution;
+ * Preliminaries, validation phase; Experiments "Settings": temperature 0). The [B*Nmax, V]
+ * logits are never written to memory:
+ *
+ *   logits[b,i,v] = sum_k hidden[b,i,k] * lm_head[v,k]     bf16 inputs, exact products, fp32 sums
+ *   target[b,i]   = the v with the largest logit (lowest v among equals; NaN never wins; a row
+ *                   with nothing above -infinity takes token 0)
+ *   then the walk of fspad_tree_accept_greedy with target[] in place of the row argmaxes.
+ *
+ *   hidden       dev [B,Nmax,hidden_dim] bf16, contiguous, 16-byte aligned (rows of unused tree
+ *                slots are read but never used)
+ *   lm_head      dev [V,hidden_dim] bf16, contiguous, 16-byte aligned (the weight matrix as the
+ *                models store it: one row per token)
+ *   hidden_dim   multiple of 256, 256..65536
+ *   draft_tokens, parent, n_nodes, path, path_len, tokens, n_tokens: as for fspad_tree_accept_greedy
+ *   node_target  dev [B,Nmax] i32 out, may be NULL: target[b,i] (-1 in unused slots)
+ *   node_top     dev [B,Nmax] f32 out, may be NULL: the winning logit (-infinity in unused slots)
+ *   workspace    dev, 16-byte aligned, >= fspad_tree_accept_lm_head_workspace_bytes(B,Nmax,V)
+ * The sums are accumulated in fp32 by the matrix cores in an order of the library's choosing: a
+ * target token is only defined bit-for-bit where the winning logit leads the runner-up by more
+ * than the fp32 accumulation error (about 1e-6 of sum_k |hidden*lm_head|); the tests require that.
+ * More than 64 rows (B*Nmax) are processed in groups of 64 that each stream the weights again.
+ * Errors as for fspad_tree_accept_greedy; never synchronises, allocates nothing.
+ */
+size_t fspad_tree_accept_lm_head_workspace_bytes(int32_t B, int32_t Nmax, int32_t V);
+fspad_status fspad_tree_accept_greedy_lm_head(int32_t B, int32_t Nmax, int32_t V, int32_t hidden_dim,
+                                              const void* hidden, const void* lm_head,
+                                              const int32_t* draft_tokens, const int32_t* parent,
+                                              const int32_t* n_nodes,
+                                              int32_t* path, int32_t* path_len,
+                                              int32_t* tokens, int32_t* n_tokens,
+                                              int32_t* node_target, float* node_top,
+                                              void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
  * Commit of the accepted path to the KV cache. The paper leaves this step implied
  * (Preliminaries: the tokens that pass validation extend the sequence from which the
  * next draft phase starts): the keys and values the verification forward computed for

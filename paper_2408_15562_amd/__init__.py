@@ -14,6 +14,8 @@ from .binding import (  # noqa: F401
     fspad_kv_commit,
     fspad_status_string,
     fspad_tree_accept_greedy,
+    fspad_tree_accept_greedy_lm_head,
+    fspad_tree_accept_lm_head_workspace_bytes,
     fspad_tree_accept_sample,
     fspad_tree_accept_workspace_bytes,
     fspad_tree_attn,

@@ -15,6 +15,7 @@
 #include <stdint.h>
 
 #include "fspad.h"
+#include "greedy_walk.h"
 
 namespace {
 
@@ -212,28 +213,8 @@ __global__ __launch_bounds__(kThreads) void accept_greedy_walk_kernel(const Acce
   }
   __syncthreads();
   if (wave != 0) return;
-  int my_par = -2, my_tok = -1;
-  if (lane < n) {
-    my_par = p.parent[o + lane];
-    my_tok = p.draft_tokens[o + lane];
-  }
-  int my_path = -1, my_out = -1;  // lane j keeps path[j] and tokens[j]
-  if (lane == 0) my_path = 0;
-  int cur = 0, len = 1;
-  for (int iter = 0; iter < p.Nmax && len < p.Nmax; ++iter) {  // bounded: a well-formed walk ends at a leaf
-    const int a = amax[cur];
-    const bool hit = lane > 0 && lane < n && my_par == cur && my_tok == a;
-    const unsigned long long bal = __ballot(hit);
-    if (bal == 0ull) break;
-    const int nxt = __ffsll(bal) - 1;  // lowest child index first
-    if (lane == len) my_path = nxt;
-    if (lane == len - 1) my_out = a;
-    cur = nxt;
-    ++len;
-  }
-  if (lane == len - 1) my_out = amax[cur];  // bonus: the target's own token after the last accepted node
-  if (lane < p.Nmax) { p.path[o + lane] = my_path; p.tokens[o + lane] = my_out; }
-  if (lane == 0) { p.path_len[b] = len; p.n_tokens[b] = len; }
+  fspad_detail::greedy_descend(amax, n, p.Nmax, lane, o, b, p.parent, p.draft_tokens, p.path, p.tokens, p.path_len,
+                               p.n_tokens);
 }
 
 // ------------------------------------------------------------------------------------------------

@@ -135,6 +135,28 @@ def test_accept_argument_checks_need_no_gpu(lib):
     assert sample(1.0, uni=None) == 1
 
 
+def test_lm_head_argument_checks_need_no_gpu(lib):
+    f = lib.fspad_tree_accept_greedy_lm_head
+    fake = ctypes.c_void_p(0x1000)   # never dereferenced: every case below fails validation first
+    i32, sz = ctypes.c_int32, ctypes.c_size_t
+    need = fspad.fspad_tree_accept_lm_head_workspace_bytes(1, 26, 32000)
+    assert need >= 26 * 250 * 8
+
+    def call(B=1, N=26, V=32000, Hd=4096, hidden=fake, w=fake, ws=fake, wsb=need):
+        return f(i32(B), i32(N), i32(V), i32(Hd), hidden, w, fake, fake, fake, fake, fake, fake, fake, None, None,
+                 ws, sz(wsb), None)
+
+    assert call(hidden=None) == 1
+    assert call(w=None) == 1
+    assert call(N=65) == 2
+    assert call(V=0) == 2
+    assert call(Hd=4000) == 2          # not a multiple of 256
+    assert call(Hd=128) == 2
+    assert call(hidden=ctypes.c_void_p(0x1008)) == 2
+    assert call(wsb=need - 1) == 5
+    assert call(ws=None) == 5
+
+
 def test_commit_argument_checks_need_no_gpu(lib):
     f = lib.fspad_kv_commit
     f.restype = ctypes.c_int

@@ -9,9 +9,12 @@ GENERATOR_VERSION = 1
 def round_to_bf16(x: np.ndarray) -> np.ndarray:
     """Round fp32 values to the nearest bf16 (ties to even) and return them as fp32."""
     x = np.ascontiguousarray(x, dtype=np.float32)
-    bits = x.view(np.uint32).astype(np.uint64)
-    rounded = (bits + 0x7FFF + ((bits >> 16) & 1)) & 0xFFFF0000
-    return rounded.astype(np.uint32).view(np.float32).reshape(x.shape)
+    bits = x.view(np.uint32)
+    rounded = (bits >> np.uint32(16)) & np.uint32(1)      # 32-bit arithmetic: no finite value wraps around
+    rounded += np.uint32(0x7FFF)
+    rounded += bits
+    rounded &= np.uint32(0xFFFF0000)
+    return rounded.view(np.float32).reshape(x.shape)
 
 
 def chain_tree(n: int) -> np.ndarray:
