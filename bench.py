@@ -54,6 +54,12 @@ def parse_args():
     ap.add_argument("--tree-build", action="store_true",
                     help="also select a tree from depth x top-k draft candidates at the top of every step "
                          "(fspad_tree_build; timing only: the step's other calls keep their pre-built tree)")
+    ap.add_argument("--lm-head", default=None, choices=["fused", "unfused"],
+                    help="greedy workloads: start the acceptance from the last hidden states instead of ready-made logits. "
+                         "fused = fspad_tree_accept_greedy_lm_head (logits never written); unfused = library GEMM to bf16 "
+                         "logits, widened to fp32, then fspad_tree_accept_greedy (the comparison)")
+    ap.add_argument("--lm-stagger", type=int, default=None, help=argparse.SUPPRESS)
+    ap.add_argument("--hidden-dim", type=int, default=None, help="hidden size for --lm-head (default: the workload's model)")
     ap.add_argument("--seed", type=int, default=2024)
     return ap.parse_args()
 
@@ -123,10 +129,26 @@ def main():
                          uniforms=torch.from_numpy(gen_uniforms(args.seed + s, B, N)).to(dev)))
     parent_d = torch.from_numpy(parent).to(dev)
     n_nodes_d = torch.from_numpy(n_nodes).to(dev)
+    hidden_dim = 0
+    if args.lm_head:
+        if accept != "greedy":
+            print("bench.py: --lm-head needs a greedy workload (or --accept greedy)", file=sys.stderr)
+            sys.exit(2)
+        hidden_dim = args.hidden_dim or {"c0": 256, "c1": 4096, "c2": 4096, "c3": 6656, "c4": 8192}[args.workload]
+        # the weights are streamed once per step; between two steps of a real model every layer's weights
+        # pass through the caches, so a few copies are rotated to keep them out of the 256 MB last-level cache
+        w_copies = [torch.empty((V, hidden_dim), device=dev, dtype=torch.bfloat16).normal_(generator=gen)
+                    .mul_(3.0 / hidden_dim ** 0.5) for _ in range(min(n_sets, 4))]
+        for i, st in enumerate(sets):
+            st["w"] = w_copies[i % len(w_copies)]
+            st["hidden"] = torch.empty((B, N, hidden_dim), device=dev, dtype=torch.bfloat16).normal_(generator=gen)
 
     if args.accept_target:
         import ctypes
         ctypes.CDLL(fspad.library_path()).fspad_debug_set_accept_target(args.accept_target)
+    if args.lm_stagger is not None:
+        import ctypes
+        ctypes.CDLL(fspad.library_path()).fspad_debug_set_lm_head_stagger(args.lm_stagger)
     if args.gqa_waves:
         import ctypes
         ctypes.CDLL(fspad.library_path()).fspad_debug_set_gqa_waves(args.gqa_waves)
@@ -150,7 +172,12 @@ def main():
     for st in sets:
         st["attn"] = [fspad.fspad_tree_attn(q, kt, vt, kc, vc, kv_len, n_nodes, mask, out=out, workspace=ws_attn,
                                             desc=desc, prepare=True) for (q, kt, vt, kc, vc, out) in st["layers"]]
-        if accept == "greedy":
+        if args.lm_head == "fused":
+            st["accept"] = fspad.fspad_tree_accept_greedy_lm_head(st["hidden"], st["w"], st["tokens"], parent_d, n_nodes_d,
+                                                                  outputs=acc_out, prepare=True)
+        elif args.lm_head == "unfused":
+            st["accept"] = unfused_lm_head_accept(torch, fspad, st, parent_d, n_nodes_d, acc_out, ws_acc)
+        elif accept == "greedy":
             st["accept"] = fspad.fspad_tree_accept_greedy(st["logits"], st["tokens"], parent_d, n_nodes_d, outputs=acc_out,
                                                           workspace=ws_acc, prepare=True)
         else:
@@ -182,7 +209,14 @@ def main():
                 call()
                 e1.record()
                 timed.append((e0, e1))
-        st["accept"]()
+        if timed is None:
+            st["accept"]()
+        else:
+            e0, e1 = event_pool.pop(), event_pool.pop()
+            e0.record()
+            st["accept"]()
+            e1.record()
+            accept_events.append((e0, e1))
         for call in st["commit"]:
             call()
 
@@ -200,7 +234,8 @@ def main():
     events = []
     event_every = args.event_every if args.event_every > 0 else max(4, steps // 12)
     # events are created ahead of the timed region (two per bracketed call)
-    event_pool = [TimingEvent(stream_handle) for _ in range(2 * 8 * (steps // event_every + 1))]
+    event_pool = [TimingEvent(stream_handle) for _ in range(2 * 9 * (steps // event_every + 1))]
+    accept_events = []
     t0 = time.perf_counter()
     # Recording an event costs the stream several microseconds, as much as a small kernel: only every
     # `event_every`-th step is bracketed, so that the timed region stays the workload's own.
@@ -212,6 +247,7 @@ def main():
     call_ms = np.array([a.elapsed_time(b) for a, b in events])  # one fspad_tree_attn call (all its kernels) each
     attn_ms = float(call_ms.mean())
     n_tokens_mean = float(acc_out[3].float().mean().item())
+    accept_ms = np.array([a.elapsed_time(b) for a, b in accept_events])  # the step's acceptance call (all its kernels)
 
     # After the timed region: the same steps when the host reads the emitted-token counts back after
     # every step, as a decoding loop must (one device-to-host copy and synchronisation per step).
@@ -253,14 +289,45 @@ def main():
         "attn_call_us": {"mean": attn_ms * 1e3, "p10": float(np.percentile(call_ms, 10)) * 1e3,
                          "p50": float(np.percentile(call_ms, 50)) * 1e3, "p90": float(np.percentile(call_ms, 90)) * 1e3,
                          "samples": int(call_ms.size)},
+        "accept_call_us": {"mean": float(accept_ms.mean()) * 1e3, "p50": float(np.percentile(accept_ms, 50)) * 1e3,
+                           "samples": int(accept_ms.size)},
         "steps_per_s_with_host_readback": 1e3 / ms_per_step_sync,
         "mean_tokens_per_step": n_tokens_mean,
         "roofline": roofline,
     }
 
+    if args.lm_head:
+        # the LM head streams its V x Hd weights once (and the B*N x Hd hidden states); per 64 rows when B*N > 64
+        passes = -(-B * N // 128)
+        head_bytes = 2 * hidden_dim * (V + B * N)
+        call_s = float(np.percentile(accept_ms, 50)) * 1e-3
+        result["config"].update(lm_head=args.lm_head, hidden_dim=hidden_dim)
+        result["lm_head"] = {"mode": args.lm_head, "call_us_p50": call_s * 1e6, "algorithmic_bytes": head_bytes,
+                             "weight_passes": passes if args.lm_head == "fused" else 1,
+                             "gb_per_s": head_bytes / call_s / 1e9, "hbm_frac": head_bytes / call_s / 1e9 / HBM_PEAK_GBS,
+                             "tflops": 2.0 * B * N * hidden_dim * V / call_s / 1e12}
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(cfg, accept, sets[0], parent, n_nodes, kv_len, args.seed)
     print(json.dumps(result))
+
+
+def unfused_lm_head_accept(torch, fspad, st, parent_d, n_nodes_d, acc_out, ws_acc):
+    """The comparison for --lm-head: a library GEMM writes bf16 logits, they are widened to fp32 and the
+    ordinary greedy acceptance reads them. All buffers are allocated here, once."""
+    B, N, Hd = st["hidden"].shape
+    V = st["w"].shape[0]
+    h2d = st["hidden"].view(B * N, Hd)
+    wt = st["w"].t()
+    logits_lp = torch.empty((B * N, V), device=h2d.device, dtype=torch.bfloat16)
+    logits = torch.empty((B, N, V), device=h2d.device, dtype=torch.float32)
+    accept = fspad.fspad_tree_accept_greedy(logits, st["tokens"], parent_d, n_nodes_d, outputs=acc_out, workspace=ws_acc,
+                                            prepare=True)
+
+    def call():
+        torch.mm(h2d, wt, out=logits_lp)
+        logits.view(B * N, V).copy_(logits_lp)
+        accept()
+    return call
 
 
 class TimingEvent:

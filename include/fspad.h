@@ -198,7 +198,10 @@ fspad_status fspad_tree_accept_sample(int32_t B, int32_t Nmax, int32_t V,
  * The sums are accumulated in fp32 by the matrix cores in an order of the library's choosing: a
  * target token is only defined bit-for-bit where the winning logit leads the runner-up by more
  * than the fp32 accumulation error (about 1e-6 of sum_k |hidden*lm_head|); the tests require that.
- * More than 64 rows (B*Nmax) are processed in groups of 64 that each stream the weights again.
+ * Identical weight rows give identical logits (and the lower token wins) only inside one aligned
+ * group of 128 tokens: each group sums over k starting from a different offset. Results are
+ * the same from run to run.
+ * More than 128 rows (B*Nmax) are processed in groups of 128 that each stream the weights again.
  * Errors as for fspad_tree_accept_greedy; never synchronises, allocates nothing.
  */
 size_t fspad_tree_accept_lm_head_workspace_bytes(int32_t B, int32_t Nmax, int32_t V);

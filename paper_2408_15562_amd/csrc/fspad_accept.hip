@@ -178,6 +178,12 @@ __global__ __launch_bounds__(kThreads) void accept_greedy_walk_kernel(const Acce
   const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n = p.n_nodes[b];
   const int64_t o = (int64_t)b * p.Nmax;
+  // the tree itself does not depend on the logits: wavefront 0 asks for it before anything else
+  int my_par = -2, my_tok = -1;
+  if (wave == 0 && lane < n) {
+    my_par = p.parent[o + lane];
+    my_tok = p.draft_tokens[o + lane];
+  }
   // thread (node = lane, quarter = wave) scans every 4th chunk entry of its node, eight loads in
   // flight at a time; the four quarters of a node meet in LDS (no lane exchange needed)
   __shared__ float q_best[4][FSPAD_MAX_NODES];
@@ -213,8 +219,7 @@ __global__ __launch_bounds__(kThreads) void accept_greedy_walk_kernel(const Acce
   }
   __syncthreads();
   if (wave != 0) return;
-  fspad_detail::greedy_descend(amax, n, p.Nmax, lane, o, b, p.parent, p.draft_tokens, p.path, p.tokens, p.path_len,
-                               p.n_tokens);
+  fspad_detail::greedy_descend(amax, n, p.Nmax, lane, o, b, my_par, my_tok, p.path, p.tokens, p.path_len, p.n_tokens);
 }
 
 // ------------------------------------------------------------------------------------------------

@@ -10,17 +10,12 @@
 namespace fspad_detail {
 
 // Called by all 64 lanes of one wavefront. target[i] (LDS) is the target's greedy token after
-// node i; lane i holds parent/draft token of node i of sequence b (row offset o = b * Nmax).
-// Writes path/tokens (unused slots -1) and the two lengths.
+// node i; lane i brings parent and draft token of node i of sequence b (my_par = -2 for lanes
+// past the tree; the caller fetches them early, they do not depend on the logits). Row offset
+// o = b * Nmax. Writes path/tokens (unused slots -1) and the two lengths.
 __device__ __forceinline__ void greedy_descend(const int* target, int n, int Nmax, int lane, int64_t o, int b,
-                                               const int32_t* parent, const int32_t* draft_tokens,
-                                               int32_t* path, int32_t* tokens, int32_t* path_len,
-                                               int32_t* n_tokens) {
-  int my_par = -2, my_tok = -1;
-  if (lane < n) {
-    my_par = parent[o + lane];
-    my_tok = draft_tokens[o + lane];
-  }
+                                               int my_par, int my_tok, int32_t* path, int32_t* tokens,
+                                               int32_t* path_len, int32_t* n_tokens) {
   int my_path = -1, my_out = -1;  // lane j keeps path[j] and tokens[j]
   if (lane == 0) my_path = 0;
   int cur = 0, len = 1;

@@ -48,20 +48,22 @@ def test_walks_go_deep_and_results_repeat(H):
 
 
 def test_equal_logits_take_the_lowest_token(H):
-    """Duplicate weight rows give bit-identical logits in any accumulation order: the lower token wins,
-    within a wavefront's tile, across wavefronts and across workgroups."""
+    """Duplicate weight rows inside one aligned group of 128 tokens are summed in the same order and
+    give bit-identical logits: the lower token wins, within a wavefront's 16 rows and across the
+    wavefronts of a workgroup."""
     import paper_2408_15562_amd as fspad
-    B, N, Hd, V = 1, 8, 256, 700
+    B, N, Hd, V = 1, 8, 512, 700
     case = H.LmHeadCase(9, B, N, Hd, V)
     hidden = case.hidden.astype(np.float64)
     w = case.w.copy()
     _, _, _, _, target, _, _ = case.cpu()
-    # give every node's winning row a twin: one in the same 16-row tile, one 40 rows on, one 300 rows on
+    # give every node's winning row a twin in the same group: 1, 3, 17, 40, ... rows further (wrapping)
     picks = {}
-    for i, off in zip(range(N), (1, 40, 300, 3, 17, 130, 500, 64)):
+    for i, off in zip(range(N), (1, 40, 100, 3, 17, 64, 127, 5)):
         t = int(target[0, i])
-        twin = (t + off) % V
-        if twin in picks or twin in target[0] or t in picks:
+        base = t // 128 * 128
+        twin = base + (t - base + off) % 128
+        if twin >= V or twin in picks or twin in target[0] or t in picks:
             continue
         w[twin] = w[t]
         picks[twin] = t
@@ -73,6 +75,20 @@ def test_equal_logits_take_the_lowest_token(H):
     assert len(picks) >= 5
     for i in range(N):
         assert got[i] == int(np.argmax(ref[i]))      # numpy's argmax is the first maximum
+
+
+@pytest.mark.parametrize("stagger", [0, 1, 3, 7])
+def test_k_rotation_between_workgroups_does_not_change_the_result(H, stagger):
+    import ctypes
+    import paper_2408_15562_amd as fspad
+    lib = ctypes.CDLL(fspad.library_path())
+    lib.fspad_debug_set_lm_head_stagger(stagger)
+    try:
+        for B, N, Hd, V in ((1, 26, 2048, 3000), (3, 60, 768, 2500), (1, 60, 1536, 1000)):
+            case = H.LmHeadCase(40 + stagger + N, B, N, Hd, V)
+            H.assert_lm_head_equal(case.gpu(), case.cpu())
+    finally:
+        lib.fspad_debug_set_lm_head_stagger(3)
 
 
 def test_config1_vicuna7b_head_full(H):
