@@ -297,8 +297,8 @@ def main():
     }
 
     if args.lm_head:
-        # the LM head streams its V x Hd weights once (and the B*N x Hd hidden states); per 64 rows when B*N > 64
-        passes = -(-B * N // 128)
+        # the LM head streams its V x Hd weights once (and the B*N x Hd hidden states); per group of rows when B*N > 256
+        passes = -(-B * N // 256)
         head_bytes = 2 * hidden_dim * (V + B * N)
         call_s = float(np.percentile(accept_ms, 50)) * 1e-3
         result["config"].update(lm_head=args.lm_head, hidden_dim=hidden_dim)

@@ -201,7 +201,8 @@ fspad_status fspad_tree_accept_sample(int32_t B, int32_t Nmax, int32_t V,
  * Identical weight rows give identical logits (and the lower token wins) only inside one aligned
  * group of 128 tokens: each group sums over k starting from a different offset. Results are
  * the same from run to run.
- * More than 128 rows (B*Nmax) are processed in groups of 128 that each stream the weights again.
+ * More than 256 rows (B*Nmax) are processed in equal groups of at most 256 that each stream the
+ * weights again.
  * Errors as for fspad_tree_accept_greedy; never synchronises, allocates nothing.
  */
 size_t fspad_tree_accept_lm_head_workspace_bytes(int32_t B, int32_t Nmax, int32_t V);

@@ -29,10 +29,7 @@ typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef const __attribute__((address_space(1))) void* GlobalPtr;
 typedef __attribute__((address_space(3))) void* LdsPtr;
 
-constexpr int kWaves = 8;                                   // wavefronts per workgroup, 16 vocabulary rows each
-constexpr int kVocabPerWg = kWaves * 16;                    // 128
-constexpr int kMaxRowTiles = 8;                             // 16-row tiles of hidden states one workgroup holds
-constexpr int kRowsPerPass = 16 * kMaxRowTiles;             // 128
+constexpr int kVocabPerWg = 128;                            // vocabulary rows per workgroup, in every shape below
 constexpr int kNone = 0x7fffffff;
 constexpr int kWalkThreads = 1024;
 
@@ -41,7 +38,7 @@ struct LmHeadParams {
   const char* weights;  // [V][K] bf16
   float* part_max;      // [n_slices][M]
   int32_t* part_idx;    // [n_slices][M]
-  int32_t M, V, K, n_slices, n_passes;
+  int32_t M, V, K, n_slices, n_passes, rows_per_pass;
   int32_t stagger;      // stages by which consecutive workgroups are offset along k (0: all start at k = 0)
 };
 
@@ -52,32 +49,39 @@ __device__ __forceinline__ void take_better(float& v, int& i, float ov, int oi) 
 
 // MT: 16-row tiles of hidden states per workgroup (rows of a pass <= 16 * MT).
 // SPS: k-steps per LDS stage of hidden states (stage = 16*MT rows x 32*SPS k).
-// kRing: weight operands (k-steps of 32, 1 KB per wavefront each) a wavefront keeps requested.
-template <int MT, int SPS, int kRing>
-__global__ __launch_bounds__(64 * kWaves, 2) void lm_head_argmax_kernel(const LmHeadParams p) {
+// kRing: weight operands (k-steps of 32) per vocabulary tile that a wavefront keeps requested.
+// WAVES x VT = 8: wavefronts per workgroup x 16-row vocabulary tiles per wavefront. Eight
+// wavefronts of one tile (two per SIMD) for up to 128 rows; for more, four wavefronts of two tiles
+// (one per SIMD, the whole register file), which halves the LDS reads per product: with 256 rows an
+// operand read of all of them for one weight tile would cost as much as its 16 products.
+template <int MT, int SPS, int kRing, int WAVES, int VT>
+__global__ __launch_bounds__(64 * WAVES, (WAVES == 8 ? 2 : 1)) void lm_head_argmax_kernel(const LmHeadParams p) {
+  static_assert(WAVES * VT * 16 == kVocabPerWg, "workgroup shape");
   constexpr int kStageK = 32 * SPS;
-  constexpr int kRowBytes = kStageK * 2;                        // 512 or 1024
+  constexpr int kRowBytes = kStageK * 2;                        // 256, 512 or 1024
   constexpr int kStageBytes = MT * 16 * kRowBytes;
-  constexpr int kChunksPerRow = kRowBytes / 16;                 // 32 or 64
+  constexpr int kChunksPerRow = kRowBytes / 16;                 // 16, 32 or 64
   constexpr int kRowsPerCopy = 1024 / kRowBytes;                // one copy instruction moves 1 KB
-  constexpr int kCopiesPerWave = kStageBytes / 1024 / kWaves;
-  static_assert(kCopiesPerWave >= 1 && kRing % SPS == 0, "stage shape");
+  constexpr int kCopiesPerWave = kStageBytes / 1024 / WAVES;
+  static_assert(kCopiesPerWave >= 1 && kRing % SPS == 0 && kRing % 4 == 0, "stage shape");
   __shared__ __attribute__((aligned(16))) char xs[2 * kStageBytes];
-  __shared__ float red_val[kWaves][MT * 16];
-  __shared__ int red_idx[kWaves][MT * 16];
+  __shared__ float red_val[WAVES][MT * 16];
+  __shared__ int red_idx[WAVES][MT * 16];
 
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int n = lane & 15, g = lane >> 4;
   const int slice = blockIdx.x / p.n_passes, pass = blockIdx.x - slice * p.n_passes;
-  const int row0 = pass * kRowsPerPass;
-  const int v0 = slice * kVocabPerWg + wave * 16;
+  const int row0 = pass * p.rows_per_pass;
+  const int v0 = slice * kVocabPerWg + wave * (16 * VT);
   const size_t row_bytes = (size_t)p.K * 2;
   const int n_steps = p.K >> 5;
   // workgroup `slice` walks k from stage `first_stage` on and wraps around
   const int first_step = p.stagger ? (int)(((unsigned)slice * (unsigned)p.stagger) % (unsigned)(n_steps / SPS)) * SPS : 0;
 
-  // weight row of this lane (rows past the vocabulary are clamped; their columns are never taken)
-  const char* wrow = p.weights + (size_t)min(v0 + n, p.V - 1) * row_bytes + g * 16;
+  // weight rows of this lane (rows past the vocabulary are clamped; their columns are never taken)
+  const char* wrow[VT];
+#pragma unroll
+  for (int nv = 0; nv < VT; ++nv) wrow[nv] = p.weights + (size_t)min(v0 + 16 * nv + n, p.V - 1) * row_bytes + g * 16;
 
   // hidden-state copies of this wavefront: LDS slot s of row r receives the row's 16-byte chunk
   // s ^ (r & 15) of the stage's k range (chunks past the end of the row are clamped: never used)
@@ -117,33 +121,36 @@ __global__ __launch_bounds__(64 * kWaves, 2) void lm_head_argmax_kernel(const Lm
   };
   // k-step ks of the weights: lane (n, g) holds k = 32*ks + 8*g .. +7 of its row (steps past the end
   // re-read the last one, so that every turn of the loop issues the same number of requests)
-  auto load_w = [&](int ks) {
+  auto load_w = [&](int nv, int ks) {
     int step = min(ks, n_steps - 1) + first_step;
     step -= step >= n_steps ? n_steps : 0;
-    const bf16x8* src = reinterpret_cast<const bf16x8*>(wrow + (size_t)step * 64);
-    return *src;
+    return *reinterpret_cast<const bf16x8*>(wrow[nv] + (size_t)step * 64);
   };
 
-  f32x4 acc[MT];
+  f32x4 acc[MT][VT];
 #pragma unroll
-  for (int t = 0; t < MT; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+  for (int t = 0; t < MT; ++t)
+#pragma unroll
+    for (int nv = 0; nv < VT; ++nv) acc[t][nv] = f32x4{0.f, 0.f, 0.f, 0.f};
 
   // The weights are requested kRing k-steps ahead, every operand register being requested again as
-  // soon as its product is issued. The hidden states of stage j+1 are requested into registers at the
-  // top of stage j and written to the other LDS stage at its end (by then they have long arrived,
-  // and the weight requests issued after them stay in flight); the barrier at the top of a stage
-  // publishes every wavefront's share of it and retires the other one.
-  bf16x8 w[kRing];
+  // soon as its products are issued. The hidden states of stage j+1 are requested into registers at
+  // the top of stage j and written to the other LDS stage at its end (by then they have long
+  // arrived, and the weight requests issued after them stay in flight); the barrier at the top of a
+  // stage publishes every wavefront's share of it and retires the other one.
+  bf16x8 w[VT][kRing];
   fetch_x(0);
 #pragma unroll
-  for (int i = 0; i < kRing; ++i) w[i] = load_w(i);
+  for (int i = 0; i < kRing; ++i)
+#pragma unroll
+    for (int nv = 0; nv < VT; ++nv) w[nv][i] = load_w(nv, i);
   store_x(0);
   const int n_stages = (n_steps + SPS - 1) / SPS;
   for (int ks0 = 0; ks0 < n_steps; ks0 += kRing) {
 #pragma unroll
     for (int kk = 0; kk < kRing; ++kk) {
       const int ks = ks0 + kk;
-      if (kk % 8 == 0 && ks >= n_steps) break;   // K is a multiple of 256: the end falls on a multiple of 8 steps
+      if (kk % 4 == 0 && ks >= n_steps) break;   // K is a multiple of 256 and the ring of 4: the end falls on a multiple of 4 steps
       if (kk % SPS == 0) {
         lds_barrier();
         if (ks / SPS + 1 < n_stages) fetch_x(ks / SPS + 1);
@@ -153,24 +160,30 @@ __global__ __launch_bounds__(64 * kWaves, 2) void lm_head_argmax_kernel(const Lm
 #pragma unroll
       for (int t = 0; t < MT; ++t) xf[t] = *reinterpret_cast<const bf16x8*>(base + t * (16 * kRowBytes));
 #pragma unroll
-      for (int t = 0; t < MT; ++t) acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w[kk], xf[t], acc[t], 0, 0, 0);
-      w[kk] = load_w(ks + kRing);
+      for (int nv = 0; nv < VT; ++nv)
+#pragma unroll
+        for (int t = 0; t < MT; ++t)
+          acc[t][nv] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w[nv][kk], xf[t], acc[t][nv], 0, 0, 0);
+#pragma unroll
+      for (int nv = 0; nv < VT; ++nv) w[nv][kk] = load_w(nv, ks + kRing);
       if (kk % SPS == SPS - 1 && ks / SPS + 1 < n_stages) store_x(ks / SPS + 1);
     }
   }
 
-  // argmax over this wavefront's 16 vocabulary rows for each hidden-state row (lane column n):
+  // argmax over this wavefront's vocabulary rows for each hidden-state row (lane column n):
   // ascending vocabulary order inside the lane, then across the four lane groups
 #pragma unroll
   for (int t = 0; t < MT; ++t) {
     float best = -INFINITY;
     int idx = kNone;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int v = v0 + 4 * g + i;
-      const float x = acc[t][i];
-      if (v < p.V && x > best) { best = x; idx = v; }
-    }
+    for (int nv = 0; nv < VT; ++nv)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int v = v0 + 16 * nv + 4 * g + i;
+        const float x = acc[t][nv][i];
+        if (v < p.V && x > best) { best = x; idx = v; }
+      }
 #pragma unroll
     for (int d = 16; d < 64; d <<= 1) {
       const float ov = __shfl_xor(best, d);
@@ -180,12 +193,12 @@ __global__ __launch_bounds__(64 * kWaves, 2) void lm_head_argmax_kernel(const Lm
     if (g == 0) { red_val[wave][t * 16 + n] = best; red_idx[wave][t * 16 + n] = idx; }
   }
   __syncthreads();
-  const int m = threadIdx.x;
-  if (m < MT * 16 && row0 + m < p.M) {
+  for (int m = threadIdx.x; m < MT * 16; m += 64 * WAVES) {
+    if (row0 + m >= p.M) break;
     float best = red_val[0][m];
     int idx = red_idx[0][m];
 #pragma unroll
-    for (int w8 = 1; w8 < kWaves; ++w8) take_better(best, idx, red_val[w8][m], red_idx[w8][m]);
+    for (int w8 = 1; w8 < WAVES; ++w8) take_better(best, idx, red_val[w8][m], red_idx[w8][m]);
     const size_t slot = (size_t)slice * p.M + row0 + m;
     p.part_max[slot] = best;
     p.part_idx[slot] = idx;
@@ -221,25 +234,26 @@ __global__ __launch_bounds__(kWalkThreads) void lm_head_walk_kernel(const LmWalk
   const int64_t rows = (int64_t)p.B * p.Nmax;
   // the tree itself does not depend on the logits: wavefront 0 asks for it before anything else
   int my_par = -2, my_tok = -1;
-  if (part == 0 && lane < n) {
+  if (part == 0 && lane < p.Nmax) {
     my_par = p.parent[o + lane];
     my_tok = p.draft_tokens[o + lane];
   }
+  if (lane >= n) my_par = -2;
   {
     float best = -INFINITY;
     int idx = kNone;
-    if (lane < n) {
-      for (int c0 = part; c0 < p.n_slices; c0 += 8 * kParts) {
-        float v[8];
-        int ix[8];
+    if (lane < p.Nmax) {   // every row of the sequence has partial results; the ones past the tree are not used
+      for (int c0 = part; c0 < p.n_slices; c0 += 16 * kParts) {
+        float v[16];
+        int ix[16];
 #pragma unroll
-        for (int k = 0; k < 8; ++k) {
+        for (int k = 0; k < 16; ++k) {
           const int c = c0 + kParts * k;
           v[k] = c < p.n_slices ? p.part_max[c * rows + o + lane] : -INFINITY;
           ix[k] = c < p.n_slices ? p.part_idx[c * rows + o + lane] : kNone;
         }
 #pragma unroll
-        for (int k = 0; k < 8; ++k) take_better(best, idx, v[k], ix[k]);
+        for (int k = 0; k < 16; ++k) take_better(best, idx, v[k], ix[k]);
       }
     }
     q_best[part][lane] = best;
@@ -273,7 +287,6 @@ int n_slices_of(int32_t V) { return (V + kVocabPerWg - 1) / kVocabPerWg; }
 // the requests in flight differ only in address bits above the row pitch and crowd a few memory
 // channels (measured on a 32000 x 4096 head: 59.8 us without, 52.4 us with).
 int g_stagger = 3;
-int rows_per_pass_of(const LmHeadParams& g) { return g.n_passes > 1 ? kRowsPerPass : g.M; }
 
 }  // namespace
 
@@ -309,20 +322,27 @@ extern "C" fspad_status fspad_tree_accept_greedy_lm_head(int32_t B, int32_t Nmax
   g.weights = static_cast<const char*>(lm_head);
   g.M = B * Nmax; g.V = V; g.K = hidden_dim;
   g.n_slices = n_slices_of(V);
-  g.n_passes = (g.M + kRowsPerPass - 1) / kRowsPerPass;
-  // (a stage of the small-tile kernels is 512 k: a hidden size that is not a multiple of it has a
-  // partial last stage, which the rotation does not handle)
-  g.stagger = (rows_per_pass_of(g) > 64 || hidden_dim % 512 == 0) ? g_stagger : 0;
+  // rows per workgroup: everything up to 128 rows in one pass of the eight-wavefront shape, more in
+  // passes of up to 256 rows of the four-wavefront shape (each pass streams the weights again)
+  g.rows_per_pass = g.M <= 128 ? g.M : 256;
+  g.n_passes = (g.M + g.rows_per_pass - 1) / g.rows_per_pass;
+  const int pass_rows = g.n_passes > 1 ? (g.M + g.n_passes - 1) / g.n_passes : g.M;   // passes of equal size
+  if (g.n_passes > 1) g.rows_per_pass = (pass_rows + 15) / 16 * 16;
   const size_t slots = (size_t)g.M * g.n_slices;
   g.part_max = static_cast<float*>(workspace);
   g.part_idx = reinterpret_cast<int32_t*>(g.part_max + slots);
   if ((int64_t)g.n_slices * g.n_passes > 0x7fffffff) return FSPAD_ERR_SHAPE;
-  const dim3 grid((unsigned)(g.n_slices * g.n_passes)), block(64 * kWaves);
-  const int rows_per_pass = rows_per_pass_of(g);
-  if (rows_per_pass <= 16) hipLaunchKernelGGL((lm_head_argmax_kernel<1, 16, 16>), grid, block, 0, stream, g);
-  else if (rows_per_pass <= 32) hipLaunchKernelGGL((lm_head_argmax_kernel<2, 16, 16>), grid, block, 0, stream, g);
-  else if (rows_per_pass <= 64) hipLaunchKernelGGL((lm_head_argmax_kernel<4, 16, 16>), grid, block, 0, stream, g);
-  else hipLaunchKernelGGL((lm_head_argmax_kernel<8, 8, 16>), grid, block, 0, stream, g);
+  // (a stage of the small shapes is 512 k: a hidden size that is not a multiple of it has a partial
+  // last stage, which the rotation does not handle)
+  g.stagger = (g.rows_per_pass > 64 || hidden_dim % 512 == 0) ? g_stagger : 0;
+  const dim3 grid((unsigned)(g.n_slices * g.n_passes));
+  const int r = g.rows_per_pass;
+  if (r <= 16) hipLaunchKernelGGL((lm_head_argmax_kernel<1, 16, 16, 8, 1>), grid, dim3(512), 0, stream, g);
+  else if (r <= 32) hipLaunchKernelGGL((lm_head_argmax_kernel<2, 16, 16, 8, 1>), grid, dim3(512), 0, stream, g);
+  else if (r <= 64) hipLaunchKernelGGL((lm_head_argmax_kernel<4, 16, 16, 8, 1>), grid, dim3(512), 0, stream, g);
+  else if (r <= 128) hipLaunchKernelGGL((lm_head_argmax_kernel<8, 8, 16, 8, 1>), grid, dim3(512), 0, stream, g);
+  else if (r <= 192) hipLaunchKernelGGL((lm_head_argmax_kernel<12, 4, 16, 4, 2>), grid, dim3(256), 0, stream, g);
+  else hipLaunchKernelGGL((lm_head_argmax_kernel<16, 4, 8, 4, 2>), grid, dim3(256), 0, stream, g);
   if (hipGetLastError() != hipSuccess) return FSPAD_ERR_HIP;
 
   LmWalkParams w{};
