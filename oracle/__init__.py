@@ -272,3 +272,30 @@ def lm_head_greedy(hidden, lm_head, draft_tokens, parent, n_nodes):
         path_len[b] = length
         n_tokens[b] = length
     return path, path_len, tokens, n_tokens, target, top, margin
+
+
+def draft_topk(logits, k):
+    """Top-k cut of one draft step's output (Preliminaries, last paragraph: the output of every
+    draft step is cut to its k most probable tokens, whose probabilities then feed the joint
+    scores of the tree). Per row: the k entries with the largest logit, best first (equal logits:
+    lower token first; NaN counts as -infinity), and their log-probabilities under the row's softmax,
+
+        logp[v] = l[v] - log(sum_u exp(l[u]))        (fp64, rounded to float32 at the end).
+
+    logits [R,V] float32 (finite, -inf or NaN), 1 <= k <= V.  Returns (tokens [R,k] int32,
+    logp [R,k] float32).  A row without any finite entry yields tokens 0..k-1 and logp -inf."""
+    x = np.array(logits, dtype=np.float64, copy=True)
+    R, V = x.shape
+    assert 1 <= k <= V
+    x[np.isnan(x)] = -np.inf
+    tokens = np.zeros((R, k), np.int32)
+    logp = np.full((R, k), -np.inf, np.float32)
+    for r in range(R):
+        row = x[r]
+        order = sorted(range(V), key=lambda v: (-row[v], v))[:k]
+        tokens[r] = order
+        m = row.max()
+        if np.isfinite(m):
+            lse = m + np.log(np.sum(np.exp(row - m)))
+            logp[r] = (row[order] - lse).astype(np.float32)
+    return tokens, logp
