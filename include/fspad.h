@@ -244,6 +244,32 @@ fspad_status fspad_kv_commit(const fspad_attn_desc* desc, const void* k_tree, co
                              int32_t* kv_len_out, void* hip_stream);
 
 /*
+ * Top-k cut of a draft step's output (Preliminaries, last paragraph: the output of every draft
+ * step is cut to its k most probable tokens, and the joint probabilities of the tree follow from
+ * their probabilities). Per row:
+ *
+ *   tokens[r,0..k-1] = the k entries with the largest logit, best first (equal logits: lower
+ *                      token first; NaN counts as -infinity; -0 == +0)
+ *   logp[r,j]        = logits[r,tokens[r,j]] - log(sum_v exp(logits[r,v]))      (log-softmax)
+ *
+ *   rows        1..65535 (one per node expanded in this draft step, over all sequences)
+ *   logits      dev [rows] rows of V fp32, row_stride elements apart (>= V); finite, -infinity
+ *               or NaN (+infinity is not supported)
+ *   k           1..min(V, FSPAD_MAX_TOPK)
+ *   tokens      dev [rows,k] i32 out;  logp dev [rows,k] f32 out -- what fspad_tree_build takes as
+ *               cand_token / cand_logp of the new candidates
+ *   workspace   dev, 16-byte aligned, >= fspad_draft_topk_workspace_bytes(rows,V,k)
+ * The sum is formed from fp32 exponentials accumulated in fp64 (logp agrees with an fp64
+ * evaluation to about 1e-6); the tokens are exact. A row without a finite entry yields tokens
+ * 0..k-1 and logp -infinity. V * k <= 2^24 is required. Never synchronises, allocates nothing.
+ */
+#define FSPAD_MAX_TOPK 16
+size_t fspad_draft_topk_workspace_bytes(int32_t rows, int32_t V, int32_t k);
+fspad_status fspad_draft_topk(int32_t rows, int32_t V, int32_t k, const float* logits, int64_t row_stride,
+                              int32_t* tokens, float* logp,
+                              void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
  * Dynamic draft tree from its candidates (Preliminaries, last paragraph: the output of every
  * draft step is cut to its top-k, joint probabilities follow from the dependencies between the
  * tokens, and one more top-k over all tokens yields a valid tree of bounded size; the

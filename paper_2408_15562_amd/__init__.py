@@ -11,6 +11,8 @@ from .binding import (  # noqa: F401
     FspadError,
     PreparedCall,
     fspad_attn_desc,
+    fspad_draft_topk,
+    fspad_draft_topk_workspace_bytes,
     fspad_kv_commit,
     fspad_status_string,
     fspad_tree_accept_greedy,

@@ -26,7 +26,7 @@ _STATUS_NAMES = {0: "FSPAD_OK", 1: "FSPAD_ERR_NULL", 2: "FSPAD_ERR_SHAPE", 3: "F
 EXPORTS = ("fspad_tree_attn_workspace_bytes", "fspad_tree_attn_set_workgroups", "fspad_tree_attn",
            "fspad_tree_accept_workspace_bytes", "fspad_tree_accept_greedy", "fspad_tree_accept_sample",
            "fspad_tree_accept_lm_head_workspace_bytes", "fspad_tree_accept_greedy_lm_head",
-           "fspad_kv_commit", "fspad_tree_build", "fspad_tree_build_mask", "fspad_tree_validate", "fspad_status_string")
+           "fspad_kv_commit", "fspad_draft_topk_workspace_bytes", "fspad_draft_topk", "fspad_tree_build", "fspad_tree_build_mask", "fspad_tree_validate", "fspad_status_string")
 
 
 class FspadError(RuntimeError):
@@ -78,6 +78,10 @@ def _lib():
                                                          vp, sz, vp]
         lib.fspad_kv_commit.restype = ctypes.c_int
         lib.fspad_kv_commit.argtypes = [ctypes.POINTER(fspad_attn_desc), vp, vp, vp, vp, i32, vp, vp, vp, vp, vp]
+        lib.fspad_draft_topk_workspace_bytes.restype = sz
+        lib.fspad_draft_topk_workspace_bytes.argtypes = [i32, i32, i32]
+        lib.fspad_draft_topk.restype = ctypes.c_int
+        lib.fspad_draft_topk.argtypes = [i32, i32, i32, vp, i64, vp, vp, vp, sz, vp]
         lib.fspad_tree_build.restype = ctypes.c_int
         lib.fspad_tree_build.argtypes = [i32, i32, i32, vp, vp, vp, vp, i32, vp, vp, vp, vp, vp, vp]
         lib.fspad_tree_build_mask.restype = ctypes.c_int
@@ -346,6 +350,30 @@ def fspad_kv_commit(k_tree: torch.Tensor, v_tree: torch.Tensor, k_cache: torch.T
             _dev_ptr(kv_len_out, "kv_len_out", torch.int32), _stream_ptr(stream))
     keep = (d, k_tree, v_tree, k_cache, v_cache, kv_len, path, path_len, kv_len_out)
     return _issue(_lib().fspad_kv_commit, "fspad_kv_commit", args, keep, kv_len_out, prepare)
+
+
+def fspad_draft_topk_workspace_bytes(rows: int, V: int, k: int) -> int:
+    return int(_lib().fspad_draft_topk_workspace_bytes(rows, V, k))
+
+
+def fspad_draft_topk(logits: torch.Tensor, k: int, outputs=None, workspace: Optional[torch.Tensor] = None,
+                     stream=None, prepare: bool = False):
+    """logits: device fp32 [rows,V] (rows may be strided, entries contiguous). Returns
+    (tokens [rows,k] i32, logp [rows,k] f32); with prepare=True a PreparedCall."""
+    if logits.dim() != 2 or logits.stride(1) != 1:
+        raise ValueError("logits must be [rows,V] with contiguous entries")
+    rows, V = logits.shape
+    if workspace is None:
+        workspace = torch.empty(max(16, fspad_draft_topk_workspace_bytes(rows, V, k)), dtype=torch.uint8,
+                                device=logits.device)
+    if outputs is None:
+        outputs = (torch.empty((rows, k), dtype=torch.int32, device=logits.device),
+                   torch.empty((rows, k), dtype=torch.float32, device=logits.device))
+    tokens, logp = outputs
+    args = (rows, V, int(k), _dev_ptr(logits, "logits", torch.float32), logits.stride(0),
+            _dev_ptr(tokens, "tokens", torch.int32), _dev_ptr(logp, "logp", torch.float32),
+            _dev_ptr(workspace, "workspace"), workspace.numel() * workspace.element_size(), _stream_ptr(stream))
+    return _issue(_lib().fspad_draft_topk, "fspad_draft_topk", args, (logits, workspace), (tokens, logp), prepare)
 
 
 def fspad_tree_build(cand_parent: torch.Tensor, cand_token: torch.Tensor, cand_logp: torch.Tensor,

@@ -157,6 +157,29 @@ def test_lm_head_argument_checks_need_no_gpu(lib):
     assert call(ws=None) == 5
 
 
+def test_topk_argument_checks_need_no_gpu(lib):
+    f = lib.fspad_draft_topk
+    fake = ctypes.c_void_p(0x1000)   # never dereferenced: every case below fails validation first
+    i32, i64, sz = ctypes.c_int32, ctypes.c_int64, ctypes.c_size_t
+    need = fspad.fspad_draft_topk_workspace_bytes(10, 32000, 10)
+    assert need >= 10 * 32 * (8 * 10 + 12)
+    assert fspad.fspad_draft_topk_workspace_bytes(10, 32000, 17) == 0
+
+    def call(rows=10, V=32000, k=10, logits=fake, stride=32000, tokens=fake, ws=fake, wsb=need):
+        return f(i32(rows), i32(V), i32(k), logits, i64(stride), tokens, fake, ws, sz(wsb), None)
+
+    assert call(logits=None) == 1
+    assert call(tokens=None) == 1
+    assert call(rows=0) == 2
+    assert call(k=0) == 2
+    assert call(k=17) == 2
+    assert call(V=5, k=6, stride=5) == 2
+    assert call(stride=100) == 2
+    assert call(logits=ctypes.c_void_p(0x1002)) == 2
+    assert call(wsb=need - 1) == 5
+    assert call(ws=None) == 5
+
+
 def test_commit_argument_checks_need_no_gpu(lib):
     f = lib.fspad_kv_commit
     f.restype = ctypes.c_int
