@@ -54,6 +54,9 @@ def parse_args():
     ap.add_argument("--tree-build", action="store_true",
                     help="also select a tree from depth x top-k draft candidates at the top of every step "
                          "(fspad_tree_build; timing only: the step's other calls keep their pre-built tree)")
+    ap.add_argument("--draft-topk", action="store_true",
+                    help="also cut the outputs of the draft steps to their top-k at the top of every step: tree_depth calls "
+                         "of fspad_draft_topk over B x top-k rows of V synthetic draft logits (timing only, like --tree-build)")
     ap.add_argument("--lm-head", default=None, choices=["fused", "unfused"],
                     help="greedy workloads: start the acceptance from the last hidden states instead of ready-made logits. "
                          "fused = fspad_tree_accept_greedy_lm_head (logits never written); unfused = library GEMM to bf16 "
@@ -184,6 +187,11 @@ def main():
             st["accept"] = fspad.fspad_tree_accept_sample(st["logits"], st["tokens"], parent_d, n_nodes_d, cfg.temperature,
                                                           st["uniforms"], outputs=acc_out, workspace=ws_acc, prepare=True)
         # the prefix length stays L from step to step: every step rewrites the same tail
+        st["topk"] = []
+        if args.draft_topk:
+            rows = B * cfg.tree_topk
+            draft_logits = torch.empty((rows, V), device=dev, dtype=torch.float32).normal_(generator=gen).mul_(3.0)
+            st["topk"] = [fspad.fspad_draft_topk(draft_logits, min(cfg.tree_topk, 16), prepare=True)] * cfg.tree_depth
         st["build"] = None
         if args.tree_build:
             cands = gen_candidates(args.seed, B, cfg.tree_depth, cfg.tree_topk, V)
@@ -193,6 +201,8 @@ def main():
 
     def step(i, timed=None):
         st = sets[i % n_sets]
+        for call in st["topk"]:
+            call()
         if st["build"] is not None:
             st["build"]()
         if timed is None:
@@ -281,7 +291,7 @@ def main():
         "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": cfg.name, "layers": cfg.layers, "batch": B, "n_q_heads": Hq, "n_kv_heads": Hkv,
                    "head_dim": D, "kv_len": L, "tree_nodes": N, "vocab": V, "accept": accept, "buffer_sets": n_sets,
-                   "kv_commit": bool(args.commit), "tree_build": bool(args.tree_build),
+                   "kv_commit": bool(args.commit), "tree_build": bool(args.tree_build), "draft_topk": bool(args.draft_topk),
                    "seed": args.seed, "generator_version": GENERATOR_VERSION, "parallelism": "single-gpu"},
         "step_gb_per_s": cfg.step_bytes() / (ms_per_step * 1e-3) / 1e9,
         "step_hbm_frac": cfg.step_bytes() / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,

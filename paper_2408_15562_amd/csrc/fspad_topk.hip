@@ -48,14 +48,32 @@ __device__ __forceinline__ unsigned long long pack(unsigned key, int token) {
 }
 __device__ __forceinline__ int token_of(unsigned long long w) { return (int)(0xffffffffu - (unsigned)w); }
 
+// One step of a maximum over lanes with a data-parallel-primitive lane pattern (no LDS round trip)
+template <int CTRL>
+__device__ __forceinline__ unsigned long long dpp_max_u64(unsigned long long x) {
+  const int lo = (int)(unsigned)x, hi = (int)(unsigned)(x >> 32);
+  const unsigned olo = (unsigned)__builtin_amdgcn_update_dpp(lo, lo, CTRL, 0xf, 0xf, false);
+  const unsigned ohi = (unsigned)__builtin_amdgcn_update_dpp(hi, hi, CTRL, 0xf, 0xf, false);
+  const unsigned long long o = ((unsigned long long)ohi << 32) | olo;
+  return o > x ? o : x;
+}
+
+// Maximum over the 64 lanes, the same value in every lane: neighbours, pairs, mirrored halves of
+// eight and of sixteen lanes (after which a row of 16 agrees), then the four rows through scalars.
 __device__ __forceinline__ unsigned long long wave_max_u64(unsigned long long x) {
+  x = dpp_max_u64<0xB1>(x);    // quad_perm [1,0,3,2]
+  x = dpp_max_u64<0x4E>(x);    // quad_perm [2,3,0,1]
+  x = dpp_max_u64<0x141>(x);   // row_half_mirror
+  x = dpp_max_u64<0x140>(x);   // row_mirror
+  unsigned long long m = 0ull;
 #pragma unroll
-  for (int d = 1; d < 64; d <<= 1) {
-    const unsigned hi = __shfl_xor((unsigned)(x >> 32), d), lo = __shfl_xor((unsigned)x, d);
+  for (int row = 0; row < 4; ++row) {
+    const unsigned lo = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)x, 16 * row);
+    const unsigned hi = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)(x >> 32), 16 * row);
     const unsigned long long o = ((unsigned long long)hi << 32) | lo;
-    x = o > x ? o : x;
+    m = o > m ? o : m;
   }
-  return x;
+  return m;
 }
 
 // Workgroup-wide maximum of one word per thread; every thread gets it. `slots` is 2 x 4 words of
