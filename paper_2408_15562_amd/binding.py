@@ -377,10 +377,11 @@ def fspad_draft_topk(logits: torch.Tensor, k: int, outputs=None, workspace: Opti
 
 
 def fspad_tree_build(cand_parent: torch.Tensor, cand_token: torch.Tensor, cand_logp: torch.Tensor,
-                     n_cand: torch.Tensor, n_keep: int, n_max: int, stream=None, prepare: bool = False):
+                     n_cand: torch.Tensor, n_keep: int, n_max: int, outputs=None, stream=None,
+                     prepare: bool = False):
     """Device tensors: cand_parent, cand_token int32 [B,M], cand_logp fp32 [B,M], n_cand int32 [B].
     Returns (parent [B,n_max], draft_tokens [B,n_max], n_nodes [B], anc_mask [B,n_max] int64 bit
-    pattern of the u64 words, node_cand [B,n_max])."""
+    pattern of the u64 words, node_cand [B,n_max]); `outputs` may bring these five tensors."""
     B, M = cand_parent.shape
     for name, t, dt in (("cand_parent", cand_parent, torch.int32), ("cand_token", cand_token, torch.int32),
                         ("cand_logp", cand_logp, torch.float32)):
@@ -389,11 +390,15 @@ def fspad_tree_build(cand_parent: torch.Tensor, cand_token: torch.Tensor, cand_l
     if n_cand.dtype != torch.int32 or tuple(n_cand.shape) != (B,):
         raise ValueError("n_cand must be an int32 [B] device tensor")
     dev = cand_parent.device
-    parent = torch.empty((B, n_max), dtype=torch.int32, device=dev)
-    tokens = torch.empty((B, n_max), dtype=torch.int32, device=dev)
-    node_cand = torch.empty((B, n_max), dtype=torch.int32, device=dev)
-    n_nodes = torch.empty((B,), dtype=torch.int32, device=dev)
-    mask = torch.empty((B, n_max), dtype=torch.int64, device=dev)
+    if outputs is None:
+        outputs = (torch.empty((B, n_max), dtype=torch.int32, device=dev), torch.empty((B, n_max), dtype=torch.int32, device=dev),
+                   torch.empty((B,), dtype=torch.int32, device=dev), torch.empty((B, n_max), dtype=torch.int64, device=dev),
+                   torch.empty((B, n_max), dtype=torch.int32, device=dev))
+    parent, tokens, n_nodes, mask, node_cand = outputs
+    for name, t, shape in (("parent", parent, (B, n_max)), ("draft_tokens", tokens, (B, n_max)), ("n_nodes", n_nodes, (B,)),
+                           ("anc_mask", mask, (B, n_max)), ("node_cand", node_cand, (B, n_max))):
+        if tuple(t.shape) != shape or not t.is_contiguous() or t.dtype != (torch.int64 if name == "anc_mask" else torch.int32):
+            raise ValueError(f"{name} must be a contiguous {shape} device tensor of the documented type")
     args = (B, M, int(n_max), _dev_ptr(cand_parent, "cand_parent"), _dev_ptr(cand_token, "cand_token"),
             _dev_ptr(cand_logp, "cand_logp"), _dev_ptr(n_cand, "n_cand"), int(n_keep), _dev_ptr(parent, "parent"),
             _dev_ptr(tokens, "draft_tokens"), _dev_ptr(n_nodes, "n_nodes"), _dev_ptr(mask, "anc_mask"),
