@@ -22,12 +22,12 @@ def H():
     (1, 1, 256, 1), (1, 2, 256, 127), (1, 16, 512, 128), (1, 17, 256, 129), (1, 26, 1024, 1000),
     (1, 33, 768, 4097), (1, 60, 512, 2000), (1, 64, 256, 640), (2, 26, 512, 999), (3, 22, 256, 3000),
     (2, 60, 1024, 1500), (5, 26, 512, 777), (4, 60, 256, 1111), (3, 60, 512, 1500), (5, 60, 256, 900),
-    (9, 58, 768, 300),
+    (9, 58, 768, 300), (1, 26, 256, 40000), (2, 60, 256, 70001),
 ])
 def test_shapes(H, B, N, Hd, V):
     """One to sixteen 16-row tiles (both workgroup shapes), more than 256 rows (several passes over
-    the weights), vocabularies that are not multiples of a workgroup's 128 rows, hidden sizes of 1
-    to 4 times 256."""
+    the weights), vocabularies that are not multiples of a workgroup's 128 rows and ones with more
+    slices than the merge takes in one turn (256), hidden sizes of 1 to 4 times 256."""
     case = H.LmHeadCase(1000 + 7 * N + V, B, N, Hd, V, topk=min(10, max(1, V // 2)))
     H.assert_lm_head_equal(case.gpu(), case.cpu())
 
