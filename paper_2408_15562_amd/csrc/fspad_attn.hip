@@ -158,7 +158,9 @@ constexpr float kLazyLog2 = 8.0f;
 // the next block's K there when it keeps a single K buffer). `after_transpose()` runs, for tiles
 // done in several passes, once v has been transposed and is dead (the caller requests the next
 // block's V into the same registers there: a whole block of lead time at no register cost).
-template <int QT, int D, typename QFn, typename MaskFn, typename AfterFn, typename AfterVFn>
+// kVReady: `v` already holds the DT transposed operands (operand e = dwords 4e .. 4e+3 of the
+// array, d = 16e + col) instead of the lane's raw 16-byte slices of 8 V rows.
+template <int QT, int D, bool kVReady = false, typename QFn, typename MaskFn, typename AfterFn, typename AfterVFn>
 __device__ __forceinline__ void process_block(RowState<QT, D>& st, const bf16x8 (&k)[2][D / 32],
                                               const unsigned (&v)[8][D / 32], QFn&& q_frag, const BlockSrc& src,
                                               MaskFn&& mask_of_tile, float c, int g4, AfterFn&& after_scores,
@@ -231,6 +233,10 @@ __device__ __forceinline__ void process_block(RowState<QT, D>& st, const bf16x8 
       for (int j = 0; j < 8; ++j) pf[tt][j] = (__bf16)__builtin_amdgcn_exp2f(fmaf(s[tt][j >> 2][j & 3], c, -m));
     }
     auto transposed = [&](int e) {  // A operand of d-tile e from the lane's 8 x DT slice of V
+      if constexpr (kVReady) {
+        const unsigned* flat = &v[0][0];
+        return __builtin_bit_cast(bf16x8, u32x4{flat[4 * e], flat[4 * e + 1], flat[4 * e + 2], flat[4 * e + 3]});
+      }
       const unsigned sel = (e & 1) ? 0x07060302u : 0x05040100u;
       u32x4 w;
 #pragma unroll
@@ -591,8 +597,9 @@ __global__ __launch_bounds__(256, (QT <= 2 ? 2 : 1)) void tree_attn_bf16_kernel(
 // the workgroup fetches each block once, every wavefront copying an eighth of it into an LDS
 // stage with the global-to-LDS load (row-contiguous requests, no registers), and all of them pick
 // their operands out of the stage. K is kept swizzled (16-byte chunk c of row r at slot c ^ f(r))
-// so that a fragment read, 16 rows by one chunk, touches 16 different bank groups; V is kept
-// row-major, which is how it is read. Three stages of one block each (two blocks each in the
+// so that a fragment read, 16 rows by one chunk, touches 16 different bank groups; V (D = 128) is
+// read with the transposing LDS load of gfx950, which hands every lane the four keys of one dim --
+// the A operand of V^T P^T as it is, without byte permutes (its 32-byte pieces are swizzled too). Three stages of one block each (two blocks each in the
 // eight-wavefront form, which halves the barriers): stage i is read while i+1 and i+2 are in flight.
 template <int D, int WAVES>
 struct Stage {
@@ -603,6 +610,10 @@ struct Stage {
   static constexpr int kBytes = 2 * kTensorBytes;            // K then V
   static constexpr int kPerWave = 2 * kLoads / WAVES;        // copy instructions per wavefront and block
   __device__ static __forceinline__ int swizzle(int r) { return D == 128 ? (r & 15) : ((r >> 1) & 7); }
+  // V, D = 128: read with the transposing LDS load, 16 lanes x 8 bytes = 4 keys x 32 bytes at a time;
+  // 32-byte piece e of key r sits at piece e ^ (r & 7), so that the 16 keys one instruction touches
+  // spread over all banks. D = 64: row-major, read as rows.
+  __device__ static __forceinline__ int v_swizzle(int r) { return D == 128 ? 2 * (r & 7) : 0; }
 };
 typedef const __attribute__((address_space(1))) void* GlobalPtr;
 typedef __attribute__((address_space(3))) void* LdsPtr;
@@ -633,7 +644,7 @@ __global__ __launch_bounds__(64 * WAVES, (WAVES == 4 ? 2 : 1)) void tree_attn_gq
     dma_tensor[i] = x / S::kLoads;
     dma_row[i] = n * S::kRowsPerLoad + lane / S::kChunks;
     const int chunk = lane & (S::kChunks - 1);
-    dma_chunk[i] = dma_tensor[i] == 0 ? (chunk ^ S::swizzle(dma_row[i])) : chunk;
+    dma_chunk[i] = dma_tensor[i] == 0 ? (chunk ^ S::swizzle(dma_row[i])) : (chunk ^ S::v_swizzle(dma_row[i]));
     dma_dst[i] = dma_tensor[i] * S::kTensorBytes + n * 1024;
   }
   // this lane's operand reads: K fragments (key tile 0; tile 1 is 16 rows further), V rows
@@ -642,6 +653,10 @@ __global__ __launch_bounds__(64 * WAVES, (WAVES == 4 ? 2 : 1)) void tree_attn_gq
   for (int ks = 0; ks < KS; ++ks) kfrag[ks] = (unsigned)col * (D * 2) + 16u * ((4 * ks + g4) ^ S::swizzle(col));
 #pragma unroll
   for (int j = 0; j < 8; ++j) vrow[j] = S::kTensorBytes + (unsigned)key_of(g4, j) * (D * 2) + (unsigned)(D / 8) * col;
+  // transposing read (D = 128): lane (col, g4) points at key 4*g4 + col/4 (+16 for the second half),
+  // dims 16e + 4*(col%4) .. +3, and receives dims 16e + col of the group's four keys
+  const unsigned vtr_off = S::kTensorBytes + (unsigned)(4 * g4 + (col >> 2)) * (D * 2) + 8u * (col & 3) +
+                       ((unsigned)((4 * g4 + (col >> 2)) & 7) << 5);
 
   const unsigned w = blockIdx.x;
   const unsigned wr = w * (unsigned)p.wg_rem, wq = wr / (unsigned)p.n_wgs;
@@ -780,17 +795,27 @@ __global__ __launch_bounds__(64 * WAVES, (WAVES == 4 ? 2 : 1)) void tree_attn_gq
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks)
               kf[kt][ks] = *reinterpret_cast<const bf16x8*>(sbase + kt * 16 * (D * 2) + kfrag[ks]);
+          if constexpr (D == 128) {
+            typedef __attribute__((ext_vector_type(4))) short s16x4;
+            typedef __attribute__((address_space(3))) s16x4* LdsS16x4;
+            unsigned* flat = &vr[0][0];
 #pragma unroll
-          for (int j = 0; j < 8; ++j) {
-            if constexpr (D == 128) {
-              const u32x4 x = *reinterpret_cast<const u32x4*>(sbase + vrow[j]);
-              vr[j][0] = x[0]; vr[j][1] = x[1]; vr[j][2] = x[2]; vr[j][3] = x[3];
-            } else {
+            for (int e = 0; e < DT; ++e) {
+              const char* src = sbase + (vtr_off ^ ((unsigned)e << 5));
+              const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LdsS16x4)src);
+              const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LdsS16x4)(src + 16 * (D * 2)));
+              const u32x2 a = __builtin_bit_cast(u32x2, lo), b2 = __builtin_bit_cast(u32x2, hi);
+              flat[4 * e] = a[0]; flat[4 * e + 1] = a[1]; flat[4 * e + 2] = b2[0]; flat[4 * e + 3] = b2[1];
+            }
+            process_block<QT, D, true>(st, kf, vr, q_frag, cur, mask_of_tile, c, g4, [] {}, [] {});
+          } else {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
               const u32x2 x = *reinterpret_cast<const u32x2*>(sbase + vrow[j]);
               vr[j][0] = x[0]; vr[j][1] = x[1];
             }
+            process_block<QT, D>(st, kf, vr, q_frag, cur, mask_of_tile, c, g4, [] {}, [] {});
           }
-          process_block<QT, D>(st, kf, vr, q_frag, cur, mask_of_tile, c, g4, [] {}, [] {});
         }
       }
       stage = stage == 2 ? 0 : stage + 1;
@@ -803,6 +828,36 @@ __global__ __launch_bounds__(64 * WAVES, (WAVES == 4 ? 2 : 1)) void tree_attn_gq
         const RowInfo ri = row_info(t);
         if (!ri.exists) continue;
         const float l_row = st.l[t][0];
+        if constexpr (D == 128) {
+          // operands from the transposing read: accumulator e holds dims 16e + 4*g4 .. +3
+          const float inv = ri.valid ? 1.0f / l_row : 0.f;
+          float* slot = p.part + (int64_t)(unit + w) * rows_per_unit * (D + 2);
+          const int lr = wave * ROWS + 16 * t + col;
+          if (!whole_unit && ri.valid && g4 == 0)
+            *reinterpret_cast<float2*>(slot + (int64_t)rows_per_unit * D + 2 * lr) = make_float2(st.m[t], l_row);
+#pragma unroll
+          for (int e = 0; e < DT; ++e) {
+            const int d0 = 16 * e + 4 * g4;
+            if (whole_unit) {
+              float vals[4];
+#pragma unroll
+              for (int i = 0; i < 4; ++i) vals[i] = ri.valid ? st.o[t][e][i] * inv : 0.f;
+              if (p.out_bf16) {
+                typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+                bf16x4 pk;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) pk[i] = (__bf16)vals[i];
+                *reinterpret_cast<bf16x4*>(reinterpret_cast<__bf16*>(p.out) + ri.out * D + d0) = pk;
+              } else {
+                *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(p.out) + ri.out * D + d0) =
+                    f32x4{vals[0], vals[1], vals[2], vals[3]};
+              }
+            } else if (ri.valid) {
+              *reinterpret_cast<f32x4*>(slot + (int64_t)lr * D + d0) = st.o[t][e];
+            }
+          }
+          continue;
+        }
 #pragma unroll
         for (int e0 = 0; e0 < DT; e0 += 4) {
           if (whole_unit) {
