@@ -299,3 +299,21 @@ def draft_topk(logits, k):
             lse = m + np.log(np.sum(np.exp(row - m)))
             logp[r] = (row[order] - lse).astype(np.float32)
     return tokens, logp
+
+
+def lm_head_logits(hidden, lm_head):
+    """logits[b,i,v] = sum_k hidden[b,i,k] * lm_head[v,k] in fp64 (Methodology, "LM Head"),
+    rounded once to float32: the values a correctly rounded fp32 LM head would hand to the
+    acceptance.  hidden [B,Nmax,Hd], lm_head [V,Hd]."""
+    hidden = np.asarray(hidden, dtype=np.float64)
+    lm_head = np.asarray(lm_head, dtype=np.float64)
+    B, Nmax, Hd = hidden.shape
+    return (hidden.reshape(B * Nmax, Hd) @ lm_head.T).reshape(B, Nmax, -1).astype(np.float32)
+
+
+def lm_head_sample(hidden, lm_head, draft_tokens, parent, n_nodes, temperature, uniforms):
+    """Tree rejection sampling straight from the target's last hidden states: the acceptance of
+    `accept_sample` (Preliminaries, validation phase; Experiments "Settings": temperature 1,
+    acceptance not relaxed) applied to `lm_head_logits`.  Returns what accept_sample returns,
+    the smallest relative decision margin per sequence included."""
+    return accept_sample(lm_head_logits(hidden, lm_head), draft_tokens, parent, n_nodes, temperature, uniforms)

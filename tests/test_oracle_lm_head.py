@@ -8,7 +8,7 @@ a chain whose every token is planted so that the whole tree is accepted."""
 import numpy as np
 
 import oracle
-from workloads import chain_tree, gen_lm_head, gen_trees
+from workloads import chain_tree, gen_draft_tokens, gen_lm_head, gen_trees
 
 
 def test_hand_worked_example():
@@ -108,3 +108,36 @@ def test_planted_chain_is_accepted_whole():
     assert np.array_equal(toks[0], target[0]) and np.array_equal(toks[1, :5], target[1, :5])
     assert (path[1, 5:] == -1).all() and (toks[1, 5:] == -1).all()
     assert np.nanmin(margin) > 0
+
+
+def test_sampling_from_hidden_states_is_the_sampling_oracle_on_the_defined_logits():
+    # integer data: the logits are exact in fp32, so the composition can be checked against logits
+    # written out by hand (einsum in integers), with the separately pinned sampling walk
+    from workloads import gen_uniforms
+    rng = np.random.default_rng(8)
+    B, N, Hd, V = 2, 14, 6, 30
+    hidden = rng.integers(-2, 3, size=(B, N, Hd)).astype(np.float64)
+    w = rng.integers(-2, 3, size=(V, Hd)).astype(np.float64)
+    parent, n_nodes = gen_trees(13, B, N, 4, 3)
+    logits = np.einsum("bik,vk->biv", hidden.astype(np.int64), w.astype(np.int64)).astype(np.float32)
+    assert np.array_equal(oracle.lm_head_logits(hidden, w), logits)
+    draft = gen_draft_tokens(13, logits, parent, n_nodes, "sample")
+    uni = gen_uniforms(13, B, N)
+    a = oracle.lm_head_sample(hidden, w, draft, parent, n_nodes, 0.7, uni)
+    r = oracle.accept_sample(logits, draft, parent, n_nodes, 0.7, uni)
+    for x, y in zip(a, r):
+        assert np.array_equal(x, y)
+
+
+def test_cold_sampling_from_hidden_states_is_the_greedy_walk():
+    from workloads import gen_uniforms
+    B, N, Hd, V = 3, 20, 64, 400
+    hidden, w = gen_lm_head(21, B, N, Hd, V)
+    parent, n_nodes = gen_trees(21, B, N, 5, 4)
+    draft = gen_draft_tokens(21, oracle.lm_head_logits(hidden, w), parent, n_nodes, "greedy", 0.5)
+    g = oracle.lm_head_greedy(hidden, w, draft, parent, n_nodes)
+    s = oracle.lm_head_sample(hidden, w, draft, parent, n_nodes, 1e-3, gen_uniforms(21, B, N))
+    assert g[6][g[4] >= 0].min() > 0.02          # the argmaxes are decided far beyond a temperature of 1e-3
+    for x, y in zip(g[:4], s[:4]):
+        assert np.array_equal(x, y)
+    assert g[1].max() >= 2
