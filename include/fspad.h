@@ -216,6 +216,35 @@ fspad_status fspad_tree_accept_greedy_lm_head(int32_t B, int32_t Nmax, int32_t V
                                               void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * Tree rejection sampling straight from the target's last hidden states, fused with the LM head
+ * (Methodology, "LM Head"; Preliminaries, validation phase; Experiments "Settings": temperature 1,
+ * acceptance not relaxed). The walk of fspad_tree_accept_sample over
+ *
+ *   logits[b,i,v] = sum_k hidden[b,i,k] * lm_head[v,k]     bf16 inputs, exact products, fp32 sums
+ *
+ * without the [B*Nmax, V] logits ever being written: the GEMM leaves, per row and group of 128
+ * tokens, the maximum and the sum of exp((l - max)/T), and sets aside the logit of every node's
+ * own token under its parent's row; the last token is drawn by locating the group that holds the
+ * crossing of u_bonus * Z and recomputing that group's 128 logits.
+ *
+ * Arguments as for fspad_tree_accept_greedy_lm_head (without node_target / node_top) plus
+ * temperature and uniforms as for fspad_tree_accept_sample; same workspace size.
+ * The exponentials are evaluated in fp32 on fp32 sums of the library's own order (the recomputed
+ * group is summed in yet another order), the sums in fp64: a decision (an accept test, the
+ * crossing of the last draw) is only defined where its relative margin is above about 1e-5; the
+ * tests compare sequences whose smallest margin exceeds 1e-4.
+ * Errors as for fspad_tree_accept_sample; never synchronises, allocates nothing.
+ */
+fspad_status fspad_tree_accept_sample_lm_head(int32_t B, int32_t Nmax, int32_t V, int32_t hidden_dim,
+                                              const void* hidden, const void* lm_head,
+                                              const int32_t* draft_tokens, const int32_t* parent,
+                                              const int32_t* n_nodes,
+                                              float temperature, const float* uniforms,
+                                              int32_t* path, int32_t* path_len,
+                                              int32_t* tokens, int32_t* n_tokens,
+                                              void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
  * Commit of the accepted path to the KV cache. The paper leaves this step implied
  * (Preliminaries: the tokens that pass validation extend the sequence from which the
  * next draft phase starts): the keys and values the verification forward computed for

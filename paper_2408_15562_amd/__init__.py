@@ -19,6 +19,7 @@ from .binding import (  # noqa: F401
     fspad_tree_accept_greedy_lm_head,
     fspad_tree_accept_lm_head_workspace_bytes,
     fspad_tree_accept_sample,
+    fspad_tree_accept_sample_lm_head,
     fspad_tree_accept_workspace_bytes,
     fspad_tree_attn,
     fspad_tree_attn_set_workgroups,

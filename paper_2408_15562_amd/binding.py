@@ -26,6 +26,7 @@ _STATUS_NAMES = {0: "FSPAD_OK", 1: "FSPAD_ERR_NULL", 2: "FSPAD_ERR_SHAPE", 3: "F
 EXPORTS = ("fspad_tree_attn_workspace_bytes", "fspad_tree_attn_set_workgroups", "fspad_tree_attn",
            "fspad_tree_accept_workspace_bytes", "fspad_tree_accept_greedy", "fspad_tree_accept_sample",
            "fspad_tree_accept_lm_head_workspace_bytes", "fspad_tree_accept_greedy_lm_head",
+           "fspad_tree_accept_sample_lm_head",
            "fspad_kv_commit", "fspad_draft_topk_workspace_bytes", "fspad_draft_topk", "fspad_tree_build", "fspad_tree_build_mask", "fspad_tree_validate", "fspad_status_string")
 
 
@@ -76,6 +77,9 @@ def _lib():
         lib.fspad_tree_accept_greedy_lm_head.restype = ctypes.c_int
         lib.fspad_tree_accept_greedy_lm_head.argtypes = [i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp,
                                                          vp, sz, vp]
+        lib.fspad_tree_accept_sample_lm_head.restype = ctypes.c_int
+        lib.fspad_tree_accept_sample_lm_head.argtypes = [i32, i32, i32, i32, vp, vp, vp, vp, vp, ctypes.c_float, vp,
+                                                         vp, vp, vp, vp, vp, sz, vp]
         lib.fspad_kv_commit.restype = ctypes.c_int
         lib.fspad_kv_commit.argtypes = [ctypes.POINTER(fspad_attn_desc), vp, vp, vp, vp, i32, vp, vp, vp, vp, vp]
         lib.fspad_draft_topk_workspace_bytes.restype = sz
@@ -319,6 +323,38 @@ def fspad_tree_accept_greedy_lm_head(hidden: torch.Tensor, lm_head: torch.Tensor
     keep = (hidden, lm_head, draft_tokens, parent, n_nodes, workspace)
     return _issue(_lib().fspad_tree_accept_greedy_lm_head, "fspad_tree_accept_greedy_lm_head", args, keep,
                   (path, path_len, tokens, n_tokens, node_target, node_top), prepare)
+
+
+def fspad_tree_accept_sample_lm_head(hidden: torch.Tensor, lm_head: torch.Tensor, draft_tokens: torch.Tensor,
+                                     parent: torch.Tensor, n_nodes: torch.Tensor, temperature: float,
+                                     uniforms: torch.Tensor, outputs=None, workspace: Optional[torch.Tensor] = None,
+                                     stream=None, prepare: bool = False):
+    """hidden [B,Nmax,Hd] bf16, lm_head [V,Hd] bf16, uniforms fp32 [B,2,Nmax], all contiguous on the
+    device. Returns (path, path_len, tokens, n_tokens); with prepare=True a PreparedCall."""
+    if hidden.dim() != 3 or lm_head.dim() != 2 or not hidden.is_contiguous() or not lm_head.is_contiguous():
+        raise ValueError("hidden must be a contiguous [B,Nmax,Hd] tensor and lm_head a contiguous [V,Hd] tensor")
+    B, Nmax, Hd = hidden.shape
+    V = lm_head.shape[0]
+    if lm_head.shape[1] != Hd:
+        raise ValueError("hidden and lm_head disagree on the hidden size")
+    for name, t in (("draft_tokens", draft_tokens), ("parent", parent), ("n_nodes", n_nodes)):
+        if t.dtype != torch.int32 or not t.is_contiguous():
+            raise ValueError(f"{name} must be a contiguous int32 device tensor")
+    if uniforms.dtype != torch.float32 or not uniforms.is_contiguous() or tuple(uniforms.shape) != (B, 2, Nmax):
+        raise ValueError("uniforms must be a contiguous fp32 [B,2,Nmax] device tensor")
+    if workspace is None:
+        workspace = torch.empty(max(16, fspad_tree_accept_lm_head_workspace_bytes(B, Nmax, V)), dtype=torch.uint8,
+                                device=hidden.device)
+    path, path_len, tokens, n_tokens = _accept_outputs(B, Nmax, hidden.device, outputs)
+    args = (B, Nmax, V, Hd, _dev_ptr(hidden, "hidden", torch.bfloat16), _dev_ptr(lm_head, "lm_head", torch.bfloat16),
+            _dev_ptr(draft_tokens, "draft_tokens"), _dev_ptr(parent, "parent"), _dev_ptr(n_nodes, "n_nodes"),
+            float(temperature), _dev_ptr(uniforms, "uniforms"),
+            _dev_ptr(path, "path"), _dev_ptr(path_len, "path_len"), _dev_ptr(tokens, "tokens"),
+            _dev_ptr(n_tokens, "n_tokens"), _dev_ptr(workspace, "workspace"),
+            workspace.numel() * workspace.element_size(), _stream_ptr(stream))
+    keep = (hidden, lm_head, draft_tokens, parent, n_nodes, uniforms, workspace)
+    return _issue(_lib().fspad_tree_accept_sample_lm_head, "fspad_tree_accept_sample_lm_head", args, keep,
+                  (path, path_len, tokens, n_tokens), prepare)
 
 
 def fspad_kv_commit(k_tree: torch.Tensor, v_tree: torch.Tensor, k_cache: torch.Tensor, v_cache: torch.Tensor,

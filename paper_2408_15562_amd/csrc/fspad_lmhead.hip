@@ -36,10 +36,17 @@ constexpr int kWalkThreads = 1024;
 struct LmHeadParams {
   const char* hidden;   // [M][K] bf16
   const char* weights;  // [V][K] bf16
-  float* part_max;      // [n_slices][M]
-  int32_t* part_idx;    // [n_slices][M]
+  float* part_max;      // greedy: [n_slices][M]; sampling: [M][n_slices]
+  int32_t* part_idx;    // greedy: [n_slices][M]
+  double* part_sum;     // sampling: [M][n_slices], sum of exp((l - part_max) / T) over the slice
+  float* node_logit;    // sampling: [M], the logit of node c's own token under its parent's row
+  const int32_t* draft_tokens;   // sampling: the tree, to know which logits the walk will ask for
+  const int32_t* parent;
+  const int32_t* n_nodes;
   int32_t M, V, K, n_slices, n_passes, rows_per_pass;
   int32_t stagger;      // stages by which consecutive workgroups are offset along k (0: all start at k = 0)
+  int32_t Nmax;
+  float inv_t_log2e;    // sampling: log2(e) / T
 };
 
 // (value, index) with "larger value, then lower index" order
@@ -54,7 +61,9 @@ __device__ __forceinline__ void take_better(float& v, int& i, float ov, int oi) 
 // wavefronts of one tile (two per SIMD) for up to 128 rows; for more, four wavefronts of two tiles
 // (one per SIMD, the whole register file), which halves the LDS reads per product: with 256 rows an
 // operand read of all of them for one weight tile would cost as much as its 16 products.
-template <int MT, int SPS, int kRing, int WAVES, int VT>
+// MODE 0: per slice and row (max, first argmax) for the greedy walk. MODE 1: per slice and row
+// (max, sum of exponentials) and the logits of the draft tokens, for the sampling walk.
+template <int MT, int SPS, int kRing, int WAVES, int VT, int MODE>
 __global__ __launch_bounds__(64 * WAVES, (WAVES == 8 ? 2 : 1)) void lm_head_argmax_kernel(const LmHeadParams p) {
   static_assert(WAVES * VT * 16 == kVocabPerWg, "workgroup shape");
   constexpr int kStageK = 32 * SPS;
@@ -170,6 +179,66 @@ __global__ __launch_bounds__(64 * WAVES, (WAVES == 8 ? 2 : 1)) void lm_head_argm
     }
   }
 
+  if constexpr (MODE == 1) {
+    // The stages are dead: the workgroup's 16*MT x 128 logits go there, as fp32, row by row
+    // (16-byte chunk c of row r at chunk c ^ (r & 15): sixteen rows written at once hit different banks).
+    constexpr int kRows = MT * 16;
+    static_assert(kRows * 512 <= 2 * kStageBytes, "the logits of a workgroup fit the two stages");
+    __syncthreads();
+    float* dump = reinterpret_cast<float*>(xs);
+#pragma unroll
+    for (int t = 0; t < MT; ++t)
+#pragma unroll
+      for (int nv = 0; nv < VT; ++nv) {
+        const int r = t * 16 + n, chunk = (wave * (16 * VT) + 16 * nv + 4 * g) >> 2;
+        *reinterpret_cast<f32x4*>(dump + r * 128 + ((chunk ^ (r & 15)) << 2)) = acc[t][nv];
+      }
+    __syncthreads();
+    // slice statistics: sixteen lanes per row, eight logits each
+    const int sub = lane & 15;
+    const int slice0 = slice * kVocabPerWg;
+    for (int r = threadIdx.x >> 4; r < kRows; r += 4 * WAVES) {   // uniform per 16 lanes
+      float x[8];
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        const int chunk = sub + 16 * h;
+        const f32x4 v4 = *reinterpret_cast<const f32x4*>(dump + r * 128 + ((chunk ^ (r & 15)) << 2));
+#pragma unroll
+        for (int i = 0; i < 4; ++i) x[4 * h + i] = (slice0 + 4 * chunk + i < p.V && v4[i] == v4[i]) ? v4[i] : -INFINITY;
+      }
+      float m = x[0];
+#pragma unroll
+      for (int i = 1; i < 8; ++i) m = fmaxf(m, x[i]);
+#pragma unroll
+      for (int d = 1; d < 16; d <<= 1) m = fmaxf(m, __shfl_xor(m, d));
+      float sum = 0.f;
+      if (m > -INFINITY) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) sum += __builtin_amdgcn_exp2f((x[i] - m) * p.inv_t_log2e);
+      }
+      double dsum = sum;
+#pragma unroll
+      for (int d = 1; d < 16; d <<= 1) dsum += __shfl_xor(dsum, d);
+      if (sub == 0 && row0 + r < p.M) {
+        const size_t slot = (size_t)(row0 + r) * p.n_slices + slice;
+        p.part_max[slot] = m;
+        p.part_sum[slot] = dsum;
+      }
+    }
+    // the logits the walk will test: node c's token under the row of c's parent
+    for (int cnode = threadIdx.x; cnode < p.M; cnode += 64 * WAVES) {
+      const int b = cnode / p.Nmax, i = cnode - b * p.Nmax;
+      if (i == 0 || i >= p.n_nodes[b]) continue;
+      const int par = p.parent[cnode], tok = p.draft_tokens[cnode];
+      if (par < 0 || par >= i || tok < slice0 || tok >= slice0 + kVocabPerWg || tok >= p.V) continue;
+      const int r = b * p.Nmax + par - row0;
+      if (r < 0 || r >= kRows) continue;
+      const int vl = tok - slice0;
+      p.node_logit[cnode] = dump[r * 128 + ((((vl >> 2) ^ (r & 15)) << 2) | (vl & 3))];
+    }
+    return;
+  }
+
   // argmax over this wavefront's vocabulary rows for each hidden-state row (lane column n):
   // ascending vocabulary order inside the lane, then across the four lane groups
 #pragma unroll
@@ -281,6 +350,251 @@ __global__ __launch_bounds__(kWalkThreads) void lm_head_walk_kernel(const LmWalk
   fspad_detail::greedy_descend(target, n, p.Nmax, lane, o, b, my_par, my_tok, p.path, p.tokens, p.path_len, p.n_tokens);
 }
 
+struct LmSampleWalkParams {
+  const float* part_max;     // [B*Nmax][n_slices]
+  const double* part_sum;
+  const float* node_logit;   // [B*Nmax]
+  const char* hidden;        // [B*Nmax][K] bf16
+  const char* weights;       // [V][K] bf16
+  const int32_t* draft_tokens;
+  const int32_t* parent;
+  const int32_t* n_nodes;
+  const float* uniforms;     // [B][2][Nmax]
+  int32_t* path;
+  int32_t* path_len;
+  int32_t* tokens;
+  int32_t* n_tokens;
+  double inv_temperature;
+  int32_t B, Nmax, V, K, n_slices;
+};
+
+// Tree rejection sampling over the slice statistics the GEMM left (one workgroup of 1024 threads per
+// sequence): (1) every row's slice maxima and sums are merged into the row's max M and normaliser Z,
+// sixteen threads per row; (2) every node's weight exp((logit - M[parent]) / T) from the logit the
+// GEMM set aside; (3) wavefront 0 walks the tree out of LDS, children in index order against the
+// running residual, exactly as the walk over materialised logits does; (4) the last token: the
+// slice that holds the crossing of u * Z follows from the slice sums (less the rejected tokens), its
+// 128 logits are recomputed (128 dot products over K, eight threads each) and searched.
+__global__ __launch_bounds__(kWalkThreads) void lm_head_sample_walk_kernel(const LmSampleWalkParams p) {
+  __shared__ int rej_tok[FSPAD_MAX_NODES];
+  __shared__ double rej_w[FSPAD_MAX_NODES];
+  __shared__ double sh_d[4];
+  __shared__ int sh_i[8];
+  __shared__ double row_M[FSPAD_MAX_NODES], row_Z[FSPAD_MAX_NODES], node_w[FSPAD_MAX_NODES];
+  __shared__ int node_par[FSPAD_MAX_NODES], node_tok[FSPAD_MAX_NODES];
+  __shared__ float node_u[2][FSPAD_MAX_NODES];
+  __shared__ float slice_logit[kVocabPerWg];
+  __shared__ double scan_part[2];
+  const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int64_t o = (int64_t)b * p.Nmax;
+  const float* u_acc = p.uniforms + (int64_t)b * 2 * p.Nmax;
+  const int n = min(p.n_nodes[b], p.Nmax);
+
+  // (1) row statistics: thread (row = tid / 16, q = tid % 16) takes every 16th slice of its row
+  {
+    const int row = tid >> 4, q = tid & 15;
+    const bool in_range = row < p.Nmax;
+    const float* pm = p.part_max + (o + (in_range ? row : 0)) * p.n_slices;
+    const double* ps = p.part_sum + (o + (in_range ? row : 0)) * p.n_slices;
+    float m = -INFINITY;
+    for (int c0 = q; c0 < p.n_slices; c0 += 128) {
+      float v[8];
+#pragma unroll
+      for (int k = 0; k < 8; ++k) v[k] = (in_range && c0 + 16 * k < p.n_slices) ? pm[c0 + 16 * k] : -INFINITY;
+#pragma unroll
+      for (int k = 0; k < 8; ++k) m = fmaxf(m, v[k]);
+    }
+#pragma unroll
+    for (int d = 1; d < 16; d <<= 1) m = fmaxf(m, __shfl_xor(m, d));
+    double z = 0.0;
+    if (m > -INFINITY) {
+      const float c2 = (float)(p.inv_temperature * 1.4426950408889634);
+      for (int c0 = q; c0 < p.n_slices; c0 += 128) {
+        float v[8];
+        double sum[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+          const bool ok = in_range && c0 + 16 * k < p.n_slices;
+          v[k] = ok ? pm[c0 + 16 * k] : -INFINITY;
+          sum[k] = ok ? ps[c0 + 16 * k] : 0.0;
+        }
+#pragma unroll
+        for (int k = 0; k < 8; ++k)
+          if (v[k] > -INFINITY) z += sum[k] * (double)__builtin_amdgcn_exp2f((v[k] - m) * c2);
+      }
+    }
+#pragma unroll
+    for (int d = 1; d < 16; d <<= 1) z += __shfl_xor(z, d);
+    if (in_range && q == 0) { row_M[row] = (double)m; row_Z[row] = z; }
+    if (tid < FSPAD_MAX_NODES) {
+      const bool ok = tid < p.Nmax;
+      node_par[tid] = ok ? p.parent[o + tid] : -2;
+      node_tok[tid] = ok ? p.draft_tokens[o + tid] : -1;
+      node_u[0][tid] = ok ? u_acc[tid] : 0.f;
+      node_u[1][tid] = ok ? u_acc[p.Nmax + tid] : 0.f;
+    }
+  }
+  __syncthreads();
+  // (2) weight of every node's draft token under its parent's row
+  if (tid < FSPAD_MAX_NODES) {
+    double w = 0.0;
+    const int par = node_par[tid], tok = node_tok[tid];
+    if (tid > 0 && tid < n && par >= 0 && par < tid && tok >= 0 && tok < p.V) {
+      const double M = row_M[par];
+      const float lx = p.node_logit[o + tid];
+      if (M > -INFINITY && lx == lx) w = exp(fmin(((double)lx - M) * p.inv_temperature, 0.0));
+    }
+    node_w[tid] = w;
+  }
+  __syncthreads();
+
+  if (wave == 0) {
+    const int my_par = node_par[lane], my_tok = node_tok[lane];
+    const double my_w = node_w[lane];
+    const float my_u = node_u[0][lane];
+    int my_path = lane == 0 ? 0 : -1, my_out = -1;
+    int cur = 0, len = 1, nrej = 0;
+    int my_rej = -1;       // lane k keeps the k-th token rejected at the current node, and its weight
+    double my_rej_w = 0.0;
+    double M = 0.0, Z = 0.0;
+    auto lane_value = [](double v, int src) {   // src is the same in every lane: scalar reads, no LDS exchange
+      const unsigned long long bits = __builtin_bit_cast(unsigned long long, v);
+      const unsigned lo = __builtin_amdgcn_readlane((unsigned)bits, src);
+      const unsigned hi = __builtin_amdgcn_readlane((unsigned)(bits >> 32), src);
+      return __builtin_bit_cast(double, ((unsigned long long)hi << 32) | lo);
+    };
+    for (int iter = 0; iter < p.Nmax; ++iter) {  // one level per iteration; a leaf ends the walk
+      M = row_M[cur];
+      Z = row_Z[cur];
+      nrej = 0;
+      my_rej = -1;
+      const bool is_kid = lane > 0 && lane < n && my_par == cur;
+      unsigned long long kids = __ballot(is_kid);
+      int accepted = -1;
+      while (kids != 0ull && len < p.Nmax) {
+        const int c = __builtin_amdgcn_readfirstlane(__ffsll(kids) - 1);
+        kids &= kids - 1ull;
+        const int x = __builtin_amdgcn_readlane(my_tok, c);
+        // a token that an earlier sibling proposed has left the residual: it weighs nothing now
+        const bool gone = __ballot(lane < nrej && my_rej == x) != 0ull;
+        const double w = gone ? 0.0 : lane_value(my_w, c);
+        const double lhs = (double)__builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, my_u), c)) * Z;
+        if (lhs < w) { accepted = c; break; }
+        Z -= w;
+        if (lane == nrej) { my_rej = x; my_rej_w = w; }
+        ++nrej;
+      }
+      if (accepted < 0) break;
+      if (lane == len) my_path = accepted;
+      const int accepted_tok = __builtin_amdgcn_readlane(my_tok, accepted);
+      if (lane == len - 1) my_out = accepted_tok;
+      cur = accepted;
+      ++len;
+    }
+    if (lane < nrej) { rej_tok[lane] = my_rej; rej_w[lane] = my_rej_w; }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+    if (lane < p.Nmax) { p.path[o + lane] = my_path; if (lane != len - 1) p.tokens[o + lane] = my_out; }
+    if (lane == 0) { p.path_len[b] = len; p.n_tokens[b] = len; }
+
+    // last token, stage 1: which slice holds the running-sum crossing of t = u * Z
+    const double t = (double)node_u[1][cur] * Z;
+    const int64_t row = o + cur;
+    const float* pm = p.part_max + row * p.n_slices;
+    const double* ps = p.part_sum + row * p.n_slices;
+    double carry = 0.0, before = 0.0;
+    int found = -1, last_pos = -1;
+    for (int c0 = 0; c0 < p.n_slices && found < 0; c0 += 64) {
+      const int c = c0 + lane;
+      double r = 0.0;
+      if (c < p.n_slices && pm[c] > -INFINITY) {
+        r = ps[c] * exp(fmin(((double)pm[c] - M) * p.inv_temperature, 0.0));
+        for (int k = 0; k < nrej; ++k)
+          if (rej_tok[k] >= c * kVocabPerWg && rej_tok[k] < (c + 1) * kVocabPerWg && rej_tok[k] < p.V) r -= rej_w[k];
+      }
+      double incl = r;
+#pragma unroll
+      for (int off = 1; off < 64; off <<= 1) {
+        const double up = __shfl_up(incl, off);
+        if (lane >= off) incl += up;
+      }
+      const unsigned long long pos = __ballot(r > 0.0);
+      if (pos) last_pos = c0 + 63 - __clzll(pos);
+      const unsigned long long hit = __ballot(c < p.n_slices && carry + incl > t);
+      if (hit) {
+        const int first = __ffsll(hit) - 1;
+        found = c0 + first;
+        before = carry + __shfl(incl - r, first);
+      } else {
+        carry += __shfl(incl, 63);
+      }
+    }
+    if (lane == 0) {
+      // rounding fallback: the last slice that still has mass, searched to its end
+      sh_i[0] = cur; sh_i[1] = len; sh_i[2] = nrej;
+      sh_i[3] = found >= 0 ? found : last_pos;
+      sh_d[0] = M;
+      sh_d[1] = found >= 0 ? t - before : INFINITY;
+    }
+  }
+  __syncthreads();
+
+  // last token, stage 2: the slice's logits again (thread (v = tid / 8, part = tid % 8) sums an eighth
+  // of K), then the crossing inside the slice
+  const int cur = sh_i[0], len = sh_i[1], nrej = sh_i[2], sl = sh_i[3];
+  if (sl < 0) {  // no mass anywhere (cannot happen with finite logits): token 0
+    if (tid == 0) p.tokens[o + len - 1] = 0;
+    return;
+  }
+  {
+    const int vl = tid >> 3, part = tid & 7;
+    const int v = sl * kVocabPerWg + vl;
+    const int per = p.K >> 3;   // a multiple of 32 elements
+    const char* wp = p.weights + ((size_t)min(v, p.V - 1) * p.K + (size_t)part * per) * 2;
+    const char* hp = p.hidden + ((size_t)(o + cur) * p.K + (size_t)part * per) * 2;
+    float dot = 0.f;
+    for (int k = 0; k < per; k += 8) {
+      const bf16x8 a = *reinterpret_cast<const bf16x8*>(wp + 2 * k);
+      const bf16x8 h = *reinterpret_cast<const bf16x8*>(hp + 2 * k);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) dot = fmaf((float)a[j], (float)h[j], dot);
+    }
+#pragma unroll
+    for (int d = 1; d < 8; d <<= 1) dot += __shfl_xor(dot, d);
+    if (part == 0) slice_logit[vl] = v < p.V ? dot : NAN;
+  }
+  __syncthreads();
+  double w = 0.0, incl = 0.0;
+  const int e = sl * kVocabPerWg + tid;
+  if (tid < kVocabPerWg) {   // two wavefronts: thread = entry of the slice
+    const float lx = slice_logit[tid];
+    bool gone = lx != lx;
+    for (int k = 0; k < nrej; ++k) gone = gone || rej_tok[k] == e;
+    w = gone ? 0.0 : exp(fmin(((double)lx - sh_d[0]) * p.inv_temperature, 0.0));
+    incl = w;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+      const double up = __shfl_up(incl, off);
+      if (lane >= off) incl += up;
+    }
+    if (lane == 63) scan_part[wave] = incl;
+  }
+  if (tid == 0) { sh_i[5] = kNone; sh_i[6] = -1; }
+  __syncthreads();
+  if (tid < kVocabPerWg) {
+    const double inclusive = (wave == 1 ? scan_part[0] : 0.0) + incl;
+    if (inclusive > sh_d[1] && w > 0.0) atomicMin(&sh_i[5], tid);
+    if (w > 0.0) atomicMax(&sh_i[6], e);
+  }
+  __syncthreads();
+  if (tid == 0) {
+    // the first entry whose running sum exceeds the target; if rounding leaves none, the last with mass
+    const int first = sh_i[5];
+    p.tokens[o + len - 1] = first != kNone ? sl * kVocabPerWg + first : (sh_i[6] < 0 ? 0 : sh_i[6]);
+  }
+}
+
 int n_slices_of(int32_t V) { return (V + kVocabPerWg - 1) / kVocabPerWg; }
 // Workgroup s starts its k loop (s * g_stagger) stages in and wraps around, so that the workgroups
 // running at the same time read different parts of their rows: with every workgroup at the same k
@@ -293,19 +607,12 @@ int g_stagger = 3;
 // Experiment knob (not part of the declared interface): the k rotation between workgroups (0: none).
 extern "C" void fspad_debug_set_lm_head_stagger(int32_t stages) { g_stagger = stages < 0 ? 0 : stages; }
 
-extern "C" size_t fspad_tree_accept_lm_head_workspace_bytes(int32_t B, int32_t Nmax, int32_t V) {
-  if (B < 1 || Nmax < 1 || V < 1) return 0;
-  const size_t slots = (size_t)B * Nmax * n_slices_of(V);
-  return (slots * 8 + 255) & ~(size_t)255;
-}
+namespace {
 
-extern "C" fspad_status fspad_tree_accept_greedy_lm_head(int32_t B, int32_t Nmax, int32_t V, int32_t hidden_dim,
-                                                         const void* hidden, const void* lm_head,
-                                                         const int32_t* draft_tokens, const int32_t* parent,
-                                                         const int32_t* n_nodes, int32_t* path, int32_t* path_len,
-                                                         int32_t* tokens, int32_t* n_tokens, int32_t* node_target,
-                                                         float* node_top, void* workspace, size_t workspace_bytes,
-                                                         void* hip_stream) {
+fspad_status check_lm_head_args(int32_t B, int32_t Nmax, int32_t V, int32_t hidden_dim, const void* hidden,
+                                const void* lm_head, const int32_t* draft_tokens, const int32_t* parent,
+                                const int32_t* n_nodes, int32_t* path, int32_t* path_len, int32_t* tokens,
+                                int32_t* n_tokens, void* workspace, size_t workspace_bytes) {
   if (!hidden || !lm_head || !draft_tokens || !parent || !n_nodes || !path || !path_len || !tokens || !n_tokens)
     return FSPAD_ERR_NULL;
   if (B < 1 || Nmax < 1 || Nmax > FSPAD_MAX_NODES || V < 1 || V > (1 << 30)) return FSPAD_ERR_SHAPE;
@@ -315,6 +622,52 @@ extern "C" fspad_status fspad_tree_accept_greedy_lm_head(int32_t B, int32_t Nmax
   if (!workspace || ((uintptr_t)workspace & 15) ||
       workspace_bytes < fspad_tree_accept_lm_head_workspace_bytes(B, Nmax, V))
     return FSPAD_ERR_WORKSPACE;
+  return FSPAD_OK;
+}
+
+// Fills in the launch shape and runs the GEMM in the given mode (0 greedy, 1 sampling).
+template <int MODE>
+fspad_status launch_lm_head(LmHeadParams& g, int32_t hidden_dim, hipStream_t stream) {
+  // rows per workgroup: everything up to 128 rows in one pass of the eight-wavefront shape, more in
+  // passes of up to 256 rows of the four-wavefront shape (each pass streams the weights again)
+  g.rows_per_pass = g.M <= 128 ? g.M : 256;
+  g.n_passes = (g.M + g.rows_per_pass - 1) / g.rows_per_pass;
+  const int pass_rows = g.n_passes > 1 ? (g.M + g.n_passes - 1) / g.n_passes : g.M;   // passes of equal size
+  if (g.n_passes > 1) g.rows_per_pass = (pass_rows + 15) / 16 * 16;
+  if ((int64_t)g.n_slices * g.n_passes > 0x7fffffff) return FSPAD_ERR_SHAPE;
+  // (a stage of the small shapes is 512 k: a hidden size that is not a multiple of it has a partial
+  // last stage, which the rotation does not handle)
+  g.stagger = (g.rows_per_pass > 64 || hidden_dim % 512 == 0) ? g_stagger : 0;
+  const dim3 grid((unsigned)(g.n_slices * g.n_passes));
+  const int r = g.rows_per_pass;
+  if (r <= 16) hipLaunchKernelGGL((lm_head_argmax_kernel<1, 16, 16, 8, 1, MODE>), grid, dim3(512), 0, stream, g);
+  else if (r <= 32) hipLaunchKernelGGL((lm_head_argmax_kernel<2, 16, 16, 8, 1, MODE>), grid, dim3(512), 0, stream, g);
+  else if (r <= 64) hipLaunchKernelGGL((lm_head_argmax_kernel<4, 16, 16, 8, 1, MODE>), grid, dim3(512), 0, stream, g);
+  else if (r <= 128) hipLaunchKernelGGL((lm_head_argmax_kernel<8, 8, 16, 8, 1, MODE>), grid, dim3(512), 0, stream, g);
+  else if (r <= 192) hipLaunchKernelGGL((lm_head_argmax_kernel<12, 4, 16, 4, 2, MODE>), grid, dim3(256), 0, stream, g);
+  else hipLaunchKernelGGL((lm_head_argmax_kernel<16, 4, 8, 4, 2, MODE>), grid, dim3(256), 0, stream, g);
+  return hipGetLastError() == hipSuccess ? FSPAD_OK : FSPAD_ERR_HIP;
+}
+
+}  // namespace
+
+extern "C" size_t fspad_tree_accept_lm_head_workspace_bytes(int32_t B, int32_t Nmax, int32_t V) {
+  if (B < 1 || Nmax < 1 || V < 1) return 0;
+  // greedy: (max, argmax) per row and slice; sampling: (max, fp64 sum) per row and slice + one logit per node
+  const size_t slots = (size_t)B * Nmax * n_slices_of(V);
+  return (slots * 12 + (size_t)B * Nmax * 4 + 255) & ~(size_t)255;
+}
+
+extern "C" fspad_status fspad_tree_accept_greedy_lm_head(int32_t B, int32_t Nmax, int32_t V, int32_t hidden_dim,
+                                                         const void* hidden, const void* lm_head,
+                                                         const int32_t* draft_tokens, const int32_t* parent,
+                                                         const int32_t* n_nodes, int32_t* path, int32_t* path_len,
+                                                         int32_t* tokens, int32_t* n_tokens, int32_t* node_target,
+                                                         float* node_top, void* workspace, size_t workspace_bytes,
+                                                         void* hip_stream) {
+  const fspad_status st = check_lm_head_args(B, Nmax, V, hidden_dim, hidden, lm_head, draft_tokens, parent, n_nodes, path,
+                                             path_len, tokens, n_tokens, workspace, workspace_bytes);
+  if (st != FSPAD_OK) return st;
   hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
 
   LmHeadParams g{};
@@ -322,28 +675,11 @@ extern "C" fspad_status fspad_tree_accept_greedy_lm_head(int32_t B, int32_t Nmax
   g.weights = static_cast<const char*>(lm_head);
   g.M = B * Nmax; g.V = V; g.K = hidden_dim;
   g.n_slices = n_slices_of(V);
-  // rows per workgroup: everything up to 128 rows in one pass of the eight-wavefront shape, more in
-  // passes of up to 256 rows of the four-wavefront shape (each pass streams the weights again)
-  g.rows_per_pass = g.M <= 128 ? g.M : 256;
-  g.n_passes = (g.M + g.rows_per_pass - 1) / g.rows_per_pass;
-  const int pass_rows = g.n_passes > 1 ? (g.M + g.n_passes - 1) / g.n_passes : g.M;   // passes of equal size
-  if (g.n_passes > 1) g.rows_per_pass = (pass_rows + 15) / 16 * 16;
   const size_t slots = (size_t)g.M * g.n_slices;
   g.part_max = static_cast<float*>(workspace);
   g.part_idx = reinterpret_cast<int32_t*>(g.part_max + slots);
-  if ((int64_t)g.n_slices * g.n_passes > 0x7fffffff) return FSPAD_ERR_SHAPE;
-  // (a stage of the small shapes is 512 k: a hidden size that is not a multiple of it has a partial
-  // last stage, which the rotation does not handle)
-  g.stagger = (g.rows_per_pass > 64 || hidden_dim % 512 == 0) ? g_stagger : 0;
-  const dim3 grid((unsigned)(g.n_slices * g.n_passes));
-  const int r = g.rows_per_pass;
-  if (r <= 16) hipLaunchKernelGGL((lm_head_argmax_kernel<1, 16, 16, 8, 1>), grid, dim3(512), 0, stream, g);
-  else if (r <= 32) hipLaunchKernelGGL((lm_head_argmax_kernel<2, 16, 16, 8, 1>), grid, dim3(512), 0, stream, g);
-  else if (r <= 64) hipLaunchKernelGGL((lm_head_argmax_kernel<4, 16, 16, 8, 1>), grid, dim3(512), 0, stream, g);
-  else if (r <= 128) hipLaunchKernelGGL((lm_head_argmax_kernel<8, 8, 16, 8, 1>), grid, dim3(512), 0, stream, g);
-  else if (r <= 192) hipLaunchKernelGGL((lm_head_argmax_kernel<12, 4, 16, 4, 2>), grid, dim3(256), 0, stream, g);
-  else hipLaunchKernelGGL((lm_head_argmax_kernel<16, 4, 8, 4, 2>), grid, dim3(256), 0, stream, g);
-  if (hipGetLastError() != hipSuccess) return FSPAD_ERR_HIP;
+  const fspad_status gs = launch_lm_head<0>(g, hidden_dim, stream);
+  if (gs != FSPAD_OK) return gs;
 
   LmWalkParams w{};
   w.part_max = g.part_max; w.part_idx = g.part_idx;
@@ -352,6 +688,46 @@ extern "C" fspad_status fspad_tree_accept_greedy_lm_head(int32_t B, int32_t Nmax
   w.node_target = node_target; w.node_top = node_top;
   w.B = B; w.Nmax = Nmax; w.n_slices = g.n_slices;
   hipLaunchKernelGGL(lm_head_walk_kernel, dim3((unsigned)B), dim3(kWalkThreads), 0, stream, w);
+  if (hipGetLastError() != hipSuccess) return FSPAD_ERR_HIP;
+  return FSPAD_OK;
+}
+
+extern "C" fspad_status fspad_tree_accept_sample_lm_head(int32_t B, int32_t Nmax, int32_t V, int32_t hidden_dim,
+                                                         const void* hidden, const void* lm_head,
+                                                         const int32_t* draft_tokens, const int32_t* parent,
+                                                         const int32_t* n_nodes, float temperature,
+                                                         const float* uniforms, int32_t* path, int32_t* path_len,
+                                                         int32_t* tokens, int32_t* n_tokens, void* workspace,
+                                                         size_t workspace_bytes, void* hip_stream) {
+  const fspad_status st = check_lm_head_args(B, Nmax, V, hidden_dim, hidden, lm_head, draft_tokens, parent, n_nodes, path,
+                                             path_len, tokens, n_tokens, workspace, workspace_bytes);
+  if (st != FSPAD_OK) return st;
+  if (!uniforms) return FSPAD_ERR_NULL;
+  if (!(temperature > 0.0f) || isinf(temperature)) return FSPAD_ERR_TEMPERATURE;
+  hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
+
+  LmHeadParams g{};
+  g.hidden = static_cast<const char*>(hidden);
+  g.weights = static_cast<const char*>(lm_head);
+  g.M = B * Nmax; g.V = V; g.K = hidden_dim; g.Nmax = Nmax;
+  g.n_slices = n_slices_of(V);
+  const size_t slots = (size_t)g.M * g.n_slices;
+  g.part_sum = static_cast<double*>(workspace);                 // 8-byte entries first
+  g.part_max = reinterpret_cast<float*>(g.part_sum + slots);
+  g.node_logit = g.part_max + slots;
+  g.draft_tokens = draft_tokens; g.parent = parent; g.n_nodes = n_nodes;
+  g.inv_t_log2e = (float)(1.4426950408889634 / (double)temperature);
+  const fspad_status gs = launch_lm_head<1>(g, hidden_dim, stream);
+  if (gs != FSPAD_OK) return gs;
+
+  LmSampleWalkParams w{};
+  w.part_max = g.part_max; w.part_sum = g.part_sum; w.node_logit = g.node_logit;
+  w.hidden = g.hidden; w.weights = g.weights;
+  w.draft_tokens = draft_tokens; w.parent = parent; w.n_nodes = n_nodes; w.uniforms = uniforms;
+  w.path = path; w.path_len = path_len; w.tokens = tokens; w.n_tokens = n_tokens;
+  w.inv_temperature = 1.0 / (double)temperature;
+  w.B = B; w.Nmax = Nmax; w.V = V; w.K = hidden_dim; w.n_slices = g.n_slices;
+  hipLaunchKernelGGL(lm_head_sample_walk_kernel, dim3((unsigned)B), dim3(kWalkThreads), 0, stream, w);
   if (hipGetLastError() != hipSuccess) return FSPAD_ERR_HIP;
   return FSPAD_OK;
 }

@@ -160,6 +160,17 @@ class LmHeadCase:
     def cpu(self):
         return list(oracle.lm_head_greedy(self.hidden, self.w, self.tokens, self.parent, self.n_nodes))
 
+    def gpu_sample(self, temperature=1.0, seed=0):
+        uni = gen_uniforms(seed, self.shape[0], self.shape[1])
+        out = fspad.fspad_tree_accept_sample_lm_head(self.hidden_dev, self.w_dev, self.tokens_dev, self.parent_dev,
+                                                     self.n_nodes_dev, temperature, torch.from_numpy(uni).to(DEV))
+        torch.cuda.synchronize()
+        return [t.cpu().numpy() for t in out]
+
+    def cpu_sample(self, temperature=1.0, seed=0):
+        uni = gen_uniforms(seed, self.shape[0], self.shape[1])
+        return list(oracle.lm_head_sample(self.hidden, self.w, self.tokens, self.parent, self.n_nodes, temperature, uni))
+
 
 # fp32 accumulation of the logits: a target token is compared only where the oracle's winning logit
 # leads the runner-up by more than this (logits ~ N(0, 3^2); K <= 8192 terms of fp32 rounding stay
@@ -184,3 +195,17 @@ def assert_lm_head_equal(gpu, cpu, require_decided=True):
     if all_decided:
         assert_accept_equal((path, path_len, tokens, n_tokens), (c_path, c_len, c_tokens, c_ntok))
     return all_decided
+
+
+# sampling from hidden states: the kernel's exponentials are fp32 on fp32 logit sums, the oracle's fp64 on
+# correctly rounded logits; a sequence is compared when every decision of its walk has a relative
+# margin above this
+LM_HEAD_SAMPLE_MARGIN = 1e-4
+
+
+def assert_lm_head_sample_equal(gpu, cpu, min_compared=0.75):
+    margin = cpu[4]
+    keep = margin >= LM_HEAD_SAMPLE_MARGIN
+    assert keep.mean() >= min_compared, f"only {keep.sum()} of {keep.size} sequences are decided: pick another seed"
+    assert_accept_equal(gpu, cpu, keep=keep)
+    return int(keep.sum())

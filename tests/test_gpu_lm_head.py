@@ -112,3 +112,52 @@ def test_missing_workspace_is_an_error(H):
     with pytest.raises(fspad.FspadError):
         fspad.fspad_tree_accept_greedy_lm_head(case.hidden_dev, case.w_dev, case.tokens_dev, case.parent_dev,
                                                case.n_nodes_dev, workspace=ws)
+
+
+@pytest.mark.parametrize("B,N,Hd,V", [
+    (1, 1, 256, 1), (1, 2, 256, 127), (2, 16, 512, 128), (3, 17, 256, 129), (4, 26, 1024, 1000),
+    (2, 33, 768, 4097), (4, 60, 512, 2000), (2, 64, 256, 640), (8, 26, 512, 999), (3, 60, 512, 1500),
+    (5, 60, 256, 900), (2, 26, 256, 40000), (2, 60, 256, 70001),
+])
+@pytest.mark.parametrize("temperature", [1.0, 0.5])
+def test_sampling_shapes(H, B, N, Hd, V, temperature):
+    """Tree rejection sampling from hidden states over the same shapes as the greedy form (every
+    workgroup shape, several passes, ragged vocabularies, more slices than one scan turn)."""
+    case = H.LmHeadCase(3000 + 7 * N + V, B, N, Hd, V, topk=min(10, max(1, V // 2)), noise=0.5)
+    for seed in (1, 2):
+        H.assert_lm_head_sample_equal(case.gpu_sample(temperature, seed), case.cpu_sample(temperature, seed),
+                                      min_compared=0.5 if B < 4 else 0.7)
+
+
+def test_sampling_walks_accept_reject_and_draw(H):
+    """Many sequences at once: accepted chains, rejections with siblings left, draws from the residual."""
+    case = H.LmHeadCase(88, 16, 40, 512, 3000, noise=0.3)
+    lens = []
+    for seed in range(4):
+        gpu, cpu = case.gpu_sample(0.7, seed), case.cpu_sample(0.7, seed)
+        H.assert_lm_head_sample_equal(gpu, cpu, min_compared=0.8)
+        lens += cpu[1].tolist()
+    assert max(lens) >= 3 and min(lens) == 1
+    again = case.gpu_sample(0.7, 3)
+    for a, b in zip(gpu, again):
+        assert np.array_equal(a, b)
+
+
+def test_sampling_config2_llama3_8b_head_full(H):
+    c = CONFIGS["c2"]
+    case = H.LmHeadCase(2026, c.batch, c.n_nodes, 4096, c.vocab, depth=c.tree_depth, topk=c.tree_topk, noise=0.5)
+    compared = 0
+    for seed in range(3):
+        gpu, cpu = case.gpu_sample(1.0, seed), case.cpu_sample(1.0, seed)
+        compared += H.assert_lm_head_sample_equal(gpu, cpu, min_compared=0.0)
+    assert compared >= 2
+
+
+def test_sampling_rejects_bad_temperature(H):
+    import paper_2408_15562_amd as fspad
+    case = H.LmHeadCase(3, 1, 8, 256, 500)
+    uni = torch.zeros((1, 2, 8), dtype=torch.float32, device=H.DEV)
+    for t in (0.0, -1.0, float("inf"), float("nan")):
+        with pytest.raises(fspad.FspadError):
+            fspad.fspad_tree_accept_sample_lm_head(case.hidden_dev, case.w_dev, case.tokens_dev, case.parent_dev,
+                                                   case.n_nodes_dev, t, uni)
