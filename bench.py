@@ -58,9 +58,9 @@ def parse_args():
                     help="also cut the outputs of the draft steps to their top-k at the top of every step: tree_depth calls "
                          "of fspad_draft_topk over B x top-k rows of V synthetic draft logits (timing only, like --tree-build)")
     ap.add_argument("--lm-head", default=None, choices=["fused", "unfused"],
-                    help="greedy workloads: start the acceptance from the last hidden states instead of ready-made logits. "
-                         "fused = fspad_tree_accept_greedy_lm_head (logits never written); unfused = library GEMM to bf16 "
-                         "logits, widened to fp32, then fspad_tree_accept_greedy (the comparison)")
+                    help="start the acceptance from the last hidden states instead of ready-made logits. "
+                         "fused = fspad_tree_accept_{greedy,sample}_lm_head (logits never written); unfused = library GEMM "
+                         "to bf16 logits, widened to fp32, then fspad_tree_accept_{greedy,sample} (the comparison)")
     ap.add_argument("--lm-stagger", type=int, default=None, help=argparse.SUPPRESS)
     ap.add_argument("--hidden-dim", type=int, default=None, help="hidden size for --lm-head (default: the workload's model)")
     ap.add_argument("--seed", type=int, default=2024)
@@ -134,9 +134,6 @@ def main():
     n_nodes_d = torch.from_numpy(n_nodes).to(dev)
     hidden_dim = 0
     if args.lm_head:
-        if accept != "greedy":
-            print("bench.py: --lm-head needs a greedy workload (or --accept greedy)", file=sys.stderr)
-            sys.exit(2)
         hidden_dim = args.hidden_dim or {"c0": 256, "c1": 4096, "c2": 4096, "c3": 6656, "c4": 8192}[args.workload]
         # the weights are streamed once per step; between two steps of a real model every layer's weights
         # pass through the caches, so a few copies are rotated to keep them out of the 256 MB last-level cache
@@ -175,11 +172,15 @@ def main():
     for st in sets:
         st["attn"] = [fspad.fspad_tree_attn(q, kt, vt, kc, vc, kv_len, n_nodes, mask, out=out, workspace=ws_attn,
                                             desc=desc, prepare=True) for (q, kt, vt, kc, vc, out) in st["layers"]]
-        if args.lm_head == "fused":
+        if args.lm_head == "fused" and accept == "greedy":
             st["accept"] = fspad.fspad_tree_accept_greedy_lm_head(st["hidden"], st["w"], st["tokens"], parent_d, n_nodes_d,
                                                                   outputs=acc_out, prepare=True)
+        elif args.lm_head == "fused":
+            st["accept"] = fspad.fspad_tree_accept_sample_lm_head(st["hidden"], st["w"], st["tokens"], parent_d, n_nodes_d,
+                                                                  cfg.temperature, st["uniforms"], outputs=acc_out, prepare=True)
         elif args.lm_head == "unfused":
-            st["accept"] = unfused_lm_head_accept(torch, fspad, st, parent_d, n_nodes_d, acc_out, ws_acc)
+            st["accept"] = unfused_lm_head_accept(torch, fspad, st, parent_d, n_nodes_d, acc_out, ws_acc, accept,
+                                                  cfg.temperature)
         elif accept == "greedy":
             st["accept"] = fspad.fspad_tree_accept_greedy(st["logits"], st["tokens"], parent_d, n_nodes_d, outputs=acc_out,
                                                           workspace=ws_acc, prepare=True)
@@ -321,22 +322,26 @@ def main():
     print(json.dumps(result))
 
 
-def unfused_lm_head_accept(torch, fspad, st, parent_d, n_nodes_d, acc_out, ws_acc):
+def unfused_lm_head_accept(torch, fspad, st, parent_d, n_nodes_d, acc_out, ws_acc, accept, temperature):
     """The comparison for --lm-head: a library GEMM writes bf16 logits, they are widened to fp32 and the
-    ordinary greedy acceptance reads them. All buffers are allocated here, once."""
+    ordinary acceptance reads them. All buffers are allocated here, once."""
     B, N, Hd = st["hidden"].shape
     V = st["w"].shape[0]
     h2d = st["hidden"].view(B * N, Hd)
     wt = st["w"].t()
     logits_lp = torch.empty((B * N, V), device=h2d.device, dtype=torch.bfloat16)
     logits = torch.empty((B, N, V), device=h2d.device, dtype=torch.float32)
-    accept = fspad.fspad_tree_accept_greedy(logits, st["tokens"], parent_d, n_nodes_d, outputs=acc_out, workspace=ws_acc,
-                                            prepare=True)
+    if accept == "greedy":
+        walk = fspad.fspad_tree_accept_greedy(logits, st["tokens"], parent_d, n_nodes_d, outputs=acc_out, workspace=ws_acc,
+                                              prepare=True)
+    else:
+        walk = fspad.fspad_tree_accept_sample(logits, st["tokens"], parent_d, n_nodes_d, temperature, st["uniforms"],
+                                              outputs=acc_out, workspace=ws_acc, prepare=True)
 
     def call():
         torch.mm(h2d, wt, out=logits_lp)
         logits.view(B * N, V).copy_(logits_lp)
-        accept()
+        walk()
     return call
 
 

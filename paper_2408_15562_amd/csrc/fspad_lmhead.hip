@@ -39,6 +39,7 @@ struct LmHeadParams {
   float* part_max;      // greedy: [n_slices][M]; sampling: [M][n_slices]
   int32_t* part_idx;    // greedy: [n_slices][M]
   double* part_sum;     // sampling: [M][n_slices], sum of exp((l - part_max) / T) over the slice
+  float* tile_sum;      // sampling: [M][n_slices][8], the same sum per 16 tokens of the slice
   float* node_logit;    // sampling: [M], the logit of node c's own token under its parent's row
   const int32_t* draft_tokens;   // sampling: the tree, to know which logits the walk will ask for
   const int32_t* parent;
@@ -211,18 +212,29 @@ __global__ __launch_bounds__(64 * WAVES, (WAVES == 8 ? 2 : 1)) void lm_head_argm
       for (int i = 1; i < 8; ++i) m = fmaxf(m, x[i]);
 #pragma unroll
       for (int d = 1; d < 16; d <<= 1) m = fmaxf(m, __shfl_xor(m, d));
-      float sum = 0.f;
+      float half[2] = {0.f, 0.f};   // this lane's share of tiles sub/4 and 4 + sub/4 (16 tokens each)
       if (m > -INFINITY) {
 #pragma unroll
-        for (int i = 0; i < 8; ++i) sum += __builtin_amdgcn_exp2f((x[i] - m) * p.inv_t_log2e);
+        for (int i = 0; i < 8; ++i) half[i >> 2] += __builtin_amdgcn_exp2f((x[i] - m) * p.inv_t_log2e);
       }
-      double dsum = sum;
 #pragma unroll
-      for (int d = 1; d < 16; d <<= 1) dsum += __shfl_xor(dsum, d);
-      if (sub == 0 && row0 + r < p.M) {
+      for (int h = 0; h < 2; ++h) {
+        half[h] += __shfl_xor(half[h], 1);
+        half[h] += __shfl_xor(half[h], 2);
+      }
+      double dsum = (sub & 3) == 0 ? (double)half[0] + (double)half[1] : 0.0;
+#pragma unroll
+      for (int d = 4; d < 16; d <<= 1) dsum += __shfl_xor(dsum, d);
+      if (row0 + r < p.M) {
         const size_t slot = (size_t)(row0 + r) * p.n_slices + slice;
-        p.part_max[slot] = m;
-        p.part_sum[slot] = dsum;
+        if ((sub & 3) == 0) {
+          p.tile_sum[slot * 8 + (sub >> 2)] = half[0];
+          p.tile_sum[slot * 8 + 4 + (sub >> 2)] = half[1];
+        }
+        if (sub == 0) {
+          p.part_max[slot] = m;
+          p.part_sum[slot] = dsum;
+        }
       }
     }
     // the logits the walk will test: node c's token under the row of c's parent
@@ -353,6 +365,7 @@ __global__ __launch_bounds__(kWalkThreads) void lm_head_walk_kernel(const LmWalk
 struct LmSampleWalkParams {
   const float* part_max;     // [B*Nmax][n_slices]
   const double* part_sum;
+  const float* tile_sum;     // [B*Nmax][n_slices][8]
   const float* node_logit;   // [B*Nmax]
   const char* hidden;        // [B*Nmax][K] bf16
   const char* weights;       // [V][K] bf16
@@ -378,13 +391,13 @@ struct LmSampleWalkParams {
 __global__ __launch_bounds__(kWalkThreads) void lm_head_sample_walk_kernel(const LmSampleWalkParams p) {
   __shared__ int rej_tok[FSPAD_MAX_NODES];
   __shared__ double rej_w[FSPAD_MAX_NODES];
-  __shared__ double sh_d[4];
+  __shared__ double sh_d[4];   // M of the last row, target, scratch, target inside the tile
   __shared__ int sh_i[8];
   __shared__ double row_M[FSPAD_MAX_NODES], row_Z[FSPAD_MAX_NODES], node_w[FSPAD_MAX_NODES];
   __shared__ int node_par[FSPAD_MAX_NODES], node_tok[FSPAD_MAX_NODES];
   __shared__ float node_u[2][FSPAD_MAX_NODES];
-  __shared__ float slice_logit[kVocabPerWg];
-  __shared__ double scan_part[2];
+  __shared__ float slice_logit[16];
+  __shared__ double wave_sum[kWalkThreads / 64];
   const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int64_t o = (int64_t)b * p.Nmax;
   const float* u_acc = p.uniforms + (int64_t)b * 2 * p.Nmax;
@@ -396,32 +409,36 @@ __global__ __launch_bounds__(kWalkThreads) void lm_head_sample_walk_kernel(const
     const bool in_range = row < p.Nmax;
     const float* pm = p.part_max + (o + (in_range ? row : 0)) * p.n_slices;
     const double* ps = p.part_sum + (o + (in_range ? row : 0)) * p.n_slices;
+    // one pass, sixteen slices in flight per thread: running (max, sum), rescaled when the max moves
+    const float c2 = (float)(p.inv_temperature * 1.4426950408889634);
     float m = -INFINITY;
-    for (int c0 = q; c0 < p.n_slices; c0 += 128) {
-      float v[8];
-#pragma unroll
-      for (int k = 0; k < 8; ++k) v[k] = (in_range && c0 + 16 * k < p.n_slices) ? pm[c0 + 16 * k] : -INFINITY;
-#pragma unroll
-      for (int k = 0; k < 8; ++k) m = fmaxf(m, v[k]);
-    }
-#pragma unroll
-    for (int d = 1; d < 16; d <<= 1) m = fmaxf(m, __shfl_xor(m, d));
     double z = 0.0;
-    if (m > -INFINITY) {
-      const float c2 = (float)(p.inv_temperature * 1.4426950408889634);
-      for (int c0 = q; c0 < p.n_slices; c0 += 128) {
-        float v[8];
-        double sum[8];
+    for (int c0 = q; c0 < p.n_slices; c0 += 256) {
+      float v[16];
+      double sum[16];
 #pragma unroll
-        for (int k = 0; k < 8; ++k) {
-          const bool ok = in_range && c0 + 16 * k < p.n_slices;
-          v[k] = ok ? pm[c0 + 16 * k] : -INFINITY;
-          sum[k] = ok ? ps[c0 + 16 * k] : 0.0;
-        }
-#pragma unroll
-        for (int k = 0; k < 8; ++k)
-          if (v[k] > -INFINITY) z += sum[k] * (double)__builtin_amdgcn_exp2f((v[k] - m) * c2);
+      for (int k = 0; k < 16; ++k) {
+        const bool ok = in_range && c0 + 16 * k < p.n_slices;
+        v[k] = ok ? pm[c0 + 16 * k] : -INFINITY;
+        sum[k] = ok ? ps[c0 + 16 * k] : 0.0;
       }
+      float m_new = m;
+#pragma unroll
+      for (int k = 0; k < 16; ++k) m_new = fmaxf(m_new, v[k]);
+      if (m_new > -INFINITY) {
+        z = m > -INFINITY ? z * (double)__builtin_amdgcn_exp2f((m - m_new) * c2) : 0.0;
+#pragma unroll
+        for (int k = 0; k < 16; ++k)
+          if (v[k] > -INFINITY) z += sum[k] * (double)__builtin_amdgcn_exp2f((v[k] - m_new) * c2);
+        m = m_new;
+      }
+    }
+    {
+      float m_all = m;
+#pragma unroll
+      for (int d = 1; d < 16; d <<= 1) m_all = fmaxf(m_all, __shfl_xor(m_all, d));
+      z = m > -INFINITY ? z * (double)__builtin_amdgcn_exp2f((m - m_all) * c2) : 0.0;
+      m = m_all;
     }
 #pragma unroll
     for (int d = 1; d < 16; d <<= 1) z += __shfl_xor(z, d);
@@ -498,20 +515,35 @@ __global__ __launch_bounds__(kWalkThreads) void lm_head_sample_walk_kernel(const
     if (lane < p.Nmax) { p.path[o + lane] = my_path; if (lane != len - 1) p.tokens[o + lane] = my_out; }
     if (lane == 0) { p.path_len[b] = len; p.n_tokens[b] = len; }
 
-    // last token, stage 1: which slice holds the running-sum crossing of t = u * Z
-    const double t = (double)node_u[1][cur] * Z;
+    if (lane == 0) {
+      sh_i[0] = cur; sh_i[1] = len; sh_i[2] = nrej;
+      sh_i[3] = kNone; sh_i[4] = -1;
+      sh_d[0] = M;
+      sh_d[1] = (double)node_u[1][cur] * Z;   // t = u * Z
+    }
+  }
+  __syncthreads();
+
+  // last token, stage 1: which slice holds the running-sum crossing of t. Thread = slice (1024 per
+  // turn): residual weight of the slice, workgroup-wide running sum, first slice above t.
+  {
+    const int cur = sh_i[0], nrej = sh_i[2];
+    const double M = sh_d[0], t = sh_d[1];
+    const float c2 = (float)(p.inv_temperature * 1.4426950408889634);
     const int64_t row = o + cur;
     const float* pm = p.part_max + row * p.n_slices;
     const double* ps = p.part_sum + row * p.n_slices;
-    double carry = 0.0, before = 0.0;
-    int found = -1, last_pos = -1;
-    for (int c0 = 0; c0 < p.n_slices && found < 0; c0 += 64) {
-      const int c = c0 + lane;
+    double carry = 0.0;
+    for (int c0 = 0; c0 < p.n_slices; c0 += kWalkThreads) {
+      const int c = c0 + tid;
       double r = 0.0;
-      if (c < p.n_slices && pm[c] > -INFINITY) {
-        r = ps[c] * exp(fmin(((double)pm[c] - M) * p.inv_temperature, 0.0));
-        for (int k = 0; k < nrej; ++k)
-          if (rej_tok[k] >= c * kVocabPerWg && rej_tok[k] < (c + 1) * kVocabPerWg && rej_tok[k] < p.V) r -= rej_w[k];
+      if (c < p.n_slices) {
+        const float mc = pm[c];
+        if (mc > -INFINITY) {
+          r = ps[c] * (double)__builtin_amdgcn_exp2f((mc - (float)M) * c2);
+          for (int k = 0; k < nrej; ++k)
+            if (rej_tok[k] >= c * kVocabPerWg && rej_tok[k] < (c + 1) * kVocabPerWg && rej_tok[k] < p.V) r -= rej_w[k];
+        }
       }
       double incl = r;
 #pragma unroll
@@ -519,79 +551,110 @@ __global__ __launch_bounds__(kWalkThreads) void lm_head_sample_walk_kernel(const
         const double up = __shfl_up(incl, off);
         if (lane >= off) incl += up;
       }
-      const unsigned long long pos = __ballot(r > 0.0);
-      if (pos) last_pos = c0 + 63 - __clzll(pos);
-      const unsigned long long hit = __ballot(c < p.n_slices && carry + incl > t);
-      if (hit) {
-        const int first = __ffsll(hit) - 1;
-        found = c0 + first;
-        before = carry + __shfl(incl - r, first);
-      } else {
-        carry += __shfl(incl, 63);
+      if (lane == 63) wave_sum[wave] = incl;
+      __syncthreads();
+      double base = carry;
+      for (int w2 = 0; w2 < wave; ++w2) base += wave_sum[w2];
+      double total = carry;
+      for (int w2 = 0; w2 < kWalkThreads / 64; ++w2) total += wave_sum[w2];
+      const double inclusive = base + incl;
+      if (c < p.n_slices && r > 0.0) {
+        atomicMax(&sh_i[4], c);                              // the last slice with mass (rounding fallback)
+        if (inclusive > t) atomicMin(&sh_i[3], c);
       }
+      __syncthreads();
+      const int found = sh_i[3];
+      if (found != kNone) {
+        if (c == found) sh_d[2] = t - (inclusive - r);       // what is left of t inside the slice
+        break;
+      }
+      carry = total;
     }
-    if (lane == 0) {
-      // rounding fallback: the last slice that still has mass, searched to its end
-      sh_i[0] = cur; sh_i[1] = len; sh_i[2] = nrej;
-      sh_i[3] = found >= 0 ? found : last_pos;
-      sh_d[0] = M;
-      sh_d[1] = found >= 0 ? t - before : INFINITY;
+    __syncthreads();
+    if (tid == 0) {
+      if (sh_i[3] == kNone) { sh_i[3] = sh_i[4]; sh_d[2] = INFINITY; }   // no crossing: the last slice with mass, to its end
+      sh_d[1] = sh_d[2];
     }
   }
   __syncthreads();
 
-  // last token, stage 2: the slice's logits again (thread (v = tid / 8, part = tid % 8) sums an eighth
-  // of K), then the crossing inside the slice
+  // last token, stage 2: which 16 tokens of the slice hold the crossing (from the tile sums, less the
+  // rejected tokens), their logits again (one wavefront per token, lanes over K), and the crossing
   const int cur = sh_i[0], len = sh_i[1], nrej = sh_i[2], sl = sh_i[3];
   if (sl < 0) {  // no mass anywhere (cannot happen with finite logits): token 0
     if (tid == 0) p.tokens[o + len - 1] = 0;
     return;
   }
-  {
-    const int vl = tid >> 3, part = tid & 7;
-    const int v = sl * kVocabPerWg + vl;
-    const int per = p.K >> 3;   // a multiple of 32 elements
-    const char* wp = p.weights + ((size_t)min(v, p.V - 1) * p.K + (size_t)part * per) * 2;
-    const char* hp = p.hidden + ((size_t)(o + cur) * p.K + (size_t)part * per) * 2;
-    float dot = 0.f;
-    for (int k = 0; k < per; k += 8) {
-      const bf16x8 a = *reinterpret_cast<const bf16x8*>(wp + 2 * k);
-      const bf16x8 h = *reinterpret_cast<const bf16x8*>(hp + 2 * k);
-#pragma unroll
-      for (int j = 0; j < 8; ++j) dot = fmaf((float)a[j], (float)h[j], dot);
+  if (tid == 0) {
+    const size_t slot = (size_t)(o + cur) * p.n_slices + sl;
+    const double f = exp(fmin(((double)p.part_max[slot] - sh_d[0]) * p.inv_temperature, 0.0));
+    double run = 0.0;
+    int tile = -1, last = -1;
+    double left = INFINITY;
+    for (int j = 0; j < 8; ++j) {
+      double r = (double)p.tile_sum[slot * 8 + j] * f;
+      const int t0 = sl * kVocabPerWg + 16 * j;
+      for (int k = 0; k < nrej; ++k)
+        if (rej_tok[k] >= t0 && rej_tok[k] < t0 + 16 && rej_tok[k] < p.V) r -= rej_w[k];
+      if (r > 0.0) last = j;
+      if (tile < 0 && run + r > sh_d[1]) { tile = j; left = sh_d[1] - run; }
+      run += r;
     }
-#pragma unroll
-    for (int d = 1; d < 8; d <<= 1) dot += __shfl_xor(dot, d);
-    if (part == 0) slice_logit[vl] = v < p.V ? dot : NAN;
+    sh_i[7] = tile >= 0 ? tile : last;      // no crossing: the last tile with mass, to its end
+    sh_d[3] = tile >= 0 ? left : INFINITY;
   }
   __syncthreads();
-  double w = 0.0, incl = 0.0;
-  const int e = sl * kVocabPerWg + tid;
-  if (tid < kVocabPerWg) {   // two wavefronts: thread = entry of the slice
-    const float lx = slice_logit[tid];
-    bool gone = lx != lx;
-    for (int k = 0; k < nrej; ++k) gone = gone || rej_tok[k] == e;
-    w = gone ? 0.0 : exp(fmin(((double)lx - sh_d[0]) * p.inv_temperature, 0.0));
-    incl = w;
+  const int tile = sh_i[7];
+  if (tile < 0) {  // the slice had mass only by rounding: its first valid token
+    if (tid == 0) p.tokens[o + len - 1] = min(sl * kVocabPerWg, p.V - 1);
+    return;
+  }
+  const int e0 = sl * kVocabPerWg + 16 * tile;
+  {
+    // wavefront w sums token e0 + w: lane l takes the 16-byte pieces l, l + 64, ... of the row
+    const int v = e0 + wave;
+    const char* wp = p.weights + ((size_t)min(v, p.V - 1) * p.K + (size_t)lane * 8) * 2;
+    const char* hp = p.hidden + ((size_t)(o + cur) * p.K + (size_t)lane * 8) * 2;
+    float dot = 0.f;
+    for (int k = 0; k < p.K; k += 512 * 4) {   // four pieces in flight per lane
+      bf16x8 a[4], h[4];
 #pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-      const double up = __shfl_up(incl, off);
-      if (lane >= off) incl += up;
+      for (int u = 0; u < 4; ++u) {
+        const bool ok = k + 512 * u + lane * 8 < p.K;
+        a[u] = ok ? *reinterpret_cast<const bf16x8*>(wp + 2 * (k + 512 * u)) : bf16x8{};
+        h[u] = ok ? *reinterpret_cast<const bf16x8*>(hp + 2 * (k + 512 * u)) : bf16x8{};
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+#pragma unroll
+        for (int j = 0; j < 8; ++j) dot = fmaf((float)a[u][j], (float)h[u][j], dot);
     }
-    if (lane == 63) scan_part[wave] = incl;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) dot += __shfl_xor(dot, d);
+    if (lane == 0) slice_logit[wave] = v < p.V ? dot : NAN;
   }
   if (tid == 0) { sh_i[5] = kNone; sh_i[6] = -1; }
   __syncthreads();
-  if (tid < kVocabPerWg) {
-    const double inclusive = (wave == 1 ? scan_part[0] : 0.0) + incl;
-    if (inclusive > sh_d[1] && w > 0.0) atomicMin(&sh_i[5], tid);
+  if (tid < 16) {   // thread = token of the tile
+    const int e = e0 + tid;
+    const float lx = slice_logit[tid];
+    bool gone = lx != lx;
+    for (int k = 0; k < nrej; ++k) gone = gone || rej_tok[k] == e;
+    const double w = gone ? 0.0 : exp(fmin(((double)lx - sh_d[0]) * p.inv_temperature, 0.0));
+    double incl = w;
+#pragma unroll
+    for (int off = 1; off < 16; off <<= 1) {
+      const double up = __shfl_up(incl, off);
+      if (lane >= off) incl += up;
+    }
+    if (incl > sh_d[3] && w > 0.0) atomicMin(&sh_i[5], tid);
     if (w > 0.0) atomicMax(&sh_i[6], e);
   }
   __syncthreads();
   if (tid == 0) {
     // the first entry whose running sum exceeds the target; if rounding leaves none, the last with mass
     const int first = sh_i[5];
-    p.tokens[o + len - 1] = first != kNone ? sl * kVocabPerWg + first : (sh_i[6] < 0 ? 0 : sh_i[6]);
+    p.tokens[o + len - 1] = first != kNone ? e0 + first : (sh_i[6] < 0 ? min(e0, p.V - 1) : sh_i[6]);
   }
 }
 
@@ -653,9 +716,10 @@ fspad_status launch_lm_head(LmHeadParams& g, int32_t hidden_dim, hipStream_t str
 
 extern "C" size_t fspad_tree_accept_lm_head_workspace_bytes(int32_t B, int32_t Nmax, int32_t V) {
   if (B < 1 || Nmax < 1 || V < 1) return 0;
-  // greedy: (max, argmax) per row and slice; sampling: (max, fp64 sum) per row and slice + one logit per node
+  // greedy: (max, argmax) per row and slice; sampling: (max, fp64 sum, eight tile sums) per row and slice
+  // + one logit per node
   const size_t slots = (size_t)B * Nmax * n_slices_of(V);
-  return (slots * 12 + (size_t)B * Nmax * 4 + 255) & ~(size_t)255;
+  return (slots * (12 + 32) + (size_t)B * Nmax * 4 + 255) & ~(size_t)255;
 }
 
 extern "C" fspad_status fspad_tree_accept_greedy_lm_head(int32_t B, int32_t Nmax, int32_t V, int32_t hidden_dim,
@@ -714,14 +778,15 @@ extern "C" fspad_status fspad_tree_accept_sample_lm_head(int32_t B, int32_t Nmax
   const size_t slots = (size_t)g.M * g.n_slices;
   g.part_sum = static_cast<double*>(workspace);                 // 8-byte entries first
   g.part_max = reinterpret_cast<float*>(g.part_sum + slots);
-  g.node_logit = g.part_max + slots;
+  g.tile_sum = g.part_max + slots;
+  g.node_logit = g.tile_sum + slots * 8;
   g.draft_tokens = draft_tokens; g.parent = parent; g.n_nodes = n_nodes;
   g.inv_t_log2e = (float)(1.4426950408889634 / (double)temperature);
   const fspad_status gs = launch_lm_head<1>(g, hidden_dim, stream);
   if (gs != FSPAD_OK) return gs;
 
   LmSampleWalkParams w{};
-  w.part_max = g.part_max; w.part_sum = g.part_sum; w.node_logit = g.node_logit;
+  w.part_max = g.part_max; w.part_sum = g.part_sum; w.tile_sum = g.tile_sum; w.node_logit = g.node_logit;
   w.hidden = g.hidden; w.weights = g.weights;
   w.draft_tokens = draft_tokens; w.parent = parent; w.n_nodes = n_nodes; w.uniforms = uniforms;
   w.path = path; w.path_len = path_len; w.tokens = tokens; w.n_tokens = n_tokens;
