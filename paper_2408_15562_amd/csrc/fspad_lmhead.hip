@@ -366,6 +366,8 @@ struct LmSampleWalkParams {
   const float* part_max;     // [B*Nmax][n_slices]
   const double* part_sum;
   const float* tile_sum;     // [B*Nmax][n_slices][8]
+  float* row_max;            // [B*Nmax], written by the row kernel: maximum of the row
+  double* row_sum;           // [B*Nmax]: sum of exp((l - row_max) / T) over the row
   const float* node_logit;   // [B*Nmax]
   const char* hidden;        // [B*Nmax][K] bf16
   const char* weights;       // [V][K] bf16
@@ -381,9 +383,62 @@ struct LmSampleWalkParams {
   int32_t B, Nmax, V, K, n_slices;
 };
 
+// exp(x) for x <= 0 as the walk needs it: the fp32 hardware exponential (the logits themselves carry
+// fp32 rounding of the same size), widened for the fp64 sums
+__device__ __forceinline__ double weight_of(double x) {
+  return (double)__builtin_amdgcn_exp2f((float)(fmin(x, 0.0) * 1.4426950408889634));
+}
+
+// Row statistics from the slice statistics: one workgroup per row of logits, thread = every 256th
+// slice, running (max, sum) rescaled when the max moves, then across the workgroup.
+__global__ __launch_bounds__(256) void lm_head_row_stats_kernel(const LmSampleWalkParams p) {
+  __shared__ float red_m[4];
+  __shared__ double red_z[4];
+  const int row = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const float* pm = p.part_max + (size_t)row * p.n_slices;
+  const double* ps = p.part_sum + (size_t)row * p.n_slices;
+  const float c2 = (float)(p.inv_temperature * 1.4426950408889634);
+  float m = -INFINITY;
+  double z = 0.0;
+  for (int c0 = tid; c0 < p.n_slices; c0 += 256 * 4) {
+    float v[4];
+    double sum[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const bool ok = c0 + 256 * k < p.n_slices;
+      v[k] = ok ? pm[c0 + 256 * k] : -INFINITY;
+      sum[k] = ok ? ps[c0 + 256 * k] : 0.0;
+    }
+    float m_new = m;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) m_new = fmaxf(m_new, v[k]);
+    if (m_new > -INFINITY) {
+      z = m > -INFINITY ? z * (double)__builtin_amdgcn_exp2f((m - m_new) * c2) : 0.0;
+#pragma unroll
+      for (int k = 0; k < 4; ++k)
+        if (v[k] > -INFINITY) z += sum[k] * (double)__builtin_amdgcn_exp2f((v[k] - m_new) * c2);
+      m = m_new;
+    }
+  }
+  float m_all = m;
+#pragma unroll
+  for (int d = 1; d < 64; d <<= 1) m_all = fmaxf(m_all, __shfl_xor(m_all, d));
+  if (lane == 0) red_m[wave] = m_all;
+  __syncthreads();
+  m_all = fmaxf(fmaxf(red_m[0], red_m[1]), fmaxf(red_m[2], red_m[3]));
+  z = m > -INFINITY ? z * (double)__builtin_amdgcn_exp2f((m - m_all) * c2) : 0.0;
+#pragma unroll
+  for (int d = 1; d < 64; d <<= 1) z += __shfl_xor(z, d);
+  if (lane == 0) red_z[wave] = z;
+  __syncthreads();
+  if (tid == 0) {
+    p.row_max[row] = m_all;
+    p.row_sum[row] = red_z[0] + red_z[1] + red_z[2] + red_z[3];
+  }
+}
+
 // Tree rejection sampling over the slice statistics the GEMM left (one workgroup of 1024 threads per
-// sequence): (1) every row's slice maxima and sums are merged into the row's max M and normaliser Z,
-// sixteen threads per row; (2) every node's weight exp((logit - M[parent]) / T) from the logit the
+// sequence): (1) every row's max M and normaliser Z come from the row kernel above; (2) every node's weight exp((logit - M[parent]) / T) from the logit the
 // GEMM set aside; (3) wavefront 0 walks the tree out of LDS, children in index order against the
 // running residual, exactly as the walk over materialised logits does; (4) the last token: the
 // slice that holds the crossing of u * Z follows from the slice sums (less the rejected tokens), its
@@ -403,46 +458,9 @@ __global__ __launch_bounds__(kWalkThreads) void lm_head_sample_walk_kernel(const
   const float* u_acc = p.uniforms + (int64_t)b * 2 * p.Nmax;
   const int n = min(p.n_nodes[b], p.Nmax);
 
-  // (1) row statistics: thread (row = tid / 16, q = tid % 16) takes every 16th slice of its row
+  // (1) row statistics (from the row kernel) and the tree
   {
-    const int row = tid >> 4, q = tid & 15;
-    const bool in_range = row < p.Nmax;
-    const float* pm = p.part_max + (o + (in_range ? row : 0)) * p.n_slices;
-    const double* ps = p.part_sum + (o + (in_range ? row : 0)) * p.n_slices;
-    // one pass, sixteen slices in flight per thread: running (max, sum), rescaled when the max moves
-    const float c2 = (float)(p.inv_temperature * 1.4426950408889634);
-    float m = -INFINITY;
-    double z = 0.0;
-    for (int c0 = q; c0 < p.n_slices; c0 += 256) {
-      float v[16];
-      double sum[16];
-#pragma unroll
-      for (int k = 0; k < 16; ++k) {
-        const bool ok = in_range && c0 + 16 * k < p.n_slices;
-        v[k] = ok ? pm[c0 + 16 * k] : -INFINITY;
-        sum[k] = ok ? ps[c0 + 16 * k] : 0.0;
-      }
-      float m_new = m;
-#pragma unroll
-      for (int k = 0; k < 16; ++k) m_new = fmaxf(m_new, v[k]);
-      if (m_new > -INFINITY) {
-        z = m > -INFINITY ? z * (double)__builtin_amdgcn_exp2f((m - m_new) * c2) : 0.0;
-#pragma unroll
-        for (int k = 0; k < 16; ++k)
-          if (v[k] > -INFINITY) z += sum[k] * (double)__builtin_amdgcn_exp2f((v[k] - m_new) * c2);
-        m = m_new;
-      }
-    }
-    {
-      float m_all = m;
-#pragma unroll
-      for (int d = 1; d < 16; d <<= 1) m_all = fmaxf(m_all, __shfl_xor(m_all, d));
-      z = m > -INFINITY ? z * (double)__builtin_amdgcn_exp2f((m - m_all) * c2) : 0.0;
-      m = m_all;
-    }
-#pragma unroll
-    for (int d = 1; d < 16; d <<= 1) z += __shfl_xor(z, d);
-    if (in_range && q == 0) { row_M[row] = (double)m; row_Z[row] = z; }
+    if (tid < p.Nmax) { row_M[tid] = (double)p.row_max[o + tid]; row_Z[tid] = p.row_sum[o + tid]; }
     if (tid < FSPAD_MAX_NODES) {
       const bool ok = tid < p.Nmax;
       node_par[tid] = ok ? p.parent[o + tid] : -2;
@@ -459,7 +477,7 @@ __global__ __launch_bounds__(kWalkThreads) void lm_head_sample_walk_kernel(const
     if (tid > 0 && tid < n && par >= 0 && par < tid && tok >= 0 && tok < p.V) {
       const double M = row_M[par];
       const float lx = p.node_logit[o + tid];
-      if (M > -INFINITY && lx == lx) w = exp(fmin(((double)lx - M) * p.inv_temperature, 0.0));
+      if (M > -INFINITY && lx == lx) w = weight_of(((double)lx - M) * p.inv_temperature);
     }
     node_w[tid] = w;
   }
@@ -585,23 +603,24 @@ __global__ __launch_bounds__(kWalkThreads) void lm_head_sample_walk_kernel(const
     if (tid == 0) p.tokens[o + len - 1] = 0;
     return;
   }
-  if (tid == 0) {
+  if (tid < 8) {   // thread = 16-token tile of the slice
     const size_t slot = (size_t)(o + cur) * p.n_slices + sl;
-    const double f = exp(fmin(((double)p.part_max[slot] - sh_d[0]) * p.inv_temperature, 0.0));
-    double run = 0.0;
-    int tile = -1, last = -1;
-    double left = INFINITY;
-    for (int j = 0; j < 8; ++j) {
-      double r = (double)p.tile_sum[slot * 8 + j] * f;
-      const int t0 = sl * kVocabPerWg + 16 * j;
-      for (int k = 0; k < nrej; ++k)
-        if (rej_tok[k] >= t0 && rej_tok[k] < t0 + 16 && rej_tok[k] < p.V) r -= rej_w[k];
-      if (r > 0.0) last = j;
-      if (tile < 0 && run + r > sh_d[1]) { tile = j; left = sh_d[1] - run; }
-      run += r;
+    double r = (double)p.tile_sum[slot * 8 + tid] * weight_of(((double)p.part_max[slot] - sh_d[0]) * p.inv_temperature);
+    const int t0 = sl * kVocabPerWg + 16 * tid;
+    for (int k = 0; k < nrej; ++k)
+      if (rej_tok[k] >= t0 && rej_tok[k] < t0 + 16 && rej_tok[k] < p.V) r -= rej_w[k];
+    double incl = r;
+#pragma unroll
+    for (int off = 1; off < 8; off <<= 1) {
+      const double up = __shfl_up(incl, off);
+      if (lane >= off) incl += up;
     }
-    sh_i[7] = tile >= 0 ? tile : last;      // no crossing: the last tile with mass, to its end
-    sh_d[3] = tile >= 0 ? left : INFINITY;
+    const unsigned long long cross = __ballot(incl > sh_d[1] && r > 0.0), mass = __ballot(r > 0.0);
+    const int tile = cross ? __ffsll(cross) - 1 : (mass ? 63 - __clzll(mass) : -1);
+    if (tid == (tile < 0 ? 0 : tile)) {
+      sh_i[7] = tile;                                   // no crossing: the last tile with mass, to its end
+      sh_d[3] = cross ? sh_d[1] - (incl - r) : INFINITY;
+    }
   }
   __syncthreads();
   const int tile = sh_i[7];
@@ -640,7 +659,7 @@ __global__ __launch_bounds__(kWalkThreads) void lm_head_sample_walk_kernel(const
     const float lx = slice_logit[tid];
     bool gone = lx != lx;
     for (int k = 0; k < nrej; ++k) gone = gone || rej_tok[k] == e;
-    const double w = gone ? 0.0 : exp(fmin(((double)lx - sh_d[0]) * p.inv_temperature, 0.0));
+    const double w = gone ? 0.0 : weight_of(((double)lx - sh_d[0]) * p.inv_temperature);
     double incl = w;
 #pragma unroll
     for (int off = 1; off < 16; off <<= 1) {
@@ -717,9 +736,9 @@ fspad_status launch_lm_head(LmHeadParams& g, int32_t hidden_dim, hipStream_t str
 extern "C" size_t fspad_tree_accept_lm_head_workspace_bytes(int32_t B, int32_t Nmax, int32_t V) {
   if (B < 1 || Nmax < 1 || V < 1) return 0;
   // greedy: (max, argmax) per row and slice; sampling: (max, fp64 sum, eight tile sums) per row and slice
-  // + one logit per node
+  // + one logit per node + (max, fp64 sum) per row
   const size_t slots = (size_t)B * Nmax * n_slices_of(V);
-  return (slots * (12 + 32) + (size_t)B * Nmax * 4 + 255) & ~(size_t)255;
+  return (slots * (12 + 32) + (size_t)B * Nmax * (4 + 12) + 255) & ~(size_t)255;
 }
 
 extern "C" fspad_status fspad_tree_accept_greedy_lm_head(int32_t B, int32_t Nmax, int32_t V, int32_t hidden_dim,
@@ -777,9 +796,11 @@ extern "C" fspad_status fspad_tree_accept_sample_lm_head(int32_t B, int32_t Nmax
   g.n_slices = n_slices_of(V);
   const size_t slots = (size_t)g.M * g.n_slices;
   g.part_sum = static_cast<double*>(workspace);                 // 8-byte entries first
-  g.part_max = reinterpret_cast<float*>(g.part_sum + slots);
+  double* row_sum = g.part_sum + slots;
+  g.part_max = reinterpret_cast<float*>(row_sum + g.M);
   g.tile_sum = g.part_max + slots;
   g.node_logit = g.tile_sum + slots * 8;
+  float* row_max = g.node_logit + g.M;
   g.draft_tokens = draft_tokens; g.parent = parent; g.n_nodes = n_nodes;
   g.inv_t_log2e = (float)(1.4426950408889634 / (double)temperature);
   const fspad_status gs = launch_lm_head<1>(g, hidden_dim, stream);
@@ -792,6 +813,9 @@ extern "C" fspad_status fspad_tree_accept_sample_lm_head(int32_t B, int32_t Nmax
   w.path = path; w.path_len = path_len; w.tokens = tokens; w.n_tokens = n_tokens;
   w.inv_temperature = 1.0 / (double)temperature;
   w.B = B; w.Nmax = Nmax; w.V = V; w.K = hidden_dim; w.n_slices = g.n_slices;
+  w.row_max = row_max; w.row_sum = row_sum;
+  hipLaunchKernelGGL(lm_head_row_stats_kernel, dim3((unsigned)g.M), dim3(256), 0, stream, w);
+  if (hipGetLastError() != hipSuccess) return FSPAD_ERR_HIP;
   hipLaunchKernelGGL(lm_head_sample_walk_kernel, dim3((unsigned)B), dim3(kWalkThreads), 0, stream, w);
   if (hipGetLastError() != hipSuccess) return FSPAD_ERR_HIP;
   return FSPAD_OK;
