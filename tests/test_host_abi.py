@@ -156,6 +156,18 @@ def test_lm_head_argument_checks_need_no_gpu(lib):
     assert call(wsb=need - 1) == 5
     assert call(ws=None) == 5
 
+    s = lib.fspad_tree_accept_sample_lm_head
+
+    def sample(T=1.0, uni=fake, Hd=4096, wsb=need):
+        return s(i32(1), i32(26), i32(32000), i32(Hd), fake, fake, fake, fake, fake, ctypes.c_float(T), uni,
+                 fake, fake, fake, fake, fake, sz(wsb), None)
+
+    for t in (0.0, -1.0, float("inf"), float("nan")):
+        assert sample(T=t) == 6
+    assert sample(uni=None) == 1
+    assert sample(Hd=4000) == 2
+    assert sample(wsb=need - 1) == 5
+
 
 def test_topk_argument_checks_need_no_gpu(lib):
     f = lib.fspad_draft_topk
