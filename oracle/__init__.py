@@ -317,3 +317,22 @@ def lm_head_sample(hidden, lm_head, draft_tokens, parent, n_nodes, temperature, 
     acceptance not relaxed) applied to `lm_head_logits`.  Returns what accept_sample returns,
     the smallest relative decision margin per sequence included."""
     return accept_sample(lm_head_logits(hidden, lm_head), draft_tokens, parent, n_nodes, temperature, uniforms)
+
+
+def feature_sampler(f, e, w_up, w_gate, w_down, residual=True):
+    """Feature Sampler of the draft model (Methodology, "Feature Sampling": three projectors and a
+    sampling operation in the intermediate space): the Up Projector lifts the feature f, the Gate
+    Projector lifts the token embedding e, the lifted embedding is activated with SiLU and
+    multiplied element by element with the lifted feature, and the Down Projector maps the product
+    back to the hidden size, where the feature path's residual connection is added:
+
+        eta = W_down (SiLU(W_gate e) * (W_up f)) [+ f]           (fp64 throughout)
+
+    f, e [rows,Hd]; w_up, w_gate [I,Hd]; w_down [Hd,I].  Returns eta [rows,Hd] float64."""
+    f = np.asarray(f, dtype=np.float64)
+    e = np.asarray(e, dtype=np.float64)
+    up = f @ np.asarray(w_up, dtype=np.float64).T
+    gate = e @ np.asarray(w_gate, dtype=np.float64).T
+    sampled = gate / (1.0 + np.exp(-gate)) * up
+    eta = sampled @ np.asarray(w_down, dtype=np.float64).T
+    return eta + f if residual else eta

@@ -21,6 +21,7 @@ from .generators import (  # noqa: F401
     gen_uniforms,
     gen_candidates,
     gen_lm_head,
+    gen_feature_sampler,
     round_to_bf16,
     chain_tree,
 )

@@ -207,3 +207,16 @@ def gen_lm_head(seed: int, batch: int, n_max: int, hidden_dim: int, vocab: int, 
     w = rng.standard_normal((vocab, hidden_dim), dtype=np.float32)
     w *= np.float32(sigma / np.sqrt(hidden_dim))
     return hidden, round_to_bf16(w)
+
+
+def gen_feature_sampler(seed: int, rows: int, hidden_dim: int, intermediate_dim: int):
+    """Inputs and projector weights of a Feature Sampler, all rounded to bf16 and returned as fp32:
+    f, e [rows,Hd] ~ N(0,1); w_up, w_gate [I,Hd] ~ N(0, 1/Hd); w_down [Hd,I] ~ N(0, 1/I) -- the scales
+    a trained layer keeps, so that every stage has O(1) entries."""
+    rng = np.random.default_rng([seed, 0xF5A])
+    f = round_to_bf16(rng.standard_normal((rows, hidden_dim), dtype=np.float32))
+    e = round_to_bf16(rng.standard_normal((rows, hidden_dim), dtype=np.float32))
+    w_up = round_to_bf16(rng.standard_normal((intermediate_dim, hidden_dim), dtype=np.float32) / np.float32(np.sqrt(hidden_dim)))
+    w_gate = round_to_bf16(rng.standard_normal((intermediate_dim, hidden_dim), dtype=np.float32) / np.float32(np.sqrt(hidden_dim)))
+    w_down = round_to_bf16(rng.standard_normal((hidden_dim, intermediate_dim), dtype=np.float32) / np.float32(np.sqrt(intermediate_dim)))
+    return f, e, w_up, w_gate, w_down
