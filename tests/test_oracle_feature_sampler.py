@@ -18,7 +18,7 @@ def test_hand_worked_case():
     s = np.array([0.75 * l3 * 1.0, 0.0, -0.25 * l3 * 3.0])
     expect = np.array([[s.sum() + 1.0, 2.0 * s[0] - 4.0 * s[2] + 2.0]])
     np.testing.assert_allclose(oracle.feature_sampler(f, e, w_up, w_gate, w_down), expect, rtol=1e-12)
-    np.testing.assert_allclose(oracle.feature_sampler(f, e, w_up, w_gate, w_down, residual=False), expect - f, rtol=1e-12)
+    np.testing.assert_allclose(oracle.feature_sampler(f, e, w_up, w_gate, w_down, residual=False), expect - f, rtol=1e-12, atol=1e-15)
 
 
 def test_against_library_layers():
