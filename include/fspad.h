@@ -273,6 +273,33 @@ fspad_status fspad_kv_commit(const fspad_attn_desc* desc, const void* k_tree, co
                              int32_t* kv_len_out, void* hip_stream);
 
 /*
+ * Feature Sampler of the draft model (Methodology, "Feature Sampling": three projectors and a
+ * sampling operation in the intermediate space). The Up Projector lifts the feature f, the Gate
+ * Projector lifts the token embedding e, the lifted embedding goes through SiLU and multiplies the
+ * lifted feature element by element, the Down Projector maps the product back to the hidden size,
+ * and the residual connection of the feature path is added:
+ *
+ *   eta[r,:] = W_down (SiLU(W_gate e[r,:]) * (W_up f[r,:])) + f[r,:]        (without "+ f" if residual == 0)
+ *
+ *   rows              1..128: the tokens of one draft step (sequences x expanded nodes)
+ *   hidden_dim, intermediate_dim   multiples of 256
+ *   f, e              dev [rows,hidden_dim] bf16
+ *   w_up, w_gate      dev [intermediate_dim,hidden_dim] bf16 (one row per intermediate channel)
+ *   w_down            dev [hidden_dim,intermediate_dim] bf16
+ *   eta               dev [rows,hidden_dim] bf16 out
+ *   workspace         dev, 16-byte aligned, >= fspad_feature_sampler_workspace_bytes(...)
+ * All pointers 16-byte aligned, all arrays contiguous. bf16 products are exact, sums are fp32 (in a
+ * fixed order: the result is the same from run to run); the gated product is rounded to bf16 before
+ * the Down Projector, eta once more at the end. Never synchronises, allocates nothing.
+ */
+size_t fspad_feature_sampler_workspace_bytes(int32_t rows, int32_t hidden_dim, int32_t intermediate_dim);
+fspad_status fspad_feature_sampler(int32_t rows, int32_t hidden_dim, int32_t intermediate_dim,
+                                   const void* f, const void* e,
+                                   const void* w_up, const void* w_gate, const void* w_down,
+                                   int32_t residual, void* eta,
+                                   void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
  * Top-k cut of a draft step's output (Preliminaries, last paragraph: the output of every draft
  * step is cut to its k most probable tokens, and the joint probabilities of the tree follow from
  * their probabilities). Per row:

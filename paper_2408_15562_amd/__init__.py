@@ -12,6 +12,8 @@ from .binding import (  # noqa: F401
     PreparedCall,
     fspad_attn_desc,
     fspad_draft_topk,
+    fspad_feature_sampler,
+    fspad_feature_sampler_workspace_bytes,
     fspad_draft_topk_workspace_bytes,
     fspad_kv_commit,
     fspad_status_string,

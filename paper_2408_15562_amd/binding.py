@@ -27,7 +27,8 @@ EXPORTS = ("fspad_tree_attn_workspace_bytes", "fspad_tree_attn_set_workgroups", 
            "fspad_tree_accept_workspace_bytes", "fspad_tree_accept_greedy", "fspad_tree_accept_sample",
            "fspad_tree_accept_lm_head_workspace_bytes", "fspad_tree_accept_greedy_lm_head",
            "fspad_tree_accept_sample_lm_head",
-           "fspad_kv_commit", "fspad_draft_topk_workspace_bytes", "fspad_draft_topk", "fspad_tree_build", "fspad_tree_build_mask", "fspad_tree_validate", "fspad_status_string")
+           "fspad_kv_commit", "fspad_feature_sampler_workspace_bytes", "fspad_feature_sampler",
+           "fspad_draft_topk_workspace_bytes", "fspad_draft_topk", "fspad_tree_build", "fspad_tree_build_mask", "fspad_tree_validate", "fspad_status_string")
 
 
 class FspadError(RuntimeError):
@@ -82,6 +83,10 @@ def _lib():
                                                          vp, vp, vp, vp, vp, sz, vp]
         lib.fspad_kv_commit.restype = ctypes.c_int
         lib.fspad_kv_commit.argtypes = [ctypes.POINTER(fspad_attn_desc), vp, vp, vp, vp, i32, vp, vp, vp, vp, vp]
+        lib.fspad_feature_sampler_workspace_bytes.restype = sz
+        lib.fspad_feature_sampler_workspace_bytes.argtypes = [i32, i32, i32]
+        lib.fspad_feature_sampler.restype = ctypes.c_int
+        lib.fspad_feature_sampler.argtypes = [i32, i32, i32, vp, vp, vp, vp, vp, i32, vp, vp, sz, vp]
         lib.fspad_draft_topk_workspace_bytes.restype = sz
         lib.fspad_draft_topk_workspace_bytes.argtypes = [i32, i32, i32]
         lib.fspad_draft_topk.restype = ctypes.c_int
@@ -386,6 +391,33 @@ def fspad_kv_commit(k_tree: torch.Tensor, v_tree: torch.Tensor, k_cache: torch.T
             _dev_ptr(kv_len_out, "kv_len_out", torch.int32), _stream_ptr(stream))
     keep = (d, k_tree, v_tree, k_cache, v_cache, kv_len, path, path_len, kv_len_out)
     return _issue(_lib().fspad_kv_commit, "fspad_kv_commit", args, keep, kv_len_out, prepare)
+
+
+def fspad_feature_sampler_workspace_bytes(rows: int, hidden_dim: int, intermediate_dim: int) -> int:
+    return int(_lib().fspad_feature_sampler_workspace_bytes(rows, hidden_dim, intermediate_dim))
+
+
+def fspad_feature_sampler(f: torch.Tensor, e: torch.Tensor, w_up: torch.Tensor, w_gate: torch.Tensor,
+                          w_down: torch.Tensor, residual: bool = True, out: Optional[torch.Tensor] = None,
+                          workspace: Optional[torch.Tensor] = None, stream=None, prepare: bool = False):
+    """f, e [rows,Hd]; w_up, w_gate [I,Hd]; w_down [Hd,I]; all contiguous bf16 device tensors. Returns
+    eta [rows,Hd] bf16; with prepare=True a PreparedCall."""
+    rows, Hd = f.shape
+    I = w_up.shape[0]
+    for name, t, shape in (("f", f, (rows, Hd)), ("e", e, (rows, Hd)), ("w_up", w_up, (I, Hd)), ("w_gate", w_gate, (I, Hd)),
+                           ("w_down", w_down, (Hd, I))):
+        if tuple(t.shape) != shape or not t.is_contiguous():
+            raise ValueError(f"{name} must be a contiguous {shape} tensor")
+    if out is None:
+        out = torch.empty((rows, Hd), dtype=torch.bfloat16, device=f.device)
+    if workspace is None:
+        workspace = torch.empty(max(16, fspad_feature_sampler_workspace_bytes(rows, Hd, I)), dtype=torch.uint8, device=f.device)
+    args = (rows, Hd, I, _dev_ptr(f, "f", torch.bfloat16), _dev_ptr(e, "e", torch.bfloat16),
+            _dev_ptr(w_up, "w_up", torch.bfloat16), _dev_ptr(w_gate, "w_gate", torch.bfloat16),
+            _dev_ptr(w_down, "w_down", torch.bfloat16), 1 if residual else 0, _dev_ptr(out, "eta", torch.bfloat16),
+            _dev_ptr(workspace, "workspace"), workspace.numel() * workspace.element_size(), _stream_ptr(stream))
+    return _issue(_lib().fspad_feature_sampler, "fspad_feature_sampler", args, (f, e, w_up, w_gate, w_down, workspace),
+                  out, prepare)
 
 
 def fspad_draft_topk_workspace_bytes(rows: int, V: int, k: int) -> int:

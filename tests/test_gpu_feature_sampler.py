@@ -1,0 +1,71 @@
+"""GPU parity of fspad_feature_sampler against the CPU oracle, through the C ABI.
+
+Bar, element by element: |eta - oracle| <= 2^-8 |oracle| + 1e-2 x RMS(oracle). The first term is the
+rounding of the result to bf16 (half an ulp is at most 2^-8 relative), the second the rounding of
+the gated product to bf16 before the Down Projector (up to 2^-8 relative per entry, summed over the
+intermediate size with weights of variance 1/I: a standard deviation of about 1.7e-3 x the RMS of the
+projector's output, five to six of them at the largest of 10^5 entries); the fp32 sums are far below both. The oracle keeps fp64
+throughout."""
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+import oracle  # noqa: E402
+from workloads import gen_feature_sampler  # noqa: E402
+
+DEV = "cuda:0"
+
+
+def _dev(a):
+    return torch.from_numpy(a).to(DEV, dtype=torch.bfloat16)
+
+
+def _check(seed, rows, Hd, I, residual=True):
+    import paper_2408_15562_amd as fspad
+    host = gen_feature_sampler(seed, rows, Hd, I)
+    out = fspad.fspad_feature_sampler(*[_dev(a) for a in host], residual=residual)
+    torch.cuda.synchronize()
+    ref = oracle.feature_sampler(*host, residual=residual)
+    err = np.abs(out.float().cpu().numpy().astype(np.float64) - ref)
+    bound = np.abs(ref) * 2.0 ** -8 + 1e-2 * np.sqrt(np.mean(ref ** 2))
+    worst = float((err / bound).max())
+    assert worst <= 1.0, f"error at {worst:.2f} of the bound"
+    return out
+
+
+@pytest.mark.parametrize("rows,Hd,I", [
+    (1, 256, 256), (4, 256, 512), (10, 512, 1280), (16, 768, 2048), (17, 1024, 2816), (32, 512, 768),
+    (40, 1280, 3328), (64, 256, 1024), (65, 512, 1536), (100, 768, 256), (128, 256, 768),
+])
+def test_shapes(rows, Hd, I):
+    """Every row-tile count (1, 2, 4, 8 tiles of 16), k ranges of one chunk and many, odd chunk counts
+    (a last split shorter than the others, a stage that is only half full)."""
+    _check(100 + rows + I, rows, Hd, I)
+
+
+def test_without_residual_and_repeatable():
+    out = _check(7, 24, 512, 1024, residual=False)
+    again = _check(7, 24, 512, 1024, residual=False)
+    assert torch.equal(out, again)
+
+
+def test_closed_gate_returns_the_feature():
+    import paper_2408_15562_amd as fspad
+    f, e, wu, wg, wd = gen_feature_sampler(8, 12, 512, 1024)
+    out = fspad.fspad_feature_sampler(_dev(f), _dev(np.zeros_like(e)), _dev(wu), _dev(wg), _dev(wd))
+    torch.cuda.synchronize()
+    assert np.array_equal(out.float().cpu().numpy(), f)      # SiLU(0) = 0: eta = f exactly
+
+
+def test_llama_7b_shapes_one_draft_step():
+    """hidden 4096, intermediate 11008 (43 chunks of 256: an odd count), the 10 rows of one draft step."""
+    _check(9, 10, 4096, 11008)
+
+
+def test_missing_workspace_is_an_error():
+    import paper_2408_15562_amd as fspad
+    host = [_dev(a) for a in gen_feature_sampler(3, 4, 256, 256)]
+    with pytest.raises(fspad.FspadError):
+        fspad.fspad_feature_sampler(*host, workspace=torch.empty(16, dtype=torch.uint8, device=DEV))

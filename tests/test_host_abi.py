@@ -169,6 +169,30 @@ def test_lm_head_argument_checks_need_no_gpu(lib):
     assert sample(wsb=need - 1) == 5
 
 
+def test_feature_sampler_argument_checks_need_no_gpu(lib):
+    f = lib.fspad_feature_sampler
+    fake = ctypes.c_void_p(0x1000)   # never dereferenced: every case below fails validation first
+    i32, sz = ctypes.c_int32, ctypes.c_size_t
+    need = fspad.fspad_feature_sampler_workspace_bytes(10, 4096, 11008)
+    assert need >= 10 * 11008 * 2
+    assert fspad.fspad_feature_sampler_workspace_bytes(129, 4096, 11008) == 0
+    assert fspad.fspad_feature_sampler_workspace_bytes(10, 4096, 11000) == 0
+
+    def call(rows=10, Hd=4096, I=11008, x=fake, w=fake, out=fake, ws=fake, wsb=need):
+        return f(i32(rows), i32(Hd), i32(I), x, fake, w, fake, fake, i32(1), out, ws, sz(wsb), None)
+
+    assert call(x=None) == 1
+    assert call(w=None) == 1
+    assert call(out=None) == 1
+    assert call(rows=0) == 2
+    assert call(rows=129) == 2
+    assert call(Hd=4000) == 2
+    assert call(I=11000) == 2
+    assert call(x=ctypes.c_void_p(0x1008)) == 2
+    assert call(wsb=need - 1) == 5
+    assert call(ws=None) == 5
+
+
 def test_topk_argument_checks_need_no_gpu(lib):
     f = lib.fspad_draft_topk
     fake = ctypes.c_void_p(0x1000)   # never dereferenced: every case below fails validation first
