@@ -57,11 +57,16 @@ def parse_args():
     ap.add_argument("--draft-topk", action="store_true",
                     help="also cut the outputs of the draft steps to their top-k at the top of every step: tree_depth calls "
                          "of fspad_draft_topk over B x top-k rows of V synthetic draft logits (timing only, like --tree-build)")
+    ap.add_argument("--feature-sampler", default=None, choices=["fused", "library"],
+                    help="also run the draft model's Feature Sampler at the top of every step: tree_depth calls over "
+                         "B x top-k rows with the workload's hidden / intermediate sizes (timing only). fused = "
+                         "fspad_feature_sampler; library = three library GEMMs + element-wise kernels (the comparison)")
     ap.add_argument("--lm-head", default=None, choices=["fused", "unfused"],
                     help="start the acceptance from the last hidden states instead of ready-made logits. "
                          "fused = fspad_tree_accept_{greedy,sample}_lm_head (logits never written); unfused = library GEMM "
                          "to bf16 logits, widened to fp32, then fspad_tree_accept_{greedy,sample} (the comparison)")
     ap.add_argument("--lm-stagger", type=int, default=None, help=argparse.SUPPRESS)
+    ap.add_argument("--sampler-target", type=int, default=0, help=argparse.SUPPRESS)
     ap.add_argument("--hidden-dim", type=int, default=None, help="hidden size for --lm-head (default: the workload's model)")
     ap.add_argument("--seed", type=int, default=2024)
     return ap.parse_args()
@@ -146,6 +151,9 @@ def main():
     if args.accept_target:
         import ctypes
         ctypes.CDLL(fspad.library_path()).fspad_debug_set_accept_target(args.accept_target)
+    if args.sampler_target:
+        import ctypes
+        ctypes.CDLL(fspad.library_path()).fspad_debug_set_sampler_target(args.sampler_target)
     if args.lm_stagger is not None:
         import ctypes
         ctypes.CDLL(fspad.library_path()).fspad_debug_set_lm_head_stagger(args.lm_stagger)
@@ -193,6 +201,23 @@ def main():
             rows = B * cfg.tree_topk
             draft_logits = torch.empty((rows, V), device=dev, dtype=torch.float32).normal_(generator=gen).mul_(3.0)
             st["topk"] = [fspad.fspad_draft_topk(draft_logits, min(cfg.tree_topk, 16), prepare=True)] * cfg.tree_depth
+        st["sampler"] = []
+        if args.feature_sampler:
+            Hd_fs, I_fs = {"c0": (256, 512), "c1": (4096, 11008), "c2": (4096, 14336), "c3": (6656, 17920),
+                           "c4": (8192, 28672)}[args.workload]
+            rows_fs = min(128, B * cfg.tree_topk)
+            if "fs_w" not in sets[0]:
+                sets[0]["fs_w"] = [[torch.empty(shape, device=dev, dtype=torch.bfloat16).normal_(generator=gen).mul_(shape[1] ** -0.5)
+                                    for shape in ((I_fs, Hd_fs), (I_fs, Hd_fs), (Hd_fs, I_fs))] for _ in range(2)]
+            wu, wg, wd = sets[0]["fs_w"][len(sets[0].get("fs_n", [])) % 2]
+            sets[0].setdefault("fs_n", []).append(1)
+            f_in = torch.empty((rows_fs, Hd_fs), device=dev, dtype=torch.bfloat16).normal_(generator=gen)
+            e_in = torch.empty((rows_fs, Hd_fs), device=dev, dtype=torch.bfloat16).normal_(generator=gen)
+            if args.feature_sampler == "fused":
+                st["sampler"] = [fspad.fspad_feature_sampler(f_in, e_in, wu, wg, wd, prepare=True)] * cfg.tree_depth
+            else:
+                st["sampler"] = [library_feature_sampler(torch, f_in, e_in, wu, wg, wd)] * cfg.tree_depth
+            st["sampler_bytes"] = 2 * (3 * Hd_fs * I_fs + 3 * rows_fs * Hd_fs)
         st["build"] = None
         if args.tree_build:
             cands = gen_candidates(args.seed, B, cfg.tree_depth, cfg.tree_topk, V)
@@ -202,6 +227,17 @@ def main():
 
     def step(i, timed=None):
         st = sets[i % n_sets]
+        if st["sampler"] and timed is not None:
+            e0, e1 = event_pool.pop(), event_pool.pop()
+            e0.record()
+            st["sampler"][0]()
+            e1.record()
+            sampler_events.append((e0, e1))
+            for call in st["sampler"][1:]:
+                call()
+        else:
+            for call in st["sampler"]:
+                call()
         for call in st["topk"]:
             call()
         if st["build"] is not None:
@@ -245,8 +281,8 @@ def main():
     events = []
     event_every = args.event_every if args.event_every > 0 else max(4, steps // 12)
     # events are created ahead of the timed region (two per bracketed call)
-    event_pool = [TimingEvent(stream_handle) for _ in range(2 * 9 * (steps // event_every + 1))]
-    accept_events = []
+    event_pool = [TimingEvent(stream_handle) for _ in range(2 * 10 * (steps // event_every + 1))]
+    accept_events, sampler_events = [], []
     t0 = time.perf_counter()
     # Recording an event costs the stream several microseconds, as much as a small kernel: only every
     # `event_every`-th step is bracketed, so that the timed region stays the workload's own.
@@ -307,6 +343,14 @@ def main():
         "roofline": roofline,
     }
 
+    if args.feature_sampler:
+        fs_ms = np.array([a.elapsed_time(b) for a, b in sampler_events])
+        call_s = float(np.percentile(fs_ms, 50)) * 1e-3
+        fs_bytes = sets[0]["sampler_bytes"]
+        result["config"].update(feature_sampler=args.feature_sampler)
+        result["feature_sampler"] = {"mode": args.feature_sampler, "call_us_p50": call_s * 1e6, "calls_per_step": cfg.tree_depth,
+                                     "algorithmic_bytes": fs_bytes, "gb_per_s": fs_bytes / call_s / 1e9,
+                                     "hbm_frac": fs_bytes / call_s / 1e9 / HBM_PEAK_GBS}
     if args.lm_head:
         # the LM head streams its V x Hd weights once (and the B*N x Hd hidden states); per group of rows when B*N > 256
         passes = -(-B * N // 256)
@@ -320,6 +364,23 @@ def main():
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(cfg, accept, sets[0], parent, n_nodes, kv_len, args.seed)
     print(json.dumps(result))
+
+
+def library_feature_sampler(torch, f_in, e_in, wu, wg, wd):
+    """The comparison for --feature-sampler: library GEMMs and element-wise kernels, buffers allocated once."""
+    rows, I = f_in.shape[0], wu.shape[0]
+    up = torch.empty((rows, I), device=f_in.device, dtype=torch.bfloat16)
+    gate = torch.empty_like(up)
+    out = torch.empty_like(f_in)
+
+    def call():
+        torch.mm(f_in, wu.t(), out=up)
+        torch.mm(e_in, wg.t(), out=gate)
+        torch.nn.functional.silu(gate, inplace=True)
+        gate.mul_(up)
+        torch.mm(gate, wd.t(), out=out)
+        out.add_(f_in)
+    return call
 
 
 def unfused_lm_head_accept(torch, fspad, st, parent_d, n_nodes_d, acc_out, ws_acc, accept, temperature):
