@@ -7,7 +7,8 @@ acceptance call over the per-node logits.  Inputs are synthetic, seeded, residen
 in HBM before the timed region; single-layer workloads rotate through enough
 independent buffer sets that they stream from HBM rather than the last-level cache.
 
-Prints ONE JSON line (see README / DESIGN for the fields).
+Prints ONE JSON line: metric / value / unit (steps per second), ms_per_step, the workload in `config`,
+the event-timed attention and acceptance calls, `roofline` of the attention call and `cpu_baseline`.
 """
 from __future__ import annotations
 
