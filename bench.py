@@ -68,6 +68,7 @@ def parse_args():
                          "to bf16 logits, widened to fp32, then fspad_tree_accept_{greedy,sample} (the comparison)")
     ap.add_argument("--lm-stagger", type=int, default=None, help=argparse.SUPPRESS)
     ap.add_argument("--sampler-target", type=int, default=0, help=argparse.SUPPRESS)
+    ap.add_argument("--short-stream", type=int, default=None, help=argparse.SUPPRESS)
     ap.add_argument("--hidden-dim", type=int, default=None, help="hidden size for --lm-head (default: the workload's model)")
     ap.add_argument("--seed", type=int, default=2024)
     return ap.parse_args()
@@ -152,6 +153,9 @@ def main():
     if args.accept_target:
         import ctypes
         ctypes.CDLL(fspad.library_path()).fspad_debug_set_accept_target(args.accept_target)
+    if args.short_stream is not None:
+        import ctypes
+        ctypes.CDLL(fspad.library_path()).fspad_debug_set_short_stream(args.short_stream)
     if args.sampler_target:
         import ctypes
         ctypes.CDLL(fspad.library_path()).fspad_debug_set_sampler_target(args.sampler_target)
