@@ -451,7 +451,7 @@ class TimingEvent:
 # reads for a 512 MiB copy (2048 B per FETCH count, 1024 B per WRITE count on this machine); figures and
 # commands in profiles/tree_verify_traffic.txt. Above the algorithmic bytes by the partial results of units
 # that are cut across workgroups (c2, c4: 256 rows per workgroup) and by the second slab group's K/V reads.
-MEASURED_TRAFFIC_BYTES = {"c1": 45764822, "c2": 62510687, "c3": 456197143, "c4": 140837940}
+MEASURED_TRAFFIC_BYTES = {"c1": 45764473, "c2": 53890269, "c3": 456196462, "c4": 140843245}
 
 
 def cpu_baseline(cfg, accept, dev_set, parent, n_nodes, kv_len, seed):
