@@ -1,7 +1,8 @@
 """Seeded random sweep over shapes inside the documented limits: every draw is a fresh combination of
 batch, tree size, head geometry, head dimension, ragged prefix lengths and node counts, cache
-strides and workgroup count (attention), or of batch, tree size, vocabulary and row padding
-(acceptance). Same bars as the fixed cases: 2e-2 x RMS for bf16 attention, bit-exact acceptance."""
+strides and workgroup count (attention), of batch, tree size, vocabulary and row padding
+(acceptance, from logits and from hidden states), or of rows, vocabulary, k and layer sizes (top-k
+cut, Feature Sampler). Same bars as the fixed cases."""
 import numpy as np
 import pytest
 import torch
@@ -55,3 +56,50 @@ def test_acceptance_random_shape(H, draw):
     cpu = case.cpu_sample(T)
     keep = cpu[4] >= H.MARGIN
     H.assert_accept_equal(case.gpu_sample(T), cpu, keep=keep)
+
+
+@pytest.mark.parametrize("draw", range(12))
+def test_lm_head_acceptance_random_shape(H, draw):
+    """Greedy and sampling acceptance from hidden states: batch, tree size, ragged node counts, hidden
+    size (multiples of 256), vocabulary (ragged slices of 128) at random."""
+    rng = np.random.default_rng([26, draw])
+    B = int(rng.integers(1, 7))
+    N = int(rng.integers(2, 65))
+    Hd = 256 * int(rng.integers(1, 7))
+    V = int(rng.choice([2, 100, 129, 1000, 4097, 20000]))
+    topk = int(min(10, max(1, min(N - 1, V - 1))))
+    N = min(N, 1 + topk + 5 * topk * topk)
+    n_nodes = rng.integers(1, N + 1, B).astype(np.int32)
+    n_nodes[int(rng.integers(0, B))] = N
+    case = H.LmHeadCase(9200 + draw, B, N, Hd, V, topk=topk, n_nodes=n_nodes, noise=0.5)
+    H.assert_lm_head_equal(case.gpu(), case.cpu(), require_decided=False)
+    T = float(rng.choice([0.5, 1.0, 1.5]))
+    H.assert_lm_head_sample_equal(case.gpu_sample(T, draw), case.cpu_sample(T, draw), min_compared=0.0)
+
+
+@pytest.mark.parametrize("draw", range(10))
+def test_draft_side_random_shape(draw):
+    """Top-k cut, tree build on its output, Feature Sampler: rows, vocabulary, k, sizes at random."""
+    import oracle
+    import paper_2408_15562_amd as fspad
+    from workloads import gen_feature_sampler, gen_logits
+    rng = np.random.default_rng([2024, draw])
+    rows = int(rng.integers(1, 41))
+    V = int(rng.choice([5, 100, 1023, 5000, 33000]))
+    k = int(min(V, rng.integers(1, 17)))
+    x = gen_logits(9300 + draw, 1, rows, V, peak=float(rng.choice([0.0, 4.0])))[0]
+    tok, lp = fspad.fspad_draft_topk(torch.from_numpy(x).to("cuda:0"), k)
+    torch.cuda.synchronize()
+    r_tok, r_lp = oracle.draft_topk(x, k)
+    np.testing.assert_array_equal(tok.cpu().numpy(), r_tok)
+    np.testing.assert_allclose(lp.cpu().numpy(), r_lp, rtol=0, atol=4e-6)
+
+    Hd, I = 256 * int(rng.integers(1, 5)), 256 * int(rng.integers(1, 9))
+    host = gen_feature_sampler(9400 + draw, rows, Hd, I)
+    residual = bool(rng.integers(0, 2))
+    out = fspad.fspad_feature_sampler(*[torch.from_numpy(a).to("cuda:0", dtype=torch.bfloat16) for a in host], residual=residual)
+    torch.cuda.synchronize()
+    ref = oracle.feature_sampler(*host, residual=residual)
+    err = np.abs(out.float().cpu().numpy().astype(np.float64) - ref)
+    bound = np.abs(ref) * 2.0 ** -8 + 1e-2 * np.sqrt(np.mean(ref ** 2))
+    assert (err <= bound).all(), (rows, Hd, I, residual, float((err / bound).max()))
