@@ -13,6 +13,15 @@
  *      (temperature 0) or by rejection sampling that leaves the target's output
  *      distribution unchanged (Experiments, "Settings": temperature 1, and the
  *      caption of Table 1: acceptance conditions are not relaxed).
+ * and the calls around that step:
+ *   3. the same acceptance straight from the target's last hidden states, fused
+ *      with the LM head (fspad_tree_accept_{greedy,sample}_lm_head);
+ *   4. the commit of the accepted path's keys / values to the cache
+ *      (fspad_kv_commit);
+ *   5. on the draft side: the Feature Sampler (Methodology, "Feature Sampling":
+ *      fspad_feature_sampler), the top-k cut of a draft step's output and the
+ *      choice of the tree from the candidates (Preliminaries, last paragraph:
+ *      fspad_draft_topk, fspad_tree_build).
  *
  * Conventions that hold for every entry point:
  *   - "dev" pointers are device (HBM) addresses, "host" pointers are host
