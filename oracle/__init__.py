@@ -336,3 +336,64 @@ def feature_sampler(f, e, w_up, w_gate, w_down, residual=True):
     sampled = gate / (1.0 + np.exp(-gate)) * up
     eta = sampled @ np.asarray(w_down, dtype=np.float64).T
     return eta + f if residual else eta
+
+
+def rms_norm(x, gain, eps):
+    """x / sqrt(mean(x^2) + eps) * gain over the last axis, fp64."""
+    x = np.asarray(x, dtype=np.float64)
+    return x / np.sqrt(np.mean(x * x, axis=-1, keepdims=True) + eps) * np.asarray(gain, dtype=np.float64)
+
+
+def rope(u, positions, theta):
+    """Rotary position encoding of head vectors u [..., D] at integer positions [...]: entry i of
+    the first half and entry i of the second half form the pair that is rotated by the angle
+    position * theta^(-2i/D)."""
+    u = np.asarray(u, dtype=np.float64)
+    D = u.shape[-1]
+    half = D // 2
+    inv_freq = float(theta) ** (-2.0 * np.arange(half, dtype=np.float64) / D)
+    ang = np.asarray(positions, dtype=np.float64)[..., None] * inv_freq
+    c, s = np.cos(ang), np.sin(ang)
+    a, b = u[..., :half], u[..., half:]
+    return np.concatenate([a * c - b * s, b * c + a * s], axis=-1)
+
+
+def draft_layer(eta, positions, w_qkv, w_o, w_gate, w_up, w_down, gain_attn, gain_mlp, k_cache, v_cache,
+                kv_len, n_nodes, parent, n_q_heads, n_kv_heads, head_dim, rms_eps=1e-6, rope_theta=10000.0):
+    """The draft model: one transformer decoder layer over the draft's token tree (Methodology,
+    first paragraph: the draft model is a Transformer Decoder Layer; "Partial Alignment
+    Distillation": the MLP's output dimension is doubled and both halves share one residual
+    connection, giving the two features f~ and f), fp64 throughout:
+
+        x   = eta                                             [B,Nmax,Hd]
+        q,k,v = split(W_qkv rmsnorm(x)), rotary encoding of q and k at `positions`
+        h   = x + W_o tree_attn(q, k, v | the draft's own cache, the tree mask)
+        m   = W_down (SiLU(W_gate rmsnorm(h)) * (W_up rmsnorm(h)))        [B,Nmax,2 Hd]
+        f~  = h + m[..., :Hd]        f = h + m[..., Hd:]
+
+    The layer is LLaMA's (pre-normalisation with RMSNorm, rotary encoding, grouped-query
+    attention, gated MLP, no biases).  w_qkv [(Hq+2Hkv) D, Hd] holds the query, key and value
+    projections stacked in that order; w_o [Hd, Hq D]; w_gate, w_up [I, Hd]; w_down [2 Hd, I].
+    positions [B,Nmax] int; the cache and tree arguments are those of `tree_attn`.
+    Returns (f_tilde, f, k_tree, v_tree): [B,Nmax,Hd] twice, [B,Nmax,Hkv,D] twice, float64;
+    rows of unused tree slots are zero."""
+    x = np.asarray(eta, dtype=np.float64)
+    B, Nmax, Hd = x.shape
+    Hq, Hkv, D = n_q_heads, n_kv_heads, head_dim
+    n_nodes = _i32(n_nodes)
+    qkv = rms_norm(x, gain_attn, rms_eps) @ np.asarray(w_qkv, dtype=np.float64).T
+    q = rope(qkv[..., :Hq * D].reshape(B, Nmax, Hq, D), np.asarray(positions)[..., None], rope_theta)
+    k = rope(qkv[..., Hq * D:(Hq + Hkv) * D].reshape(B, Nmax, Hkv, D), np.asarray(positions)[..., None], rope_theta)
+    v = qkv[..., (Hq + Hkv) * D:].reshape(B, Nmax, Hkv, D)
+    a = tree_attn(q, k, v, k_cache, v_cache, kv_len, n_nodes, parent)
+    h = x + a.reshape(B, Nmax, Hq * D) @ np.asarray(w_o, dtype=np.float64).T
+    hn = rms_norm(h, gain_mlp, rms_eps)
+    gate = hn @ np.asarray(w_gate, dtype=np.float64).T
+    m = (gate / (1.0 + np.exp(-gate)) * (hn @ np.asarray(w_up, dtype=np.float64).T)) @ np.asarray(w_down, dtype=np.float64).T
+    f_tilde, f = h + m[..., :Hd], h + m[..., Hd:]
+    used = (np.arange(Nmax)[None, :] < n_nodes[:, None])
+    for arr in (f_tilde, f):
+        arr[~used] = 0.0
+    k = np.where(used[..., None, None], k, 0.0)
+    v = np.where(used[..., None, None], v, 0.0)
+    return f_tilde, f, k, v

@@ -22,6 +22,8 @@ from .generators import (  # noqa: F401
     gen_candidates,
     gen_lm_head,
     gen_feature_sampler,
+    gen_draft_layer,
+    tree_depths,
     round_to_bf16,
     chain_tree,
 )

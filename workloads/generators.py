@@ -220,3 +220,39 @@ def gen_feature_sampler(seed: int, rows: int, hidden_dim: int, intermediate_dim:
     w_gate = round_to_bf16(rng.standard_normal((intermediate_dim, hidden_dim), dtype=np.float32) / np.float32(np.sqrt(hidden_dim)))
     w_down = round_to_bf16(rng.standard_normal((hidden_dim, intermediate_dim), dtype=np.float32) / np.float32(np.sqrt(intermediate_dim)))
     return f, e, w_up, w_gate, w_down
+
+
+def tree_depths(parent: np.ndarray, n_nodes: np.ndarray) -> np.ndarray:
+    """depth [B,Nmax] of every node below its root (root 0; unused slots 0)."""
+    depth = np.zeros(parent.shape, dtype=np.int32)
+    for b in range(parent.shape[0]):
+        for i in range(1, int(n_nodes[b])):
+            depth[b, i] = depth[b, parent[b, i]] + 1
+    return depth
+
+
+def gen_draft_layer(seed: int, batch: int, n_max: int, hidden_dim: int, intermediate_dim: int,
+                    n_q_heads: int, n_kv_heads: int, head_dim: int, l_cap: int):
+    """Inputs, weights and cache of one draft decoder layer, all rounded to bf16 and returned as
+    fp32 in a dict: eta [B,N,Hd] ~ N(0,1); projection weights ~ N(0, 1/fan_in) (w_qkv
+    [(Hq+2Hkv)D,Hd], w_o [Hd,HqD], w_gate / w_up [I,Hd], w_down [2Hd,I]) so that every stage keeps
+    O(1) entries; normalisation gains ~ 1 + 0.1 N(0,1); the draft's own cache k_cache / v_cache
+    [B,Hkv,Lcap,D] ~ N(0,1)."""
+    rng = np.random.default_rng([seed, 0xD1A7])
+
+    def normal(shape, scale=1.0):
+        return round_to_bf16(rng.standard_normal(shape, dtype=np.float32) * np.float32(scale))
+
+    qkv_rows = (n_q_heads + 2 * n_kv_heads) * head_dim
+    return {
+        "eta": normal((batch, n_max, hidden_dim)),
+        "w_qkv": normal((qkv_rows, hidden_dim), 1.0 / np.sqrt(hidden_dim)),
+        "w_o": normal((hidden_dim, n_q_heads * head_dim), 1.0 / np.sqrt(n_q_heads * head_dim)),
+        "w_gate": normal((intermediate_dim, hidden_dim), 1.0 / np.sqrt(hidden_dim)),
+        "w_up": normal((intermediate_dim, hidden_dim), 1.0 / np.sqrt(hidden_dim)),
+        "w_down": normal((2 * hidden_dim, intermediate_dim), 1.0 / np.sqrt(intermediate_dim)),
+        "gain_attn": round_to_bf16(1.0 + 0.1 * rng.standard_normal(hidden_dim, dtype=np.float32)),
+        "gain_mlp": round_to_bf16(1.0 + 0.1 * rng.standard_normal(hidden_dim, dtype=np.float32)),
+        "k_cache": normal((batch, n_kv_heads, l_cap, head_dim)),
+        "v_cache": normal((batch, n_kv_heads, l_cap, head_dim)),
+    }
