@@ -19,7 +19,9 @@
  *   4. the commit of the accepted path's keys / values to the cache
  *      (fspad_kv_commit);
  *   5. on the draft side: the Feature Sampler (Methodology, "Feature Sampling":
- *      fspad_feature_sampler), the top-k cut of a draft step's output and the
+ *      fspad_feature_sampler), the draft decoder layer with the doubled MLP
+ *      output ("Partial Alignment Distillation": fspad_draft_layer), the top-k cut of
+ *      a draft step's output and the
  *      choice of the tree from the candidates (Preliminaries, last paragraph:
  *      fspad_draft_topk, fspad_tree_build).
  *
@@ -307,6 +309,71 @@ fspad_status fspad_feature_sampler(int32_t rows, int32_t hidden_dim, int32_t int
                                    const void* w_up, const void* w_gate, const void* w_down,
                                    int32_t residual, void* eta,
                                    void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * The draft model: one transformer decoder layer over the draft's token tree (Methodology, first
+ * paragraph: the draft model is a Transformer Decoder Layer that maps the sequence eta to the next
+ * features; "Partial Alignment Distillation": the output dimension of its MLP is doubled and both
+ * halves share one residual connection, which gives the two features f~ (mapped to tokens by the
+ * LM head) and f (the Feature Sampler's input of the next step)).
+ *
+ *   x        = eta
+ *   q, k, v  = split(W_qkv rmsnorm(x; gain_attn)); q and k rotary-encoded at `positions`
+ *   h        = x + W_o attn          attn = fspad_tree_attn(q, k, v | draft cache, anc_mask)
+ *   m        = W_down (SiLU(W_gate rmsnorm(h; gain_mlp)) * (W_up rmsnorm(h; gain_mlp)))
+ *   f~       = h + m[:, :Hd]         f = h + m[:, Hd:]
+ *
+ * The layer is LLaMA's: rmsnorm(x; g) = x / sqrt(mean(x^2) + rms_eps) * g; the rotary encoding
+ * turns the pair (entry i, entry i + D/2) of every query and key head by
+ * positions[b,n] * rope_theta^(-2i/D); no biases. The caller commits the accepted rows of k_tree /
+ * v_tree to the draft's cache with fspad_kv_commit.
+ *
+ *   desc.attn   geometry of the draft's attention and of its cache as for fspad_tree_attn;
+ *               io_dtype and out_dtype FSPAD_BF16; batch * n_nodes_max <= 128;
+ *               n_q_heads * head_dim a multiple of 256
+ *   hidden_dim, intermediate_dim  Hd, I: multiples of 256
+ *   weights     dev bf16, row-major [out][in], 16-byte aligned: w_qkv [(Hq+2Hkv) D, Hd] (query,
+ *               key, value rows in that order), w_o [Hd, Hq D], w_gate and w_up [I, Hd],
+ *               w_down [2 Hd, I] (rows 0..Hd-1 produce f~, rows Hd.. produce f), gain_attn and
+ *               gain_mlp [Hd]
+ *   eta         dev [B,Nmax,Hd] bf16
+ *   positions   dev [B,Nmax] i32 (prefix length + depth of the node)
+ *   k_cache, v_cache, kv_len (HOST), n_nodes (HOST), anc_mask: as for fspad_tree_attn
+ *   k_tree, v_tree  dev [B,Nmax,Hkv,D] bf16 OUT: keys (rotary-encoded) and values of the nodes
+ *   f_tilde, f  dev [B,Nmax,Hd] bf16 OUT; rows of unused tree slots hold unspecified values
+ *   workspace   dev, 16-byte aligned, at least fspad_draft_layer_workspace_bytes(desc,
+ *               max_b kv_len[b]) bytes (0 = unsupported shape); contents ignored on entry, undefined on
+ *               exit; two calls that may overlap in time need different workspaces
+ * Products of bf16 values are summed in fp32 in a fixed order; the activations between the
+ * projections (normalised inputs, q / k / v, attention output, h, the gated product) are rounded to
+ * bf16 once each, as a bf16 model stores them.
+ */
+typedef struct {
+  fspad_attn_desc attn;
+  int32_t hidden_dim;
+  int32_t intermediate_dim;
+  float rms_eps;     /* >= 0 */
+  float rope_theta;  /* > 0, e.g. 10000 */
+} fspad_draft_layer_desc;
+
+typedef struct {
+  const void* w_qkv;
+  const void* w_o;
+  const void* w_gate;
+  const void* w_up;
+  const void* w_down;
+  const void* gain_attn;
+  const void* gain_mlp;
+} fspad_draft_layer_weights;
+
+size_t fspad_draft_layer_workspace_bytes(const fspad_draft_layer_desc* desc, int32_t max_kv_len);
+
+fspad_status fspad_draft_layer(const fspad_draft_layer_desc* desc, const fspad_draft_layer_weights* weights,
+                               const void* eta, const int32_t* positions,
+                               const void* k_cache, const void* v_cache,
+                               const int32_t* kv_len, const int32_t* n_nodes, const uint64_t* anc_mask,
+                               void* k_tree, void* v_tree, void* f_tilde, void* f,
+                               void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
  * Top-k cut of a draft step's output (Preliminaries, last paragraph: the output of every draft

@@ -13,6 +13,8 @@ from .binding import (  # noqa: F401
     fspad_attn_desc,
     fspad_draft_topk,
     fspad_feature_sampler,
+    fspad_draft_layer,
+    fspad_draft_layer_workspace_bytes,
     fspad_feature_sampler_workspace_bytes,
     fspad_draft_topk_workspace_bytes,
     fspad_kv_commit,

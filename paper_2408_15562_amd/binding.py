@@ -28,7 +28,9 @@ EXPORTS = ("fspad_tree_attn_workspace_bytes", "fspad_tree_attn_set_workgroups", 
            "fspad_tree_accept_lm_head_workspace_bytes", "fspad_tree_accept_greedy_lm_head",
            "fspad_tree_accept_sample_lm_head",
            "fspad_kv_commit", "fspad_feature_sampler_workspace_bytes", "fspad_feature_sampler",
-           "fspad_draft_topk_workspace_bytes", "fspad_draft_topk", "fspad_tree_build", "fspad_tree_build_mask", "fspad_tree_validate", "fspad_status_string")
+           "fspad_draft_layer_workspace_bytes", "fspad_draft_layer",
+           "fspad_draft_topk_workspace_bytes", "fspad_draft_topk", "fspad_tree_build", "fspad_tree_build_mask",
+           "fspad_tree_validate", "fspad_status_string")
 
 
 class FspadError(RuntimeError):
@@ -44,6 +46,16 @@ class fspad_attn_desc(ctypes.Structure):
                 ("out_dtype", ctypes.c_int32), ("softmax_scale", ctypes.c_float),
                 ("cache_stride_batch", ctypes.c_int64), ("cache_stride_head", ctypes.c_int64),
                 ("cache_stride_token", ctypes.c_int64)]
+
+
+class fspad_draft_layer_desc(ctypes.Structure):
+    _fields_ = [("attn", fspad_attn_desc), ("hidden_dim", ctypes.c_int32), ("intermediate_dim", ctypes.c_int32),
+                ("rms_eps", ctypes.c_float), ("rope_theta", ctypes.c_float)]
+
+
+class fspad_draft_layer_weights(ctypes.Structure):
+    _fields_ = [(name, ctypes.c_void_p) for name in
+                ("w_qkv", "w_o", "w_gate", "w_up", "w_down", "gain_attn", "gain_mlp")]
 
 
 _LIB = None
@@ -87,6 +99,11 @@ def _lib():
         lib.fspad_feature_sampler_workspace_bytes.argtypes = [i32, i32, i32]
         lib.fspad_feature_sampler.restype = ctypes.c_int
         lib.fspad_feature_sampler.argtypes = [i32, i32, i32, vp, vp, vp, vp, vp, i32, vp, vp, sz, vp]
+        lib.fspad_draft_layer_workspace_bytes.restype = sz
+        lib.fspad_draft_layer_workspace_bytes.argtypes = [ctypes.POINTER(fspad_draft_layer_desc), i32]
+        lib.fspad_draft_layer.restype = ctypes.c_int
+        lib.fspad_draft_layer.argtypes = [ctypes.POINTER(fspad_draft_layer_desc),
+                                          ctypes.POINTER(fspad_draft_layer_weights)] + [vp] * 11 + [vp, sz, vp]
         lib.fspad_draft_topk_workspace_bytes.restype = sz
         lib.fspad_draft_topk_workspace_bytes.argtypes = [i32, i32, i32]
         lib.fspad_draft_topk.restype = ctypes.c_int
@@ -418,6 +435,77 @@ def fspad_feature_sampler(f: torch.Tensor, e: torch.Tensor, w_up: torch.Tensor, 
             _dev_ptr(workspace, "workspace"), workspace.numel() * workspace.element_size(), _stream_ptr(stream))
     return _issue(_lib().fspad_feature_sampler, "fspad_feature_sampler", args, (f, e, w_up, w_gate, w_down, workspace),
                   out, prepare)
+
+
+def fspad_draft_layer_workspace_bytes(desc: fspad_draft_layer_desc, max_kv_len: int) -> int:
+    return int(_lib().fspad_draft_layer_workspace_bytes(ctypes.byref(desc), int(max_kv_len)))
+
+
+_DRAFT_LAYER_WEIGHTS = ("w_qkv", "w_o", "w_gate", "w_up", "w_down", "gain_attn", "gain_mlp")
+
+
+def fspad_draft_layer(eta: torch.Tensor, positions: torch.Tensor, weights: dict, k_cache: Optional[torch.Tensor],
+                      v_cache: Optional[torch.Tensor], kv_len, n_nodes, anc_mask: torch.Tensor, n_q_heads: int,
+                      n_kv_heads: int, head_dim: int, rms_eps: float = 1e-6, rope_theta: float = 10000.0,
+                      outputs=None, workspace: Optional[torch.Tensor] = None, stream=None, prepare: bool = False):
+    """eta [B,Nmax,Hd] bf16; positions [B,Nmax] int32 (device); weights: dict of contiguous bf16 device
+    tensors w_qkv [(Hq+2Hkv)D,Hd], w_o [Hd,HqD], w_gate, w_up [I,Hd], w_down [2Hd,I], gain_attn, gain_mlp
+    [Hd]; k_cache, v_cache [B,Hkv,Lcap,D] views of the draft's own cache (or None); kv_len, n_nodes HOST
+    int32 [B]; anc_mask device 64-bit [B,Nmax]. Returns (f_tilde, f, k_tree, v_tree): [B,Nmax,Hd] twice and
+    [B,Nmax,Hkv,D] twice, bf16 (pass them as `outputs` to reuse buffers); with prepare=True a PreparedCall."""
+    B, Nmax, Hd = eta.shape
+    Hq, Hkv, D = int(n_q_heads), int(n_kv_heads), int(head_dim)
+    I = weights["w_up"].shape[0]
+    shapes = {"w_qkv": ((Hq + 2 * Hkv) * D, Hd), "w_o": (Hd, Hq * D), "w_gate": (I, Hd), "w_up": (I, Hd),
+              "w_down": (2 * Hd, I), "gain_attn": (Hd,), "gain_mlp": (Hd,)}
+    for name in _DRAFT_LAYER_WEIGHTS:
+        t = weights[name]
+        if tuple(t.shape) != shapes[name] or not t.is_contiguous():
+            raise ValueError(f"{name} must be a contiguous {shapes[name]} tensor")
+    if not eta.is_contiguous() or not positions.is_contiguous() or tuple(positions.shape) != (B, Nmax):
+        raise ValueError("eta must be contiguous and positions a contiguous [B,Nmax] tensor")
+    if k_cache is not None and (v_cache is None or v_cache.stride() != k_cache.stride()
+                                or v_cache.dtype != eta.dtype or k_cache.dtype != eta.dtype):
+        raise ValueError("k_cache and v_cache must share strides and the dtype of eta")
+    if anc_mask.dtype not in (torch.int64, torch.uint64) or not anc_mask.is_contiguous():
+        raise ValueError("anc_mask must be a contiguous 64-bit integer tensor")
+    desc = fspad_draft_layer_desc()
+    a = desc.attn
+    a.batch, a.n_nodes_max, a.n_q_heads, a.n_kv_heads, a.head_dim = B, Nmax, Hq, Hkv, D
+    a.io_dtype = a.out_dtype = _dtype_code(eta.dtype)
+    a.softmax_scale = 0.0
+    if k_cache is not None:
+        if k_cache.stride(3) != 1:
+            raise ValueError("head_dim must be contiguous in the cache")
+        a.cache_stride_batch, a.cache_stride_head, a.cache_stride_token = k_cache.stride(0), k_cache.stride(1), k_cache.stride(2)
+    else:
+        a.cache_stride_batch = a.cache_stride_head = 0
+        a.cache_stride_token = D
+    desc.hidden_dim, desc.intermediate_dim, desc.rms_eps, desc.rope_theta = Hd, I, float(rms_eps), float(rope_theta)
+    w = fspad_draft_layer_weights()
+    for name in _DRAFT_LAYER_WEIGHTS:
+        setattr(w, name, _dev_ptr(weights[name], name, torch.bfloat16))
+    kv_len = _host_i32(kv_len, "kv_len")
+    n_nodes = _host_i32(n_nodes, "n_nodes")
+    if kv_len.shape != (B,) or n_nodes.shape != (B,):
+        raise ValueError("kv_len and n_nodes must have one entry per sequence")
+    if outputs is None:
+        outputs = (torch.empty((B, Nmax, Hd), dtype=torch.bfloat16, device=eta.device),
+                   torch.empty((B, Nmax, Hd), dtype=torch.bfloat16, device=eta.device),
+                   torch.empty((B, Nmax, Hkv, D), dtype=torch.bfloat16, device=eta.device),
+                   torch.empty((B, Nmax, Hkv, D), dtype=torch.bfloat16, device=eta.device))
+    f_tilde, f, k_tree, v_tree = outputs
+    if workspace is None:
+        need = fspad_draft_layer_workspace_bytes(desc, int(kv_len.max(initial=0)))
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=eta.device)
+    args = (ctypes.byref(desc), ctypes.byref(w), _dev_ptr(eta, "eta", torch.bfloat16),
+            _dev_ptr(positions, "positions", torch.int32), _dev_ptr(k_cache, "k_cache"), _dev_ptr(v_cache, "v_cache"),
+            kv_len.ctypes.data, n_nodes.ctypes.data, _dev_ptr(anc_mask, "anc_mask"),
+            _dev_ptr(k_tree, "k_tree", torch.bfloat16), _dev_ptr(v_tree, "v_tree", torch.bfloat16),
+            _dev_ptr(f_tilde, "f_tilde", torch.bfloat16), _dev_ptr(f, "f", torch.bfloat16),
+            _dev_ptr(workspace, "workspace"), workspace.numel() * workspace.element_size(), _stream_ptr(stream))
+    keep = (desc, w, eta, positions, dict(weights), k_cache, v_cache, kv_len, n_nodes, anc_mask, outputs, workspace)
+    return _issue(_lib().fspad_draft_layer, "fspad_draft_layer", args, keep, outputs, prepare)
 
 
 def fspad_draft_topk_workspace_bytes(rows: int, V: int, k: int) -> int:
