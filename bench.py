@@ -62,6 +62,11 @@ def parse_args():
                     help="also run the draft model's Feature Sampler at the top of every step: tree_depth calls over "
                          "B x top-k rows with the workload's hidden / intermediate sizes (timing only). fused = "
                          "fspad_feature_sampler; library = three library GEMMs + element-wise kernels (the comparison)")
+    ap.add_argument("--draft-layer", default=None, choices=["fused", "library"],
+                    help="also run the draft model's decoder layer (doubled MLP output) at the top of every step: "
+                         "tree_depth calls, each over a top-k-node tree per sequence on a cache of kv_len tokens, with the "
+                         "workload's head geometry and hidden / intermediate sizes (timing only; B x top-k <= 128). fused = "
+                         "fspad_draft_layer; library = library GEMMs, attention and element-wise kernels (the comparison)")
     ap.add_argument("--lm-head", default=None, choices=["fused", "unfused"],
                     help="start the acceptance from the last hidden states instead of ready-made logits. "
                          "fused = fspad_tree_accept_{greedy,sample}_lm_head (logits never written); unfused = library GEMM "
@@ -84,7 +89,8 @@ def main():
     import torch
 
     import paper_2408_15562_amd as fspad
-    from workloads import CONFIGS, GENERATOR_VERSION, gen_candidates, gen_draft_tokens, gen_logits, gen_trees, gen_uniforms
+    from workloads import (CONFIGS, GENERATOR_VERSION, gen_candidates, gen_draft_tokens, gen_logits, gen_trees, gen_uniforms,
+                           tree_depths)
 
     fspad.library_path()  # fail loudly if the HIP library is missing
     if not torch.cuda.is_available():
@@ -125,7 +131,7 @@ def main():
     for s in range(n_sets):
         layers = []
         for _ in range(cfg.layers):
-            cap = L + N if args.commit else L
+            cap = L + N if (args.commit or args.draft_layer == "library") else L   # room behind the prefix
             kc = torch.empty((B, Hkv, cap, D), device=dev, dtype=tdt).normal_(generator=gen)
             vc = torch.empty((B, Hkv, cap, D), device=dev, dtype=tdt).normal_(generator=gen)
             q = torch.empty((B, N, Hq, D), device=dev, dtype=tdt).normal_(generator=gen)
@@ -208,8 +214,7 @@ def main():
             st["topk"] = [fspad.fspad_draft_topk(draft_logits, min(cfg.tree_topk, 16), prepare=True)] * cfg.tree_depth
         st["sampler"] = []
         if args.feature_sampler:
-            Hd_fs, I_fs = {"c0": (256, 512), "c1": (4096, 11008), "c2": (4096, 14336), "c3": (6656, 17920),
-                           "c4": (8192, 28672)}[args.workload]
+            Hd_fs, I_fs = DRAFT_DIMS[args.workload]
             rows_fs = min(128, B * cfg.tree_topk)
             if "fs_w" not in sets[0]:
                 sets[0]["fs_w"] = [[torch.empty(shape, device=dev, dtype=torch.bfloat16).normal_(generator=gen).mul_(shape[1] ** -0.5)
@@ -223,6 +228,37 @@ def main():
             else:
                 st["sampler"] = [library_feature_sampler(torch, f_in, e_in, wu, wg, wd)] * cfg.tree_depth
             st["sampler_bytes"] = 2 * (3 * Hd_fs * I_fs + 3 * rows_fs * Hd_fs)
+        st["layer"] = []
+        if args.draft_layer:
+            Hd_dl, I_dl = DRAFT_DIMS[args.workload]
+            n_dl = cfg.tree_topk
+            if B * n_dl > 128 or cfg.dtype != "bf16":
+                raise SystemExit("--draft-layer: the layer takes at most 128 rows (batch x top-k) of bf16 per call")
+            if "dl_w" not in sets[0]:
+                dl_parent, dl_n = gen_trees(args.seed, B, n_dl, 2, n_dl)
+                sets[0]["dl_tree"] = (dl_parent, dl_n, torch.from_numpy(
+                    fspad.fspad_tree_build_mask(dl_parent, dl_n).view(np.int64)).to(dev),
+                    torch.from_numpy((kv_len[:, None] + tree_depths(dl_parent, dl_n)).astype(np.int32)).to(dev))
+                shapes = {"w_qkv": ((Hq + 2 * Hkv) * D, Hd_dl), "w_o": (Hd_dl, Hq * D), "w_gate": (I_dl, Hd_dl),
+                          "w_up": (I_dl, Hd_dl), "w_down": (2 * Hd_dl, I_dl)}
+                sets[0]["dl_w"] = []
+                for _ in range(2):      # two copies, used in turn: 1 GB between two uses of a weight
+                    wts = {k: torch.empty(shp, device=dev, dtype=torch.bfloat16).normal_(generator=gen).mul_(shp[1] ** -0.5)
+                           for k, shp in shapes.items()}
+                    wts["gain_attn"] = torch.ones(Hd_dl, device=dev, dtype=torch.bfloat16)
+                    wts["gain_mlp"] = torch.ones(Hd_dl, device=dev, dtype=torch.bfloat16)
+                    sets[0]["dl_w"].append(wts)
+            dl_parent, dl_n, dl_mask, dl_pos = sets[0]["dl_tree"]
+            wts = sets[0]["dl_w"][len(sets[0].get("dl_n", [])) % 2]
+            sets[0].setdefault("dl_n", []).append(1)
+            eta_in = torch.empty((B, n_dl, Hd_dl), device=dev, dtype=torch.bfloat16).normal_(generator=gen)
+            kc0, vc0 = st["layers"][0][3], st["layers"][0][4]    # the cache of the first layer stands in for the draft's
+            if args.draft_layer == "fused":
+                st["layer"] = [fspad.fspad_draft_layer(eta_in, dl_pos, wts, kc0, vc0, kv_len, dl_n, dl_mask, Hq, Hkv, D,
+                                                       prepare=True)] * cfg.tree_depth
+            else:
+                st["layer"] = [library_draft_layer(torch, eta_in, dl_pos, wts, kc0, vc0, L, dl_parent, dl_n, Hq, Hkv, D)] * cfg.tree_depth
+            st["layer_bytes"] = 2 * (sum(w_.numel() for w_ in wts.values()) + 3 * B * n_dl * Hd_dl) + 4 * B * Hkv * L * D
         st["build"] = None
         if args.tree_build:
             cands = gen_candidates(args.seed, B, cfg.tree_depth, cfg.tree_topk, V)
@@ -242,6 +278,17 @@ def main():
                 call()
         else:
             for call in st["sampler"]:
+                call()
+        if st["layer"] and timed is not None:
+            e0, e1 = event_pool.pop(), event_pool.pop()
+            e0.record()
+            st["layer"][0]()
+            e1.record()
+            layer_events.append((e0, e1))
+            for call in st["layer"][1:]:
+                call()
+        else:
+            for call in st["layer"]:
                 call()
         for call in st["topk"]:
             call()
@@ -286,8 +333,8 @@ def main():
     events = []
     event_every = args.event_every if args.event_every > 0 else max(4, steps // 12)
     # events are created ahead of the timed region (two per bracketed call)
-    event_pool = [TimingEvent(stream_handle) for _ in range(2 * 10 * (steps // event_every + 1))]
-    accept_events, sampler_events = [], []
+    event_pool = [TimingEvent(stream_handle) for _ in range(2 * 11 * (steps // event_every + 1))]
+    accept_events, sampler_events, layer_events = [], [], []
     t0 = time.perf_counter()
     # Recording an event costs the stream several microseconds, as much as a small kernel: only every
     # `event_every`-th step is bracketed, so that the timed region stays the workload's own.
@@ -356,6 +403,14 @@ def main():
         result["feature_sampler"] = {"mode": args.feature_sampler, "call_us_p50": call_s * 1e6, "calls_per_step": cfg.tree_depth,
                                      "algorithmic_bytes": fs_bytes, "gb_per_s": fs_bytes / call_s / 1e9,
                                      "hbm_frac": fs_bytes / call_s / 1e9 / HBM_PEAK_GBS}
+    if args.draft_layer:
+        dl_ms = np.array([a.elapsed_time(b) for a, b in layer_events])
+        call_s = float(np.percentile(dl_ms, 50)) * 1e-3
+        dl_bytes = sets[0]["layer_bytes"]
+        result["config"].update(draft_layer=args.draft_layer)
+        result["draft_layer"] = {"mode": args.draft_layer, "call_us_p50": call_s * 1e6, "calls_per_step": cfg.tree_depth,
+                                 "rows": B * cfg.tree_topk, "algorithmic_bytes": dl_bytes, "gb_per_s": dl_bytes / call_s / 1e9,
+                                 "hbm_frac": dl_bytes / call_s / 1e9 / HBM_PEAK_GBS}
     if args.lm_head:
         # the LM head streams its V x Hd weights once (and the B*N x Hd hidden states); per group of rows when B*N > 256
         passes = -(-B * N // 256)
@@ -369,6 +424,52 @@ def main():
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(cfg, accept, sets[0], parent, n_nodes, kv_len, args.seed)
     print(json.dumps(result))
+
+
+def library_draft_layer(torch, eta, pos, w, k_cache, v_cache, L, parent, n_nodes, Hq, Hkv, D):
+    """The comparison for --draft-layer: the same layer from library GEMMs, the library's fused attention
+    under a dense mask and element-wise kernels. The tree's keys / values are written behind the prefix
+    of the cache and the attention reads prefix and tree in one go. Temporaries come from torch's caching
+    allocator (no device allocation after the warm-up)."""
+    F = torch.nn.functional
+    B, N, Hd = eta.shape
+    dev = eta.device
+    x = eta.view(B * N, Hd)
+    half = D // 2
+    inv_freq = 10000.0 ** (-torch.arange(half, device=dev, dtype=torch.float32) * 2.0 / D)
+    ang = pos.view(B * N, 1).float() * inv_freq
+    cos, sin = ang.cos()[:, None, :], ang.sin()[:, None, :]
+    allowed = torch.zeros((B, 1, N, L + N), dtype=torch.bool, device=dev)
+    allowed[..., :L] = True
+    for b in range(B):
+        for i in range(int(n_nodes[b])):
+            j = i
+            while j >= 0:
+                allowed[b, 0, i, L + j] = True
+                j = int(parent[b, j])
+    kc = k_cache[:, :, :L + N]
+    vc = v_cache[:, :, :L + N]
+    w_down_a, w_down_b = w["w_down"][:Hd], w["w_down"][Hd:]
+
+    def rope(u):
+        a, b = u[..., :half].float(), u[..., half:].float()
+        return torch.cat([a * cos - b * sin, b * cos + a * sin], dim=-1).to(torch.bfloat16)
+
+    def call():
+        xn = F.rms_norm(x, (Hd,), w["gain_attn"], 1e-6)
+        qkv = torch.mm(xn, w["w_qkv"].t())
+        q = rope(qkv[:, :Hq * D].view(B * N, Hq, D)).view(B, N, Hq, D).transpose(1, 2)
+        k = rope(qkv[:, Hq * D:(Hq + Hkv) * D].view(B * N, Hkv, D)).view(B, N, Hkv, D)
+        v = qkv[:, (Hq + Hkv) * D:].view(B, N, Hkv, D)
+        kc[:, :, L:] = k.transpose(1, 2)
+        vc[:, :, L:] = v.transpose(1, 2)
+        a = F.scaled_dot_product_attention(q, kc, vc, attn_mask=allowed, enable_gqa=Hq != Hkv)
+        h = x + torch.mm(a.transpose(1, 2).reshape(B * N, Hq * D), w["w_o"].t())
+        hn = F.rms_norm(h, (Hd,), w["gain_mlp"], 1e-6)
+        s = F.silu(torch.mm(hn, w["w_gate"].t())) * torch.mm(hn, w["w_up"].t())
+        m = torch.mm(s, w["w_down"].t())
+        return h + m[:, :Hd], h + m[:, Hd:]
+    return call
 
 
 def library_feature_sampler(torch, f_in, e_in, wu, wg, wd):
@@ -451,6 +552,9 @@ class TimingEvent:
 # reads for a 512 MiB copy (2048 B per FETCH count, 1024 B per WRITE count on this machine); figures and
 # commands in profiles/tree_verify_traffic.txt. Above the algorithmic bytes by the partial results of units
 # that are cut across workgroups (c2, c4: 256 rows per workgroup) and by the second slab group's K/V reads.
+# hidden and intermediate size of the draft side per workload (the target model's own)
+DRAFT_DIMS = {"c0": (256, 512), "c1": (4096, 11008), "c2": (4096, 14336), "c3": (6656, 17920), "c4": (8192, 28672)}
+
 MEASURED_TRAFFIC_BYTES = {"c1": 45764473, "c2": 53890269, "c3": 456196462, "c4": 140843245}
 
 

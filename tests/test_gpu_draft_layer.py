@@ -134,3 +134,71 @@ def test_bad_arguments_are_errors():
     with pytest.raises(fspad.FspadError):        # n_nodes beyond the pitch
         fspad.fspad_draft_layer(_dev(host["eta"]), pos, w, common[0], common[1], [8], [Nmax + 1], mask, Hq, Hkv, D)
     torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("draw", range(10))
+def test_random_shape(draw):
+    """Batch, tree size, head geometry, layer sizes and prefix lengths at random (at most 128 rows)."""
+    rng = np.random.default_rng([515, draw])
+    Nmax = int(rng.integers(1, 41))
+    B = int(rng.integers(1, max(2, min(5, 128 // Nmax + 1))))
+    D = int(rng.choice([64, 128]))
+    Hkv = int(rng.choice([1, 2, 4]))
+    Hq = Hkv * int(rng.choice([1, 2, 4]))
+    while (Hq * D) % 256:
+        Hq *= 2
+    Hd, I = 256 * int(rng.integers(1, 4)), 256 * int(rng.integers(1, 7))
+    kv_len = [int(rng.choice([0, 1, 63, 64, 200, 777, 1500])) for _ in range(B)]
+    n_nodes = [int(rng.integers(1, Nmax + 1)) for _ in range(B)]
+    _run(9500 + draw, B, Nmax, Hd, I, Hq, Hkv, D, kv_len, n_nodes, cache_pad=int(rng.integers(0, 9)))
+
+
+def test_captured_layer_replays_like_eager():
+    """Feature Sampler and decoder layer of one draft step under graph capture: every replay, with
+    scrubbed outputs and workspaces, gives what the eager calls gave."""
+    import paper_2408_15562_amd as fspad
+    from workloads import gen_feature_sampler
+    B, Nmax, Hd, I, Hq, Hkv, D, L = 2, 10, 512, 1024, 4, 2, 128, 300
+    kv_len = np.array([L, L - 40], dtype=np.int32)
+    parent, n_nodes = gen_trees(4, B, Nmax, 4, 3)
+    pos = torch.from_numpy((kv_len[:, None] + tree_depths(parent, n_nodes)).astype(np.int32)).to(DEV)
+    host = gen_draft_layer(4, B, Nmax, Hd, I, Hq, Hkv, D, L)
+    mask = torch.from_numpy(fspad.fspad_tree_build_mask(parent, n_nodes).view(np.int64)).to(DEV)
+    w = {k: _dev(host[k]) for k in WEIGHTS}
+    kc, vc = _dev(host["k_cache"]), _dev(host["v_cache"])
+    f_in, e_in, wu, wg, wd = [_dev(a) for a in gen_feature_sampler(4, B * Nmax, Hd, I)]
+    eta = torch.empty((B, Nmax, Hd), dtype=torch.bfloat16, device=DEV)
+    outs = (torch.empty((B, Nmax, Hd), dtype=torch.bfloat16, device=DEV), torch.empty((B, Nmax, Hd), dtype=torch.bfloat16, device=DEV),
+            torch.empty((B, Nmax, Hkv, D), dtype=torch.bfloat16, device=DEV), torch.empty((B, Nmax, Hkv, D), dtype=torch.bfloat16, device=DEV))
+    ws_fs = torch.empty(fspad.fspad_feature_sampler_workspace_bytes(B * Nmax, Hd, I), dtype=torch.uint8, device=DEV)
+    ws = torch.empty(1 << 24, dtype=torch.uint8, device=DEV)
+
+    def step():
+        fspad.fspad_feature_sampler(f_in, e_in, wu, wg, wd, out=eta.view(B * Nmax, Hd), workspace=ws_fs)
+        fspad.fspad_draft_layer(eta, pos, w, kc, vc, kv_len, n_nodes, mask, Hq, Hkv, D, outputs=outs, workspace=ws)
+
+    used = torch.from_numpy(np.arange(Nmax)[None, :] < n_nodes[:, None]).to(DEV)
+
+    def snapshot():
+        torch.cuda.synchronize()
+        return [eta.clone()] + [t[used].clone() for t in outs]
+
+    def scrub():
+        for t in (eta, *outs):
+            t.fill_(7.0)
+        ws.random_(); ws_fs.random_()
+        torch.cuda.synchronize()
+
+    step()
+    eager = snapshot()
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        scrub()
+        with torch.cuda.graph(graph, stream=side):
+            step()
+    for _ in range(3):
+        scrub()
+        graph.replay()
+        for a, b in zip(eager, snapshot()):
+            assert torch.equal(a, b)

@@ -193,6 +193,58 @@ def test_feature_sampler_argument_checks_need_no_gpu(lib):
     assert call(ws=None) == 5
 
 
+def test_draft_layer_argument_checks_need_no_gpu(lib):
+    from paper_2408_15562_amd.binding import fspad_draft_layer_desc, fspad_draft_layer_weights
+    f = lib.fspad_draft_layer
+    fake = ctypes.c_void_p(0x1000)   # never dereferenced: every case below fails validation first
+    sz = ctypes.c_size_t
+
+    def desc(B=1, N=26, Hq=32, Hkv=32, D=128, Hd=4096, I=11008, dtype=1, eps=1e-6, theta=10000.0):
+        d = fspad_draft_layer_desc()
+        a = d.attn
+        a.batch, a.n_nodes_max, a.n_q_heads, a.n_kv_heads, a.head_dim = B, N, Hq, Hkv, D
+        a.io_dtype = a.out_dtype = dtype
+        a.cache_stride_batch, a.cache_stride_head, a.cache_stride_token = Hkv * 4096 * D, 4096 * D, D
+        d.hidden_dim, d.intermediate_dim, d.rms_eps, d.rope_theta = Hd, I, eps, theta
+        return d
+
+    need = fspad.fspad_draft_layer_workspace_bytes(desc(), 2048)
+    assert need >= 26 * 11008 * 2 + 26 * 4096 * 2 * 4
+    for bad in (desc(N=65), desc(B=3, N=64), desc(Hd=4000), desc(I=11000), desc(D=96), desc(Hq=30, Hkv=4),
+                desc(Hq=3, Hkv=3, D=64), desc(dtype=0), desc(theta=0.0), desc(eps=-1.0)):
+        assert fspad.fspad_draft_layer_workspace_bytes(bad, 2048) == 0
+
+    def weights(**over):
+        w = fspad_draft_layer_weights()
+        for name, _ in fspad_draft_layer_weights._fields_:
+            setattr(w, name, over.get(name, 0x1000))
+        return w
+
+    kv = (ctypes.c_int32 * 1)(2048)
+    nn = (ctypes.c_int32 * 1)(26)
+
+    def call(d=None, w=None, eta=fake, pos=fake, kv_len=kv, n_nodes=nn, out=fake, ws=fake, wsb=need):
+        d = d if d is not None else desc()
+        w = w if w is not None else weights()
+        return f(ctypes.byref(d), ctypes.byref(w), eta, pos, fake, fake, kv_len, n_nodes, fake, fake, fake, out, fake,
+                 ws, sz(wsb), None)
+
+    assert call(eta=None) == 1
+    assert call(pos=None) == 1
+    assert call(out=None) == 1
+    assert call(w=weights(w_down=None)) == 1
+    assert call(w=weights(gain_mlp=None)) == 1
+    assert call(d=desc(dtype=0)) == 4
+    assert call(d=desc(Hd=4000)) == 2
+    assert call(d=desc(B=3, N=64)) == 2                    # more than 128 rows
+    assert call(eta=ctypes.c_void_p(0x1008)) == 2
+    assert call(w=weights(w_o=0x1004)) == 2
+    assert call(n_nodes=(ctypes.c_int32 * 1)(27)) == 2
+    assert call(kv_len=(ctypes.c_int32 * 1)(-1)) == 2
+    assert call(wsb=need - 1) == 5
+    assert call(ws=None) == 5
+
+
 def test_topk_argument_checks_need_no_gpu(lib):
     f = lib.fspad_draft_topk
     fake = ctypes.c_void_p(0x1000)   # never dereferenced: every case below fails validation first
