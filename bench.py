@@ -73,6 +73,7 @@ def parse_args():
                          "to bf16 logits, widened to fp32, then fspad_tree_accept_{greedy,sample} (the comparison)")
     ap.add_argument("--lm-stagger", type=int, default=None, help=argparse.SUPPRESS)
     ap.add_argument("--sampler-target", type=int, default=0, help=argparse.SUPPRESS)
+    ap.add_argument("--sampler-stagger", type=int, default=None, help=argparse.SUPPRESS)
     ap.add_argument("--short-stream", type=int, default=None, help=argparse.SUPPRESS)
     ap.add_argument("--hidden-dim", type=int, default=None, help="hidden size for --lm-head (default: the workload's model)")
     ap.add_argument("--seed", type=int, default=2024)
@@ -165,6 +166,9 @@ def main():
     if args.sampler_target:
         import ctypes
         ctypes.CDLL(fspad.library_path()).fspad_debug_set_sampler_target(args.sampler_target)
+    if args.sampler_stagger is not None:
+        import ctypes
+        ctypes.CDLL(fspad.library_path()).fspad_debug_set_sampler_stagger(args.sampler_stagger)
     if args.lm_stagger is not None:
         import ctypes
         ctypes.CDLL(fspad.library_path()).fspad_debug_set_lm_head_stagger(args.lm_stagger)

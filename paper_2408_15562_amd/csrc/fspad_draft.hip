@@ -34,7 +34,8 @@ using fspad_detail::bf16x8;
 using fspad_detail::f32x4;
 using fspad_detail::StreamGemm;
 
-constexpr int kWaves = 8;            // wavefronts per workgroup, 16 weight rows each
+constexpr int kWaves = 8;            // wavefronts per workgroup, 16 weight rows each (with 4, twice the
+                                     // workgroups: 166 against 158 us for the decoder layer at 4096 / 11008)
 constexpr int kSliceRows = 128;      // weight rows per workgroup
 constexpr int kChunkK = 256;         // k is cut in multiples of this
 constexpr int kMaxRows = 128;        // rows of X per call
@@ -45,6 +46,7 @@ struct PartialGemmParams {
   float* part;             // [problem][split][rows][N] fp32
   int32_t rows, N, K;
   int32_t n_slices, n_splits, chunks_per_split;
+  int32_t stagger;         // stages by which consecutive slices are offset along k (0: none)
 };
 
 // Workgroup (slice, split) of problem blockIdx.y: X[rows, k range] . W[slice rows, k range]^T
@@ -64,7 +66,13 @@ __global__ __launch_bounds__(64 * kWaves, 2) void partial_gemm_kernel(const Part
   f32x4 acc[MT][1];
 #pragma unroll
   for (int t = 0; t < MT; ++t) acc[t][0] = f32x4{0.f, 0.f, 0.f, 0.f};
-  G::run(xs, p.x[prob] + k_off, p.w[prob] + k_off, (size_t)p.K * 2, p.rows, p.N, 0, v0, chunks * (kChunkK / 32), 0, acc);
+  // consecutive slices start their k range p.stagger stages apart and wrap around: workgroups that
+  // run at the same time then read different parts of their rows, instead of crowding the few
+  // memory channels that one k offset of rows a power-of-two pitch apart maps to
+  const int n_steps = chunks * (kChunkK / 32);
+  const int n_stages = n_steps / SPS;
+  const int first_step = (p.stagger && n_steps % SPS == 0) ? (int)(((unsigned)slice * (unsigned)p.stagger) % (unsigned)n_stages) * SPS : 0;
+  G::run(xs, p.x[prob] + k_off, p.w[prob] + k_off, (size_t)p.K * 2, p.rows, p.N, 0, v0, n_steps, first_step, acc);
 
   // lane (n, g) holds columns v0 + 4g .. +3 of row 16t + n
   float* out = p.part + ((size_t)prob * p.n_splits + split) * p.rows * p.N;
@@ -162,6 +170,54 @@ __global__ __launch_bounds__(256) void rms_norm_kernel(const RmsNormParams p) {
   }
 }
 
+// Output projection's epilogue and the normalisation that follows it, one row per workgroup:
+// h = sum of the partials + residual (rounded to bf16, written), then out = rmsnorm(h) of the rounded
+// values, as rms_norm_kernel would compute it from h. Every thread re-reads only what it wrote.
+struct CombineNormParams {
+  const float* part;       // [split][rows][Hd]
+  const char* residual;    // [rows][Hd] bf16
+  const char* gain;        // [Hd] bf16
+  char* h;                 // [rows][Hd] bf16
+  char* out;               // [rows][Hd] bf16
+  int32_t rows, Hd, n_splits;
+  float eps;
+};
+__global__ __launch_bounds__(256) void combine_norm_kernel(const CombineNormParams p) {
+  typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+  __shared__ float wave_sum[4];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const size_t row_at = (size_t)blockIdx.x * p.Hd, plane = (size_t)p.rows * p.Hd;
+  const int n_quads = p.Hd / 4;
+  float ss = 0.f;
+  for (int q = tid; q < n_quads; q += 256) {
+    f32x4 a = {0.f, 0.f, 0.f, 0.f};
+    for (int s = 0; s < p.n_splits; ++s) a += *reinterpret_cast<const f32x4*>(p.part + (size_t)s * plane + row_at + 4 * q);
+    const bf16x4 r = *reinterpret_cast<const bf16x4*>(p.residual + (row_at + 4 * q) * 2);
+    bf16x4 o;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      o[i] = (__bf16)(a[i] + (float)r[i]);
+      const float t = (float)o[i];
+      ss += t * t;
+    }
+    *reinterpret_cast<bf16x4*>(p.h + (row_at + 4 * q) * 2) = o;
+  }
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) ss += __shfl_xor(ss, off);
+  if (lane == 0) wave_sum[wave] = ss;
+  __syncthreads();
+  const float total = (wave_sum[0] + wave_sum[1]) + (wave_sum[2] + wave_sum[3]);
+  const float inv = 1.0f / sqrtf(total / (float)p.Hd + p.eps);
+  for (int q = tid; q < n_quads; q += 256) {
+    const bf16x4 hv = *reinterpret_cast<const bf16x4*>(p.h + (row_at + 4 * q) * 2);
+    const bf16x4 gv = *reinterpret_cast<const bf16x4*>(p.gain + 8 * q);
+    bf16x4 o;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) o[i] = (__bf16)((float)hv[i] * inv * (float)gv[i]);
+    *reinterpret_cast<bf16x4*>(p.out + (row_at + 4 * q) * 2) = o;
+  }
+}
+
 // Sum of the q / k / v projection's partials, rotary encoding of the query and key heads, scatter
 // into the attention's layouts. A thread owns four columns of the first half of one head of one
 // row and the four partner columns of the second half: entry i of the first half and entry i of
@@ -232,7 +288,11 @@ void plan_splits(int n_slices, int n_chunks, int problems, int& n_splits, int& c
   n_splits = (n_chunks + chunks_per_split - 1) / chunks_per_split;
 }
 
-void launch_partial(const PartialGemmParams& g, int problems, hipStream_t stream) {
+// measured at 4096 / 11008, 4 rows: Feature Sampler 78.4 us without the rotation, 72.1 / 72.4 / 71.5 us with
+// 1 / 3 / 5 stages between consecutive slices; decoder layer 164.5 against 158.5 / 158.3 / 158.8 us
+int g_stagger = 3;
+void launch_partial(PartialGemmParams g, int problems, hipStream_t stream) {
+  g.stagger = g_stagger;
   const dim3 grid((unsigned)(g.n_slices * g.n_splits), (unsigned)problems);
   if (g.rows <= 16) hipLaunchKernelGGL((partial_gemm_kernel<1, 16>), grid, dim3(512), 0, stream, g);
   else if (g.rows <= 32) hipLaunchKernelGGL((partial_gemm_kernel<2, 16>), grid, dim3(512), 0, stream, g);
@@ -260,6 +320,7 @@ Plan make_plan(int rows, int Hd, int I) {
 
 // Experiment knob (not part of the declared interface): workgroups a projector launch aims for.
 extern "C" void fspad_debug_set_sampler_target(int32_t wgs) { g_target_wgs = wgs < 1 ? 1 : wgs; }
+extern "C" void fspad_debug_set_sampler_stagger(int32_t stages) { g_stagger = stages < 0 ? 0 : stages; }
 
 extern "C" size_t fspad_feature_sampler_workspace_bytes(int32_t rows, int32_t hidden_dim, int32_t intermediate_dim) {
   if (rows < 1 || rows > kMaxRows || hidden_dim < kChunkK || hidden_dim % kChunkK || intermediate_dim < kChunkK ||
@@ -478,9 +539,14 @@ extern "C" fspad_status fspad_draft_layer(const fspad_draft_layer_desc* desc, co
   // h = eta + W_o attn
   if ((st = linear_partials(attn, nullptr, w->w_o, nullptr, 1, pl.rows, pl.Hd, pl.attn_n, pl.o, part, stream)) != FSPAD_OK)
     return st;
-  if ((st = combine<1>(part, eta, h, nullptr, pl.rows, pl.Hd, pl.o.splits, stream)) != FSPAD_OK) return st;
-  // MLP with the doubled down projection; both halves start from h
-  if ((st = rms_norm(h, w->gain_mlp, xn, pl.rows, pl.Hd, desc->rms_eps, stream)) != FSPAD_OK) return st;
+  // and its normalised form for the MLP (whose doubled down projection adds both halves to h)
+  {
+    CombineNormParams c{};
+    c.part = part; c.residual = static_cast<const char*>(eta); c.gain = static_cast<const char*>(w->gain_mlp);
+    c.h = h; c.out = xn; c.rows = pl.rows; c.Hd = pl.Hd; c.n_splits = pl.o.splits; c.eps = desc->rms_eps;
+    hipLaunchKernelGGL(combine_norm_kernel, dim3((unsigned)pl.rows), dim3(256), 0, stream, c);
+    if (hipGetLastError() != hipSuccess) return FSPAD_ERR_HIP;
+  }
   if ((st = linear_partials(xn, xn, w->w_up, w->w_gate, 2, pl.rows, pl.I, pl.Hd, pl.up, part, stream)) != FSPAD_OK) return st;
   if ((st = combine<0>(part, nullptr, s, nullptr, pl.rows, pl.I, pl.up.splits, stream)) != FSPAD_OK) return st;
   if ((st = linear_partials(s, nullptr, w->w_down, nullptr, 1, pl.rows, 2 * pl.Hd, pl.I, pl.down, part, stream)) != FSPAD_OK)
