@@ -172,7 +172,8 @@ __global__ __launch_bounds__(256) void rms_norm_kernel(const RmsNormParams p) {
 
 // Output projection's epilogue and the normalisation that follows it, one row per workgroup:
 // h = sum of the partials + residual (rounded to bf16, written), then out = rmsnorm(h) of the rounded
-// values, as rms_norm_kernel would compute it from h. Every thread re-reads only what it wrote.
+// values, as rms_norm_kernel would compute it from h. Every thread re-reads only what it wrote. 1024
+// threads: with the few rows of a draft step the row's loads must all be in flight at once.
 struct CombineNormParams {
   const float* part;       // [split][rows][Hd]
   const char* residual;    // [rows][Hd] bf16
@@ -182,14 +183,14 @@ struct CombineNormParams {
   int32_t rows, Hd, n_splits;
   float eps;
 };
-__global__ __launch_bounds__(256) void combine_norm_kernel(const CombineNormParams p) {
+__global__ __launch_bounds__(1024) void combine_norm_kernel(const CombineNormParams p) {
   typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
-  __shared__ float wave_sum[4];
+  __shared__ float wave_sum[16];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const size_t row_at = (size_t)blockIdx.x * p.Hd, plane = (size_t)p.rows * p.Hd;
   const int n_quads = p.Hd / 4;
   float ss = 0.f;
-  for (int q = tid; q < n_quads; q += 256) {
+  for (int q = tid; q < n_quads; q += 1024) {
     f32x4 a = {0.f, 0.f, 0.f, 0.f};
     for (int s = 0; s < p.n_splits; ++s) a += *reinterpret_cast<const f32x4*>(p.part + (size_t)s * plane + row_at + 4 * q);
     const bf16x4 r = *reinterpret_cast<const bf16x4*>(p.residual + (row_at + 4 * q) * 2);
@@ -206,9 +207,11 @@ __global__ __launch_bounds__(256) void combine_norm_kernel(const CombineNormPara
   for (int off = 32; off > 0; off >>= 1) ss += __shfl_xor(ss, off);
   if (lane == 0) wave_sum[wave] = ss;
   __syncthreads();
-  const float total = (wave_sum[0] + wave_sum[1]) + (wave_sum[2] + wave_sum[3]);
+  float total = 0.f;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) total += wave_sum[i];
   const float inv = 1.0f / sqrtf(total / (float)p.Hd + p.eps);
-  for (int q = tid; q < n_quads; q += 256) {
+  for (int q = tid; q < n_quads; q += 1024) {
     const bf16x4 hv = *reinterpret_cast<const bf16x4*>(p.h + (row_at + 4 * q) * 2);
     const bf16x4 gv = *reinterpret_cast<const bf16x4*>(p.gain + 8 * q);
     bf16x4 o;
@@ -544,7 +547,7 @@ extern "C" fspad_status fspad_draft_layer(const fspad_draft_layer_desc* desc, co
     CombineNormParams c{};
     c.part = part; c.residual = static_cast<const char*>(eta); c.gain = static_cast<const char*>(w->gain_mlp);
     c.h = h; c.out = xn; c.rows = pl.rows; c.Hd = pl.Hd; c.n_splits = pl.o.splits; c.eps = desc->rms_eps;
-    hipLaunchKernelGGL(combine_norm_kernel, dim3((unsigned)pl.rows), dim3(256), 0, stream, c);
+    hipLaunchKernelGGL(combine_norm_kernel, dim3((unsigned)pl.rows), dim3(1024), 0, stream, c);
     if (hipGetLastError() != hipSuccess) return FSPAD_ERR_HIP;
   }
   if ((st = linear_partials(xn, xn, w->w_up, w->w_gate, 2, pl.rows, pl.I, pl.Hd, pl.up, part, stream)) != FSPAD_OK) return st;
