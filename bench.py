@@ -74,6 +74,9 @@ def parse_args():
     ap.add_argument("--lm-stagger", type=int, default=None, help=argparse.SUPPRESS)
     ap.add_argument("--sampler-target", type=int, default=0, help=argparse.SUPPRESS)
     ap.add_argument("--sampler-stagger", type=int, default=None, help=argparse.SUPPRESS)
+    ap.add_argument("--packed-weights", action="store_true",
+                    help="with --feature-sampler fused / --draft-layer fused: the weight matrices are repacked once into "
+                         "the tile order of fspad_pack_weight (same results, faster streaming)")
     ap.add_argument("--short-stream", type=int, default=None, help=argparse.SUPPRESS)
     ap.add_argument("--hidden-dim", type=int, default=None, help="hidden size for --lm-head (default: the workload's model)")
     ap.add_argument("--seed", type=int, default=2024)
@@ -223,12 +226,15 @@ def main():
             if "fs_w" not in sets[0]:
                 sets[0]["fs_w"] = [[torch.empty(shape, device=dev, dtype=torch.bfloat16).normal_(generator=gen).mul_(shape[1] ** -0.5)
                                     for shape in ((I_fs, Hd_fs), (I_fs, Hd_fs), (Hd_fs, I_fs))] for _ in range(2)]
+                if args.packed_weights and args.feature_sampler == "fused":
+                    sets[0]["fs_w"] = [[fspad.fspad_pack_weight(w_) for w_ in ws_] for ws_ in sets[0]["fs_w"]]
             wu, wg, wd = sets[0]["fs_w"][len(sets[0].get("fs_n", [])) % 2]
             sets[0].setdefault("fs_n", []).append(1)
             f_in = torch.empty((rows_fs, Hd_fs), device=dev, dtype=torch.bfloat16).normal_(generator=gen)
             e_in = torch.empty((rows_fs, Hd_fs), device=dev, dtype=torch.bfloat16).normal_(generator=gen)
             if args.feature_sampler == "fused":
-                st["sampler"] = [fspad.fspad_feature_sampler(f_in, e_in, wu, wg, wd, prepare=True)] * cfg.tree_depth
+                st["sampler"] = [fspad.fspad_feature_sampler(f_in, e_in, wu, wg, wd, prepare=True,
+                                                             packed=args.packed_weights)] * cfg.tree_depth
             else:
                 st["sampler"] = [library_feature_sampler(torch, f_in, e_in, wu, wg, wd)] * cfg.tree_depth
             st["sampler_bytes"] = 2 * (3 * Hd_fs * I_fs + 3 * rows_fs * Hd_fs)
@@ -249,6 +255,8 @@ def main():
                 for _ in range(2):      # two copies, used in turn: 1 GB between two uses of a weight
                     wts = {k: torch.empty(shp, device=dev, dtype=torch.bfloat16).normal_(generator=gen).mul_(shp[1] ** -0.5)
                            for k, shp in shapes.items()}
+                    if args.packed_weights and args.draft_layer == "fused":
+                        wts = {k: fspad.fspad_pack_weight(w_) for k, w_ in wts.items()}
                     wts["gain_attn"] = torch.ones(Hd_dl, device=dev, dtype=torch.bfloat16)
                     wts["gain_mlp"] = torch.ones(Hd_dl, device=dev, dtype=torch.bfloat16)
                     sets[0]["dl_w"].append(wts)
@@ -259,7 +267,7 @@ def main():
             kc0, vc0 = st["layers"][0][3], st["layers"][0][4]    # the cache of the first layer stands in for the draft's
             if args.draft_layer == "fused":
                 st["layer"] = [fspad.fspad_draft_layer(eta_in, dl_pos, wts, kc0, vc0, kv_len, dl_n, dl_mask, Hq, Hkv, D,
-                                                       prepare=True)] * cfg.tree_depth
+                                                       prepare=True, packed=args.packed_weights)] * cfg.tree_depth
             else:
                 st["layer"] = [library_draft_layer(torch, eta_in, dl_pos, wts, kc0, vc0, L, dl_parent, dl_n, Hq, Hkv, D)] * cfg.tree_depth
             st["layer_bytes"] = 2 * (sum(w_.numel() for w_ in wts.values()) + 3 * B * n_dl * Hd_dl) + 4 * B * Hkv * L * D
@@ -403,7 +411,7 @@ def main():
         fs_ms = np.array([a.elapsed_time(b) for a, b in sampler_events])
         call_s = float(np.percentile(fs_ms, 50)) * 1e-3
         fs_bytes = sets[0]["sampler_bytes"]
-        result["config"].update(feature_sampler=args.feature_sampler)
+        result["config"].update(feature_sampler=args.feature_sampler, packed_weights=bool(args.packed_weights))
         result["feature_sampler"] = {"mode": args.feature_sampler, "call_us_p50": call_s * 1e6, "calls_per_step": cfg.tree_depth,
                                      "algorithmic_bytes": fs_bytes, "gb_per_s": fs_bytes / call_s / 1e9,
                                      "hbm_frac": fs_bytes / call_s / 1e9 / HBM_PEAK_GBS}
@@ -411,7 +419,7 @@ def main():
         dl_ms = np.array([a.elapsed_time(b) for a, b in layer_events])
         call_s = float(np.percentile(dl_ms, 50)) * 1e-3
         dl_bytes = sets[0]["layer_bytes"]
-        result["config"].update(draft_layer=args.draft_layer)
+        result["config"].update(draft_layer=args.draft_layer, packed_weights=bool(args.packed_weights))
         result["draft_layer"] = {"mode": args.draft_layer, "call_us_p50": call_s * 1e6, "calls_per_step": cfg.tree_depth,
                                  "rows": B * cfg.tree_topk, "algorithmic_bytes": dl_bytes, "gb_per_s": dl_bytes / call_s / 1e9,
                                  "hbm_frac": dl_bytes / call_s / 1e9 / HBM_PEAK_GBS}

@@ -397,3 +397,19 @@ def draft_layer(eta, positions, w_qkv, w_o, w_gate, w_up, w_down, gain_attn, gai
     k = np.where(used[..., None, None], k, 0.0)
     v = np.where(used[..., None, None], v, 0.0)
     return f_tilde, f, k, v
+
+
+def pack_weight(w):
+    """Tile order of a row-major [N,K] matrix (a storage format of the library's draft-side weights,
+    not a step of the paper): tiles of 16 rows x 32 columns, tile rows one after another, within a
+    tile row along k; inside a tile, slot n + 16 g holds w[16 t + n, 32 s + 8 g : 32 s + 8 g + 8].
+    Rows past N in the last tile row are zeros.  Returns a flat array of ceil(N/16)*16*K entries."""
+    w = np.asarray(w)
+    N, K = w.shape
+    assert K % 32 == 0
+    T, S = (N + 15) // 16, K // 32
+    padded = np.zeros((T * 16, K), dtype=w.dtype)
+    padded[:N] = w
+    tiles = padded.reshape(T, 16, S, 4, 8)               # [t, n, s, g, j]
+    out = tiles.transpose(0, 2, 3, 1, 4)                 # [t, s, g, n, j]: slot n + 16 g
+    return out.reshape(-1)

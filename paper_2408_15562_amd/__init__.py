@@ -18,6 +18,8 @@ from .binding import (  # noqa: F401
     fspad_feature_sampler_workspace_bytes,
     fspad_draft_topk_workspace_bytes,
     fspad_kv_commit,
+    fspad_pack_weight,
+    fspad_packed_weight_bytes,
     fspad_status_string,
     fspad_tree_accept_greedy,
     fspad_tree_accept_greedy_lm_head,

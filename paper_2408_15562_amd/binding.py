@@ -28,7 +28,7 @@ EXPORTS = ("fspad_tree_attn_workspace_bytes", "fspad_tree_attn_set_workgroups", 
            "fspad_tree_accept_lm_head_workspace_bytes", "fspad_tree_accept_greedy_lm_head",
            "fspad_tree_accept_sample_lm_head",
            "fspad_kv_commit", "fspad_feature_sampler_workspace_bytes", "fspad_feature_sampler",
-           "fspad_draft_layer_workspace_bytes", "fspad_draft_layer",
+           "fspad_draft_layer_workspace_bytes", "fspad_draft_layer", "fspad_packed_weight_bytes", "fspad_pack_weight",
            "fspad_draft_topk_workspace_bytes", "fspad_draft_topk", "fspad_tree_build", "fspad_tree_build_mask",
            "fspad_tree_validate", "fspad_status_string")
 
@@ -50,7 +50,7 @@ class fspad_attn_desc(ctypes.Structure):
 
 class fspad_draft_layer_desc(ctypes.Structure):
     _fields_ = [("attn", fspad_attn_desc), ("hidden_dim", ctypes.c_int32), ("intermediate_dim", ctypes.c_int32),
-                ("rms_eps", ctypes.c_float), ("rope_theta", ctypes.c_float)]
+                ("rms_eps", ctypes.c_float), ("rope_theta", ctypes.c_float), ("weights_packed", ctypes.c_int32)]
 
 
 class fspad_draft_layer_weights(ctypes.Structure):
@@ -99,6 +99,10 @@ def _lib():
         lib.fspad_feature_sampler_workspace_bytes.argtypes = [i32, i32, i32]
         lib.fspad_feature_sampler.restype = ctypes.c_int
         lib.fspad_feature_sampler.argtypes = [i32, i32, i32, vp, vp, vp, vp, vp, i32, vp, vp, sz, vp]
+        lib.fspad_packed_weight_bytes.restype = sz
+        lib.fspad_packed_weight_bytes.argtypes = [i32, i32]
+        lib.fspad_pack_weight.restype = ctypes.c_int
+        lib.fspad_pack_weight.argtypes = [i32, i32, vp, vp, vp]
         lib.fspad_draft_layer_workspace_bytes.restype = sz
         lib.fspad_draft_layer_workspace_bytes.argtypes = [ctypes.POINTER(fspad_draft_layer_desc), i32]
         lib.fspad_draft_layer.restype = ctypes.c_int
@@ -414,11 +418,32 @@ def fspad_feature_sampler_workspace_bytes(rows: int, hidden_dim: int, intermedia
     return int(_lib().fspad_feature_sampler_workspace_bytes(rows, hidden_dim, intermediate_dim))
 
 
+def fspad_packed_weight_bytes(n_rows: int, k: int) -> int:
+    return int(_lib().fspad_packed_weight_bytes(int(n_rows), int(k)))
+
+
+def fspad_pack_weight(w: torch.Tensor, stream=None) -> torch.Tensor:
+    """Repack a contiguous [N,K] bf16 device matrix into the tile order the draft-side projections stream
+    fastest (pass the result with packed=True). Returns a new tensor of the same shape (N a multiple of 16;
+    its bytes are the tiles, not rows) or, when N is not a multiple of 16, a flat bf16 tensor."""
+    N, K = w.shape
+    if not w.is_contiguous() or w.dtype != torch.bfloat16:
+        raise ValueError("w must be a contiguous bf16 matrix")
+    need = fspad_packed_weight_bytes(N, K)
+    if need == 0:
+        raise FspadError(2, "fspad_pack_weight")
+    out = torch.empty(need // 2, dtype=torch.bfloat16, device=w.device)
+    _check(_lib().fspad_pack_weight(N, K, _dev_ptr(w, "w"), _dev_ptr(out, "packed"), _stream_ptr(stream)), "fspad_pack_weight")
+    return out.view(N, K) if N % 16 == 0 else out
+
+
 def fspad_feature_sampler(f: torch.Tensor, e: torch.Tensor, w_up: torch.Tensor, w_gate: torch.Tensor,
                           w_down: torch.Tensor, residual: bool = True, out: Optional[torch.Tensor] = None,
-                          workspace: Optional[torch.Tensor] = None, stream=None, prepare: bool = False):
-    """f, e [rows,Hd]; w_up, w_gate [I,Hd]; w_down [Hd,I]; all contiguous bf16 device tensors. Returns
-    eta [rows,Hd] bf16; with prepare=True a PreparedCall."""
+                          workspace: Optional[torch.Tensor] = None, stream=None, prepare: bool = False,
+                          packed: bool = False):
+    """f, e [rows,Hd]; w_up, w_gate [I,Hd]; w_down [Hd,I]; all contiguous bf16 device tensors (packed=True:
+    the three weight matrices went through fspad_pack_weight). Returns eta [rows,Hd] bf16; with
+    prepare=True a PreparedCall."""
     rows, Hd = f.shape
     I = w_up.shape[0]
     for name, t, shape in (("f", f, (rows, Hd)), ("e", e, (rows, Hd)), ("w_up", w_up, (I, Hd)), ("w_gate", w_gate, (I, Hd)),
@@ -431,7 +456,8 @@ def fspad_feature_sampler(f: torch.Tensor, e: torch.Tensor, w_up: torch.Tensor, 
         workspace = torch.empty(max(16, fspad_feature_sampler_workspace_bytes(rows, Hd, I)), dtype=torch.uint8, device=f.device)
     args = (rows, Hd, I, _dev_ptr(f, "f", torch.bfloat16), _dev_ptr(e, "e", torch.bfloat16),
             _dev_ptr(w_up, "w_up", torch.bfloat16), _dev_ptr(w_gate, "w_gate", torch.bfloat16),
-            _dev_ptr(w_down, "w_down", torch.bfloat16), 1 if residual else 0, _dev_ptr(out, "eta", torch.bfloat16),
+            _dev_ptr(w_down, "w_down", torch.bfloat16), (1 if residual else 0) | (2 if packed else 0),
+            _dev_ptr(out, "eta", torch.bfloat16),
             _dev_ptr(workspace, "workspace"), workspace.numel() * workspace.element_size(), _stream_ptr(stream))
     return _issue(_lib().fspad_feature_sampler, "fspad_feature_sampler", args, (f, e, w_up, w_gate, w_down, workspace),
                   out, prepare)
@@ -447,10 +473,11 @@ _DRAFT_LAYER_WEIGHTS = ("w_qkv", "w_o", "w_gate", "w_up", "w_down", "gain_attn",
 def fspad_draft_layer(eta: torch.Tensor, positions: torch.Tensor, weights: dict, k_cache: Optional[torch.Tensor],
                       v_cache: Optional[torch.Tensor], kv_len, n_nodes, anc_mask: torch.Tensor, n_q_heads: int,
                       n_kv_heads: int, head_dim: int, rms_eps: float = 1e-6, rope_theta: float = 10000.0,
-                      outputs=None, workspace: Optional[torch.Tensor] = None, stream=None, prepare: bool = False):
+                      outputs=None, workspace: Optional[torch.Tensor] = None, stream=None, prepare: bool = False,
+                      packed: bool = False):
     """eta [B,Nmax,Hd] bf16; positions [B,Nmax] int32 (device); weights: dict of contiguous bf16 device
     tensors w_qkv [(Hq+2Hkv)D,Hd], w_o [Hd,HqD], w_gate, w_up [I,Hd], w_down [2Hd,I], gain_attn, gain_mlp
-    [Hd]; k_cache, v_cache [B,Hkv,Lcap,D] views of the draft's own cache (or None); kv_len, n_nodes HOST
+    [Hd] (packed=True: the five matrices went through fspad_pack_weight); k_cache, v_cache [B,Hkv,Lcap,D] views of the draft's own cache (or None); kv_len, n_nodes HOST
     int32 [B]; anc_mask device 64-bit [B,Nmax]. Returns (f_tilde, f, k_tree, v_tree): [B,Nmax,Hd] twice and
     [B,Nmax,Hkv,D] twice, bf16 (pass them as `outputs` to reuse buffers); with prepare=True a PreparedCall."""
     B, Nmax, Hd = eta.shape
@@ -482,6 +509,7 @@ def fspad_draft_layer(eta: torch.Tensor, positions: torch.Tensor, weights: dict,
         a.cache_stride_batch = a.cache_stride_head = 0
         a.cache_stride_token = D
     desc.hidden_dim, desc.intermediate_dim, desc.rms_eps, desc.rope_theta = Hd, I, float(rms_eps), float(rope_theta)
+    desc.weights_packed = 1 if packed else 0
     w = fspad_draft_layer_weights()
     for name in _DRAFT_LAYER_WEIGHTS:
         setattr(w, name, _dev_ptr(weights[name], name, torch.bfloat16))

@@ -47,12 +47,13 @@ struct PartialGemmParams {
   int32_t rows, N, K;
   int32_t n_slices, n_splits, chunks_per_split;
   int32_t stagger;         // stages by which consecutive slices are offset along k (0: none)
+  int32_t packed;          // w is in the tile order of fspad_pack_weight
 };
 
 // Workgroup (slice, split) of problem blockIdx.y: X[rows, k range] . W[slice rows, k range]^T
-template <int MT, int SPS>
+template <int MT, int SPS, bool PACKED = false>
 __global__ __launch_bounds__(64 * kWaves, 2) void partial_gemm_kernel(const PartialGemmParams p) {
-  typedef StreamGemm<MT, SPS, 16, kWaves, 1> G;
+  typedef StreamGemm<MT, SPS, 16, kWaves, 1, PACKED> G;
   __shared__ __attribute__((aligned(16))) char xs[2 * G::kStageBytes];
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int n = lane & 15, g = lane >> 4;
@@ -72,7 +73,7 @@ __global__ __launch_bounds__(64 * kWaves, 2) void partial_gemm_kernel(const Part
   const int n_steps = chunks * (kChunkK / 32);
   const int n_stages = n_steps / SPS;
   const int first_step = (p.stagger && n_steps % SPS == 0) ? (int)(((unsigned)slice * (unsigned)p.stagger) % (unsigned)n_stages) * SPS : 0;
-  G::run(xs, p.x[prob] + k_off, p.w[prob] + k_off, (size_t)p.K * 2, p.rows, p.N, 0, v0, n_steps, first_step, acc);
+  G::run(xs, p.x[prob] + k_off, p.w[prob] + (PACKED ? k_off * 16 : k_off), (size_t)p.K * 2, p.rows, p.N, 0, v0, n_steps, first_step, acc);
 
   // lane (n, g) holds columns v0 + 4g .. +3 of row 16t + n
   float* out = p.part + ((size_t)prob * p.n_splits + split) * p.rows * p.N;
@@ -297,6 +298,13 @@ int g_stagger = 3;
 void launch_partial(PartialGemmParams g, int problems, hipStream_t stream) {
   g.stagger = g_stagger;
   const dim3 grid((unsigned)(g.n_slices * g.n_splits), (unsigned)problems);
+  if (g.packed) {
+    if (g.rows <= 16) hipLaunchKernelGGL((partial_gemm_kernel<1, 16, true>), grid, dim3(512), 0, stream, g);
+    else if (g.rows <= 32) hipLaunchKernelGGL((partial_gemm_kernel<2, 16, true>), grid, dim3(512), 0, stream, g);
+    else if (g.rows <= 64) hipLaunchKernelGGL((partial_gemm_kernel<4, 16, true>), grid, dim3(512), 0, stream, g);
+    else hipLaunchKernelGGL((partial_gemm_kernel<8, 8, true>), grid, dim3(512), 0, stream, g);
+    return;
+  }
   if (g.rows <= 16) hipLaunchKernelGGL((partial_gemm_kernel<1, 16>), grid, dim3(512), 0, stream, g);
   else if (g.rows <= 32) hipLaunchKernelGGL((partial_gemm_kernel<2, 16>), grid, dim3(512), 0, stream, g);
   else if (g.rows <= 64) hipLaunchKernelGGL((partial_gemm_kernel<4, 16>), grid, dim3(512), 0, stream, g);
@@ -335,8 +343,10 @@ extern "C" size_t fspad_feature_sampler_workspace_bytes(int32_t rows, int32_t hi
 
 extern "C" fspad_status fspad_feature_sampler(int32_t rows, int32_t hidden_dim, int32_t intermediate_dim, const void* f,
                                               const void* e, const void* w_up, const void* w_gate, const void* w_down,
-                                              int32_t residual, void* eta, void* workspace, size_t workspace_bytes,
+                                              int32_t flags, void* eta, void* workspace, size_t workspace_bytes,
                                               void* hip_stream) {
+  if (flags & ~(FSPAD_SAMPLER_RESIDUAL | FSPAD_WEIGHTS_PACKED)) return FSPAD_ERR_SHAPE;
+  const int residual = flags & FSPAD_SAMPLER_RESIDUAL, packed = (flags & FSPAD_WEIGHTS_PACKED) != 0;
   if (!f || !e || !w_up || !w_gate || !w_down || !eta) return FSPAD_ERR_NULL;
   if (rows < 1 || rows > kMaxRows) return FSPAD_ERR_SHAPE;
   if (hidden_dim < kChunkK || hidden_dim % kChunkK || hidden_dim > (1 << 16)) return FSPAD_ERR_SHAPE;
@@ -357,6 +367,7 @@ extern "C" fspad_status fspad_feature_sampler(int32_t rows, int32_t hidden_dim, 
   g.w[0] = static_cast<const char*>(w_up); g.w[1] = static_cast<const char*>(w_gate);
   g.part = part; g.rows = rows; g.N = intermediate_dim; g.K = hidden_dim;
   g.n_slices = pl.slices_up; g.n_splits = pl.splits_up; g.chunks_per_split = pl.cps_up;
+  g.packed = packed;
   launch_partial(g, 2, stream);
   if (hipGetLastError() != hipSuccess) return FSPAD_ERR_HIP;
   CombineParams c{};
@@ -416,6 +427,7 @@ bool layer_shape_ok(const fspad_draft_layer_desc* d) {
   const int64_t attn_n = (int64_t)a.n_q_heads * a.head_dim;
   if (attn_n % kChunkK || attn_n > (1 << 16)) return false;
   if (!(d->rms_eps >= 0.0f) || !(d->rope_theta > 0.0f)) return false;
+  if (d->weights_packed != 0 && d->weights_packed != 1) return false;
   return true;
 }
 
@@ -449,12 +461,13 @@ LayerPlan make_layer_plan(const fspad_draft_layer_desc* d, int32_t max_kv_len) {
 }
 
 fspad_status linear_partials(const void* x0, const void* x1, const void* w0, const void* w1, int problems, int rows, int N,
-                             int K, const Stage& st, float* part, hipStream_t stream) {
+                             int K, const Stage& st, float* part, bool packed, hipStream_t stream) {
   PartialGemmParams g{};
   g.x[0] = static_cast<const char*>(x0); g.x[1] = static_cast<const char*>(x1);
   g.w[0] = static_cast<const char*>(w0); g.w[1] = static_cast<const char*>(w1);
   g.part = part; g.rows = rows; g.N = N; g.K = K;
   g.n_slices = st.slices; g.n_splits = st.splits; g.chunks_per_split = st.cps;
+  g.packed = packed;
   launch_partial(g, problems, stream);
   return hipGetLastError() == hipSuccess ? FSPAD_OK : FSPAD_ERR_HIP;
 }
@@ -511,6 +524,7 @@ extern "C" fspad_status fspad_draft_layer(const fspad_draft_layer_desc* desc, co
   hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
   const LayerPlan pl = make_layer_plan(desc, max_kv);
   const fspad_attn_desc& a = desc->attn;
+  const bool packed = desc->weights_packed != 0;
 
   char* at = static_cast<char*>(workspace);
   char* xn = at; at += pl.xn_bytes;            // normalised input of a projection, [rows][Hd] bf16
@@ -524,7 +538,7 @@ extern "C" fspad_status fspad_draft_layer(const fspad_draft_layer_desc* desc, co
   fspad_status st;
   // q, k, v = rotary(W_qkv rmsnorm(eta))
   if ((st = rms_norm(eta, w->gain_attn, xn, pl.rows, pl.Hd, desc->rms_eps, stream)) != FSPAD_OK) return st;
-  if ((st = linear_partials(xn, nullptr, w->w_qkv, nullptr, 1, pl.rows, pl.qkv_n, pl.Hd, pl.qkv, part, stream)) != FSPAD_OK)
+  if ((st = linear_partials(xn, nullptr, w->w_qkv, nullptr, 1, pl.rows, pl.qkv_n, pl.Hd, pl.qkv, part, packed, stream)) != FSPAD_OK)
     return st;
   {
     QkvRopeParams r{};
@@ -540,7 +554,7 @@ extern "C" fspad_status fspad_draft_layer(const fspad_draft_layer_desc* desc, co
                        pl.attn_ws_bytes, hip_stream);
   if (st != FSPAD_OK) return st;
   // h = eta + W_o attn
-  if ((st = linear_partials(attn, nullptr, w->w_o, nullptr, 1, pl.rows, pl.Hd, pl.attn_n, pl.o, part, stream)) != FSPAD_OK)
+  if ((st = linear_partials(attn, nullptr, w->w_o, nullptr, 1, pl.rows, pl.Hd, pl.attn_n, pl.o, part, packed, stream)) != FSPAD_OK)
     return st;
   // and its normalised form for the MLP (whose doubled down projection adds both halves to h)
   {
@@ -550,9 +564,44 @@ extern "C" fspad_status fspad_draft_layer(const fspad_draft_layer_desc* desc, co
     hipLaunchKernelGGL(combine_norm_kernel, dim3((unsigned)pl.rows), dim3(1024), 0, stream, c);
     if (hipGetLastError() != hipSuccess) return FSPAD_ERR_HIP;
   }
-  if ((st = linear_partials(xn, xn, w->w_up, w->w_gate, 2, pl.rows, pl.I, pl.Hd, pl.up, part, stream)) != FSPAD_OK) return st;
+  if ((st = linear_partials(xn, xn, w->w_up, w->w_gate, 2, pl.rows, pl.I, pl.Hd, pl.up, part, packed, stream)) != FSPAD_OK) return st;
   if ((st = combine<0>(part, nullptr, s, nullptr, pl.rows, pl.I, pl.up.splits, stream)) != FSPAD_OK) return st;
-  if ((st = linear_partials(s, nullptr, w->w_down, nullptr, 1, pl.rows, 2 * pl.Hd, pl.I, pl.down, part, stream)) != FSPAD_OK)
+  if ((st = linear_partials(s, nullptr, w->w_down, nullptr, 1, pl.rows, 2 * pl.Hd, pl.I, pl.down, part, packed, stream)) != FSPAD_OK)
     return st;
   return combine<2>(part, h, f_tilde, f, pl.rows, 2 * pl.Hd, pl.down.splits, stream);
+}
+
+// ------------------------------------------------------------------------------------------------
+// Weight repacking: row-major [N][K] -> tile order (see stream_gemm.h). One thread per 16 bytes.
+namespace {
+__global__ __launch_bounds__(256) void pack_weight_kernel(const char* w, char* packed, int32_t n_rows, int32_t K) {
+  const int steps = K / 32;
+  const size_t total = (size_t)((n_rows + 15) / 16) * steps * 64;
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= total) return;
+  const int lane = (int)(i & 63), n = lane & 15, g = lane >> 4;
+  const size_t tile_step = i >> 6;
+  const int step = (int)(tile_step % steps);
+  const size_t row = (tile_step / steps) * 16 + n;
+  bf16x8 v = {0, 0, 0, 0, 0, 0, 0, 0};
+  if (row < (size_t)n_rows) v = *reinterpret_cast<const bf16x8*>(w + (row * K + 32 * step + 8 * g) * 2);
+  *reinterpret_cast<bf16x8*>(packed + i * 16) = v;
+}
+}  // namespace
+
+extern "C" size_t fspad_packed_weight_bytes(int32_t n_rows, int32_t k) {
+  if (n_rows < 1 || k < 32 || k % 32) return 0;
+  return (size_t)((n_rows + 15) / 16) * 16 * (size_t)k * 2;
+}
+
+extern "C" fspad_status fspad_pack_weight(int32_t n_rows, int32_t k, const void* w, void* packed, void* hip_stream) {
+  if (!w || !packed) return FSPAD_ERR_NULL;
+  if (n_rows < 1 || k < 32 || k % 32) return FSPAD_ERR_SHAPE;
+  if ((((uintptr_t)w) | ((uintptr_t)packed)) & 15) return FSPAD_ERR_SHAPE;
+  const size_t threads = fspad_packed_weight_bytes(n_rows, k) / 16;
+  if ((threads + 255) / 256 > 0x7fffffffu) return FSPAD_ERR_SHAPE;
+  hipLaunchKernelGGL(pack_weight_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0,
+                     reinterpret_cast<hipStream_t>(hip_stream), static_cast<const char*>(w), static_cast<char*>(packed),
+                     n_rows, k);
+  return hipGetLastError() == hipSuccess ? FSPAD_OK : FSPAD_ERR_HIP;
 }

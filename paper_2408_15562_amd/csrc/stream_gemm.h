@@ -26,7 +26,12 @@ typedef __attribute__((ext_vector_type(4))) float f32x4;
 // weight tiles per wavefront. x_base / w_base point at the first k of the range, rows are row_bytes
 // apart; the range is n_steps k-steps (a multiple of 8) and is walked from first_step on, wrapping
 // around (first_step a multiple of SPS; 0 unless n_steps is a multiple of SPS). xs: 2 stages of LDS.
-template <int MT, int SPS, int kRing, int WAVES, int VT>
+// PACKED: W is stored tile by tile instead of row by row -- the 16 rows x 32 k of one operand are
+// 1 KB in lane order (lane (n, g) at byte 16 * (n + 16 g)), the k-steps of a 16-row tile follow one
+// another, then the next 16 rows. A wavefront's request is then one contiguous KB instead of sixteen
+// 64-byte pieces a row pitch apart; row_bytes is still 2 K, v0 a multiple of 16, and w_base points at
+// the first k-step of the range within tile row 0.
+template <int MT, int SPS, int kRing, int WAVES, int VT, bool PACKED = false>
 struct StreamGemm {
   static constexpr int kStageK = 32 * SPS;
   static constexpr int kRowBytes = kStageK * 2;                        // 256, 512 or 1024
@@ -44,7 +49,9 @@ struct StreamGemm {
     // weight rows of this lane (rows past the vocabulary are clamped; their columns are never taken)
     const char* wrow[VT];
 #pragma unroll
-    for (int nv = 0; nv < VT; ++nv) wrow[nv] = w_base + (size_t)min(v0 + 16 * nv + n, n_wrows - 1) * row_bytes + g * 16;
+    for (int nv = 0; nv < VT; ++nv)
+      wrow[nv] = PACKED ? w_base + (size_t)min(v0 + 16 * nv, n_wrows - 16) * row_bytes + lane * 16
+                        : w_base + (size_t)min(v0 + 16 * nv + n, n_wrows - 1) * row_bytes + g * 16;
 
     // hidden-state copies of this wavefront: LDS slot s of row r receives the row's 16-byte chunk
     // s ^ (r & 15) of the stage's k range (chunks past the end of the row are clamped: never used)
@@ -87,7 +94,7 @@ struct StreamGemm {
     auto load_w = [&](int nv, int ks) {
       int step = min(ks, n_steps - 1) + first_step;
       step -= step >= n_steps ? n_steps : 0;
-      return *reinterpret_cast<const bf16x8*>(wrow[nv] + (size_t)step * 64);
+      return *reinterpret_cast<const bf16x8*>(wrow[nv] + (size_t)step * (PACKED ? 1024 : 64));
     };
 
     // The weights are requested kRing k-steps ahead, every operand register being requested again as

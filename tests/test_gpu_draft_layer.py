@@ -202,3 +202,24 @@ def test_captured_layer_replays_like_eager():
         graph.replay()
         for a, b in zip(eager, snapshot()):
             assert torch.equal(a, b)
+
+
+@pytest.mark.parametrize("B,Nmax,Hd,I,Hq,Hkv,D,L", [(1, 9, 256, 512, 4, 2, 64, 37), (2, 40, 512, 1280, 4, 4, 128, 300),
+                                                  (1, 26, 4096, 11008, 32, 32, 128, 2048)])
+def test_packed_weights_give_the_same_bits(B, Nmax, Hd, I, Hq, Hkv, D, L):
+    import paper_2408_15562_amd as fspad
+    kv_len = np.full(B, L, dtype=np.int32)
+    parent, n_nodes = gen_trees(21, B, Nmax, 6, 8)
+    pos = torch.from_numpy((kv_len[:, None] + tree_depths(parent, n_nodes)).astype(np.int32)).to(DEV)
+    host = gen_draft_layer(21, B, Nmax, Hd, I, Hq, Hkv, D, L)
+    mask = torch.from_numpy(fspad.fspad_tree_build_mask(parent, n_nodes).view(np.int64)).to(DEV)
+    w = {k: _dev(host[k]) for k in WEIGHTS}
+    wp = {k: (fspad.fspad_pack_weight(v) if v.dim() == 2 else v) for k, v in w.items()}
+    common = (_dev(host["k_cache"]), _dev(host["v_cache"]), kv_len, n_nodes, mask, Hq, Hkv, D)
+    eta = _dev(host["eta"])
+    plain = fspad.fspad_draft_layer(eta, pos, w, *common)
+    packed = fspad.fspad_draft_layer(eta, pos, wp, *common, packed=True)
+    torch.cuda.synchronize()
+    used = torch.from_numpy(np.arange(Nmax)[None, :] < n_nodes[:, None]).to(DEV)
+    for a, b in zip(plain, packed):
+        assert torch.equal(a[used], b[used])

@@ -69,3 +69,24 @@ def test_missing_workspace_is_an_error():
     host = [_dev(a) for a in gen_feature_sampler(3, 4, 256, 256)]
     with pytest.raises(fspad.FspadError):
         fspad.fspad_feature_sampler(*host, workspace=torch.empty(16, dtype=torch.uint8, device=DEV))
+
+
+@pytest.mark.parametrize("N,K", [(16, 32), (40, 96), (256, 256), (1000, 512), (4096, 1024)])
+def test_pack_weight_is_the_tile_order(N, K):
+    import paper_2408_15562_amd as fspad
+    from workloads import round_to_bf16
+    w = round_to_bf16(np.random.default_rng(N + K).standard_normal((N, K), dtype=np.float32))
+    packed = fspad.fspad_pack_weight(_dev(w))
+    torch.cuda.synchronize()
+    assert np.array_equal(packed.float().cpu().numpy().reshape(-1), oracle.pack_weight(w))
+
+
+@pytest.mark.parametrize("rows,Hd,I", [(4, 256, 512), (17, 1024, 2816), (40, 1280, 3328), (100, 768, 256), (10, 4096, 11008)])
+def test_packed_weights_give_the_same_bits(rows, Hd, I):
+    """The tile order changes where a weight lies, not the order of the sums."""
+    import paper_2408_15562_amd as fspad
+    f, e, wu, wg, wd = [_dev(a) for a in gen_feature_sampler(300 + rows, rows, Hd, I)]
+    plain = fspad.fspad_feature_sampler(f, e, wu, wg, wd)
+    packed = fspad.fspad_feature_sampler(f, e, *[fspad.fspad_pack_weight(w) for w in (wu, wg, wd)], packed=True)
+    torch.cuda.synchronize()
+    assert torch.equal(plain, packed)

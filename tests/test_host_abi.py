@@ -191,6 +191,24 @@ def test_feature_sampler_argument_checks_need_no_gpu(lib):
     assert call(x=ctypes.c_void_p(0x1008)) == 2
     assert call(wsb=need - 1) == 5
     assert call(ws=None) == 5
+    # flags: residual = 1, packed weights = 2; anything else is refused
+    assert f(i32(10), i32(4096), i32(11008), fake, fake, fake, fake, fake, i32(4), fake, fake, sz(need), None) == 2
+    assert f(i32(10), i32(4096), i32(11008), fake, fake, fake, fake, fake, i32(3), fake, None, sz(need), None) == 5
+
+
+def test_pack_weight_argument_checks_need_no_gpu(lib):
+    fake = ctypes.c_void_p(0x1000)
+    i32 = ctypes.c_int32
+    assert fspad.fspad_packed_weight_bytes(4096, 11008) == 4096 * 11008 * 2
+    assert fspad.fspad_packed_weight_bytes(40, 96) == 48 * 96 * 2          # last tile row padded
+    assert fspad.fspad_packed_weight_bytes(40, 100) == 0
+    assert fspad.fspad_packed_weight_bytes(0, 96) == 0
+    f = lib.fspad_pack_weight
+    assert f(i32(40), i32(96), None, fake, None) == 1
+    assert f(i32(40), i32(96), fake, None, None) == 1
+    assert f(i32(40), i32(100), fake, fake, None) == 2
+    assert f(i32(0), i32(96), fake, fake, None) == 2
+    assert f(i32(40), i32(96), ctypes.c_void_p(0x1008), fake, None) == 2
 
 
 def test_draft_layer_argument_checks_need_no_gpu(lib):
@@ -199,19 +217,20 @@ def test_draft_layer_argument_checks_need_no_gpu(lib):
     fake = ctypes.c_void_p(0x1000)   # never dereferenced: every case below fails validation first
     sz = ctypes.c_size_t
 
-    def desc(B=1, N=26, Hq=32, Hkv=32, D=128, Hd=4096, I=11008, dtype=1, eps=1e-6, theta=10000.0):
+    def desc(B=1, N=26, Hq=32, Hkv=32, D=128, Hd=4096, I=11008, dtype=1, eps=1e-6, theta=10000.0, packed=0):
         d = fspad_draft_layer_desc()
         a = d.attn
         a.batch, a.n_nodes_max, a.n_q_heads, a.n_kv_heads, a.head_dim = B, N, Hq, Hkv, D
         a.io_dtype = a.out_dtype = dtype
         a.cache_stride_batch, a.cache_stride_head, a.cache_stride_token = Hkv * 4096 * D, 4096 * D, D
         d.hidden_dim, d.intermediate_dim, d.rms_eps, d.rope_theta = Hd, I, eps, theta
+        d.weights_packed = packed
         return d
 
     need = fspad.fspad_draft_layer_workspace_bytes(desc(), 2048)
     assert need >= 26 * 11008 * 2 + 26 * 4096 * 2 * 4
     for bad in (desc(N=65), desc(B=3, N=64), desc(Hd=4000), desc(I=11000), desc(D=96), desc(Hq=30, Hkv=4),
-                desc(Hq=3, Hkv=3, D=64), desc(dtype=0), desc(theta=0.0), desc(eps=-1.0)):
+                desc(Hq=3, Hkv=3, D=64), desc(dtype=0), desc(theta=0.0), desc(eps=-1.0), desc(packed=2)):
         assert fspad.fspad_draft_layer_workspace_bytes(bad, 2048) == 0
 
     def weights(**over):

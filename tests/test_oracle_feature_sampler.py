@@ -51,3 +51,21 @@ def test_closed_gate_leaves_the_residual_and_open_gate_is_linear():
     a = oracle.feature_sampler(f, e, wu, wg, wd)
     b = oracle.feature_sampler(3.0 * f, e, wu, wg, wd)
     np.testing.assert_allclose(b, 3.0 * a, rtol=1e-12)
+
+
+def test_tile_order_of_the_weights_element_by_element():
+    """The packed order against its definition, one element at a time, on a matrix whose entries
+    name their own position; a ragged last tile row is padded with zeros."""
+    N, K = 40, 96
+    w = (np.arange(N)[:, None] * 1000 + np.arange(K)[None, :]).astype(np.float64)
+    p = oracle.pack_weight(w)
+    assert p.shape == (48 * K,)
+    S = K // 32
+    for t in range(3):
+        for s_ in range(S):
+            for n in range(16):
+                for g in range(4):
+                    for j in range(8):
+                        row, col = 16 * t + n, 32 * s_ + 8 * g + j
+                        got = p[((t * S + s_) * 64 + n + 16 * g) * 8 + j]
+                        assert got == (w[row, col] if row < N else 0.0)
