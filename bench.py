@@ -75,7 +75,7 @@ def parse_args():
     ap.add_argument("--sampler-target", type=int, default=0, help=argparse.SUPPRESS)
     ap.add_argument("--sampler-stagger", type=int, default=None, help=argparse.SUPPRESS)
     ap.add_argument("--packed-weights", action="store_true",
-                    help="with --feature-sampler fused / --draft-layer fused: the weight matrices are repacked once into "
+                    help="with --feature-sampler fused / --draft-layer fused / --lm-head fused: the weight matrices are repacked once into "
                          "the tile order of fspad_pack_weight (same results, faster streaming)")
     ap.add_argument("--short-stream", type=int, default=None, help=argparse.SUPPRESS)
     ap.add_argument("--hidden-dim", type=int, default=None, help="hidden size for --lm-head (default: the workload's model)")
@@ -156,6 +156,9 @@ def main():
         # pass through the caches, so a few copies are rotated to keep them out of the 256 MB last-level cache
         w_copies = [torch.empty((V, hidden_dim), device=dev, dtype=torch.bfloat16).normal_(generator=gen)
                     .mul_(3.0 / hidden_dim ** 0.5) for _ in range(min(n_sets, 4))]
+        lm_packed = bool(args.packed_weights and args.lm_head == "fused")
+        if lm_packed:
+            w_copies = [fspad.fspad_pack_weight(w_).reshape(-1) for w_ in w_copies]
         for i, st in enumerate(sets):
             st["w"] = w_copies[i % len(w_copies)]
             st["hidden"] = torch.empty((B, N, hidden_dim), device=dev, dtype=torch.bfloat16).normal_(generator=gen)
@@ -200,10 +203,11 @@ def main():
                                             desc=desc, prepare=True) for (q, kt, vt, kc, vc, out) in st["layers"]]
         if args.lm_head == "fused" and accept == "greedy":
             st["accept"] = fspad.fspad_tree_accept_greedy_lm_head(st["hidden"], st["w"], st["tokens"], parent_d, n_nodes_d,
-                                                                  outputs=acc_out, prepare=True)
+                                                                  outputs=acc_out, prepare=True, packed=lm_packed, vocab=V)
         elif args.lm_head == "fused":
             st["accept"] = fspad.fspad_tree_accept_sample_lm_head(st["hidden"], st["w"], st["tokens"], parent_d, n_nodes_d,
-                                                                  cfg.temperature, st["uniforms"], outputs=acc_out, prepare=True)
+                                                                  cfg.temperature, st["uniforms"], outputs=acc_out, prepare=True,
+                                                                  packed=lm_packed, vocab=V)
         elif args.lm_head == "unfused":
             st["accept"] = unfused_lm_head_accept(torch, fspad, st, parent_d, n_nodes_d, acc_out, ws_acc, accept,
                                                   cfg.temperature)
@@ -428,7 +432,7 @@ def main():
         passes = -(-B * N // 256)
         head_bytes = 2 * hidden_dim * (V + B * N)
         call_s = float(np.percentile(accept_ms, 50)) * 1e-3
-        result["config"].update(lm_head=args.lm_head, hidden_dim=hidden_dim)
+        result["config"].update(lm_head=args.lm_head, hidden_dim=hidden_dim, packed_weights=bool(args.packed_weights))
         result["lm_head"] = {"mode": args.lm_head, "call_us_p50": call_s * 1e6, "algorithmic_bytes": head_bytes,
                              "weight_passes": passes if args.lm_head == "fused" else 1,
                              "gb_per_s": head_bytes / call_s / 1e9, "hbm_frac": head_bytes / call_s / 1e9 / HBM_PEAK_GBS,

@@ -201,6 +201,8 @@ fspad_status fspad_tree_accept_sample(int32_t B, int32_t Nmax, int32_t V,
  *                slots are read but never used)
  *   lm_head      dev [V,hidden_dim] bf16, contiguous, 16-byte aligned (the weight matrix as the
  *                models store it: one row per token)
+ *   flags        0, or FSPAD_WEIGHTS_PACKED (defined below): lm_head went through
+ *                fspad_pack_weight(V, hidden_dim, ...) and is in tile order (same results, faster)
  *   hidden_dim   multiple of 256, 256..65536
  *   draft_tokens, parent, n_nodes, path, path_len, tokens, n_tokens: as for fspad_tree_accept_greedy
  *   node_target  dev [B,Nmax] i32 out, may be NULL: target[b,i] (-1 in unused slots)
@@ -218,7 +220,7 @@ fspad_status fspad_tree_accept_sample(int32_t B, int32_t Nmax, int32_t V,
  */
 size_t fspad_tree_accept_lm_head_workspace_bytes(int32_t B, int32_t Nmax, int32_t V);
 fspad_status fspad_tree_accept_greedy_lm_head(int32_t B, int32_t Nmax, int32_t V, int32_t hidden_dim,
-                                              const void* hidden, const void* lm_head,
+                                              const void* hidden, const void* lm_head, int32_t flags,
                                               const int32_t* draft_tokens, const int32_t* parent,
                                               const int32_t* n_nodes,
                                               int32_t* path, int32_t* path_len,
@@ -247,7 +249,7 @@ fspad_status fspad_tree_accept_greedy_lm_head(int32_t B, int32_t Nmax, int32_t V
  * Errors as for fspad_tree_accept_sample; never synchronises, allocates nothing.
  */
 fspad_status fspad_tree_accept_sample_lm_head(int32_t B, int32_t Nmax, int32_t V, int32_t hidden_dim,
-                                              const void* hidden, const void* lm_head,
+                                              const void* hidden, const void* lm_head, int32_t flags,
                                               const int32_t* draft_tokens, const int32_t* parent,
                                               const int32_t* n_nodes,
                                               float temperature, const float* uniforms,
@@ -284,8 +286,8 @@ fspad_status fspad_kv_commit(const fspad_attn_desc* desc, const void* k_tree, co
                              int32_t* kv_len_out, void* hip_stream);
 
 /*
- * Tile order for the weights of the draft-side projections (an option of fspad_feature_sampler and
- * fspad_draft_layer; no passage of the paper: it is a storage format). A row-major [n_rows][k] bf16
+ * Tile order for the weights of the skinny projections (an option of fspad_feature_sampler,
+ * fspad_draft_layer and the LM-head acceptance; no passage of the paper: it is a storage format). A row-major [n_rows][k] bf16
  * matrix is cut into tiles of 16 rows x 32 columns, stored tile row by tile row, within a tile row
  * along k; the 1 KB of a tile holds, at byte 16 * (n + 16 g), the eight values
  * w[16 t + n][32 s + 8 g .. + 7] (t: tile row, s: tile along k, n in 0..15, g in 0..3). Rows past
@@ -298,7 +300,8 @@ fspad_status fspad_kv_commit(const fspad_attn_desc* desc, const void* k_tree, co
  *   both 16-byte aligned and not overlapping. Done once per weight matrix, ahead of time.
  */
 #define FSPAD_SAMPLER_RESIDUAL 1 /* fspad_feature_sampler flags: add the residual f */
-#define FSPAD_WEIGHTS_PACKED 2   /* fspad_feature_sampler flags: w_up, w_gate, w_down are in tile order */
+#define FSPAD_WEIGHTS_PACKED 2   /* flags of fspad_feature_sampler and of the LM-head acceptance: the weight
+                                    matrices are in tile order */
 size_t fspad_packed_weight_bytes(int32_t n_rows, int32_t k);
 fspad_status fspad_pack_weight(int32_t n_rows, int32_t k, const void* w, void* packed, void* hip_stream);
 

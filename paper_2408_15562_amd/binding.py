@@ -88,10 +88,10 @@ def _lib():
         lib.fspad_tree_accept_lm_head_workspace_bytes.restype = sz
         lib.fspad_tree_accept_lm_head_workspace_bytes.argtypes = [i32, i32, i32]
         lib.fspad_tree_accept_greedy_lm_head.restype = ctypes.c_int
-        lib.fspad_tree_accept_greedy_lm_head.argtypes = [i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp,
+        lib.fspad_tree_accept_greedy_lm_head.argtypes = [i32, i32, i32, i32, vp, vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp,
                                                          vp, sz, vp]
         lib.fspad_tree_accept_sample_lm_head.restype = ctypes.c_int
-        lib.fspad_tree_accept_sample_lm_head.argtypes = [i32, i32, i32, i32, vp, vp, vp, vp, vp, ctypes.c_float, vp,
+        lib.fspad_tree_accept_sample_lm_head.argtypes = [i32, i32, i32, i32, vp, vp, i32, vp, vp, vp, ctypes.c_float, vp,
                                                          vp, vp, vp, vp, vp, sz, vp]
         lib.fspad_kv_commit.restype = ctypes.c_int
         lib.fspad_kv_commit.argtypes = [ctypes.POINTER(fspad_attn_desc), vp, vp, vp, vp, i32, vp, vp, vp, vp, vp]
@@ -317,18 +317,31 @@ def fspad_tree_accept_lm_head_workspace_bytes(B: int, Nmax: int, V: int) -> int:
     return int(_lib().fspad_tree_accept_lm_head_workspace_bytes(B, Nmax, V))
 
 
+def _lm_head_shapes(hidden, lm_head, packed, vocab):
+    if hidden.dim() != 3 or not hidden.is_contiguous() or not lm_head.is_contiguous():
+        raise ValueError("hidden must be a contiguous [B,Nmax,Hd] tensor and lm_head contiguous")
+    B, Nmax, Hd = hidden.shape
+    if packed and (vocab is not None or lm_head.dim() != 2):
+        if vocab is None:
+            raise ValueError("a flat packed lm_head needs `vocab`")
+        V = int(vocab)
+        if lm_head.numel() != (V + 15) // 16 * 16 * Hd:
+            raise ValueError("packed lm_head does not have ceil(V/16)*16*Hd entries")
+        return B, Nmax, Hd, V
+    if lm_head.dim() != 2 or lm_head.shape[1] != Hd:
+        raise ValueError("lm_head must be a [V,Hd] tensor with the hidden size of `hidden`")
+    return B, Nmax, Hd, lm_head.shape[0]
+
+
 def fspad_tree_accept_greedy_lm_head(hidden: torch.Tensor, lm_head: torch.Tensor, draft_tokens: torch.Tensor,
                                      parent: torch.Tensor, n_nodes: torch.Tensor, outputs=None, node_outputs=None,
-                                     workspace: Optional[torch.Tensor] = None, stream=None, prepare: bool = False):
-    """hidden [B,Nmax,Hd] bf16, lm_head [V,Hd] bf16, both contiguous on the device. Returns
+                                     workspace: Optional[torch.Tensor] = None, stream=None, prepare: bool = False,
+                                     packed: bool = False, vocab: Optional[int] = None):
+    """hidden [B,Nmax,Hd] bf16, lm_head [V,Hd] bf16, both contiguous on the device (packed=True: lm_head
+    is what fspad_pack_weight returned; give `vocab` when that is a flat tensor). Returns
     (path, path_len, tokens, n_tokens, node_target [B,Nmax] i32, node_top [B,Nmax] f32); with
     prepare=True a PreparedCall."""
-    if hidden.dim() != 3 or lm_head.dim() != 2 or not hidden.is_contiguous() or not lm_head.is_contiguous():
-        raise ValueError("hidden must be a contiguous [B,Nmax,Hd] tensor and lm_head a contiguous [V,Hd] tensor")
-    B, Nmax, Hd = hidden.shape
-    V = lm_head.shape[0]
-    if lm_head.shape[1] != Hd:
-        raise ValueError("hidden and lm_head disagree on the hidden size")
+    B, Nmax, Hd, V = _lm_head_shapes(hidden, lm_head, packed, vocab)
     for name, t in (("draft_tokens", draft_tokens), ("parent", parent), ("n_nodes", n_nodes)):
         if t.dtype != torch.int32 or not t.is_contiguous():
             raise ValueError(f"{name} must be a contiguous int32 device tensor")
@@ -341,6 +354,7 @@ def fspad_tree_accept_greedy_lm_head(hidden: torch.Tensor, lm_head: torch.Tensor
                         torch.empty((B, Nmax), dtype=torch.float32, device=hidden.device))
     node_target, node_top = node_outputs
     args = (B, Nmax, V, Hd, _dev_ptr(hidden, "hidden", torch.bfloat16), _dev_ptr(lm_head, "lm_head", torch.bfloat16),
+            2 if packed else 0,
             _dev_ptr(draft_tokens, "draft_tokens"), _dev_ptr(parent, "parent"), _dev_ptr(n_nodes, "n_nodes"),
             _dev_ptr(path, "path"), _dev_ptr(path_len, "path_len"), _dev_ptr(tokens, "tokens"),
             _dev_ptr(n_tokens, "n_tokens"), _dev_ptr(node_target, "node_target", torch.int32),
@@ -354,15 +368,12 @@ def fspad_tree_accept_greedy_lm_head(hidden: torch.Tensor, lm_head: torch.Tensor
 def fspad_tree_accept_sample_lm_head(hidden: torch.Tensor, lm_head: torch.Tensor, draft_tokens: torch.Tensor,
                                      parent: torch.Tensor, n_nodes: torch.Tensor, temperature: float,
                                      uniforms: torch.Tensor, outputs=None, workspace: Optional[torch.Tensor] = None,
-                                     stream=None, prepare: bool = False):
+                                     stream=None, prepare: bool = False, packed: bool = False,
+                                     vocab: Optional[int] = None):
     """hidden [B,Nmax,Hd] bf16, lm_head [V,Hd] bf16, uniforms fp32 [B,2,Nmax], all contiguous on the
-    device. Returns (path, path_len, tokens, n_tokens); with prepare=True a PreparedCall."""
-    if hidden.dim() != 3 or lm_head.dim() != 2 or not hidden.is_contiguous() or not lm_head.is_contiguous():
-        raise ValueError("hidden must be a contiguous [B,Nmax,Hd] tensor and lm_head a contiguous [V,Hd] tensor")
-    B, Nmax, Hd = hidden.shape
-    V = lm_head.shape[0]
-    if lm_head.shape[1] != Hd:
-        raise ValueError("hidden and lm_head disagree on the hidden size")
+    device (packed / vocab as for the greedy call). Returns (path, path_len, tokens, n_tokens); with
+    prepare=True a PreparedCall."""
+    B, Nmax, Hd, V = _lm_head_shapes(hidden, lm_head, packed, vocab)
     for name, t in (("draft_tokens", draft_tokens), ("parent", parent), ("n_nodes", n_nodes)):
         if t.dtype != torch.int32 or not t.is_contiguous():
             raise ValueError(f"{name} must be a contiguous int32 device tensor")
@@ -373,6 +384,7 @@ def fspad_tree_accept_sample_lm_head(hidden: torch.Tensor, lm_head: torch.Tensor
                                 device=hidden.device)
     path, path_len, tokens, n_tokens = _accept_outputs(B, Nmax, hidden.device, outputs)
     args = (B, Nmax, V, Hd, _dev_ptr(hidden, "hidden", torch.bfloat16), _dev_ptr(lm_head, "lm_head", torch.bfloat16),
+            2 if packed else 0,
             _dev_ptr(draft_tokens, "draft_tokens"), _dev_ptr(parent, "parent"), _dev_ptr(n_nodes, "n_nodes"),
             float(temperature), _dev_ptr(uniforms, "uniforms"),
             _dev_ptr(path, "path"), _dev_ptr(path_len, "path_len"), _dev_ptr(tokens, "tokens"),

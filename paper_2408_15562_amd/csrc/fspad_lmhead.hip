@@ -37,7 +37,7 @@ constexpr int kWalkThreads = 1024;
 
 struct LmHeadParams {
   const char* hidden;   // [M][K] bf16
-  const char* weights;  // [V][K] bf16
+  const char* weights;  // [V][K] bf16, row-major or (PACKED) in the tile order of fspad_pack_weight
   float* part_max;      // greedy: [n_slices][M]; sampling: [M][n_slices]
   int32_t* part_idx;    // greedy: [n_slices][M]
   double* part_sum;     // sampling: [M][n_slices], sum of exp((l - part_max) / T) over the slice
@@ -63,10 +63,10 @@ __device__ __forceinline__ void take_better(float& v, int& i, float ov, int oi) 
 // product but measured slower at 256 rows: 178 against 152 us on a 32000 x 6656 head).
 // MODE 0: per slice and row (max, first argmax) for the greedy walk. MODE 1: per slice and row
 // (max, sum of exponentials) and the logits of the draft tokens, for the sampling walk.
-template <int MT, int SPS, int kRing, int WAVES, int VT, int MODE>
+template <int MT, int SPS, int kRing, int WAVES, int VT, int MODE, bool PACKED>
 __global__ __launch_bounds__(64 * WAVES, (WAVES == 8 ? 2 : 1)) void lm_head_argmax_kernel(const LmHeadParams p) {
   static_assert(WAVES * VT * 16 == kVocabPerWg, "workgroup shape");
-  typedef StreamGemm<MT, SPS, kRing, WAVES, VT> G;
+  typedef StreamGemm<MT, SPS, kRing, WAVES, VT, PACKED> G;
   constexpr int kStageBytes = G::kStageBytes;
   __shared__ __attribute__((aligned(16))) char xs[2 * kStageBytes];
   __shared__ float red_val[WAVES][MT * 16];
@@ -86,7 +86,8 @@ __global__ __launch_bounds__(64 * WAVES, (WAVES == 8 ? 2 : 1)) void lm_head_argm
   for (int t = 0; t < MT; ++t)
 #pragma unroll
     for (int nv = 0; nv < VT; ++nv) acc[t][nv] = f32x4{0.f, 0.f, 0.f, 0.f};
-  G::run(xs, p.hidden, p.weights, (size_t)p.K * 2, p.M, p.V, row0, v0, n_steps, first_step, acc);
+  // (the tile order pads the vocabulary to whole tiles of 16 rows)
+  G::run(xs, p.hidden, p.weights, (size_t)p.K * 2, p.M, PACKED ? (p.V + 15) / 16 * 16 : p.V, row0, v0, n_steps, first_step, acc);
 
   if constexpr (MODE == 1) {
     // The stages are dead: the workgroup's 16*MT x 128 logits go there, as fp32, row by row
@@ -278,7 +279,7 @@ struct LmSampleWalkParams {
   double* row_sum;           // [B*Nmax]: sum of exp((l - row_max) / T) over the row
   const float* node_logit;   // [B*Nmax]
   const char* hidden;        // [B*Nmax][K] bf16
-  const char* weights;       // [V][K] bf16
+  const char* weights;       // [V][K] bf16, row-major or in tile order (packed)
   const int32_t* draft_tokens;
   const int32_t* parent;
   const int32_t* n_nodes;
@@ -289,6 +290,7 @@ struct LmSampleWalkParams {
   int32_t* n_tokens;
   double inv_temperature;
   int32_t B, Nmax, V, K, n_slices;
+  int32_t packed;            // weights are in the tile order of fspad_pack_weight
 };
 
 // exp(x) for x <= 0 as the walk needs it: the fp32 hardware exponential (the logits themselves carry
@@ -540,7 +542,12 @@ __global__ __launch_bounds__(kWalkThreads) void lm_head_sample_walk_kernel(const
   {
     // wavefront w sums token e0 + w: lane l takes the 16-byte pieces l, l + 64, ... of the row
     const int v = e0 + wave;
-    const char* wp = p.weights + ((size_t)min(v, p.V - 1) * p.K + (size_t)lane * 8) * 2;
+    // row-major: piece c of row r at (r K + 8 c) * 2; tile order: piece c = 4 s + g of row r = 16 t + n
+    // at ((t K/32 + s) 64 + n + 16 g) * 16. Lane l's pieces l, l + 64, ... are 16 k-steps apart.
+    const int vr = min(v, p.V - 1);
+    const char* wp = p.packed ? p.weights + (((size_t)(vr >> 4) * (p.K >> 5) + (lane >> 2)) * 64 + (vr & 15) + 16 * (lane & 3)) * 16
+                              : p.weights + ((size_t)vr * p.K + (size_t)lane * 8) * 2;
+    const int wstep = p.packed ? 16 * 1024 : 1024;   // bytes between a lane's consecutive pieces
     const char* hp = p.hidden + ((size_t)(o + cur) * p.K + (size_t)lane * 8) * 2;
     float dot = 0.f;
     for (int k = 0; k < p.K; k += 512 * 4) {   // four pieces in flight per lane
@@ -548,7 +555,7 @@ __global__ __launch_bounds__(kWalkThreads) void lm_head_sample_walk_kernel(const
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
         const bool ok = k + 512 * u + lane * 8 < p.K;
-        a[u] = ok ? *reinterpret_cast<const bf16x8*>(wp + 2 * (k + 512 * u)) : bf16x8{};
+        a[u] = ok ? *reinterpret_cast<const bf16x8*>(wp + (size_t)(k / 512 + u) * wstep) : bf16x8{};
         h[u] = ok ? *reinterpret_cast<const bf16x8*>(hp + 2 * (k + 512 * u)) : bf16x8{};
       }
 #pragma unroll
@@ -616,7 +623,7 @@ fspad_status check_lm_head_args(int32_t B, int32_t Nmax, int32_t V, int32_t hidd
 }
 
 // Fills in the launch shape and runs the GEMM in the given mode (0 greedy, 1 sampling).
-template <int MODE>
+template <int MODE, bool PACKED>
 fspad_status launch_lm_head(LmHeadParams& g, int32_t hidden_dim, hipStream_t stream) {
   // rows per workgroup: everything up to 128 rows in one pass of the eight-wavefront shape, more in
   // passes of up to 256 rows (each pass streams the weights again)
@@ -630,12 +637,12 @@ fspad_status launch_lm_head(LmHeadParams& g, int32_t hidden_dim, hipStream_t str
   g.stagger = (g.rows_per_pass > 64 || hidden_dim % 512 == 0) ? g_stagger : 0;
   const dim3 grid((unsigned)(g.n_slices * g.n_passes));
   const int r = g.rows_per_pass;
-  if (r <= 16) hipLaunchKernelGGL((lm_head_argmax_kernel<1, 16, 16, 8, 1, MODE>), grid, dim3(512), 0, stream, g);
-  else if (r <= 32) hipLaunchKernelGGL((lm_head_argmax_kernel<2, 16, 16, 8, 1, MODE>), grid, dim3(512), 0, stream, g);
-  else if (r <= 64) hipLaunchKernelGGL((lm_head_argmax_kernel<4, 16, 16, 8, 1, MODE>), grid, dim3(512), 0, stream, g);
-  else if (r <= 128) hipLaunchKernelGGL((lm_head_argmax_kernel<8, 8, 16, 8, 1, MODE>), grid, dim3(512), 0, stream, g);
-  else if (r <= 192) hipLaunchKernelGGL((lm_head_argmax_kernel<12, 4, 16, 8, 1, MODE>), grid, dim3(512), 0, stream, g);
-  else hipLaunchKernelGGL((lm_head_argmax_kernel<16, 4, 16, 8, 1, MODE>), grid, dim3(512), 0, stream, g);
+  if (r <= 16) hipLaunchKernelGGL((lm_head_argmax_kernel<1, 16, 16, 8, 1, MODE, PACKED>), grid, dim3(512), 0, stream, g);
+  else if (r <= 32) hipLaunchKernelGGL((lm_head_argmax_kernel<2, 16, 16, 8, 1, MODE, PACKED>), grid, dim3(512), 0, stream, g);
+  else if (r <= 64) hipLaunchKernelGGL((lm_head_argmax_kernel<4, 16, 16, 8, 1, MODE, PACKED>), grid, dim3(512), 0, stream, g);
+  else if (r <= 128) hipLaunchKernelGGL((lm_head_argmax_kernel<8, 8, 16, 8, 1, MODE, PACKED>), grid, dim3(512), 0, stream, g);
+  else if (r <= 192) hipLaunchKernelGGL((lm_head_argmax_kernel<12, 4, 16, 8, 1, MODE, PACKED>), grid, dim3(512), 0, stream, g);
+  else hipLaunchKernelGGL((lm_head_argmax_kernel<16, 4, 16, 8, 1, MODE, PACKED>), grid, dim3(512), 0, stream, g);
   return hipGetLastError() == hipSuccess ? FSPAD_OK : FSPAD_ERR_HIP;
 }
 
@@ -650,7 +657,7 @@ extern "C" size_t fspad_tree_accept_lm_head_workspace_bytes(int32_t B, int32_t N
 }
 
 extern "C" fspad_status fspad_tree_accept_greedy_lm_head(int32_t B, int32_t Nmax, int32_t V, int32_t hidden_dim,
-                                                         const void* hidden, const void* lm_head,
+                                                         const void* hidden, const void* lm_head, int32_t flags,
                                                          const int32_t* draft_tokens, const int32_t* parent,
                                                          const int32_t* n_nodes, int32_t* path, int32_t* path_len,
                                                          int32_t* tokens, int32_t* n_tokens, int32_t* node_target,
@@ -659,6 +666,7 @@ extern "C" fspad_status fspad_tree_accept_greedy_lm_head(int32_t B, int32_t Nmax
   const fspad_status st = check_lm_head_args(B, Nmax, V, hidden_dim, hidden, lm_head, draft_tokens, parent, n_nodes, path,
                                              path_len, tokens, n_tokens, workspace, workspace_bytes);
   if (st != FSPAD_OK) return st;
+  if (flags & ~FSPAD_WEIGHTS_PACKED) return FSPAD_ERR_SHAPE;
   hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
 
   LmHeadParams g{};
@@ -669,7 +677,8 @@ extern "C" fspad_status fspad_tree_accept_greedy_lm_head(int32_t B, int32_t Nmax
   const size_t slots = (size_t)g.M * g.n_slices;
   g.part_max = static_cast<float*>(workspace);
   g.part_idx = reinterpret_cast<int32_t*>(g.part_max + slots);
-  const fspad_status gs = launch_lm_head<0>(g, hidden_dim, stream);
+  const fspad_status gs = (flags & FSPAD_WEIGHTS_PACKED) ? launch_lm_head<0, true>(g, hidden_dim, stream)
+                                                         : launch_lm_head<0, false>(g, hidden_dim, stream);
   if (gs != FSPAD_OK) return gs;
 
   LmWalkParams w{};
@@ -684,7 +693,7 @@ extern "C" fspad_status fspad_tree_accept_greedy_lm_head(int32_t B, int32_t Nmax
 }
 
 extern "C" fspad_status fspad_tree_accept_sample_lm_head(int32_t B, int32_t Nmax, int32_t V, int32_t hidden_dim,
-                                                         const void* hidden, const void* lm_head,
+                                                         const void* hidden, const void* lm_head, int32_t flags,
                                                          const int32_t* draft_tokens, const int32_t* parent,
                                                          const int32_t* n_nodes, float temperature,
                                                          const float* uniforms, int32_t* path, int32_t* path_len,
@@ -694,6 +703,7 @@ extern "C" fspad_status fspad_tree_accept_sample_lm_head(int32_t B, int32_t Nmax
                                              path_len, tokens, n_tokens, workspace, workspace_bytes);
   if (st != FSPAD_OK) return st;
   if (!uniforms) return FSPAD_ERR_NULL;
+  if (flags & ~FSPAD_WEIGHTS_PACKED) return FSPAD_ERR_SHAPE;
   if (!(temperature > 0.0f) || isinf(temperature)) return FSPAD_ERR_TEMPERATURE;
   hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
 
@@ -711,7 +721,8 @@ extern "C" fspad_status fspad_tree_accept_sample_lm_head(int32_t B, int32_t Nmax
   float* row_max = g.node_logit + g.M;
   g.draft_tokens = draft_tokens; g.parent = parent; g.n_nodes = n_nodes;
   g.inv_t_log2e = (float)(1.4426950408889634 / (double)temperature);
-  const fspad_status gs = launch_lm_head<1>(g, hidden_dim, stream);
+  const fspad_status gs = (flags & FSPAD_WEIGHTS_PACKED) ? launch_lm_head<1, true>(g, hidden_dim, stream)
+                                                         : launch_lm_head<1, false>(g, hidden_dim, stream);
   if (gs != FSPAD_OK) return gs;
 
   LmSampleWalkParams w{};
@@ -721,6 +732,7 @@ extern "C" fspad_status fspad_tree_accept_sample_lm_head(int32_t B, int32_t Nmax
   w.path = path; w.path_len = path_len; w.tokens = tokens; w.n_tokens = n_tokens;
   w.inv_temperature = 1.0 / (double)temperature;
   w.B = B; w.Nmax = Nmax; w.V = V; w.K = hidden_dim; w.n_slices = g.n_slices;
+  w.packed = (flags & FSPAD_WEIGHTS_PACKED) != 0;
   w.row_max = row_max; w.row_sum = row_sum;
   hipLaunchKernelGGL(lm_head_row_stats_kernel, dim3((unsigned)g.M), dim3(256), 0, stream, w);
   if (hipGetLastError() != hipSuccess) return FSPAD_ERR_HIP;

@@ -151,19 +151,28 @@ class LmHeadCase:
         self.parent_dev = torch.from_numpy(np.ascontiguousarray(self.parent, np.int32)).to(DEV)
         self.n_nodes_dev = torch.from_numpy(np.asarray(self.n_nodes, np.int32)).to(DEV)
 
-    def gpu(self):
-        out = fspad.fspad_tree_accept_greedy_lm_head(self.hidden_dev, self.w_dev, self.tokens_dev, self.parent_dev,
-                                                     self.n_nodes_dev)
+    def packed_w(self):
+        """the LM head in the library's tile order (flat: the vocabulary may not fill the last tile row)"""
+        if not hasattr(self, "_packed"):
+            self._packed = fspad.fspad_pack_weight(self.w_dev).reshape(-1)
+        return self._packed
+
+    def gpu(self, packed=False):
+        out = fspad.fspad_tree_accept_greedy_lm_head(self.hidden_dev, self.packed_w() if packed else self.w_dev,
+                                                     self.tokens_dev, self.parent_dev, self.n_nodes_dev, packed=packed,
+                                                     vocab=self.shape[3] if packed else None)
         torch.cuda.synchronize()
         return [t.cpu().numpy() for t in out]
 
     def cpu(self):
         return list(oracle.lm_head_greedy(self.hidden, self.w, self.tokens, self.parent, self.n_nodes))
 
-    def gpu_sample(self, temperature=1.0, seed=0):
+    def gpu_sample(self, temperature=1.0, seed=0, packed=False):
         uni = gen_uniforms(seed, self.shape[0], self.shape[1])
-        out = fspad.fspad_tree_accept_sample_lm_head(self.hidden_dev, self.w_dev, self.tokens_dev, self.parent_dev,
-                                                     self.n_nodes_dev, temperature, torch.from_numpy(uni).to(DEV))
+        out = fspad.fspad_tree_accept_sample_lm_head(self.hidden_dev, self.packed_w() if packed else self.w_dev,
+                                                     self.tokens_dev, self.parent_dev, self.n_nodes_dev, temperature,
+                                                     torch.from_numpy(uni).to(DEV), packed=packed,
+                                                     vocab=self.shape[3] if packed else None)
         torch.cuda.synchronize()
         return [t.cpu().numpy() for t in out]
 

@@ -161,3 +161,19 @@ def test_sampling_rejects_bad_temperature(H):
         with pytest.raises(fspad.FspadError):
             fspad.fspad_tree_accept_sample_lm_head(case.hidden_dev, case.w_dev, case.tokens_dev, case.parent_dev,
                                                    case.n_nodes_dev, t, uni)
+
+
+@pytest.mark.parametrize("B,N,Hd,V", [
+    (1, 2, 256, 127), (1, 17, 256, 129), (1, 26, 1024, 1000), (1, 33, 768, 4097), (2, 60, 1024, 1500),
+    (5, 60, 256, 900), (9, 58, 768, 300), (2, 60, 256, 70001), (1, 26, 4096, 32000),
+])
+def test_tile_order_weights_give_the_same_bits(H, B, N, Hd, V):
+    """The LM head in the tile order of fspad_pack_weight: every output of the greedy form (winning
+    logits included) and of the sampling form equals, bit for bit, the one from row-major weights --
+    the order of the sums does not change. Vocabularies that leave the last tile row ragged included."""
+    case = H.LmHeadCase(4000 + 7 * N + V, B, N, Hd, V, topk=min(10, max(1, V // 2)), noise=0.5)
+    for a, b in zip(case.gpu(), case.gpu(packed=True)):
+        assert np.array_equal(a, b, equal_nan=True)
+    for seed in (1, 2):
+        for a, b in zip(case.gpu_sample(0.8, seed), case.gpu_sample(0.8, seed, packed=True)):
+            assert np.array_equal(a, b)

@@ -142,8 +142,8 @@ def test_lm_head_argument_checks_need_no_gpu(lib):
     need = fspad.fspad_tree_accept_lm_head_workspace_bytes(1, 26, 32000)
     assert need >= 26 * 250 * 8
 
-    def call(B=1, N=26, V=32000, Hd=4096, hidden=fake, w=fake, ws=fake, wsb=need):
-        return f(i32(B), i32(N), i32(V), i32(Hd), hidden, w, fake, fake, fake, fake, fake, fake, fake, None, None,
+    def call(B=1, N=26, V=32000, Hd=4096, hidden=fake, w=fake, ws=fake, wsb=need, flags=0):
+        return f(i32(B), i32(N), i32(V), i32(Hd), hidden, w, i32(flags), fake, fake, fake, fake, fake, fake, fake, None, None,
                  ws, sz(wsb), None)
 
     assert call(hidden=None) == 1
@@ -153,14 +153,18 @@ def test_lm_head_argument_checks_need_no_gpu(lib):
     assert call(Hd=4000) == 2          # not a multiple of 256
     assert call(Hd=128) == 2
     assert call(hidden=ctypes.c_void_p(0x1008)) == 2
+    assert call(flags=1) == 2          # only "packed weights" (2) is a flag here
+    assert call(flags=2, wsb=need - 1) == 5
     assert call(wsb=need - 1) == 5
     assert call(ws=None) == 5
 
     s = lib.fspad_tree_accept_sample_lm_head
 
-    def sample(T=1.0, uni=fake, Hd=4096, wsb=need):
-        return s(i32(1), i32(26), i32(32000), i32(Hd), fake, fake, fake, fake, fake, ctypes.c_float(T), uni,
+    def sample(T=1.0, uni=fake, Hd=4096, wsb=need, flags=0):
+        return s(i32(1), i32(26), i32(32000), i32(Hd), fake, fake, i32(flags), fake, fake, fake, ctypes.c_float(T), uni,
                  fake, fake, fake, fake, fake, sz(wsb), None)
+
+    assert sample(flags=4) == 2
 
     for t in (0.0, -1.0, float("inf"), float("nan")):
         assert sample(T=t) == 6
