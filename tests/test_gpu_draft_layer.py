@@ -223,3 +223,60 @@ def test_packed_weights_give_the_same_bits(B, Nmax, Hd, I, Hq, Hkv, D, L):
     used = torch.from_numpy(np.arange(Nmax)[None, :] < n_nodes[:, None]).to(DEV)
     for a, b in zip(plain, packed):
         assert torch.equal(a[used], b[used])
+
+
+def test_layer_keys_join_the_draft_cache_and_serve_the_next_step():
+    """Two draft steps chained on the device: the keys / values the layer returns are committed to the
+    draft's cache along a root-to-leaf path (fspad_kv_commit reads them as they are), and the layer
+    runs again over a new tree on the longer prefix. The oracle does the same in fp64."""
+    import paper_2408_15562_amd as fspad
+    B, Nmax, Hd, I, Hq, Hkv, D, L = 2, 12, 256, 512, 4, 2, 64, 90
+    cap = L + Nmax
+    kv_len = np.array([L, L - 33], dtype=np.int32)
+    host = gen_draft_layer(31, B, Nmax, Hd, I, Hq, Hkv, D, cap)
+    w = {k: _dev(host[k]) for k in WEIGHTS}
+    kc, vc = _dev(host["k_cache"]), _dev(host["v_cache"])
+    names = [host[k] for k in WEIGHTS]
+
+    def tree(seed):
+        parent, n_nodes = gen_trees(seed, B, Nmax, 5, 3)
+        return parent, n_nodes, torch.from_numpy(fspad.fspad_tree_build_mask(parent, n_nodes).view(np.int64)).to(DEV)
+
+    # step 1
+    parent, n_nodes, mask = tree(32)
+    pos = (kv_len[:, None] + tree_depths(parent, n_nodes)).astype(np.int32)
+    out1 = fspad.fspad_draft_layer(_dev(host["eta"]), torch.from_numpy(pos).to(DEV), w, kc, vc, kv_len, n_nodes, mask, Hq, Hkv, D)
+    ref1 = oracle.draft_layer(host["eta"], pos, *names, host["k_cache"], host["v_cache"], kv_len, n_nodes, parent, Hq, Hkv, D)
+    # the accepted path: from the deepest node of each tree up to its root
+    depth = tree_depths(parent, n_nodes)
+    path = np.full((B, Nmax), -1, dtype=np.int32)
+    path_len = np.zeros(B, dtype=np.int32)
+    for b in range(B):
+        node, chain = int(np.argmax(depth[b, : n_nodes[b]])), []
+        while node >= 0:
+            chain.append(node)
+            node = int(parent[b, node])
+        chain = chain[::-1]
+        path[b, : len(chain)] = chain
+        path_len[b] = len(chain)
+    assert path_len.min() >= 2
+    fspad.fspad_kv_commit(out1[2], out1[3], kc, vc, kv_len, torch.from_numpy(path).to(DEV), torch.from_numpy(path_len).to(DEV))
+    k_ref, v_ref, len2 = oracle.kv_commit(ref1[2], ref1[3], host["k_cache"].astype(np.float64),
+                                          host["v_cache"].astype(np.float64), kv_len, path, path_len)
+    # step 2: a new tree and new inputs on the longer prefix
+    parent2, n_nodes2, mask2 = tree(33)
+    eta2 = gen_draft_layer(34, B, Nmax, Hd, I, Hq, Hkv, D, 1)["eta"]
+    pos2 = (len2[:, None] + tree_depths(parent2, n_nodes2)).astype(np.int32)
+    out2 = fspad.fspad_draft_layer(_dev(eta2), torch.from_numpy(pos2).to(DEV), w, kc, vc, len2, n_nodes2, mask2, Hq, Hkv, D)
+    torch.cuda.synchronize()
+    ref2 = oracle.draft_layer(eta2, pos2, *names, k_ref, v_ref, len2, n_nodes2, parent2, Hq, Hkv, D)
+    used = np.arange(Nmax)[None, :] < n_nodes2[:, None]
+    worst = [_worst(out2[0], ref2[0], used, 2e-2), _worst(out2[1], ref2[1], used, 2e-2),
+             _worst(out2[2], ref2[2], used, 1e-2), _worst(out2[3], ref2[3], used, 1e-2)]
+    assert max(worst) <= 1.0, worst
+    # the committed cache rows are the layer's own keys, moved bit for bit
+    got_k = kc.float().cpu().numpy()
+    k1 = out1[2].float().cpu().numpy()
+    for b in range(B):
+        for j in range(path_len[b]):
+            assert np.array_equal(got_k[b, :, kv_len[b] + j], k1[b, path[b, j]])
