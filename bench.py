@@ -375,6 +375,17 @@ def main():
     t3 = time.perf_counter()
     ms_per_step_sync = (t3 - t2) * 1e3 / sync_steps
 
+    # Also after the timed region: the same number of steps over ONE buffer set, i.e. with whatever fits
+    # of a step's inputs resident in the 256 MB last-level cache (the headline value rotates the sets so
+    # that every step streams from HBM). Reported separately and labelled as such.
+    torch.cuda.synchronize()
+    t4 = time.perf_counter()
+    for i in range(steps):
+        step(0)
+    torch.cuda.synchronize()
+    ms_per_step_resident = (time.perf_counter() - t4) * 1e3 / steps
+    props = torch.cuda.get_device_properties(0)
+
     attn_bytes = cfg.attn_bytes_per_layer()
     attn_flops = cfg.attn_flops_per_layer()
     achieved_gbs = attn_bytes / (attn_ms * 1e-3) / 1e9
@@ -407,6 +418,9 @@ def main():
         "accept_call_us": {"mean": float(accept_ms.mean()) * 1e3, "p50": float(np.percentile(accept_ms, 50)) * 1e3,
                            "samples": int(accept_ms.size)},
         "steps_per_s_with_host_readback": 1e3 / ms_per_step_sync,
+        "steps_per_s_one_buffer_set_cache_resident": 1e3 / ms_per_step_resident,
+        "device": {"name": props.name, "arch": getattr(props, "gcnArchName", ""), "compute_units": props.multi_processor_count,
+                   "hbm_bytes": props.total_memory, "clocks": read_clock_levels()},
         "mean_tokens_per_step": n_tokens_mean,
         "roofline": roofline,
     }
@@ -440,6 +454,25 @@ def main():
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(cfg, accept, sets[0], parent, n_nodes, kv_len, args.seed)
     print(json.dumps(result))
+
+
+def read_clock_levels():
+    """Engine / memory clock levels of the first GPU as the driver lists them (the active level carries a
+    '*'); None where the files cannot be read. Read after the timed region; changes nothing."""
+    import glob
+    out = {}
+    for key, name in (("sclk", "pp_dpm_sclk"), ("mclk", "pp_dpm_mclk")):
+        out[key] = None
+        for path in sorted(glob.glob(f"/sys/class/drm/card*/device/{name}")):
+            try:
+                with open(path) as fh:
+                    levels = [line.strip() for line in fh if line.strip()]
+            except OSError:
+                continue
+            if levels:
+                out[key] = levels
+                break
+    return out
 
 
 def library_draft_layer(torch, eta, pos, w, k_cache, v_cache, L, parent, n_nodes, Hq, Hkv, D):
