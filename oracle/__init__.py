@@ -413,3 +413,95 @@ def pack_weight(w):
     tiles = padded.reshape(T, 16, S, 4, 8)               # [t, n, s, g, j]
     out = tiles.transpose(0, 2, 3, 1, 4)                 # [t, s, g, n, j]: slot n + 16 g
     return out.reshape(-1)
+
+
+def accept_sample_draft(logits, draft_logits, draft_tokens, parent, n_nodes, temperature, uniforms):
+    """Tree acceptance for drafts that were SAMPLED from a draft distribution q (Introduction: the
+    draft-then-verify scheme of speculative sampling, which the method's lossless property rests
+    on), in its multi-candidate form: at a node with target distribution p = softmax(l / T) and
+    draft distribution q = softmax(l_draft / T), the children (drawn from q one after another,
+    without replacement, in sibling order) are tested in that order:
+
+        accept x    <=>  u * q(x) < p(x)                (probability min(1, p(x) / q(x)))
+        reject x    :    p <- max(p - q, 0) / sum(max(p - q, 0));   q(x) <- 0, q <- q / sum(q)
+
+    and when no child is accepted the step's last token is drawn from what p has become (inverse
+    CDF with the node's second uniform, vocabulary order).  The token emitted at every position
+    then follows the target's p exactly.  With q a point mass on each draft token this is
+    `accept_sample`.  NaN logits carry no mass; tokens outside [0, V) are never accepted.
+
+    logits, draft_logits [B,Nmax,V]; uniforms [B,2,Nmax] as for accept_sample.  fp64 throughout.
+    Returns (path, path_len, tokens, n_tokens, min_margin): the margin is the smallest distance of
+    any decision from its threshold (|u q(x) - p(x)| for a test; for the draw, the distance of the
+    target from the two running sums that bracket it, relative to the total)."""
+    logits = np.asarray(logits)
+    draft_logits = np.asarray(draft_logits)
+    B, Nmax, V = logits.shape
+    assert draft_logits.shape == logits.shape
+    if not (temperature > 0.0) or np.isinf(temperature):
+        raise ValueError("temperature must be positive and finite")
+    draft_tokens, parent, n_nodes = _i32(draft_tokens), _i32(parent), _i32(n_nodes)
+    uniforms = np.asarray(uniforms, dtype=np.float64)
+    assert uniforms.shape == (B, 2, Nmax)
+    path = np.full((B, Nmax), -1, dtype=np.int32)
+    tokens = np.full((B, Nmax), -1, dtype=np.int32)
+    path_len = np.zeros(B, dtype=np.int32)
+    margin = np.full(B, np.inf)
+
+    def softmax(row):
+        row = np.asarray(row, dtype=np.float64)
+        ok = ~np.isnan(row)
+        w = np.zeros(V)
+        if ok.any():
+            w[ok] = np.exp((row[ok] - row[ok].max()) / float(temperature))
+        s = w.sum()
+        return w / s if s > 0 else w
+
+    for b in range(B):
+        n = int(n_nodes[b])
+        cur, length = 0, 1
+        path[b, 0] = 0
+        while True:
+            p, q = softmax(logits[b, cur]), softmax(draft_logits[b, cur])
+            nxt = -1
+            for c in range(cur + 1, n):
+                if parent[b, c] != cur:
+                    continue
+                x = int(draft_tokens[b, c])
+                px, qx = (p[x], q[x]) if 0 <= x < V else (0.0, 0.0)
+                lhs = uniforms[b, 0, c] * qx
+                margin[b] = min(margin[b], abs(lhs - px))
+                if lhs < px:
+                    nxt = c
+                    break
+                r = np.maximum(p - q, 0.0)
+                z = r.sum()
+                if z > 0:
+                    p = r / z
+                if 0 <= x < V:
+                    q[x] = 0.0
+                s = q.sum()
+                if s > 0:
+                    q = q / s
+            if nxt >= 0:
+                tokens[b, length - 1] = draft_tokens[b, nxt]
+                path[b, length] = nxt
+                length += 1
+                cur = nxt
+                continue
+            run = np.cumsum(p)
+            total = run[-1] if V else 0.0
+            t = uniforms[b, 1, cur] * total
+            hit = np.nonzero(run > t)[0]
+            if hit.size:
+                v = int(hit[0])
+                before = run[v - 1] if v > 0 else 0.0
+                margin[b] = min(margin[b], (t - before) / total, (run[v] - t) / total)
+            else:
+                mass = np.nonzero(p > 0)[0]
+                v = int(mass[-1]) if mass.size else 0
+                margin[b] = 0.0
+            tokens[b, length - 1] = v
+            break
+        path_len[b] = length
+    return path, path_len, tokens, path_len.copy(), margin

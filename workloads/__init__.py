@@ -23,6 +23,7 @@ from .generators import (  # noqa: F401
     gen_lm_head,
     gen_feature_sampler,
     gen_draft_layer,
+    gen_sampled_drafts,
     tree_depths,
     round_to_bf16,
     chain_tree,

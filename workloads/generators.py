@@ -256,3 +256,29 @@ def gen_draft_layer(seed: int, batch: int, n_max: int, hidden_dim: int, intermed
         "k_cache": normal((batch, n_kv_heads, l_cap, head_dim)),
         "v_cache": normal((batch, n_kv_heads, l_cap, head_dim)),
     }
+
+
+def gen_sampled_drafts(seed: int, logits: np.ndarray, parent: np.ndarray, n_nodes: np.ndarray,
+                       temperature: float = 1.0, noise: float = 1.0):
+    """A draft distribution per node and children drawn from it: draft_logits [B,N,V] fp32 =
+    logits + N(0, noise^2) (a drafter that is close to the target), and tokens [B,N] i32 whose
+    sibling groups are draws WITHOUT replacement, in sibling order, from softmax(draft_logits / T)
+    of their parent (Gumbel top-m).  The root's own token is arbitrary."""
+    rng = np.random.default_rng([seed, 0x5D4A])
+    batch, n_max, vocab = logits.shape
+    draft_logits = (logits + noise * rng.standard_normal(logits.shape)).astype(np.float32)
+    tok = np.zeros((batch, n_max), dtype=np.int32)
+    for b in range(batch):
+        n = int(n_nodes[b])
+        tok[b, 0] = rng.integers(0, vocab)
+        for p in range(n):
+            kids = [c for c in range(p + 1, n) if parent[b, c] == p]
+            if not kids:
+                continue
+            key = draft_logits[b, p].astype(np.float64) / float(temperature) + rng.gumbel(size=vocab)
+            m = min(len(kids), vocab)
+            top = np.argsort(-key, kind="stable")[:m]
+            tok[b, kids[:m]] = top.astype(np.int32)
+            for extra in kids[m:]:          # more siblings than tokens: repeat the last (never accepted twice)
+                tok[b, extra] = top[-1]
+    return draft_logits, tok
