@@ -187,6 +187,41 @@ fspad_status fspad_tree_accept_sample(int32_t B, int32_t Nmax, int32_t V,
                                       void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * Lossless acceptance for drafts that were SAMPLED from a draft distribution (Introduction: the
+ * draft-then-verify scheme of speculative sampling, whose accept-or-resample rule is what keeps the
+ * target's output distribution; fspad_tree_accept_sample is its special case for the deterministic
+ * top-k drafts of the paper's trees, where the draft distribution is a point mass).
+ *
+ * At a node with target distribution p = softmax(logits / T) and draft distribution
+ * q = softmax(draft_logits / T), the children -- drawn from q one after another without
+ * replacement, stored in that order -- are tested in order:
+ *   accept x  <=>  u_acc * q(x) < p(x)                       (probability min(1, p(x) / q(x)))
+ *   reject x   :   p <- max(p - q, 0) / sum_v max(p - q, 0);  q(x) <- 0,  q <- q / sum_v q
+ * When no child is accepted (or the node is a leaf) the step's last token is the first v whose
+ * running sum of p (vocabulary order) exceeds u_draw * sum_v p. Every emitted token then follows
+ * the target's distribution at its position.
+ *
+ *   logits, draft_logits  dev [B,Nmax,V] fp32 with the same row_stride (>= V); row (b,i) of
+ *                draft_logits is the distribution node i's children were drawn from. NaN
+ *                entries carry no mass.
+ *   draft_tokens, parent, n_nodes, temperature, uniforms, path, path_len, tokens, n_tokens:
+ *                as for fspad_tree_accept_sample (tokens outside [0,V) are never accepted)
+ *   workspace    dev, 16-byte aligned, >= fspad_tree_accept_sample_draft_workspace_bytes(B,Nmax,V)
+ *                (2 V fp64 entries per sequence); two calls that may overlap need different ones
+ * All arithmetic that takes a decision is fp64. One workgroup walks each sequence: the cost is a
+ * few passes over the two rows of every node on the accepted path (not over all B*Nmax rows).
+ */
+size_t fspad_tree_accept_sample_draft_workspace_bytes(int32_t B, int32_t Nmax, int32_t V);
+fspad_status fspad_tree_accept_sample_draft(int32_t B, int32_t Nmax, int32_t V,
+                                            const float* logits, const float* draft_logits, int64_t row_stride,
+                                            const int32_t* draft_tokens, const int32_t* parent,
+                                            const int32_t* n_nodes,
+                                            float temperature, const float* uniforms,
+                                            int32_t* path, int32_t* path_len,
+                                            int32_t* tokens, int32_t* n_tokens,
+                                            void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
  * Greedy acceptance straight from the target's last hidden states, fused with the LM head
  * (Methodology, "LM Head": the final linear map from features to the vocabulary distribution;
  * Preliminaries, validation phase; Experiments "Settings": temperature 0). The [B*Nmax, V]

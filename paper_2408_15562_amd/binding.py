@@ -25,6 +25,7 @@ _STATUS_NAMES = {0: "FSPAD_OK", 1: "FSPAD_ERR_NULL", 2: "FSPAD_ERR_SHAPE", 3: "F
 
 EXPORTS = ("fspad_tree_attn_workspace_bytes", "fspad_tree_attn_set_workgroups", "fspad_tree_attn",
            "fspad_tree_accept_workspace_bytes", "fspad_tree_accept_greedy", "fspad_tree_accept_sample",
+           "fspad_tree_accept_sample_draft_workspace_bytes", "fspad_tree_accept_sample_draft",
            "fspad_tree_accept_lm_head_workspace_bytes", "fspad_tree_accept_greedy_lm_head",
            "fspad_tree_accept_sample_lm_head",
            "fspad_kv_commit", "fspad_feature_sampler_workspace_bytes", "fspad_feature_sampler",
@@ -85,6 +86,11 @@ def _lib():
         lib.fspad_tree_accept_sample.restype = ctypes.c_int
         lib.fspad_tree_accept_sample.argtypes = [i32, i32, i32, vp, i64, vp, vp, vp, ctypes.c_float, vp,
                                                  vp, vp, vp, vp, vp, sz, vp]
+        lib.fspad_tree_accept_sample_draft_workspace_bytes.restype = sz
+        lib.fspad_tree_accept_sample_draft_workspace_bytes.argtypes = [i32, i32, i32]
+        lib.fspad_tree_accept_sample_draft.restype = ctypes.c_int
+        lib.fspad_tree_accept_sample_draft.argtypes = [i32, i32, i32, vp, vp, i64, vp, vp, vp, ctypes.c_float, vp,
+                                                       vp, vp, vp, vp, vp, sz, vp]
         lib.fspad_tree_accept_lm_head_workspace_bytes.restype = sz
         lib.fspad_tree_accept_lm_head_workspace_bytes.argtypes = [i32, i32, i32]
         lib.fspad_tree_accept_greedy_lm_head.restype = ctypes.c_int
@@ -310,6 +316,36 @@ def fspad_tree_accept_sample(logits: torch.Tensor, draft_tokens: torch.Tensor, p
             workspace.numel() * workspace.element_size(), _stream_ptr(stream))
     keep = (logits, draft_tokens, parent, n_nodes, uniforms, workspace)
     return _issue(_lib().fspad_tree_accept_sample, "fspad_tree_accept_sample", args, keep,
+                  (path, path_len, tokens, n_tokens), prepare)
+
+
+def fspad_tree_accept_sample_draft_workspace_bytes(B: int, Nmax: int, V: int) -> int:
+    return int(_lib().fspad_tree_accept_sample_draft_workspace_bytes(B, Nmax, V))
+
+
+def fspad_tree_accept_sample_draft(logits: torch.Tensor, draft_logits: torch.Tensor, draft_tokens: torch.Tensor,
+                                   parent: torch.Tensor, n_nodes: torch.Tensor, temperature: float,
+                                   uniforms: torch.Tensor, outputs=None, workspace: Optional[torch.Tensor] = None,
+                                   stream=None, prepare: bool = False):
+    """logits, draft_logits fp32 [B,Nmax,V] with the same strides (vocabulary contiguous); uniforms fp32
+    [B,2,Nmax]; everything on the device. Returns (path, path_len, tokens, n_tokens); with prepare=True a
+    PreparedCall."""
+    if workspace is None:
+        workspace = torch.empty(max(16, fspad_tree_accept_sample_draft_workspace_bytes(*logits.shape)), dtype=torch.uint8,
+                                device=logits.device)
+    B, Nmax, V, workspace = _accept_common(logits, draft_tokens, parent, n_nodes, workspace)
+    if draft_logits.dtype != torch.float32 or draft_logits.shape != logits.shape or draft_logits.stride() != logits.stride():
+        raise ValueError("draft_logits must have the dtype, shape and strides of logits")
+    if uniforms.dtype != torch.float32 or not uniforms.is_contiguous() or tuple(uniforms.shape) != (B, 2, Nmax):
+        raise ValueError("uniforms must be a contiguous fp32 [B,2,Nmax] device tensor")
+    path, path_len, tokens, n_tokens = _accept_outputs(B, Nmax, logits.device, outputs)
+    args = (B, Nmax, V, _dev_ptr(logits, "logits", torch.float32), _dev_ptr(draft_logits, "draft_logits", torch.float32),
+            logits.stride(1), _dev_ptr(draft_tokens, "draft_tokens"), _dev_ptr(parent, "parent"),
+            _dev_ptr(n_nodes, "n_nodes"), float(temperature), _dev_ptr(uniforms, "uniforms"), _dev_ptr(path, "path"),
+            _dev_ptr(path_len, "path_len"), _dev_ptr(tokens, "tokens"), _dev_ptr(n_tokens, "n_tokens"),
+            _dev_ptr(workspace, "workspace"), workspace.numel() * workspace.element_size(), _stream_ptr(stream))
+    keep = (logits, draft_logits, draft_tokens, parent, n_nodes, uniforms, workspace)
+    return _issue(_lib().fspad_tree_accept_sample_draft, "fspad_tree_accept_sample_draft", args, keep,
                   (path, path_len, tokens, n_tokens), prepare)
 
 

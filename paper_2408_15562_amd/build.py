@@ -8,7 +8,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _ROOT = os.path.dirname(_HERE)
 CSRC = os.path.join(_HERE, "csrc")
 LIB_PATH = os.path.join(_HERE, "libfspad.so")
-SOURCES = ["fspad_host.cpp", "fspad_attn.hip", "fspad_accept.hip", "fspad_commit.hip", "fspad_tree.hip", "fspad_lmhead.hip", "fspad_topk.hip", "fspad_draft.hip"]
+SOURCES = ["fspad_host.cpp", "fspad_attn.hip", "fspad_accept.hip", "fspad_accept_draft.hip", "fspad_commit.hip", "fspad_tree.hip", "fspad_lmhead.hip", "fspad_topk.hip", "fspad_draft.hip"]
 
 
 def hipcc_command(out: str = LIB_PATH):
@@ -23,7 +23,7 @@ def is_stale() -> bool:
     if not os.path.exists(LIB_PATH):
         return True
     built = os.path.getmtime(LIB_PATH)
-    deps = [os.path.join(CSRC, s) for s in SOURCES + ["greedy_walk.h", "stream_gemm.h"]] + [os.path.join(_ROOT, "include", "fspad.h")]
+    deps = [os.path.join(CSRC, s) for s in SOURCES + ["greedy_walk.h", "stream_gemm.h", "exp_nonpos.h"]] + [os.path.join(_ROOT, "include", "fspad.h")]
     return any(os.path.getmtime(d) > built for d in deps)
 
 
