@@ -32,7 +32,9 @@ def parse_args():
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=None)
     ap.add_argument("--workload", default="c1", choices=["c0", "c1", "c2", "c3", "c4"])
-    ap.add_argument("--accept", default=None, choices=["greedy", "sample"], help="override the workload's acceptance mode")
+    ap.add_argument("--accept", default=None, choices=["greedy", "sample", "sample-draft"],
+                    help="override the workload's acceptance mode (sample-draft: drafts sampled from a draft distribution, "
+                         "accepted against it with fspad_tree_accept_sample_draft)")
     ap.add_argument("--sets", type=int, default=None, help="independent buffer sets to rotate through")
     ap.add_argument("--splits", type=int, default=0, help="force the number of attention workgroups (0 = automatic)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -93,8 +95,8 @@ def main():
     import torch
 
     import paper_2408_15562_amd as fspad
-    from workloads import (CONFIGS, GENERATOR_VERSION, gen_candidates, gen_draft_tokens, gen_logits, gen_trees, gen_uniforms,
-                           tree_depths)
+    from workloads import (CONFIGS, GENERATOR_VERSION, gen_candidates, gen_draft_tokens, gen_logits, gen_sampled_drafts, gen_trees,
+                           gen_uniforms, tree_depths)
 
     fspad.library_path()  # fail loudly if the HIP library is missing
     if not torch.cuda.is_available():
@@ -144,9 +146,13 @@ def main():
             out = torch.empty((B, N, Hq, D), device=dev, dtype=tdt)
             layers.append((q, kt, vt, kc, vc, out))
         logits_h = gen_logits(args.seed + s, B, N, V)
-        tokens_h = gen_draft_tokens(args.seed + s, logits_h, parent, n_nodes, accept)
+        if accept == "sample-draft":
+            draft_logits_h, tokens_h = gen_sampled_drafts(args.seed + s, logits_h, parent, n_nodes, cfg.temperature)
+        else:
+            draft_logits_h, tokens_h = None, gen_draft_tokens(args.seed + s, logits_h, parent, n_nodes, accept)
         sets.append(dict(layers=layers, logits=torch.from_numpy(logits_h).to(dev), tokens=torch.from_numpy(tokens_h).to(dev),
-                         uniforms=torch.from_numpy(gen_uniforms(args.seed + s, B, N)).to(dev)))
+                         uniforms=torch.from_numpy(gen_uniforms(args.seed + s, B, N)).to(dev),
+                         draft_logits=None if draft_logits_h is None else torch.from_numpy(draft_logits_h).to(dev)))
     parent_d = torch.from_numpy(parent).to(dev)
     n_nodes_d = torch.from_numpy(n_nodes).to(dev)
     hidden_dim = 0
@@ -191,6 +197,8 @@ def main():
     desc = fspad.make_attn_desc(sets[0]["layers"][0][0], sets[0]["layers"][0][1], sets[0]["layers"][0][3], tdt, 0.0)
     ws_attn = torch.empty(max(16, fspad.fspad_tree_attn_workspace_bytes(desc, L)), dtype=torch.uint8, device=dev)
     ws_acc = torch.empty(fspad.fspad_tree_accept_workspace_bytes(B, N, V), dtype=torch.uint8, device=dev)
+    ws_draft = (torch.empty(fspad.fspad_tree_accept_sample_draft_workspace_bytes(B, N, V), dtype=torch.uint8, device=dev)
+                if accept == "sample-draft" else None)
     acc_out = (torch.empty((B, N), dtype=torch.int32, device=dev), torch.empty((B,), dtype=torch.int32, device=dev),
                torch.empty((B, N), dtype=torch.int32, device=dev), torch.empty((B,), dtype=torch.int32, device=dev))
 
@@ -211,6 +219,10 @@ def main():
         elif args.lm_head == "unfused":
             st["accept"] = unfused_lm_head_accept(torch, fspad, st, parent_d, n_nodes_d, acc_out, ws_acc, accept,
                                                   cfg.temperature)
+        elif accept == "sample-draft":
+            st["accept"] = fspad.fspad_tree_accept_sample_draft(st["logits"], st["draft_logits"], st["tokens"], parent_d,
+                                                                n_nodes_d, cfg.temperature, st["uniforms"], outputs=acc_out,
+                                                                workspace=ws_draft, prepare=True)
         elif accept == "greedy":
             st["accept"] = fspad.fspad_tree_accept_greedy(st["logits"], st["tokens"], parent_d, n_nodes_d, outputs=acc_out,
                                                           workspace=ws_acc, prepare=True)
@@ -634,6 +646,9 @@ def cpu_baseline(cfg, accept, dev_set, parent, n_nodes, kv_len, seed):
         t1 = time.perf_counter()
         if accept == "greedy":
             oracle.accept_greedy(logits, tokens, parent, n_nodes)
+        elif accept == "sample-draft":
+            oracle.accept_sample_draft(logits, dev_set["draft_logits"].cpu().numpy(), tokens, parent, n_nodes, cfg.temperature,
+                                       uniforms)
         else:
             oracle.accept_sample(logits, tokens, parent, n_nodes, cfg.temperature, uniforms)
         t2 = time.perf_counter()

@@ -12,7 +12,9 @@
  *      discarded (Preliminaries, validation-phase paragraph), either greedy
  *      (temperature 0) or by rejection sampling that leaves the target's output
  *      distribution unchanged (Experiments, "Settings": temperature 1, and the
- *      caption of Table 1: acceptance conditions are not relaxed).
+ *      caption of Table 1: acceptance conditions are not relaxed); also in the
+ *      general form for drafts sampled from a draft distribution
+ *      (fspad_tree_accept_sample_draft).
  * and the calls around that step:
  *   3. the same acceptance straight from the target's last hidden states, fused
  *      with the LM head (fspad_tree_accept_{greedy,sample}_lm_head);

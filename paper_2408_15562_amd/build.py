@@ -8,7 +8,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _ROOT = os.path.dirname(_HERE)
 CSRC = os.path.join(_HERE, "csrc")
 LIB_PATH = os.path.join(_HERE, "libfspad.so")
-SOURCES = ["fspad_host.cpp", "fspad_attn.hip", "fspad_accept.hip", "fspad_accept_draft.hip", "fspad_commit.hip", "fspad_tree.hip", "fspad_lmhead.hip", "fspad_topk.hip", "fspad_draft.hip"]
+SOURCES = ["fspad_host.cpp", "fspad_attn.hip", "fspad_accept.hip", "fspad_commit.hip", "fspad_tree.hip", "fspad_lmhead.hip", "fspad_topk.hip", "fspad_draft.hip"]
 
 
 def hipcc_command(out: str = LIB_PATH):

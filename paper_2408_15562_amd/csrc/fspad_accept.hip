@@ -538,6 +538,229 @@ void launch_rows(const AcceptParams& p, bool vec, hipStream_t stream) {
 #undef FSPAD_ROWS
 }
 
+// ------------------------------------------------------------------------------------------------
+// Acceptance for drafts that were sampled from a draft distribution q (Introduction: the
+// draft-then-verify scheme of speculative sampling), in its multi-candidate form: at a node with
+// target distribution p and draft distribution q the children are tested in sibling order,
+//     accept x  <=>  u q(x) < p(x);      reject x:  p <- max(p - q, 0) / sum,  q(x) <- 0, q <- q / sum
+// and when none is accepted the step's last token is drawn from what p has become.
+//
+// The streaming pass above leaves the chunk statistics of both logit arrays; one workgroup of 1024
+// threads per sequence then walks the tree. Every decision is taken in fp64; all threads take it
+// from the same values, so the control flow stays uniform without an exchange. A rejection or the
+// draw needs the node's two whole rows: they are then written out unnormalised (fp64, 2 V entries
+// per sequence) with their scale factors in registers, and every further rejection is one pass.
+constexpr int kDraftThreads = 1024;
+constexpr int kDraftWaves = kDraftThreads / 64;
+
+struct DraftAcceptParams {
+  const float* logits;        // [B][Nmax][row_stride]
+  const float* draft_logits;  // same layout
+  int64_t row_stride;
+  const int32_t* draft_tokens;
+  const int32_t* parent;
+  const int32_t* n_nodes;
+  const float* uniforms;      // [B][2][Nmax]
+  int32_t* path;
+  int32_t* path_len;
+  int32_t* tokens;
+  int32_t* n_tokens;
+  double* work;               // [B][2][V]: unnormalised p and q of the current node
+  const float* part_max_p;    // [B*Nmax][n_chunks] chunk statistics of logits (accept_rows_kernel<1>)
+  const double* part_sum_p;
+  const float* part_max_q;    // the same of draft_logits
+  const double* part_sum_q;
+  double inv_temperature;
+  int32_t B, Nmax, V, n_chunks;
+};
+
+__device__ __forceinline__ double wg_sum(double v, double* sh) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
+  __syncthreads();                  // sh may still be read from the previous reduction
+  if (lane == 0) sh[wave] = v;
+  __syncthreads();
+  double s = 0.0;
+#pragma unroll
+  for (int i = 0; i < kDraftWaves; ++i) s += sh[i];   // the same order in every thread
+  return s;
+}
+
+__device__ __forceinline__ float wg_max(float v, float* sh) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off));
+  __syncthreads();
+  if (lane == 0) sh[wave] = v;
+  __syncthreads();
+  float m = sh[0];
+#pragma unroll
+  for (int i = 1; i < kDraftWaves; ++i) m = fmaxf(m, sh[i]);
+  return m;
+}
+
+__global__ __launch_bounds__(kDraftThreads) void accept_sample_draft_kernel(const DraftAcceptParams p) {
+  __shared__ double sh_d[kDraftWaves];
+  __shared__ float sh_f[kDraftWaves];
+  __shared__ double scan_incl[kDraftThreads];
+  __shared__ int sh_tok, sh_last;
+  const int b = blockIdx.x, tid = threadIdx.x;
+  const int64_t o = (int64_t)b * p.Nmax;
+  const int n = p.n_nodes[b];
+  const float* u_acc = p.uniforms + (int64_t)b * 2 * p.Nmax;
+  const float* u_draw = u_acc + p.Nmax;
+  double* wp = p.work + (int64_t)b * 2 * p.V;
+  double* wq = wp + p.V;
+  const int V = p.V;
+
+  for (int i = tid; i < p.Nmax; i += kDraftThreads) { p.path[o + i] = i == 0 ? 0 : -1; p.tokens[o + i] = -1; }
+
+  int cur = 0, len = 1;
+  for (;;) {
+    // row statistics of the node from the chunk statistics of the streaming pass: p(v) = exp((l[v] - mp) / T) / zp
+    const float* lrow = p.logits + (o + cur) * p.row_stride;
+    const float* qrow = p.draft_logits + (o + cur) * p.row_stride;
+    float mp = -INFINITY, mq = -INFINITY;
+    for (int c = tid; c < p.n_chunks; c += kDraftThreads) {
+      mp = fmaxf(mp, p.part_max_p[(o + cur) * p.n_chunks + c]);
+      mq = fmaxf(mq, p.part_max_q[(o + cur) * p.n_chunks + c]);
+    }
+    mp = wg_max(mp, sh_f);
+    mq = wg_max(mq, sh_f);
+    double zp = 0.0, zq = 0.0;
+    for (int c = tid; c < p.n_chunks; c += kDraftThreads) {
+      const float cp = p.part_max_p[(o + cur) * p.n_chunks + c], cq = p.part_max_q[(o + cur) * p.n_chunks + c];
+      if (cp > -INFINITY) zp += p.part_sum_p[(o + cur) * p.n_chunks + c] * exp_nonpos(((double)cp - (double)mp) * p.inv_temperature);
+      if (cq > -INFINITY) zq += p.part_sum_q[(o + cur) * p.n_chunks + c] * exp_nonpos(((double)cq - (double)mq) * p.inv_temperature);
+    }
+    zp = wg_sum(zp, sh_d);
+    zq = wg_sum(zq, sh_d);
+    double sp = zp > 0.0 ? 1.0 / zp : 0.0, sq = zq > 0.0 ? 1.0 / zq : 0.0;
+    // The unnormalised weights of the whole rows are written out only when a rejection or the draw
+    // needs them: a node whose first child is accepted costs two logits.
+    bool filled = false;
+    auto fill = [&]() {
+      __syncthreads();
+      double fp = 0.0, fq = 0.0;
+      for (int v = tid; v < V; v += kDraftThreads) {
+        const float a = lrow[v], c = qrow[v];
+        const double ea = (a == a && mp > -INFINITY) ? exp_nonpos(((double)a - (double)mp) * p.inv_temperature) : 0.0;
+        const double ec = (c == c && mq > -INFINITY) ? exp_nonpos(((double)c - (double)mq) * p.inv_temperature) : 0.0;
+        wp[v] = ea; wq[v] = ec;
+        fp += ea; fq += ec;
+      }
+      fp = wg_sum(fp, sh_d);
+      fq = wg_sum(fq, sh_d);
+      sp = fp > 0.0 ? 1.0 / fp : 0.0;          // p(v) = wp[v] * sp, q(v) = wq[v] * sq
+      sq = fq > 0.0 ? 1.0 / fq : 0.0;
+      filled = true;
+      __syncthreads();                          // wp / wq are visible to every thread
+    };
+
+    int next = -1;
+    for (int c = cur + 1; c < n && len < p.Nmax; ++c) {
+      if (p.parent[o + c] != cur) continue;
+      const int x = p.draft_tokens[o + c];
+      const bool valid = x >= 0 && x < V;
+      double px = 0.0, qx = 0.0;
+      if (valid && filled) {
+        px = wp[x] * sp; qx = wq[x] * sq;
+      } else if (valid) {
+        const float a = lrow[x], d = qrow[x];
+        px = (a == a && mp > -INFINITY) ? exp_nonpos(((double)a - (double)mp) * p.inv_temperature) * sp : 0.0;
+        qx = (d == d && mq > -INFINITY) ? exp_nonpos(((double)d - (double)mq) * p.inv_temperature) * sq : 0.0;
+      }
+      if ((double)u_acc[c] * qx < px) { next = c; break; }
+      if (!filled) fill();
+      // rejected: p <- max(p - q, 0), renormalised; q loses x and is renormalised
+      __syncthreads();                       // every thread has read wp[x], wq[x]
+      double z = 0.0;
+      for (int v = tid; v < V; v += kDraftThreads) {
+        const double r = fmax(wp[v] * sp - wq[v] * sq, 0.0);
+        z += r;
+      }
+      z = wg_sum(z, sh_d);
+      if (z > 0.0) {
+        for (int v = tid; v < V; v += kDraftThreads) wp[v] = fmax(wp[v] * sp - wq[v] * sq, 0.0);
+        sp = 1.0 / z;
+      }
+      __syncthreads();                       // every thread is done with the old wq[x]
+      if (valid && tid == 0) wq[x] = 0.0;
+      __syncthreads();
+      // what q keeps once x is gone, summed again from the entries (a difference of the old sum and
+      // wq[x] would cancel when the drafter was nearly certain of x)
+      double s = 0.0;
+      for (int v = tid; v < V; v += kDraftThreads) s += wq[v];
+      s = wg_sum(s, sh_d);
+      sq = s > 0.0 ? 1.0 / s : sq;
+      __syncthreads();
+    }
+    if (next >= 0) {
+      if (tid == 0) { p.tokens[o + len - 1] = p.draft_tokens[o + next]; p.path[o + len] = next; }
+      ++len;
+      cur = next;
+      __syncthreads();                       // the next node overwrites wp / wq
+      continue;
+    }
+
+    if (!filled) fill();
+    // no child accepted: inverse-CDF draw from the current p. Thread k owns the contiguous entries
+    // [k * per, (k + 1) * per); the target is u times the sum formed in the same order as the scan.
+    const int per = (V + kDraftThreads - 1) / kDraftThreads;
+    const int v0 = tid * per, v1 = min(V, v0 + per);
+    double mine = 0.0;
+    for (int v = v0; v < v1; ++v) mine += wp[v];
+    scan_incl[tid] = mine;
+    __syncthreads();
+    for (int off = 1; off < kDraftThreads; off <<= 1) {   // Hillis-Steele inclusive scan
+      const double add = tid >= off ? scan_incl[tid - off] : 0.0;
+      __syncthreads();
+      scan_incl[tid] += add;
+      __syncthreads();
+    }
+    const double total = scan_incl[kDraftThreads - 1];
+    const double t = (double)u_draw[cur] * total;
+    if (tid == 0) { sh_tok = -1; sh_last = kDraftThreads; }
+    __syncthreads();
+    // the scanned sums chain from 0 to the total, so some segment brackets t; they are formed in
+    // different orders and need not be monotone to the last bit: the first bracketing segment counts
+    const double before = tid > 0 ? scan_incl[tid - 1] : 0.0;
+    if (before <= t && t < scan_incl[tid]) atomicMin(&sh_last, tid);
+    __syncthreads();
+    if (tid == sh_last) {
+      double run = before;
+      int tok = -1;
+      for (int v = v0; v < v1; ++v) {
+        run += wp[v];
+        if (run > t) { tok = v; break; }
+      }
+      if (tok < 0)   // the segment's own sum said "here" but its running sum fell short: its last entry with mass
+        for (int v = v1 - 1; v >= v0; --v)
+          if (wp[v] > 0.0) { tok = v; break; }
+      sh_tok = tok;
+    }
+    __syncthreads();
+    if (sh_tok < 0) {   // rounding left no crossing: the last entry with mass (0 if none)
+      int last = -1;
+      for (int v = v1 - 1; v >= v0; --v)
+        if (wp[v] > 0.0) { last = v; break; }
+      if (tid == 0) sh_last = -1;
+      __syncthreads();
+      if (last >= 0) atomicMax(&sh_last, last);   // the highest such entry over the workgroup
+      __syncthreads();
+      if (tid == 0) sh_tok = sh_last < 0 ? 0 : sh_last;
+      __syncthreads();
+    }
+    if (tid == 0) {
+      p.tokens[o + len - 1] = sh_tok;
+      p.path_len[b] = len;
+      p.n_tokens[b] = len;
+    }
+    return;
+  }
+}
+
 }  // namespace
 
 // Experiment knob (not part of the declared interface): workgroups the row pass aims for.
@@ -588,4 +811,47 @@ extern "C" fspad_status fspad_tree_accept_sample(int32_t B, int32_t Nmax, int32_
   hipLaunchKernelGGL(accept_sample_walk_kernel, dim3((unsigned)B), dim3(kThreads), 0, stream, p);
   if (hipGetLastError() != hipSuccess) return FSPAD_ERR_HIP;
   return FSPAD_OK;
+}
+
+extern "C" size_t fspad_tree_accept_sample_draft_workspace_bytes(int32_t B, int32_t Nmax, int32_t V) {
+  if (B < 1 || Nmax < 1 || V < 1) return 0;
+  // chunk statistics of both logit arrays, then 2 V fp64 entries per sequence
+  return 2 * fspad_tree_accept_workspace_bytes(B, Nmax, V) + (((size_t)B * 2 * (size_t)V * 8 + 255) & ~(size_t)255);
+}
+
+extern "C" fspad_status fspad_tree_accept_sample_draft(int32_t B, int32_t Nmax, int32_t V, const float* logits,
+                                                       const float* draft_logits, int64_t row_stride,
+                                                       const int32_t* draft_tokens, const int32_t* parent,
+                                                       const int32_t* n_nodes, float temperature, const float* uniforms,
+                                                       int32_t* path, int32_t* path_len, int32_t* tokens,
+                                                       int32_t* n_tokens, void* workspace, size_t workspace_bytes,
+                                                       void* hip_stream) {
+  if (!draft_logits || !uniforms) return FSPAD_ERR_NULL;
+  const size_t need = fspad_tree_accept_sample_draft_workspace_bytes(B, Nmax, V);
+  const fspad_status st = check_accept_args(B, Nmax, V, logits, row_stride, draft_tokens, parent, n_nodes, path, path_len,
+                                            tokens, n_tokens, workspace, workspace_bytes >= need ? workspace_bytes : 0);
+  if (st != FSPAD_OK) return st;
+  if (!(temperature > 0.0f) || temperature > 3.0e38f) return FSPAD_ERR_TEMPERATURE;
+  hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
+  const size_t region = fspad_tree_accept_workspace_bytes(B, Nmax, V);
+  char* ws = static_cast<char*>(workspace);
+  AcceptParams pa{}, pb{};
+  fill_params(pa, B, Nmax, V, logits, row_stride, draft_tokens, parent, n_nodes, path, path_len, tokens, n_tokens, ws);
+  fill_params(pb, B, Nmax, V, draft_logits, row_stride, draft_tokens, parent, n_nodes, path, path_len, tokens, n_tokens,
+              ws + region);
+  pa.inv_temperature = pb.inv_temperature = 1.0 / (double)temperature;
+  launch_rows<1>(pa, rows_vectorisable(logits, row_stride), stream);
+  if (hipGetLastError() != hipSuccess) return FSPAD_ERR_HIP;
+  launch_rows<1>(pb, rows_vectorisable(draft_logits, row_stride), stream);
+  if (hipGetLastError() != hipSuccess) return FSPAD_ERR_HIP;
+  DraftAcceptParams p{};
+  p.logits = logits; p.draft_logits = draft_logits; p.row_stride = row_stride;
+  p.draft_tokens = draft_tokens; p.parent = parent; p.n_nodes = n_nodes; p.uniforms = uniforms;
+  p.path = path; p.path_len = path_len; p.tokens = tokens; p.n_tokens = n_tokens;
+  p.work = reinterpret_cast<double*>(ws + 2 * region);
+  p.part_max_p = pa.part_max; p.part_sum_p = pa.part_sum; p.part_max_q = pb.part_max; p.part_sum_q = pb.part_sum;
+  p.inv_temperature = pa.inv_temperature;
+  p.B = B; p.Nmax = Nmax; p.V = V; p.n_chunks = pa.n_chunks;
+  hipLaunchKernelGGL(accept_sample_draft_kernel, dim3((unsigned)B), dim3(kDraftThreads), 0, stream, p);
+  return hipGetLastError() == hipSuccess ? FSPAD_OK : FSPAD_ERR_HIP;
 }
