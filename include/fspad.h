@@ -209,7 +209,8 @@ fspad_status fspad_tree_accept_sample(int32_t B, int32_t Nmax, int32_t V,
  *   draft_tokens, parent, n_nodes, temperature, uniforms, path, path_len, tokens, n_tokens:
  *                as for fspad_tree_accept_sample (tokens outside [0,V) are never accepted)
  *   workspace    dev, 16-byte aligned, >= fspad_tree_accept_sample_draft_workspace_bytes(B,Nmax,V)
- *                (2 V fp64 entries per sequence); two calls that may overlap need different ones
+ *                (3 V fp64 entries per sequence and the chunk statistics of both logit arrays); two
+ *                calls that may overlap need different ones
  * All arithmetic that takes a decision is fp64. One workgroup walks each sequence: the cost is a
  * few passes over the two rows of every node on the accepted path (not over all B*Nmax rows).
  */

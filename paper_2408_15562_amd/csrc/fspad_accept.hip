@@ -565,7 +565,7 @@ struct DraftAcceptParams {
   int32_t* path_len;
   int32_t* tokens;
   int32_t* n_tokens;
-  double* work;               // [B][2][V]: unnormalised p and q of the current node
+  double* work;               // [B][3][V]: unnormalised p, a spare for the next p, and q of the current node
   const float* part_max_p;    // [B*Nmax][n_chunks] chunk statistics of logits (accept_rows_kernel<1>)
   const double* part_sum_p;
   const float* part_max_q;    // the same of draft_logits
@@ -603,15 +603,15 @@ __device__ __forceinline__ float wg_max(float v, float* sh) {
 __global__ __launch_bounds__(kDraftThreads) void accept_sample_draft_kernel(const DraftAcceptParams p) {
   __shared__ double sh_d[kDraftWaves];
   __shared__ float sh_f[kDraftWaves];
-  __shared__ double scan_incl[kDraftThreads];
   __shared__ int sh_tok, sh_last;
   const int b = blockIdx.x, tid = threadIdx.x;
   const int64_t o = (int64_t)b * p.Nmax;
   const int n = p.n_nodes[b];
   const float* u_acc = p.uniforms + (int64_t)b * 2 * p.Nmax;
   const float* u_draw = u_acc + p.Nmax;
-  double* wp = p.work + (int64_t)b * 2 * p.V;
-  double* wq = wp + p.V;
+  double* wp = p.work + (int64_t)b * 3 * p.V;   // unnormalised p of the current node
+  double* wp_spare = wp + p.V;                  // where a rejection writes the next p
+  double* wq = wp + 2 * p.V;                    // unnormalised q
   const int V = p.V;
 
   for (int i = tid; i < p.Nmax; i += kDraftThreads) { p.path[o + i] = i == 0 ? 0 : -1; p.tokens[o + i] = -1; }
@@ -640,22 +640,18 @@ __global__ __launch_bounds__(kDraftThreads) void accept_sample_draft_kernel(cons
     // The unnormalised weights of the whole rows are written out only when a rejection or the draw
     // needs them: a node whose first child is accepted costs two logits.
     bool filled = false;
-    auto fill = [&]() {
+    auto weight_p = [&](int v) {
+      const float a = lrow[v];
+      return (a == a && mp > -INFINITY) ? exp_nonpos(((double)a - (double)mp) * p.inv_temperature) : 0.0;
+    };
+    auto weight_q = [&](int v) {
+      const float c = qrow[v];
+      return (c == c && mq > -INFINITY) ? exp_nonpos(((double)c - (double)mq) * p.inv_temperature) : 0.0;
+    };
+    auto fill_p = [&]() {   // p alone, for a draw at a node without a rejection: p(v) = wp[v] * sp
       __syncthreads();
-      double fp = 0.0, fq = 0.0;
-      for (int v = tid; v < V; v += kDraftThreads) {
-        const float a = lrow[v], c = qrow[v];
-        const double ea = (a == a && mp > -INFINITY) ? exp_nonpos(((double)a - (double)mp) * p.inv_temperature) : 0.0;
-        const double ec = (c == c && mq > -INFINITY) ? exp_nonpos(((double)c - (double)mq) * p.inv_temperature) : 0.0;
-        wp[v] = ea; wq[v] = ec;
-        fp += ea; fq += ec;
-      }
-      fp = wg_sum(fp, sh_d);
-      fq = wg_sum(fq, sh_d);
-      sp = fp > 0.0 ? 1.0 / fp : 0.0;          // p(v) = wp[v] * sp, q(v) = wq[v] * sq
-      sq = fq > 0.0 ? 1.0 / fq : 0.0;
-      filled = true;
-      __syncthreads();                          // wp / wq are visible to every thread
+      for (int v = tid; v < V; v += kDraftThreads) wp[v] = weight_p(v);
+      __syncthreads();
     };
 
     int next = -1;
@@ -672,27 +668,52 @@ __global__ __launch_bounds__(kDraftThreads) void accept_sample_draft_kernel(cons
         qx = (d == d && mq > -INFINITY) ? exp_nonpos(((double)d - (double)mq) * p.inv_temperature) * sq : 0.0;
       }
       if ((double)u_acc[c] * qx < px) { next = c; break; }
-      if (!filled) fill();
       // rejected: p <- max(p - q, 0), renormalised; q loses x and is renormalised
+      if (!filled) {
+        // the first rejection at this node: the rows are formed and the rejection applied in the same pass
+        __syncthreads();
+        double z = 0.0, s = 0.0;
+        for (int v = tid; v < V; v += kDraftThreads) {
+          const double qv = weight_q(v);
+          const double r = fmax(weight_p(v) * sp - qv * sq, 0.0);
+          const double keep = (valid && v == x) ? 0.0 : qv;
+          wp[v] = r;
+          wq[v] = keep;
+          z += r;
+          s += keep;
+        }
+        z = wg_sum(z, sh_d);
+        s = wg_sum(s, sh_d);
+        if (z > 0.0) {
+          sp = 1.0 / z;
+        } else {                               // p = q exactly: p is kept
+          for (int v = tid; v < V; v += kDraftThreads) wp[v] = weight_p(v);
+        }
+        sq = s > 0.0 ? 1.0 / s : sq;
+        filled = true;
+        __syncthreads();
+        continue;
+      }
+      // One pass (a workgroup streams its rows at the rate of one compute unit, so passes are what a
+      // rejection costs): the residual goes to the spare buffer while its sum forms, and what q keeps
+      // once x is gone is summed from the entries alongside (a difference of the old sum and wq[x]
+      // would cancel when the drafter was nearly certain of x).
       __syncthreads();                       // every thread has read wp[x], wq[x]
-      double z = 0.0;
+      double z = 0.0, s = 0.0;
       for (int v = tid; v < V; v += kDraftThreads) {
-        const double r = fmax(wp[v] * sp - wq[v] * sq, 0.0);
+        const double qv = wq[v];
+        const double r = fmax(wp[v] * sp - qv * sq, 0.0);
+        wp_spare[v] = r;
         z += r;
+        s += (valid && v == x) ? 0.0 : qv;
       }
       z = wg_sum(z, sh_d);
-      if (z > 0.0) {
-        for (int v = tid; v < V; v += kDraftThreads) wp[v] = fmax(wp[v] * sp - wq[v] * sq, 0.0);
+      s = wg_sum(s, sh_d);                   // (its barriers: every thread is done with the old wq[x])
+      if (z > 0.0) {                         // else p = q exactly: p is kept
+        double* const tmp = wp; wp = wp_spare; wp_spare = tmp;
         sp = 1.0 / z;
       }
-      __syncthreads();                       // every thread is done with the old wq[x]
       if (valid && tid == 0) wq[x] = 0.0;
-      __syncthreads();
-      // what q keeps once x is gone, summed again from the entries (a difference of the old sum and
-      // wq[x] would cancel when the drafter was nearly certain of x)
-      double s = 0.0;
-      for (int v = tid; v < V; v += kDraftThreads) s += wq[v];
-      s = wg_sum(s, sh_d);
       sq = s > 0.0 ? 1.0 / s : sq;
       __syncthreads();
     }
@@ -704,47 +725,76 @@ __global__ __launch_bounds__(kDraftThreads) void accept_sample_draft_kernel(cons
       continue;
     }
 
-    if (!filled) fill();
-    // no child accepted: inverse-CDF draw from the current p. Thread k owns the contiguous entries
-    // [k * per, (k + 1) * per); the target is u times the sum formed in the same order as the scan.
-    const int per = (V + kDraftThreads - 1) / kDraftThreads;
-    const int v0 = tid * per, v1 = min(V, v0 + per);
+    if (!filled) fill_p();
+    // no child accepted: inverse-CDF draw from the current p. Wavefront w owns the contiguous range
+    // [w * per_wave, (w + 1) * per_wave) and walks it in chunks of 64 consecutive entries (one per
+    // lane: the loads are contiguous), summing chunk totals in chunk order; the same chunk totals, in
+    // the same order, locate the crossing afterwards.
+    const int lane = tid & 63, wave = tid >> 6;
+    const int per_wave = (V + kDraftThreads - 1) / kDraftThreads * 64;
+    const int w0 = wave * per_wave, w1 = min(V, w0 + per_wave);
+    auto chunk_total = [&](double x) {
+#pragma unroll
+      for (int off = 32; off > 0; off >>= 1) x += __shfl_xor(x, off);
+      return x;
+    };
     double mine = 0.0;
-    for (int v = v0; v < v1; ++v) mine += wp[v];
-    scan_incl[tid] = mine;
+    for (int c0 = w0; c0 < w1; c0 += 64) mine += chunk_total(c0 + lane < w1 ? wp[c0 + lane] : 0.0);
+    __syncthreads();                  // sh_d may still be read from the last reduction
+    if (lane == 0) sh_d[wave] = mine;
+    if (tid == 0) sh_tok = -1;
     __syncthreads();
-    for (int off = 1; off < kDraftThreads; off <<= 1) {   // Hillis-Steele inclusive scan
-      const double add = tid >= off ? scan_incl[tid - off] : 0.0;
-      __syncthreads();
-      scan_incl[tid] += add;
-      __syncthreads();
+    double total = 0.0, before = 0.0;
+    for (int w = 0; w < kDraftWaves; ++w) {
+      if (w == wave) before = total;
+      total += sh_d[w];
     }
-    const double total = scan_incl[kDraftThreads - 1];
     const double t = (double)u_draw[cur] * total;
-    if (tid == 0) { sh_tok = -1; sh_last = kDraftThreads; }
-    __syncthreads();
-    // the scanned sums chain from 0 to the total, so some segment brackets t; they are formed in
-    // different orders and need not be monotone to the last bit: the first bracketing segment counts
-    const double before = tid > 0 ? scan_incl[tid - 1] : 0.0;
-    if (before <= t && t < scan_incl[tid]) atomicMin(&sh_last, tid);
-    __syncthreads();
-    if (tid == sh_last) {
+    // the first wavefront whose range brackets t (the same arithmetic in every thread)
+    int owner = -1;
+    {
+      double run = 0.0;
+      for (int w = 0; w < kDraftWaves && owner < 0; ++w) {
+        run += sh_d[w];
+        if (run > t) owner = w;
+      }
+    }
+    if (wave == owner) {
       double run = before;
       int tok = -1;
-      for (int v = v0; v < v1; ++v) {
-        run += wp[v];
-        if (run > t) { tok = v; break; }
+      for (int c0 = w0; c0 < w1 && tok < 0; c0 += 64) {
+        const double x = c0 + lane < w1 ? wp[c0 + lane] : 0.0;
+        const double tot = chunk_total(x);
+        if (run + tot > t) {
+          double incl = x;            // running sum inside the chunk, lane order
+#pragma unroll
+          for (int off = 1; off < 64; off <<= 1) {
+            const double up = __shfl_up(incl, off);
+            if (lane >= off) incl += up;
+          }
+          const unsigned long long hit = __ballot(run + incl > t && x > 0.0);
+          const unsigned long long mass = __ballot(x > 0.0);
+          // (the chunk's total and its lane-order running sum are formed in different orders: if the
+          // running sum falls short by rounding, the chunk's last entry with mass)
+          tok = c0 + (hit ? __ffsll(hit) - 1 : 63 - __clzll(mass));
+        }
+        run += tot;
       }
-      if (tok < 0)   // the segment's own sum said "here" but its running sum fell short: its last entry with mass
-        for (int v = v1 - 1; v >= v0; --v)
-          if (wp[v] > 0.0) { tok = v; break; }
-      sh_tok = tok;
+      if (tok < 0) {   // the range's total said "here", its chunk-by-chunk sum fell short: its last entry with mass
+        int last = -1;
+        for (int c0 = w0; c0 < w1; c0 += 64)
+          if (c0 + lane < w1 && wp[c0 + lane] > 0.0) last = c0 + lane;
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) last = max(last, __shfl_xor(last, off));
+        tok = last;
+      }
+      if (lane == 0) sh_tok = tok;
     }
     __syncthreads();
-    if (sh_tok < 0) {   // rounding left no crossing: the last entry with mass (0 if none)
+    if (sh_tok < 0) {   // no mass at all, or rounding left no crossing: the last entry with mass (0 if none)
       int last = -1;
-      for (int v = v1 - 1; v >= v0; --v)
-        if (wp[v] > 0.0) { last = v; break; }
+      for (int c0 = w0; c0 < w1; c0 += 64)
+        if (c0 + lane < w1 && wp[c0 + lane] > 0.0) last = c0 + lane;
       if (tid == 0) sh_last = -1;
       __syncthreads();
       if (last >= 0) atomicMax(&sh_last, last);   // the highest such entry over the workgroup
@@ -815,8 +865,8 @@ extern "C" fspad_status fspad_tree_accept_sample(int32_t B, int32_t Nmax, int32_
 
 extern "C" size_t fspad_tree_accept_sample_draft_workspace_bytes(int32_t B, int32_t Nmax, int32_t V) {
   if (B < 1 || Nmax < 1 || V < 1) return 0;
-  // chunk statistics of both logit arrays, then 2 V fp64 entries per sequence
-  return 2 * fspad_tree_accept_workspace_bytes(B, Nmax, V) + (((size_t)B * 2 * (size_t)V * 8 + 255) & ~(size_t)255);
+  // chunk statistics of both logit arrays, then 3 V fp64 entries per sequence
+  return 2 * fspad_tree_accept_workspace_bytes(B, Nmax, V) + (((size_t)B * 3 * (size_t)V * 8 + 255) & ~(size_t)255);
 }
 
 extern "C" fspad_status fspad_tree_accept_sample_draft(int32_t B, int32_t Nmax, int32_t V, const float* logits,

@@ -178,7 +178,7 @@ def test_sampled_draft_acceptance_argument_checks_need_no_gpu(lib):
     fake = ctypes.c_void_p(0x1000)   # never dereferenced: every case below fails validation first
     i32, i64, sz = ctypes.c_int32, ctypes.c_int64, ctypes.c_size_t
     need = fspad.fspad_tree_accept_sample_draft_workspace_bytes(2, 26, 32000)
-    assert need >= 2 * 2 * 32000 * 8
+    assert need >= 2 * 3 * 32000 * 8
 
     def call(B=2, N=26, V=32000, logits=fake, dl=fake, stride=32000, T=1.0, uni=fake, ws=fake, wsb=need):
         return f(i32(B), i32(N), i32(V), logits, dl, i64(stride), fake, fake, fake, ctypes.c_float(T), uni,
