@@ -131,3 +131,52 @@ def test_bad_arguments_are_errors():
         fspad.fspad_tree_accept_sample_draft(logits, logits, tok, par, nn, 1.0, uni,
                                              workspace=torch.empty(16, dtype=torch.uint8, device=DEV))
     torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("draw", range(10))
+def test_random_shape(draw):
+    """Batch, tree size, vocabulary, temperature, drafter noise and target peakedness at random."""
+    rng = np.random.default_rng([616, draw])
+    B = int(rng.integers(1, 7))
+    N = int(rng.integers(1, 65))
+    V = int(rng.choice([3, 64, 65, 1000, 4097, 20000, 50257]))
+    T = float(rng.choice([0.5, 1.0, 1.7]))
+    n_nodes = [int(rng.integers(1, N + 1)) for _ in range(B)]
+    _run(6000 + draw, B, N, V, T, useed=draw, peak=float(rng.choice([0.0, 2.0, 4.0])), noise=float(rng.choice([0.2, 1.0, 3.0])),
+         n_nodes=n_nodes, row_pad=int(rng.choice([0, 0, 4])), depth=8, topk=int(rng.integers(3, 11)), min_compared=max(1, B - 1))
+
+
+def test_captured_call_replays_like_eager():
+    import paper_2408_15562_amd as fspad
+    B, N, V, T = 3, 30, 5000, 1.0
+    parent, n_nodes, logits, draft_logits, tokens = _case(91, B, N, V, T, peak=2.0, noise=0.5)
+    dev = [torch.from_numpy(a).to(DEV) for a in (logits, draft_logits, tokens, parent, n_nodes, gen_uniforms(1, B, N))]
+    outs = tuple(torch.empty(s, dtype=torch.int32, device=DEV) for s in ((B, N), (B,), (B, N), (B,)))
+    ws = torch.empty(fspad.fspad_tree_accept_sample_draft_workspace_bytes(B, N, V), dtype=torch.uint8, device=DEV)
+
+    def step():
+        fspad.fspad_tree_accept_sample_draft(dev[0], dev[1], dev[2], dev[3], dev[4], T, dev[5], outputs=outs, workspace=ws)
+
+    def snapshot():
+        torch.cuda.synchronize()
+        return [t.clone() for t in outs]
+
+    def scrub():
+        for t in outs:
+            t.fill_(-9)
+        ws.random_()
+        torch.cuda.synchronize()
+
+    step()
+    eager = snapshot()
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        scrub()
+        with torch.cuda.graph(graph, stream=side):
+            step()
+    for _ in range(3):
+        scrub()
+        graph.replay()
+        for a, b in zip(eager, snapshot()):
+            assert torch.equal(a, b)
