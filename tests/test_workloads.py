@@ -59,3 +59,34 @@ def test_config_byte_counts_match_stated_sizes():
     assert abs(c3.step_bytes() / 1e9 - 26.97) < 0.1      # Vicuna-33B stack: 26.97 GB per step
     assert abs(CONFIGS["c4"].step_flops() / 1e12 - 2.586) < 0.01
     assert chain_tree(4).tolist() == [-1, 0, 1, 2]
+
+
+def test_sampled_drafts_are_distinct_per_parent_and_repeatable():
+    from workloads import gen_logits, gen_sampled_drafts, gen_trees
+    B, N, V = 3, 20, 50
+    parent, n_nodes = gen_trees(5, B, N, 4, 4, n_nodes=[20, 7, 1])
+    logits = gen_logits(5, B, N, V)
+    dl, tok = gen_sampled_drafts(5, logits, parent, n_nodes, 0.8)
+    dl2, tok2 = gen_sampled_drafts(5, logits, parent, n_nodes, 0.8)
+    assert np.array_equal(dl, dl2) and np.array_equal(tok, tok2)
+    assert dl.dtype == np.float32 and dl.shape == logits.shape and tok.dtype == np.int32
+    assert not np.array_equal(dl, logits)
+    for b in range(B):
+        for p in range(int(n_nodes[b])):
+            kids = [c for c in range(p + 1, int(n_nodes[b])) if parent[b, c] == p]
+            assert len(set(tok[b, kids].tolist())) == len(kids)       # drawn without replacement
+            assert all(0 <= t < V for t in tok[b, kids])
+
+
+def test_draft_layer_inputs_are_bf16_values_with_unit_scale():
+    from workloads import gen_draft_layer, round_to_bf16, tree_depths, gen_trees
+    d = gen_draft_layer(3, 2, 5, 256, 512, 4, 2, 64, 16)
+    assert d["w_qkv"].shape == (8 * 64, 256) and d["w_down"].shape == (512, 512) and d["k_cache"].shape == (2, 2, 16, 64)
+    for k, a in d.items():
+        assert a.dtype == np.float32 and np.array_equal(a, round_to_bf16(a)), k
+    assert 0.8 < d["eta"].std() < 1.2
+    assert 0.8 < (d["eta"][0] @ d["w_qkv"].T).std() < 1.2           # projections keep O(1) entries
+    parent, n_nodes = gen_trees(3, 2, 5, 3, 2, n_nodes=[5, 2])
+    depth = tree_depths(parent, n_nodes)
+    assert depth[0, 0] == 0 and all(depth[0, i] == depth[0, parent[0, i]] + 1 for i in range(1, 5))
+    assert depth[1, 2:].tolist() == [0, 0, 0]
