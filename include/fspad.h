@@ -82,6 +82,11 @@ typedef struct {
   int64_t cache_stride_batch; /* k_cache/v_cache element (b,g,j,d) is at                */
   int64_t cache_stride_head;  /*   b*stride_batch + g*stride_head + j*stride_token + d  */
   int64_t cache_stride_token; /* >= D; all three multiples of 8 elements (16 bytes bf16) */
+  int32_t workgroups;      /* tuning: 0 = the built-in choice; 1..4096 forces the number of workgroups the
+                              bf16 path spreads its key blocks over. Results do not depend on it beyond
+                              fp32 rounding of the merge; fspad_tree_attn_workspace_bytes reads it too, so
+                              sizing and call must see the same value */
+  int32_t reserved;        /* 0 */
 } fspad_attn_desc;
 
 /*
@@ -109,12 +114,6 @@ typedef struct {
  * probabilities rounded to bf16.
  */
 size_t fspad_tree_attn_workspace_bytes(const fspad_attn_desc* desc, int32_t max_kv_len);
-
-/* Tuning knob, process-wide: force the number of workgroups the bf16 path spreads
- * its key blocks over (1..4096); 0 restores the built-in choice. It changes
- * fspad_tree_attn_workspace_bytes too, so set it before sizing the workspace.
- * Not needed for correct results. */
-void fspad_tree_attn_set_workgroups(int32_t workgroups);
 
 fspad_status fspad_tree_attn(const fspad_attn_desc* desc,
                              const void* q, const void* k_tree, const void* v_tree,

@@ -30,7 +30,6 @@ from .binding import (  # noqa: F401
     fspad_tree_accept_sample_lm_head,
     fspad_tree_accept_workspace_bytes,
     fspad_tree_attn,
-    fspad_tree_attn_set_workgroups,
     fspad_tree_attn_workspace_bytes,
     fspad_tree_build,
     fspad_tree_build_mask,

@@ -23,7 +23,7 @@ FSPAD_MAX_NODES = 64
 _STATUS_NAMES = {0: "FSPAD_OK", 1: "FSPAD_ERR_NULL", 2: "FSPAD_ERR_SHAPE", 3: "FSPAD_ERR_TREE",
                  4: "FSPAD_ERR_DTYPE", 5: "FSPAD_ERR_WORKSPACE", 6: "FSPAD_ERR_TEMPERATURE", 7: "FSPAD_ERR_HIP"}
 
-EXPORTS = ("fspad_tree_attn_workspace_bytes", "fspad_tree_attn_set_workgroups", "fspad_tree_attn",
+EXPORTS = ("fspad_tree_attn_workspace_bytes", "fspad_tree_attn",
            "fspad_tree_accept_workspace_bytes", "fspad_tree_accept_greedy", "fspad_tree_accept_sample",
            "fspad_tree_accept_sample_draft_workspace_bytes", "fspad_tree_accept_sample_draft",
            "fspad_tree_accept_lm_head_workspace_bytes", "fspad_tree_accept_greedy_lm_head",
@@ -46,7 +46,7 @@ class fspad_attn_desc(ctypes.Structure):
                 ("n_kv_heads", ctypes.c_int32), ("head_dim", ctypes.c_int32), ("io_dtype", ctypes.c_int32),
                 ("out_dtype", ctypes.c_int32), ("softmax_scale", ctypes.c_float),
                 ("cache_stride_batch", ctypes.c_int64), ("cache_stride_head", ctypes.c_int64),
-                ("cache_stride_token", ctypes.c_int64)]
+                ("cache_stride_token", ctypes.c_int64), ("workgroups", ctypes.c_int32), ("reserved", ctypes.c_int32)]
 
 
 class fspad_draft_layer_desc(ctypes.Structure):
@@ -75,8 +75,6 @@ def _lib():
         lib.fspad_status_string.argtypes = [ctypes.c_int]
         lib.fspad_tree_attn_workspace_bytes.restype = sz
         lib.fspad_tree_attn_workspace_bytes.argtypes = [ctypes.POINTER(fspad_attn_desc), i32]
-        lib.fspad_tree_attn_set_workgroups.restype = None
-        lib.fspad_tree_attn_set_workgroups.argtypes = [i32]
         lib.fspad_tree_attn.restype = ctypes.c_int
         lib.fspad_tree_attn.argtypes = [ctypes.POINTER(fspad_attn_desc)] + [vp] * 9 + [vp, sz, vp]
         lib.fspad_tree_accept_workspace_bytes.restype = sz
@@ -193,7 +191,8 @@ def _dtype_code(dt: torch.dtype) -> int:
 
 
 def make_attn_desc(q: torch.Tensor, k_tree: torch.Tensor, k_cache: Optional[torch.Tensor],
-                   out_dtype: Optional[torch.dtype] = None, softmax_scale: float = 0.0) -> fspad_attn_desc:
+                   out_dtype: Optional[torch.dtype] = None, softmax_scale: float = 0.0,
+                   workgroups: int = 0) -> fspad_attn_desc:
     """Fill the descriptor from tensor shapes; cache strides are taken from k_cache."""
     B, Nmax, Hq, D = q.shape
     Hkv = k_tree.shape[2]
@@ -202,6 +201,7 @@ def make_attn_desc(q: torch.Tensor, k_tree: torch.Tensor, k_cache: Optional[torc
     d.io_dtype = _dtype_code(q.dtype)
     d.out_dtype = _dtype_code(out_dtype if out_dtype is not None else q.dtype)
     d.softmax_scale = float(softmax_scale)
+    d.workgroups = int(workgroups)
     if k_cache is not None:
         if k_cache.stride(3) != 1:
             raise ValueError("head_dim must be contiguous in the cache")
@@ -217,18 +217,15 @@ def fspad_tree_attn_workspace_bytes(desc: fspad_attn_desc, max_kv_len: int) -> i
     return int(_lib().fspad_tree_attn_workspace_bytes(ctypes.byref(desc), int(max_kv_len)))
 
 
-def fspad_tree_attn_set_workgroups(splits: int) -> None:
-    _lib().fspad_tree_attn_set_workgroups(int(splits))
-
-
 def fspad_tree_attn(q: torch.Tensor, k_tree: torch.Tensor, v_tree: torch.Tensor,
                     k_cache: Optional[torch.Tensor], v_cache: Optional[torch.Tensor],
                     kv_len, n_nodes, anc_mask: torch.Tensor, out: Optional[torch.Tensor] = None,
                     workspace: Optional[torch.Tensor] = None, softmax_scale: float = 0.0,
                     out_dtype: Optional[torch.dtype] = None, stream=None,
-                    desc: Optional[fspad_attn_desc] = None, prepare: bool = False):
+                    desc: Optional[fspad_attn_desc] = None, prepare: bool = False, workgroups: int = 0):
     """q [B,Nmax,Hq,D]; k_tree,v_tree [B,Nmax,Hkv,D]; k_cache,v_cache [B,Hkv,Lcap,D] views (any
-    batch/head/token strides); kv_len,n_nodes HOST int32 [B]; anc_mask device int64/uint64 [B,Nmax].
+    batch/head/token strides); kv_len,n_nodes HOST int32 [B]; anc_mask device int64/uint64 [B,Nmax];
+    workgroups: the descriptor's tuning field (0 = built-in choice), used when no desc is given.
     Returns out [B,Nmax,Hq,D]; with prepare=True a PreparedCall that issues the call each time it is called."""
     for name, t in (("q", q), ("k_tree", k_tree), ("v_tree", v_tree)):
         if not t.is_contiguous():
@@ -238,7 +235,7 @@ def fspad_tree_attn(q: torch.Tensor, k_tree: torch.Tensor, v_tree: torch.Tensor,
         raise ValueError("k_cache and v_cache must share strides and the dtype of q")
     if desc is None:
         desc = make_attn_desc(q, k_tree, k_cache, out_dtype if out_dtype is not None else
-                              (out.dtype if out is not None else None), softmax_scale)
+                              (out.dtype if out is not None else None), softmax_scale, workgroups)
     kv_len = _host_i32(kv_len, "kv_len")
     n_nodes = _host_i32(n_nodes, "n_nodes")
     if kv_len.shape != (desc.batch,) or n_nodes.shape != (desc.batch,):

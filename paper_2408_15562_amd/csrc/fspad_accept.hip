@@ -481,10 +481,10 @@ __global__ __launch_bounds__(kThreads) void accept_sample_walk_kernel(const Acce
 
 // Largest chunk that still gives about a thousand workgroups (rows x chunks), so that a few rows of
 // a small vocabulary are spread over the whole chip.
-int g_target_wgs = 1024;
+constexpr int kTargetWorkgroups = 1024;
 int pick_chunk(int32_t B, int32_t Nmax, int32_t V) {
   int chunk = kMaxChunk;
-  while (chunk > kMinChunk && (int64_t)B * Nmax * ((V + chunk - 1) / chunk) < g_target_wgs) chunk >>= 1;
+  while (chunk > kMinChunk && (int64_t)B * Nmax * ((V + chunk - 1) / chunk) < kTargetWorkgroups) chunk >>= 1;
   return chunk;
 }
 
@@ -813,9 +813,6 @@ __global__ __launch_bounds__(kDraftThreads) void accept_sample_draft_kernel(cons
 
 }  // namespace
 
-// Experiment knob (not part of the declared interface): workgroups the row pass aims for.
-extern "C" void fspad_debug_set_accept_target(int32_t wgs) { g_target_wgs = wgs; }
-
 extern "C" size_t fspad_tree_accept_workspace_bytes(int32_t B, int32_t Nmax, int32_t V) {
   if (B < 1 || Nmax < 1 || V < 1) return 0;
   const size_t slots = (size_t)B * Nmax * ((V + kMinChunk - 1) / kMinChunk);  // room for the finest split
@@ -877,6 +874,7 @@ extern "C" fspad_status fspad_tree_accept_sample_draft(int32_t B, int32_t Nmax, 
                                                        int32_t* n_tokens, void* workspace, size_t workspace_bytes,
                                                        void* hip_stream) {
   if (!draft_logits || !uniforms) return FSPAD_ERR_NULL;
+  if (((uintptr_t)draft_logits) & 3) return FSPAD_ERR_SHAPE;
   const size_t need = fspad_tree_accept_sample_draft_workspace_bytes(B, Nmax, V);
   const fspad_status st = check_accept_args(B, Nmax, V, logits, row_stride, draft_tokens, parent, n_nodes, path, path_len,
                                             tokens, n_tokens, workspace, workspace_bytes >= need ? workspace_bytes : 0);

@@ -1065,10 +1065,9 @@ struct Plan {
 
 constexpr int64_t kComputeUnits = 256;
 constexpr int64_t kMaxWorkgroups = 32768;
-int64_t kShortStreamBlocks = 16;  // blocks per workgroup below which a stream counts as short (experiment knob below)
-int g_forced_wgs = 0;
-int g_max_qt = 4;
-int g_max_ws = 8;
+constexpr int64_t kShortStreamBlocks = 16;  // blocks per workgroup below which a stream counts as short
+constexpr int kMaxQT = 4;                   // 16-row tiles per wavefront at most
+constexpr int kMaxForcedWorkgroups = 4096;  // upper limit of fspad_attn_desc.workgroups
 
 // Row tiling of one kv head's N*G query rows: slabs of 16*QT rows, WS slabs per workgroup.
 void plan_rows(const fspad_attn_desc& d, Plan& pl, int max_ws = 4) {
@@ -1077,11 +1076,10 @@ void plan_rows(const fspad_attn_desc& d, Plan& pl, int max_ws = 4) {
   const int G = d.n_q_heads / d.n_kv_heads;
   const int rows = d.n_nodes_max * G;
   int best_cost = 1 << 30;
-  for (int qt = g_max_qt; qt >= 1; --qt) {  // ties go to the larger tile: fewer re-reads of K/V
+  for (int qt = kMaxQT; qt >= 1; --qt) {  // ties go to the larger tile: fewer re-reads of K/V
     const int ns = (rows + 16 * qt - 1) / (16 * qt);
     int ws = ns == 1 ? 1 : (ns == 2 ? 2 : 4);
-    if (ws > g_max_ws) ws = g_max_ws;
-    if (ws > max_ws) ws = max_ws;  // (ws is 4 at most here; 8 is the eight-wavefront kernel's own plan)
+    if (ws > max_ws) ws = max_ws;
     const int gy = (ns + ws - 1) / ws;
     const int cost = gy * ws * qt;
     if (cost < best_cost) { best_cost = cost; pl.QT = qt; pl.NS = ns; pl.WS = ws; pl.GY = gy; }
@@ -1089,17 +1087,16 @@ void plan_rows(const fspad_attn_desc& d, Plan& pl, int max_ws = 4) {
   pl.rows_per_unit = pl.WS * 16 * pl.QT;
 }
 
-// The shared-stage kernel's plan: 32-row slabs, one per wavefront, four or eight per workgroup.
+// The shared-stage kernel's plan: 32-row slabs, one per wavefront, four per workgroup.
 bool gqa_plan_applies(const fspad_attn_desc& d) {
-  return g_max_ws >= 8 && d.n_nodes_max * (d.n_q_heads / d.n_kv_heads) > 4 * 32;
+  return d.n_nodes_max * (d.n_q_heads / d.n_kv_heads) > 4 * 32;
 }
-int g_gqa_waves = 4;
 void plan_rows_gqa(const fspad_attn_desc& d, Plan& pl) {
   pl.shared_stage = true;
   pl.short_stream = false;
   pl.QT = 2;
   pl.NS = (d.n_nodes_max * (d.n_q_heads / d.n_kv_heads) + 31) / 32;
-  pl.WS = g_gqa_waves;
+  pl.WS = 4;
   pl.GY = (pl.NS + pl.WS - 1) / pl.WS;
   pl.rows_per_unit = 32 * pl.WS;
 }
@@ -1115,7 +1112,7 @@ int blocks_of(int kv_len, int n_nodes) {
 // the compute units: every unit is then cut into the same number of pieces and no workgroup
 // straddles two units (a second segment costs a short-lived workgroup as much as its blocks do).
 // With one piece per unit nothing is cut and nothing is merged.
-int plan_wgs(const Plan& pl, int64_t total_blocks, int64_t units, bool uniform) {
+int plan_wgs(const Plan& pl, int64_t total_blocks, int64_t units, bool uniform, int forced) {
   const int KW = pl.WS >= 4 ? 1 : 4 / pl.WS;
   // (eight wavefronts of 256 registers fill a compute unit by themselves)
   const int64_t resident = (pl.QT <= 2 && pl.WS < 8 && !pl.short_stream) ? 512 : 256;
@@ -1136,7 +1133,7 @@ int plan_wgs(const Plan& pl, int64_t total_blocks, int64_t units, bool uniform) 
       if (short_pieces && 4 * units * pieces >= 3 * (wgs < kComputeUnits ? wgs : kComputeUnits)) wgs = units * pieces;
     }
   }
-  if (g_forced_wgs > 0) wgs = g_forced_wgs;
+  if (forced > 0) wgs = forced < kMaxForcedWorkgroups ? forced : kMaxForcedWorkgroups;
   if (wgs > kMaxWorkgroups) wgs = kMaxWorkgroups;  // the kernels form w * (T mod W) in 32 bits
   if (wgs > total_blocks) wgs = total_blocks;
   if (wgs < 1) wgs = 1;
@@ -1162,6 +1159,7 @@ fspad_status check_desc(const fspad_attn_desc* d) {
   if (d->io_dtype != FSPAD_F32 && d->io_dtype != FSPAD_BF16) return FSPAD_ERR_DTYPE;
   if (d->out_dtype != FSPAD_F32 && d->out_dtype != d->io_dtype) return FSPAD_ERR_DTYPE;
   if (!(d->softmax_scale >= 0.f) || d->softmax_scale > 3.0e38f) return FSPAD_ERR_SHAPE;
+  if (d->workgroups < 0) return FSPAD_ERR_SHAPE;
   return FSPAD_OK;
 }
 
@@ -1178,17 +1176,6 @@ void launch_bf16(const Plan& pl, const AttnParams& prm, hipStream_t stream) {
 
 }  // namespace
 
-// Experiment knobs (not part of the declared interface; the benchmark's hidden flags use them):
-// upper limits for the row slabs per workgroup and the 16-row tiles per wavefront.
-extern "C" void fspad_debug_set_gqa_waves(int32_t waves) { g_gqa_waves = waves >= 8 ? 8 : 4; }
-extern "C" void fspad_debug_set_short_stream(int32_t blocks) { kShortStreamBlocks = blocks < 0 ? 0 : blocks; }
-extern "C" void fspad_debug_set_max_ws(int32_t ws) { g_max_ws = ws >= 8 ? 8 : (ws >= 4 ? 4 : (ws >= 2 ? 2 : 1)); }
-extern "C" void fspad_debug_set_max_qt(int32_t qt) { g_max_qt = qt < 1 ? 1 : (qt > 4 ? 4 : qt); }
-
-extern "C" void fspad_tree_attn_set_workgroups(int32_t workgroups) {
-  g_forced_wgs = workgroups > 0 ? (workgroups > 4096 ? 4096 : workgroups) : 0;
-}
-
 extern "C" size_t fspad_tree_attn_workspace_bytes(const fspad_attn_desc* desc, int32_t max_kv_len) {
   if (check_desc(desc) != FSPAD_OK || max_kv_len < 0) return 0;
   if (desc->io_dtype == FSPAD_F32) return 16;
@@ -1203,8 +1190,8 @@ extern "C" size_t fspad_tree_attn_workspace_bytes(const fspad_attn_desc* desc, i
     const int nb = desc->batch < kMaxBatchPerLaunch ? desc->batch : kMaxBatchPerLaunch;
     const int64_t units = (int64_t)nb * desc->n_kv_heads * pl.GY;
     const int64_t total = units * blocks_of(max_kv_len, desc->n_nodes_max);
-    int64_t wgs = plan_wgs(pl, total, units, true);
-    const int64_t wgs_cut = plan_wgs(pl, total, units, false);  // a ragged batch of the same size
+    int64_t wgs = plan_wgs(pl, total, units, true, desc->workgroups);
+    const int64_t wgs_cut = plan_wgs(pl, total, units, false, desc->workgroups);  // a ragged batch of the same size
     if (wgs_cut > wgs) wgs = wgs_cut;
     const int64_t slots = units + wgs;
     const size_t bytes = (size_t)slots * slot_bytes(*desc, pl);
@@ -1284,7 +1271,7 @@ extern "C" fspad_status fspad_tree_attn(const fspad_attn_desc* desc, const void*
       if (pl.WS == 4) {
         const int64_t units4 = (int64_t)nb * d.n_kv_heads * pl.GY;
         const int64_t total4 = (int64_t)d.n_kv_heads * pl.GY * seq_blocks;
-        const bool short_stream = total4 < kShortStreamBlocks * plan_wgs(pl, total4, units4, uniform);
+        const bool short_stream = total4 < kShortStreamBlocks * plan_wgs(pl, total4, units4, uniform, d.workgroups);
         if (gqa_plan_applies(d)) {
           // more than four 32-row slabs per kv head: wavefronts of 32 rows that share every K/V
           // block through LDS (measured on a 32/8-head layer, 4096 keys, 60 nodes: 24.9 us against
@@ -1296,7 +1283,7 @@ extern "C" fspad_status fspad_tree_attn(const fspad_attn_desc* desc, const void*
         }
       }
       sl.WS = pl.WS; sl.NS = pl.NS; sl.GY = pl.GY;
-      sl.ws_shift = pl.WS == 8 ? 3 : (pl.WS == 4 ? 2 : (pl.WS == 2 ? 1 : 0));
+      sl.ws_shift = pl.WS == 4 ? 2 : (pl.WS == 2 ? 1 : 0);
       sl.gy_magic = pl.GY > 1 ? (uint32_t)(((1ull << 32) + pl.GY - 1) / pl.GY) : 0u;
       const int64_t units_per_seq = (int64_t)d.n_kv_heads * pl.GY;
       int64_t total = 0;
@@ -1308,16 +1295,13 @@ extern "C" fspad_status fspad_tree_attn(const fspad_attn_desc* desc, const void*
       sl.bstart[nb] = (int32_t)total;
       sl.total_blocks = (int32_t)total;
       const int64_t units = (int64_t)nb * units_per_seq;
-      sl.n_wgs = plan_wgs(pl, total, units, uniform);
+      sl.n_wgs = plan_wgs(pl, total, units, uniform, d.workgroups);
       sl.wg_quot = (int32_t)(total / sl.n_wgs);
       sl.wg_rem = (int32_t)(total % sl.n_wgs);
       const int64_t slots = units + sl.n_wgs;
       const size_t need = (size_t)slots * slot_bytes(d, pl);
       if (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 15)) return FSPAD_ERR_WORKSPACE;
-      if (pl.WS == 8) {
-        if (d.head_dim == 128) hipLaunchKernelGGL((tree_attn_gqa_kernel<128, 8>), dim3((unsigned)sl.n_wgs), dim3(512), 0, stream, sl);
-        else hipLaunchKernelGGL((tree_attn_gqa_kernel<64, 8>), dim3((unsigned)sl.n_wgs), dim3(512), 0, stream, sl);
-      } else if (pl.shared_stage) {
+      if (pl.shared_stage) {
         if (d.head_dim == 128) hipLaunchKernelGGL((tree_attn_gqa_kernel<128, 4>), dim3((unsigned)sl.n_wgs), dim3(256), 0, stream, sl);
         else hipLaunchKernelGGL((tree_attn_gqa_kernel<64, 4>), dim3((unsigned)sl.n_wgs), dim3(256), 0, stream, sl);
       } else if (d.head_dim == 128) {

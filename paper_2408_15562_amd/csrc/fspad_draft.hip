@@ -283,9 +283,9 @@ __global__ __launch_bounds__(256) void qkv_rope_kernel(const QkvRopeParams p) {
 // with this target, 83 and 95 us with one workgroup per unit, 84 and 97 us with two: a workgroup
 // that streams few chunks is mostly set-up, and every split adds a partial tile to write and read
 // back), never less than two chunks per split
-int g_target_wgs = 180;
+constexpr int kTargetWorkgroups = 180;
 void plan_splits(int n_slices, int n_chunks, int problems, int& n_splits, int& chunks_per_split) {
-  int want = (2 * g_target_wgs + n_slices * problems) / (2 * n_slices * problems);   // rounded to nearest
+  int want = (2 * kTargetWorkgroups + n_slices * problems) / (2 * n_slices * problems);   // rounded to nearest
   if (want < 1) want = 1;
   chunks_per_split = (n_chunks + want - 1) / want;
   if (chunks_per_split < 2) chunks_per_split = n_chunks < 2 ? n_chunks : 2;
@@ -294,9 +294,9 @@ void plan_splits(int n_slices, int n_chunks, int problems, int& n_splits, int& c
 
 // measured at 4096 / 11008, 4 rows: Feature Sampler 78.4 us without the rotation, 72.1 / 72.4 / 71.5 us with
 // 1 / 3 / 5 stages between consecutive slices; decoder layer 164.5 against 158.5 / 158.3 / 158.8 us
-int g_stagger = 3;
+constexpr int kStagger = 3;
 void launch_partial(PartialGemmParams g, int problems, hipStream_t stream) {
-  g.stagger = g_stagger;
+  g.stagger = kStagger;
   const dim3 grid((unsigned)(g.n_slices * g.n_splits), (unsigned)problems);
   if (g.packed) {
     if (g.rows <= 16) hipLaunchKernelGGL((partial_gemm_kernel<1, 16, true>), grid, dim3(512), 0, stream, g);
@@ -328,10 +328,6 @@ Plan make_plan(int rows, int Hd, int I) {
 }
 
 }  // namespace
-
-// Experiment knob (not part of the declared interface): workgroups a projector launch aims for.
-extern "C" void fspad_debug_set_sampler_target(int32_t wgs) { g_target_wgs = wgs < 1 ? 1 : wgs; }
-extern "C" void fspad_debug_set_sampler_stagger(int32_t stages) { g_stagger = stages < 0 ? 0 : stages; }
 
 extern "C" size_t fspad_feature_sampler_workspace_bytes(int32_t rows, int32_t hidden_dim, int32_t intermediate_dim) {
   if (rows < 1 || rows > kMaxRows || hidden_dim < kChunkK || hidden_dim % kChunkK || intermediate_dim < kChunkK ||

@@ -593,16 +593,13 @@ __global__ __launch_bounds__(kWalkThreads) void lm_head_sample_walk_kernel(const
 }
 
 int n_slices_of(int32_t V) { return (V + kVocabPerWg - 1) / kVocabPerWg; }
-// Workgroup s starts its k loop (s * g_stagger) stages in and wraps around, so that the workgroups
+// Workgroup s starts its k loop (s * kStagger) stages in and wraps around, so that the workgroups
 // running at the same time read different parts of their rows: with every workgroup at the same k
 // the requests in flight differ only in address bits above the row pitch and crowd a few memory
 // channels (measured on a 32000 x 4096 head: 59.8 us without, 52.4 us with).
-int g_stagger = 3;
+constexpr int kStagger = 3;
 
 }  // namespace
-
-// Experiment knob (not part of the declared interface): the k rotation between workgroups (0: none).
-extern "C" void fspad_debug_set_lm_head_stagger(int32_t stages) { g_stagger = stages < 0 ? 0 : stages; }
 
 namespace {
 
@@ -634,7 +631,7 @@ fspad_status launch_lm_head(LmHeadParams& g, int32_t hidden_dim, hipStream_t str
   if ((int64_t)g.n_slices * g.n_passes > 0x7fffffff) return FSPAD_ERR_SHAPE;
   // (a stage of the small shapes is 512 k: a hidden size that is not a multiple of it has a partial
   // last stage, which the rotation does not handle)
-  g.stagger = (g.rows_per_pass > 64 || hidden_dim % 512 == 0) ? g_stagger : 0;
+  g.stagger = (g.rows_per_pass > 64 || hidden_dim % 512 == 0) ? kStagger : 0;
   const dim3 grid((unsigned)(g.n_slices * g.n_passes));
   const int r = g.rows_per_pass;
   if (r <= 16) hipLaunchKernelGGL((lm_head_argmax_kernel<1, 16, 16, 8, 1, MODE, PACKED>), grid, dim3(512), 0, stream, g);

@@ -6,7 +6,7 @@ import torch
 
 import oracle
 import paper_2408_15562_amd as fspad
-from workloads import gen_draft_tokens, gen_lm_head, gen_logits, gen_qkv, gen_trees, gen_uniforms
+from workloads import gen_draft_tokens, gen_lm_head, gen_lm_head_exact, gen_logits, gen_qkv, gen_trees, gen_uniforms
 
 DEV = "cuda:0"
 TOL = {"bf16": 2e-2, "f32": 1e-5}   # max-abs-error relative to the RMS of the oracle output
@@ -48,13 +48,10 @@ class AttnCase:
         self.mask_dev = torch.from_numpy(self.mask.view(np.int64)).to(DEV)
 
     def run_gpu(self, out_dtype=torch.float32, scale=0.0, splits=0):
-        fspad.fspad_tree_attn_set_workgroups(splits)
-        try:
-            out = fspad.fspad_tree_attn(self.q, self.k_tree, self.v_tree, self.k_cache, self.v_cache, self.kv_len,
-                                        self.n_nodes, self.mask_dev, softmax_scale=scale, out_dtype=out_dtype)
-            torch.cuda.synchronize()
-        finally:
-            fspad.fspad_tree_attn_set_workgroups(0)
+        out = fspad.fspad_tree_attn(self.q, self.k_tree, self.v_tree, self.k_cache, self.v_cache, self.kv_len,
+                                    self.n_nodes, self.mask_dev, softmax_scale=scale, out_dtype=out_dtype,
+                                    workgroups=splits)
+        torch.cuda.synchronize()
         return out
 
     def run_oracle(self, scale=None, heads=None, nthreads=16):
@@ -139,10 +136,10 @@ class LmHeadCase:
     """Greedy acceptance from hidden states on both sides. The draft tokens are the top entries of a
     perturbed copy of the oracle's own logits, so that walks go several levels deep."""
 
-    def __init__(self, seed, B, N, Hd, V, depth=6, topk=10, n_nodes=None, noise=1.0):
+    def __init__(self, seed, B, N, Hd, V, depth=6, topk=10, n_nodes=None, noise=1.0, exact=False):
         topk = min(topk, max(1, N - 1))
         self.parent, self.n_nodes = gen_trees(seed, B, N, depth, topk, n_nodes=n_nodes)
-        self.hidden, self.w = gen_lm_head(seed, B, N, Hd, V)
+        self.hidden, self.w = (gen_lm_head_exact if exact else gen_lm_head)(seed, B, N, Hd, V)
         logits = (self.hidden.reshape(B * N, Hd) @ self.w.T).reshape(B, N, V)   # fp32: only steers the drafts
         self.tokens = gen_draft_tokens(seed, logits, self.parent, self.n_nodes, "greedy", noise)
         self.shape = (B, N, Hd, V)
@@ -212,9 +209,25 @@ def assert_lm_head_equal(gpu, cpu, require_decided=True):
 LM_HEAD_SAMPLE_MARGIN = 1e-4
 
 
+LM_HEAD_SAMPLE_STATS = {"sequences": 0, "compared": 0, "excluded": 0, "excluded_that_differ": 0}
+
+
 def assert_lm_head_sample_equal(gpu, cpu, min_compared=0.75):
+    """Sequences whose smallest decision margin is above LM_HEAD_SAMPLE_MARGIN must agree bit for bit.
+    The others are not asserted on, but they are counted: how many of them actually differ is
+    printed (and accumulated in LM_HEAD_SAMPLE_STATS), so that the exclusion is measured, not assumed."""
     margin = cpu[4]
     keep = margin >= LM_HEAD_SAMPLE_MARGIN
     assert keep.mean() >= min_compared, f"only {keep.sum()} of {keep.size} sequences are decided: pick another seed"
     assert_accept_equal(gpu, cpu, keep=keep)
+    same = np.ones(keep.shape, dtype=bool)
+    for g, c in zip(gpu, cpu[:4]):
+        same &= (g.reshape(len(keep), -1) == c.reshape(len(keep), -1)).all(axis=1)
+    differ = int((~same & ~keep).sum())
+    LM_HEAD_SAMPLE_STATS["sequences"] += int(keep.size)
+    LM_HEAD_SAMPLE_STATS["compared"] += int(keep.sum())
+    LM_HEAD_SAMPLE_STATS["excluded"] += int((~keep).sum())
+    LM_HEAD_SAMPLE_STATS["excluded_that_differ"] += differ
+    print(f"lm_head sampling: {int(keep.sum())}/{keep.size} sequences above the margin (all equal); "
+          f"{int((~keep).sum())} below it, of which {differ} differ from the oracle")
     return int(keep.sum())

@@ -59,22 +59,13 @@ def test_bf16_gqa_and_head_dim(H, Hq, Hkv, D, N):
     _check(H, case, H.TOL["bf16"])
 
 
-@pytest.mark.parametrize("waves", [4, 8])
 @pytest.mark.parametrize("N,Hq,Hkv,D", [(60, 8, 2, 128), (40, 4, 1, 64), (26, 16, 2, 128), (64, 8, 1, 64)])
 @pytest.mark.parametrize("L,splits", [(0, 0), (33, 0), (200, 0), (1000, 0), (1000, 7), (3000, 64)])
-def test_bf16_shared_stage_kernel_both_workgroup_sizes(H, waves, N, Hq, Hkv, D, L, splits):
+def test_bf16_shared_stage_kernel(H, N, Hq, Hkv, D, L, splits):
     """Grouped-query shapes with more than 128 rows per KV head take the kernel whose wavefronts
-    share K/V blocks through LDS; its workgroup size is a library knob, and both sizes must agree
-    with the oracle (the eight-wavefront one keeps two blocks per stage)."""
-    import ctypes
-    import paper_2408_15562_amd as fspad
-    lib = ctypes.CDLL(fspad.library_path())
-    lib.fspad_debug_set_gqa_waves(waves)
-    try:
-        case = H.AttnCase(31 * N + L + waves, 2, N, Hq, Hkv, D, L, "bf16", l_cap=L + 9)
-        _check(H, case, H.TOL["bf16"], **({"splits": splits} if splits else {}))
-    finally:
-        lib.fspad_debug_set_gqa_waves(4)
+    share K/V blocks through LDS."""
+    case = H.AttnCase(31 * N + L + 4, 2, N, Hq, Hkv, D, L, "bf16", l_cap=L + 9)
+    _check(H, case, H.TOL["bf16"], **({"splits": splits} if splits else {}))
 
 
 @pytest.mark.parametrize("splits", [1, 2, 3, 7, 16, 50, 333, 4096])

@@ -27,6 +27,11 @@ def test_library_exports_every_declared_symbol(lib):
     assert declared == set(fspad.EXPORTS)
     for name in declared:
         assert hasattr(lib, name), name
+    # ... and nothing beyond it: the dynamic symbol table holds no other fspad_* name
+    import subprocess
+    table = subprocess.run(["nm", "-D", "--defined-only", fspad.library_path()], capture_output=True, text=True, check=True).stdout
+    exported = {line.split()[-1] for line in table.splitlines() if line.split() and line.split()[-1].startswith("fspad_")}
+    assert exported == declared, sorted(exported ^ declared)
 
 
 def test_status_strings():
@@ -105,6 +110,7 @@ def test_attn_argument_checks_need_no_gpu(lib):
     assert call(_desc(), nnp=(ctypes.c_int32 * 1)(27)) == 2
     assert call(_desc(), kvp=(ctypes.c_int32 * 1)(-1)) == 2
     assert call(_desc(), wsb=16) == 5
+    assert call(_desc(workgroups=-1)) == 2
     assert binding.fspad_tree_attn_workspace_bytes(_desc(), 2048) > 16
     assert binding.fspad_tree_attn_workspace_bytes(_desc(head_dim=96), 2048) == 0
 
