@@ -48,6 +48,87 @@ def test_first_emitted_token_follows_the_target(m, grid):
     np.testing.assert_allclose(got, [0.5, 0.3, 0.15, 0.05], atol=1.5 / grid)
 
 
+def _log_rows(*rows):
+    return np.log(np.array(rows, dtype=np.float64))[None]          # [1, nodes, V]
+
+
+def test_exact_counts_on_a_rational_case_one_level():
+    """Target p = (1/2, 1/4, 1/8, 1/8) against drafter q = (1/8, 1/8, 1/4, 1/2): every threshold of the
+    rule (min(1, p/q) in {1, 1/2, 1/4}; the residual after one rejection (3/4, 1/4, 0, 0); after two
+    (7/8, 1/8, 0, 0) or (1, 0, 0, 0); the running sums of every distribution a draw can see) is a
+    multiple of 1/8, so with every uniform on the midpoints of an 8-cell grid the emitted-token counts,
+    weighted with the exact probability of each ordered draw of the drafter, must equal p as
+    fractions -- no tolerance."""
+    from fractions import Fraction as F
+    p = [F(1, 2), F(1, 4), F(1, 8), F(1, 8)]
+    q = [F(1, 8), F(1, 8), F(1, 4), F(1, 2)]
+    grid = 8
+    us = (np.arange(grid) + 0.5) / grid
+    for m in (1, 2):
+        rows = _log_rows(*([[float(x) for x in p]] * (m + 1)))
+        qrows = _log_rows(*([[float(x) for x in q]] * (m + 1)))
+        parent = np.array([[-1] + [0] * m], dtype=np.int32)
+        total = [F(0)] * 4
+        for draw in itertools.permutations(range(4), m):
+            prob, rest = F(1), F(1)
+            for x in draw:
+                prob *= q[x] / rest
+                rest -= q[x]
+            tokens = np.array([[0] + list(draw)], dtype=np.int32)
+            counts = [0] * 4
+            for u in itertools.product(us, repeat=m + 1):
+                uni = np.zeros((1, 2, m + 1))
+                uni[0, 0, 1:] = u[:m]
+                uni[0, 1, :] = u[m]
+                _, _, emitted, _, margin = oracle.accept_sample_draft(rows, qrows, tokens, parent, [m + 1], 1.0, uni)
+                assert margin[0] > 1e-3          # no walk sits on a threshold
+                counts[int(emitted[0, 0])] += 1
+            for y in range(4):
+                total[y] += prob * F(counts[y], grid ** (m + 1))
+        assert total == p, (m, total)
+
+
+def test_exact_counts_on_a_two_level_tree():
+    """Root -> A -> B, A drawn from the root's drafter row, B from A's. Given that A (token x) was
+    accepted, the second emitted token must follow A's own target row exactly:
+        sum_y q_A(y) * #(walks through A that emit b second | x, y) / grid^3 = min(1, p(x)/q(x)) * p_A(b)
+    as fractions, for every x and b; every threshold is again a multiple of 1/8."""
+    from fractions import Fraction as F
+    p0 = [F(1, 2), F(1, 4), F(1, 8), F(1, 8)]; q0 = [F(1, 8), F(1, 8), F(1, 4), F(1, 2)]
+    pA = [F(1, 8), F(1, 8), F(1, 4), F(1, 2)]; qA = [F(1, 2), F(1, 4), F(1, 8), F(1, 8)]
+    pB = p0                                     # the leaf's own row: running sums 1/2, 3/4, 7/8
+    f = lambda r: [float(x) for x in r]
+    rows, qrows = _log_rows(f(p0), f(pA), f(pB)), _log_rows(f(q0), f(qA), f(q0))
+    parent = np.array([[-1, 0, 1]], dtype=np.int32)
+    grid = 8
+    us = (np.arange(grid) + 0.5) / grid
+    first = [F(0)] * 4                          # distribution of the first emitted token, over everything
+    for x in range(4):
+        second = [F(0)] * 4
+        through_a = F(0)
+        for y in range(4):
+            tokens = np.array([[0, x, y]], dtype=np.int32)
+            cnt_first, cnt_second, cnt_a = [0] * 4, [0] * 4, 0
+            for ua, ub, ud in itertools.product(us, repeat=3):
+                uni = np.zeros((1, 2, 3))
+                uni[0, 0, 1], uni[0, 0, 2], uni[0, 1, :] = ua, ub, ud
+                path, plen, emitted, _, margin = oracle.accept_sample_draft(rows, qrows, tokens, parent, [3], 1.0, uni)
+                assert margin[0] > 1e-3
+                cnt_first[int(emitted[0, 0])] += 1
+                if plen[0] >= 2:
+                    assert path[0, 1] == 1 and emitted[0, 0] == x
+                    cnt_a += 1
+                    cnt_second[int(emitted[0, 1])] += 1
+            for b in range(4):
+                second[b] += qA[y] * F(cnt_second[b], grid ** 3)
+                first[b] += q0[x] * qA[y] * F(cnt_first[b], grid ** 3)
+            through_a += qA[y] * F(cnt_a, grid ** 3)
+        accept_x = min(F(1), p0[x] / q0[x])
+        assert through_a == accept_x, (x, through_a)
+        assert second == [accept_x * pb for pb in pA], (x, second)
+    assert first == p0, first
+
+
 def test_point_mass_drafts_are_the_topk_acceptance():
     rng = np.random.default_rng(3)
     B, N, V = 3, 9, 50

@@ -1,14 +1,41 @@
 """CPU pins of the oracle's dynamic-tree selection (no GPU): a hand-worked example, brute force
 over every ancestor-closed subset on tiny candidate sets, structural invariants on
-EAGLE-2-shaped candidate sets, the host mask builder as an independent check of the emitted
-ancestor words, and tie handling."""
+EAGLE-2-shaped candidate sets, a closure and a validator written out here as independent checks of
+the emitted arrays, and tie handling. Nothing of the GPU library is used."""
 import itertools
 
 import numpy as np
 
 import oracle
-import paper_2408_15562_amd as fspad
 from workloads import gen_candidates
+
+
+def _well_formed(parent, tokens, n_nodes, V):
+    """parent[0] = -1, every later parent precedes its child, tokens in range, siblings distinct."""
+    for b in range(parent.shape[0]):
+        n = int(n_nodes[b])
+        if n < 1 or parent[b, 0] != -1:
+            return False
+        seen = set()
+        for i in range(1, n):
+            p, t = int(parent[b, i]), int(tokens[b, i])
+            if not (0 <= p < i) or not (0 <= t < V) or (p, t) in seen:
+                return False
+            seen.add((p, t))
+    return True
+
+
+def _ancestor_words(parent, n_nodes):
+    """bit t of word [b,i] <=> t is i or one of its ancestors, by walking up from every node."""
+    words = np.zeros(parent.shape, dtype=np.uint64)
+    for b in range(parent.shape[0]):
+        for i in range(int(n_nodes[b])):
+            w, a = 0, i
+            while a >= 0:
+                w |= 1 << a
+                a = int(parent[b, a])
+            words[b, i] = w
+    return words
 
 
 def test_hand_worked_example():
@@ -58,8 +85,8 @@ def test_invariants_on_shaped_candidates():
     for n_keep, n_max in ((60, 64), (26, 26), (1, 8)):
         parent, tokens, n_nodes, mask, cand = oracle.tree_build(par, tok, logp, n_cand, n_keep, n_max)
         assert np.array_equal(n_nodes, np.minimum(n_cand, n_keep))
-        assert fspad.fspad_tree_validate(parent, tokens, n_nodes, 32000) == 0       # a well-formed tree
-        assert np.array_equal(mask, fspad.fspad_tree_build_mask(parent, n_nodes))   # independent mask builder
+        assert _well_formed(parent, tokens, n_nodes, 32000)
+        assert np.array_equal(mask, _ancestor_words(parent, n_nodes))               # independent closure
         for b in range(par.shape[0]):
             n = int(n_nodes[b])
             c = cand[b, :n]
@@ -85,4 +112,4 @@ def test_ties_go_to_the_lower_index_and_nan_ranks_last():
     assert cand[0].tolist() == [0, 1, 2, 4]
     par, tok, logp, n_cand = gen_candidates(12, 3, 5, 4, 1000, ties=True)
     parent, tokens, n_nodes, mask, cand = oracle.tree_build(par, tok, logp, n_cand, 26, 26)
-    assert fspad.fspad_tree_validate(parent, tokens, n_nodes, 1000) == 0
+    assert _well_formed(parent, tokens, n_nodes, 1000)
