@@ -21,6 +21,7 @@ from .generators import (  # noqa: F401
     gen_uniforms,
     gen_candidates,
     gen_lm_head,
+    gen_lm_head_exact,
     gen_feature_sampler,
     gen_draft_layer,
     gen_sampled_drafts,

@@ -209,6 +209,16 @@ def gen_lm_head(seed: int, batch: int, n_max: int, hidden_dim: int, vocab: int, 
     return hidden, round_to_bf16(w)
 
 
+def gen_lm_head_exact(seed: int, batch: int, n_max: int, hidden_dim: int, vocab: int):
+    """Hidden states with entries in {-2..2} and LM-head weights with entries in {-1/8, 0, 1/8}: every
+    product and every partial sum of a logit is a multiple of 1/8 below 2^8, so the logits are exact in
+    fp32 whatever the order of summation (spread about 2.8 at hidden_dim 256)."""
+    rng = np.random.default_rng([seed, 0xE8AC])
+    hidden = rng.integers(-2, 3, (batch, n_max, hidden_dim)).astype(np.float32)
+    w = rng.integers(-1, 2, (vocab, hidden_dim)).astype(np.float32) * np.float32(0.125)
+    return hidden, w
+
+
 def gen_feature_sampler(seed: int, rows: int, hidden_dim: int, intermediate_dim: int):
     """Inputs and projector weights of a Feature Sampler, all rounded to bf16 and returned as fp32:
     f, e [rows,Hd] ~ N(0,1); w_up, w_gate [I,Hd] ~ N(0, 1/Hd); w_down [Hd,I] ~ N(0, 1/I) -- the scales
