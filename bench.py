@@ -7,14 +7,20 @@ acceptance call over the per-node logits.  Inputs are synthetic, seeded, residen
 in HBM before the timed region; single-layer workloads rotate through enough
 independent buffer sets that they stream from HBM rather than the last-level cache.
 
-Prints ONE JSON line: metric / value / unit (steps per second), ms_per_step, the workload in `config`,
-the event-timed attention and acceptance calls, `roofline` of the attention call and `cpu_baseline`.
+Prints ONE JSON line.  Its top level is the headline workload (default c3, the Vicuna-33B-shaped
+stack): metric / value / unit (steps per second), ms_per_step, the workload in `config`, the
+event-timed attention and acceptance calls, `roofline` of the attention call, `step_roofline` of the
+whole step and `cpu_baseline`.  `other_workloads` holds a short run of each of the other
+configurations (same keys, fewer of them), `measured_roofs` what a plain streaming read and a
+register-resident matrix-core loop reach on this machine; every roofline carries `frac` against the
+published peak and `frac_vs_measured` against those.  `--only` prints the one workload alone.
 """
 from __future__ import annotations
 
 import argparse
 import json
 import os
+import re
 import sys
 import time
 
@@ -24,6 +30,7 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0      # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0
+TRAFFIC_PROFILE = os.path.join("profiles", "tree_verify_traffic.txt")
 
 
 def parse_args():
@@ -31,26 +38,26 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=None)
-    ap.add_argument("--workload", default="c1", choices=["c0", "c1", "c2", "c3", "c4"])
+    ap.add_argument("--workload", default="c3", choices=["c0", "c1", "c2", "c3", "c4"])
+    ap.add_argument("--only", action="store_true",
+                    help="run the one workload alone: no short runs of the other workloads, no measured roofs "
+                         "(profiling runs; the extra options below imply it)")
     ap.add_argument("--accept", default=None, choices=["greedy", "sample", "sample-draft"],
                     help="override the workload's acceptance mode (sample-draft: drafts sampled from a draft distribution, "
                          "accepted against it with fspad_tree_accept_sample_draft)")
     ap.add_argument("--sets", type=int, default=None, help="independent buffer sets to rotate through")
-    ap.add_argument("--splits", type=int, default=0, help="force the number of attention workgroups (0 = automatic)")
+    ap.add_argument("--splits", type=int, default=0,
+                    help="fspad_attn_desc.workgroups: force the number of attention workgroups (0 = the library's choice)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--max-qt", type=int, default=0, help=argparse.SUPPRESS)
-    ap.add_argument("--max-ws", type=int, default=0, help=argparse.SUPPRESS)
-    ap.add_argument("--gqa-waves", type=int, default=0, help=argparse.SUPPRESS)
     ap.add_argument("--event-every", type=int, default=0,
                     help="bracket the attention calls of every n-th timed step with timing events (0 = every max(4, steps/12)-th)")
-    ap.add_argument("--accept-target", type=int, default=0, help=argparse.SUPPRESS)
     ap.add_argument("--layers", type=int, default=None, help="profiling only: run fewer layers of a stack (the result line is then not the workload's)")
     ap.add_argument("--nodes", type=int, default=None, help="experiments only: override the tree size")
     ap.add_argument("--heads", type=int, default=None, help="experiments only: override the head count (MHA)")
     ap.add_argument("--kv-len", type=int, default=None, help="experiments only: override the prefix length")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
-                    help="profiling only: before the timed region, copy a buffer of this many MiB three times "
-                         "(a kernel of known HBM traffic next to which rocprofv3 byte counters can be scaled)")
+                    help="profiling only: before the timed region, copy a buffer of this many MiB three times with "
+                         "roofs_copy_kernel (a kernel of known HBM traffic next to which rocprofv3 byte counters can be scaled)")
     ap.add_argument("--commit", action="store_true",
                     help="also append the accepted path's keys/values to every layer's cache after the acceptance "
                          "(fspad_kv_commit; the caches then carry room for one more tree)")
@@ -73,13 +80,9 @@ def parse_args():
                     help="start the acceptance from the last hidden states instead of ready-made logits. "
                          "fused = fspad_tree_accept_{greedy,sample}_lm_head (logits never written); unfused = library GEMM "
                          "to bf16 logits, widened to fp32, then fspad_tree_accept_{greedy,sample} (the comparison)")
-    ap.add_argument("--lm-stagger", type=int, default=None, help=argparse.SUPPRESS)
-    ap.add_argument("--sampler-target", type=int, default=0, help=argparse.SUPPRESS)
-    ap.add_argument("--sampler-stagger", type=int, default=None, help=argparse.SUPPRESS)
     ap.add_argument("--packed-weights", action="store_true",
                     help="with --feature-sampler fused / --draft-layer fused / --lm-head fused: the weight matrices are repacked once into "
                          "the tile order of fspad_pack_weight (same results, faster streaming)")
-    ap.add_argument("--short-stream", type=int, default=None, help=argparse.SUPPRESS)
     ap.add_argument("--hidden-dim", type=int, default=None, help="hidden size for --lm-head (default: the workload's model)")
     ap.add_argument("--seed", type=int, default=2024)
     return ap.parse_args()
@@ -91,6 +94,45 @@ def main():
         print("bench.py: this build runs on exactly one GPU (no collectives, no sharding); use --gpus 1", file=sys.stderr)
         sys.exit(2)
 
+    import torch
+
+    import paper_2408_15562_amd as fspad
+
+    fspad.library_path()  # fail loudly if the HIP library is missing
+    if not torch.cuda.is_available():
+        raise RuntimeError("bench.py needs a GPU")
+    torch.cuda.set_device(torch.device("cuda:0"))
+    extras = any((args.commit, args.tree_build, args.draft_topk, args.feature_sampler, args.draft_layer, args.lm_head,
+                  args.layers is not None, args.nodes is not None, args.heads is not None, args.kv_len is not None,
+                  args.copy_calibration, args.accept is not None, args.splits))
+    only = args.only or extras or args.workload == "c0"
+    # everything runs on one side stream: the prepared calls, the timing events and the captured graph share it
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        result = run_workload(args, args.workload, args.steps, args.warmup, primary=True)
+        if not only:
+            others = {}
+            for name in ("c1", "c2", "c3", "c4"):
+                if name == args.workload:
+                    continue
+                rec = run_workload(args, name, None, None, primary=False)
+                others[name] = {k: rec[k] for k in ("value", "unit", "steps", "warmup", "ms_per_step", "config", "step_roofline",
+                                                    "roofline", "attn_call_us", "accept_call_us", "steps_per_s_graph_replay",
+                                                    "steps_per_s_one_buffer_set_cache_resident", "mean_tokens_per_step") if k in rec}
+            result["other_workloads"] = others
+            roofs = measure_roofs(torch, torch.cuda.current_stream().cuda_stream)
+            result["measured_roofs"] = roofs
+            for rec in [result] + list(others.values()):
+                for key in ("roofline", "step_roofline"):
+                    r = rec[key]
+                    r["frac_vs_measured"] = r["achieved"] / (roofs["hbm_read_gb_per_s"] if r["bound"] == "hbm"
+                                                            else roofs["mfma_bf16_tflops"])
+    print(json.dumps(result))
+
+
+def run_workload(args, workload, steps_arg, warmup_arg, primary):
+    """Builds the workload's buffers, times its steps and returns its record. `primary`: the headline
+    workload (honours every command-line option and carries cpu_baseline); otherwise a short plain run."""
     import numpy as np
     import torch
 
@@ -98,12 +140,13 @@ def main():
     from workloads import (CONFIGS, GENERATOR_VERSION, gen_candidates, gen_draft_tokens, gen_logits, gen_sampled_drafts, gen_trees,
                            gen_uniforms, tree_depths)
 
-    fspad.library_path()  # fail loudly if the HIP library is missing
-    if not torch.cuda.is_available():
-        raise RuntimeError("bench.py needs a GPU")
+    if not primary:   # none of the command line's experiment options apply to the short runs
+        args = argparse.Namespace(**{**vars(args), **dict(
+            accept=None, sets=None, splits=0, layers=None, nodes=None, heads=None, kv_len=None, copy_calibration=0, commit=False,
+            tree_build=False, draft_topk=False, feature_sampler=None, draft_layer=None, lm_head=None, packed_weights=False,
+            hidden_dim=None, no_cpu_baseline=True, event_every=0)})
     dev = torch.device("cuda:0")
-    torch.cuda.set_device(dev)
-    cfg = CONFIGS[args.workload]
+    cfg = CONFIGS[workload]
     if args.layers is not None:
         import dataclasses
         cfg = dataclasses.replace(cfg, layers=args.layers, name=cfg.name + f"-{args.layers}layers")
@@ -124,8 +167,8 @@ def main():
     # single-layer workloads are far smaller than the 256 MB last-level cache: rotate buffer sets
     set_bytes = cfg.step_bytes()
     n_sets = args.sets if args.sets is not None else (1 if set_bytes > 2e9 else max(2, int(np.ceil(1.0e9 / set_bytes))))
-    steps = args.steps if args.steps is not None else (20 if set_bytes > 2e9 else 200)
-    warmup = args.warmup if args.warmup is not None else (3 if set_bytes > 2e9 else 20)
+    steps = steps_arg if steps_arg is not None else (20 if set_bytes > 2e9 else 200)
+    warmup = warmup_arg if warmup_arg is not None else (3 if set_bytes > 2e9 else 20)
 
     gen = torch.Generator(device=dev)
     gen.manual_seed(args.seed)
@@ -157,7 +200,7 @@ def main():
     n_nodes_d = torch.from_numpy(n_nodes).to(dev)
     hidden_dim = 0
     if args.lm_head:
-        hidden_dim = args.hidden_dim or {"c0": 256, "c1": 4096, "c2": 4096, "c3": 6656, "c4": 8192}[args.workload]
+        hidden_dim = args.hidden_dim or {"c0": 256, "c1": 4096, "c2": 4096, "c3": 6656, "c4": 8192}[workload]
         # the weights are streamed once per step; between two steps of a real model every layer's weights
         # pass through the caches, so a few copies are rotated to keep them out of the 256 MB last-level cache
         w_copies = [torch.empty((V, hidden_dim), device=dev, dtype=torch.bfloat16).normal_(generator=gen)
@@ -169,32 +212,8 @@ def main():
             st["w"] = w_copies[i % len(w_copies)]
             st["hidden"] = torch.empty((B, N, hidden_dim), device=dev, dtype=torch.bfloat16).normal_(generator=gen)
 
-    if args.accept_target:
-        import ctypes
-        ctypes.CDLL(fspad.library_path()).fspad_debug_set_accept_target(args.accept_target)
-    if args.short_stream is not None:
-        import ctypes
-        ctypes.CDLL(fspad.library_path()).fspad_debug_set_short_stream(args.short_stream)
-    if args.sampler_target:
-        import ctypes
-        ctypes.CDLL(fspad.library_path()).fspad_debug_set_sampler_target(args.sampler_target)
-    if args.sampler_stagger is not None:
-        import ctypes
-        ctypes.CDLL(fspad.library_path()).fspad_debug_set_sampler_stagger(args.sampler_stagger)
-    if args.lm_stagger is not None:
-        import ctypes
-        ctypes.CDLL(fspad.library_path()).fspad_debug_set_lm_head_stagger(args.lm_stagger)
-    if args.gqa_waves:
-        import ctypes
-        ctypes.CDLL(fspad.library_path()).fspad_debug_set_gqa_waves(args.gqa_waves)
-    if args.max_ws:
-        import ctypes
-        ctypes.CDLL(fspad.library_path()).fspad_debug_set_max_ws(args.max_ws)
-    if args.max_qt:
-        import ctypes
-        ctypes.CDLL(fspad.library_path()).fspad_debug_set_max_qt(args.max_qt)
-    fspad.fspad_tree_attn_set_workgroups(args.splits)
-    desc = fspad.make_attn_desc(sets[0]["layers"][0][0], sets[0]["layers"][0][1], sets[0]["layers"][0][3], tdt, 0.0)
+    desc = fspad.make_attn_desc(sets[0]["layers"][0][0], sets[0]["layers"][0][1], sets[0]["layers"][0][3], tdt, 0.0,
+                                workgroups=args.splits)
     ws_attn = torch.empty(max(16, fspad.fspad_tree_attn_workspace_bytes(desc, L)), dtype=torch.uint8, device=dev)
     ws_acc = torch.empty(fspad.fspad_tree_accept_workspace_bytes(B, N, V), dtype=torch.uint8, device=dev)
     ws_draft = (torch.empty(fspad.fspad_tree_accept_sample_draft_workspace_bytes(B, N, V), dtype=torch.uint8, device=dev)
@@ -237,7 +256,7 @@ def main():
             st["topk"] = [fspad.fspad_draft_topk(draft_logits, min(cfg.tree_topk, 16), prepare=True)] * cfg.tree_depth
         st["sampler"] = []
         if args.feature_sampler:
-            Hd_fs, I_fs = DRAFT_DIMS[args.workload]
+            Hd_fs, I_fs = DRAFT_DIMS[workload]
             rows_fs = min(128, B * cfg.tree_topk)
             if "fs_w" not in sets[0]:
                 sets[0]["fs_w"] = [[torch.empty(shape, device=dev, dtype=torch.bfloat16).normal_(generator=gen).mul_(shape[1] ** -0.5)
@@ -256,7 +275,7 @@ def main():
             st["sampler_bytes"] = 2 * (3 * Hd_fs * I_fs + 3 * rows_fs * Hd_fs)
         st["layer"] = []
         if args.draft_layer:
-            Hd_dl, I_dl = DRAFT_DIMS[args.workload]
+            Hd_dl, I_dl = DRAFT_DIMS[workload]
             n_dl = cfg.tree_topk
             if B * n_dl > 128 or cfg.dtype != "bf16":
                 raise SystemExit("--draft-layer: the layer takes at most 128 rows (batch x top-k) of bf16 per call")
@@ -351,7 +370,7 @@ def main():
         src = torch.empty(args.copy_calibration << 20, dtype=torch.uint8, device=dev).random_(generator=gen)
         dst = torch.empty_like(src)
         for _ in range(3):
-            dst.copy_(src)
+            roofs_call("roofs_hbm_copy", src.data_ptr(), dst.data_ptr(), src.numel(), 2048, stream_handle)
         torch.cuda.synchronize()
         del src, dst
 
@@ -396,6 +415,26 @@ def main():
         step(0)
     torch.cuda.synchronize()
     ms_per_step_resident = (time.perf_counter() - t4) * 1e3 / steps
+
+    # And the same steps replayed from a captured graph (one graph holds a step over every buffer set, so
+    # the replays stream from HBM like the timed loop): the launch cost of the 2 to 4 kernels of a small
+    # step is then the graph's, not Python's and the runtime's. Only the verification calls are captured.
+    graph_steps_per_s = None
+    if not (args.feature_sampler or args.draft_layer or args.lm_head == "unfused"):
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=torch.cuda.current_stream()):
+            for i in range(n_sets):
+                step(i)
+        replays = max(1, steps // n_sets)
+        for _ in range(2):
+            graph.replay()
+        torch.cuda.synchronize()
+        t5 = time.perf_counter()
+        for _ in range(replays):
+            graph.replay()
+        torch.cuda.synchronize()
+        graph_steps_per_s = replays * n_sets / (time.perf_counter() - t5)
+        del graph
     props = torch.cuda.get_device_properties(0)
 
     attn_bytes = cfg.attn_bytes_per_layer()
@@ -409,9 +448,19 @@ def main():
                         frac=achieved_tflops / MFMA_BF16_PEAK_TFLOPS)
     else:
         roofline = dict(bound="hbm", achieved=achieved_gbs, peak=HBM_PEAK_GBS, unit="GB/s", frac=achieved_gbs / HBM_PEAK_GBS)
+    traffic = read_profiled_traffic(workload) if (default_shape and not args.splits) else None
     roofline.update(kernel="fspad_tree_attn (split-KV kernel + merge kernel)", launch_ms=attn_ms,
                     algorithmic_bytes=attn_bytes, algorithmic_flops=attn_flops,
-                    traffic=MEASURED_TRAFFIC_BYTES.get(args.workload) if default_shape else None)
+                    hbm_frac=achieved_gbs / HBM_PEAK_GBS, mfma_frac=achieved_tflops / MFMA_BF16_PEAK_TFLOPS,
+                    traffic=traffic, traffic_source=TRAFFIC_PROFILE if traffic is not None else None)
+    # the whole step (every layer's attention call and the acceptance call, launch gaps included) against the same roof
+    step_s = ms_per_step * 1e-3
+    if mfma_bound:
+        step_roofline = dict(bound="mfma", achieved=cfg.step_flops() / step_s / 1e12, peak=MFMA_BF16_PEAK_TFLOPS, unit="TFLOP/s")
+    else:
+        step_roofline = dict(bound="hbm", achieved=cfg.step_bytes() / step_s / 1e9, peak=HBM_PEAK_GBS, unit="GB/s")
+    step_roofline["frac"] = step_roofline["achieved"] / step_roofline["peak"]
+    step_roofline.update(algorithmic_bytes=cfg.step_bytes(), algorithmic_flops=cfg.step_flops())
 
     result = {
         "metric": "tree-verify steps/s", "value": 1e3 / ms_per_step, "unit": "steps/s", "n_gpus": 1, "steps": steps,
@@ -423,6 +472,7 @@ def main():
                    "seed": args.seed, "generator_version": GENERATOR_VERSION, "parallelism": "single-gpu"},
         "step_gb_per_s": cfg.step_bytes() / (ms_per_step * 1e-3) / 1e9,
         "step_hbm_frac": cfg.step_bytes() / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "step_roofline": step_roofline,
         "attn_tflops": achieved_tflops, "attn_gb_per_s": achieved_gbs,
         "attn_call_us": {"mean": attn_ms * 1e3, "p10": float(np.percentile(call_ms, 10)) * 1e3,
                          "p50": float(np.percentile(call_ms, 50)) * 1e3, "p90": float(np.percentile(call_ms, 90)) * 1e3,
@@ -431,6 +481,7 @@ def main():
                            "samples": int(accept_ms.size)},
         "steps_per_s_with_host_readback": 1e3 / ms_per_step_sync,
         "steps_per_s_one_buffer_set_cache_resident": 1e3 / ms_per_step_resident,
+        "steps_per_s_graph_replay": graph_steps_per_s,
         "device": {"name": props.name, "arch": getattr(props, "gcnArchName", ""), "compute_units": props.multi_processor_count,
                    "hbm_bytes": props.total_memory, "clocks": read_clock_levels()},
         "mean_tokens_per_step": n_tokens_mean,
@@ -463,9 +514,88 @@ def main():
                              "weight_passes": passes if args.lm_head == "fused" else 1,
                              "gb_per_s": head_bytes / call_s / 1e9, "hbm_frac": head_bytes / call_s / 1e9 / HBM_PEAK_GBS,
                              "tflops": 2.0 * B * N * hidden_dim * V / call_s / 1e12}
-    if not args.no_cpu_baseline:
+    if primary and not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(cfg, accept, sets[0], parent, n_nodes, kv_len, args.seed)
-    print(json.dumps(result))
+    del sets
+    torch.cuda.synchronize()
+    torch.cuda.empty_cache()
+    return result
+
+
+_ROOFS = None
+
+
+def roofs_call(name, *call_args):
+    """One call into libfspad_roofs.so (the benchmark's measurement kernels; not the verification library)."""
+    import ctypes
+    global _ROOFS
+    if _ROOFS is None:
+        from paper_2408_15562_amd.build import ROOFS_LIB_PATH
+        if not os.path.exists(ROOFS_LIB_PATH):
+            raise RuntimeError(f"{ROOFS_LIB_PATH} is missing: build it first (__graft_entry__.build())")
+        lib = ctypes.CDLL(ROOFS_LIB_PATH)
+        vp, sz, i32 = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int
+        lib.roofs_hbm_read.argtypes = [vp, sz, vp, i32, vp]
+        lib.roofs_hbm_copy.argtypes = [vp, vp, sz, i32, vp]
+        lib.roofs_mfma_bf16.argtypes = [i32, i32, i32, vp, vp]
+        _ROOFS = lib
+    rc = getattr(_ROOFS, name)(*call_args)
+    if rc != 0:
+        raise RuntimeError(f"{name} failed: {rc}")
+
+
+def measure_roofs(torch, stream_handle):
+    """What this machine reaches on the two roofs, with the simplest kernels that can reach them: a
+    streaming read of 4 GiB, 16 bytes per lane (HBM), and a register-resident loop of bf16 matrix-core
+    instructions (both tile shapes; the better one counts). Event-timed, five launches each after two
+    warm-up launches."""
+    dev = torch.device("cuda:0")
+    sink = torch.zeros(64, dtype=torch.float32, device=dev)
+
+    def timed(launch, reps=5):
+        for _ in range(2):
+            launch()
+        torch.cuda.synchronize()
+        e0, e1 = TimingEvent(stream_handle), TimingEvent(stream_handle)
+        e0.record()
+        for _ in range(reps):
+            launch()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e-3 / reps
+
+    nbytes = 4 << 30
+    buf = torch.empty(nbytes, dtype=torch.uint8, device=dev).random_()
+    best_read = 0.0
+    for wgs in (2048, 4096, 8192):
+        t = timed(lambda: roofs_call("roofs_hbm_read", buf.data_ptr(), nbytes, sink.data_ptr(), wgs, stream_handle))
+        best_read = max(best_read, nbytes / t / 1e9)
+    del buf
+    mfma = {}
+    iters, wgs = 4096, 1024
+    for shape, per_wave in ((16, 8 * 16 * 16 * 32 * 2), (32, 4 * 32 * 32 * 16 * 2)):
+        t = timed(lambda: roofs_call("roofs_mfma_bf16", shape, iters, wgs, sink.data_ptr(), stream_handle))
+        mfma[shape] = wgs * 4 * iters * per_wave / t / 1e12
+    torch.cuda.empty_cache()
+    return {"hbm_read_gb_per_s": best_read, "hbm_read_frac_of_published": best_read / HBM_PEAK_GBS,
+            "hbm_read_bytes": nbytes, "mfma_bf16_tflops": max(mfma.values()),
+            "mfma_bf16_frac_of_published": max(mfma.values()) / MFMA_BF16_PEAK_TFLOPS,
+            "mfma_bf16_16x16x32_tflops": mfma[16], "mfma_bf16_32x32x16_tflops": mfma[32]}
+
+
+def read_profiled_traffic(workload):
+    """HBM bytes of one fspad_tree_attn call as the profiler's byte counters measured them (not measured in
+    this run): the line `traffic_bytes_per_call <workload> <bytes>` of profiles/tree_verify_traffic.txt,
+    which is refreshed whenever the attention kernels or their work split change. None if there is none."""
+    try:
+        with open(os.path.join(ROOT, TRAFFIC_PROFILE)) as fh:
+            for line in fh:
+                m = re.match(r"\s*traffic_bytes_per_call\s+(\w+)\s+(\d+)", line)
+                if m and m.group(1) == workload:
+                    return int(m.group(2))
+    except OSError:
+        pass
+    return None
 
 
 def read_clock_levels():
@@ -608,42 +738,28 @@ class TimingEvent:
             TimingEvent._hip.hipEventDestroy(self._ev)
 
 
-# HBM bytes moved by one fspad_tree_attn call (its kernels together, read + written) at the default shape of
-# each workload, from two rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE), each scaled by what the same counter
-# reads for a 512 MiB copy (2048 B per FETCH count, 1024 B per WRITE count on this machine); figures and
-# commands in profiles/tree_verify_traffic.txt. Above the algorithmic bytes by the partial results of units
-# that are cut across workgroups (c2, c4: 256 rows per workgroup) and by the second slab group's K/V reads.
 # hidden and intermediate size of the draft side per workload (the target model's own)
 DRAFT_DIMS = {"c0": (256, 512), "c1": (4096, 11008), "c2": (4096, 14336), "c3": (6656, 17920), "c4": (8192, 28672)}
 
-MEASURED_TRAFFIC_BYTES = {"c1": 45764473, "c2": 53890269, "c3": 456196462, "c4": 140843245}
-
 
 def cpu_baseline(cfg, accept, dev_set, parent, n_nodes, kv_len, seed):
-    """The CPU oracle, as it stands, on this machine's host cores, on a bounded sample of the workload."""
+    """The CPU oracle, as it stands, on this machine's host cores, on a bounded sample of the workload: once
+    with OpenMP over the sampled heads (`value`, the figure of the contract) and once single-threaded on a
+    smaller sample; both extrapolated linearly to the whole step where the sample is partial."""
     import numpy as np
 
     import oracle
-    cores = min(os.cpu_count() or 1, int(os.environ.get("OMP_NUM_THREADS", "16")), 16)
+    nproc = os.cpu_count() or 1
+    cores = min(nproc, int(os.environ.get("OMP_NUM_THREADS", "16")), 16)
     B, N, Hq, Hkv = cfg.batch, cfg.n_nodes, cfg.n_q_heads, cfg.n_kv_heads
     G = Hq // Hkv
-    # sample: all sequences, a subset of the query heads of ONE layer, sized to a few seconds of CPU work
-    work_per_head = 2.0 * N * (cfg.kv_len + N) * cfg.head_dim * 2 * B     # flops of one query head, all sequences
-    heads = int(max(1, min(Hq, 4.0e9 // work_per_head)))
-    head_ids = sorted(set(np.linspace(0, Hq - 1, heads).astype(int).tolist()))
-    kvh = [h // G for h in head_ids]
     q, kt, vt, kc, vc, _ = dev_set["layers"][0]
-    host = [q[:, :, head_ids].float().cpu().numpy(), kt[:, :, kvh].float().cpu().numpy(), vt[:, :, kvh].float().cpu().numpy(),
-            kc[:, kvh].float().cpu().numpy(), vc[:, kvh].float().cpu().numpy()]
     logits = dev_set["logits"].cpu().numpy()
     tokens = dev_set["tokens"].cpu().numpy()
     uniforms = dev_set["uniforms"].cpu().numpy()
-    t_attn, t_acc, reps = 0.0, 0.0, 0
-    t_start = time.perf_counter()
-    while reps < 1 or (time.perf_counter() - t_start < 10.0 and reps < 50):
-        t0 = time.perf_counter()
-        oracle.tree_attn(*host, kv_len, n_nodes, parent, nthreads=cores)
-        t1 = time.perf_counter()
+    work_per_head = 2.0 * N * (cfg.kv_len + N) * cfg.head_dim * 2 * B     # flops of one query head, all sequences
+
+    def accept_once():
         if accept == "greedy":
             oracle.accept_greedy(logits, tokens, parent, n_nodes)
         elif accept == "sample-draft":
@@ -651,18 +767,39 @@ def cpu_baseline(cfg, accept, dev_set, parent, n_nodes, kv_len, seed):
                                        uniforms)
         else:
             oracle.accept_sample(logits, tokens, parent, n_nodes, cfg.temperature, uniforms)
-        t2 = time.perf_counter()
-        t_attn += t1 - t0
-        t_acc += t2 - t1
-        reps += 1
-    # whole step = every head of every layer (attention extrapolated linearly from the sampled heads) + acceptance
-    step_s = (t_attn / reps) * (Hq / len(head_ids)) * cfg.layers + t_acc / reps
-    extrap = len(head_ids) < Hq or cfg.layers > 1
-    return {"value": 1.0 / step_s, "unit": "steps/s", "cores": cores, "kind": "oracle",
-            "sample": (f"{reps} repetitions of: attention of {len(head_ids)}/{Hq} query heads of 1/{cfg.layers} layers, all "
-                       f"{B} sequences (OpenMP over heads, {cores} threads) + full {accept} acceptance (1 thread)"
-                       + ("; step time extrapolated linearly to all heads and layers" if extrap else "")),
-            "extrapolated": extrap}
+
+    def leg(threads, flop_budget, seconds):
+        # sample: all sequences, a subset of the query heads of ONE layer, sized to a few seconds of CPU work
+        heads = int(max(1, min(Hq, flop_budget // work_per_head)))
+        head_ids = sorted(set(np.linspace(0, Hq - 1, heads).astype(int).tolist()))
+        kvh = [h // G for h in head_ids]
+        host = [q[:, :, head_ids].float().cpu().numpy(), kt[:, :, kvh].float().cpu().numpy(), vt[:, :, kvh].float().cpu().numpy(),
+                kc[:, kvh].float().cpu().numpy(), vc[:, kvh].float().cpu().numpy()]
+        t_attn, t_acc, reps = 0.0, 0.0, 0
+        t_start = time.perf_counter()
+        while reps < 1 or (time.perf_counter() - t_start < seconds and reps < 50):
+            t0 = time.perf_counter()
+            oracle.tree_attn(*host, kv_len, n_nodes, parent, nthreads=threads)
+            t1 = time.perf_counter()
+            accept_once()
+            t2 = time.perf_counter()
+            t_attn += t1 - t0
+            t_acc += t2 - t1
+            reps += 1
+        # whole step = every head of every layer (attention extrapolated linearly from the sampled heads) + acceptance
+        step_s = (t_attn / reps) * (Hq / len(head_ids)) * cfg.layers + t_acc / reps
+        extrap = len(head_ids) < Hq or cfg.layers > 1
+        sample = (f"{reps} repetitions of: attention of {len(head_ids)}/{Hq} query heads of 1/{cfg.layers} layers, all "
+                  f"{B} sequences ({threads} thread{'s' if threads > 1 else ''}) + full {accept} acceptance (1 thread)"
+                  + ("; step time extrapolated linearly to all heads and layers" if extrap else ""))
+        return step_s, sample, extrap
+
+    omp_s, omp_sample, extrap = leg(cores, 4.0e9, 10.0)
+    one_s, one_sample, one_extrap = leg(1, 5.0e8, 6.0)
+    return {"value": 1.0 / omp_s, "unit": "steps/s", "cores": cores, "kind": "oracle", "sample": omp_sample,
+            "extrapolated": extrap, "nproc": nproc,
+            "single_thread": {"value": 1.0 / one_s, "unit": "steps/s", "cores": 1, "sample": one_sample,
+                              "extrapolated": one_extrap}}
 
 
 if __name__ == "__main__":
