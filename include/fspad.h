@@ -153,6 +153,31 @@ fspad_status fspad_tree_accept_greedy(int32_t B, int32_t Nmax, int32_t V,
                                       void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * fspad_tree_accept_greedy for callers that cannot allocate device memory or pass a workspace
+ * (code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): the same
+ * kernels, arguments and results, with the per-(row, chunk) statistics kept in a fixed device
+ * array that is part of the library image instead of a caller workspace.
+ *
+ *   limit   fspad_tree_accept_workspace_bytes(B,Nmax,V) <= FSPAD_STATIC_SCRATCH_BYTES (1 MiB; e.g.
+ *           B*Nmax = 512 rows of V = 128256); larger problems return FSPAD_ERR_WORKSPACE and
+ *           nothing is launched
+ *   memory  every GPU the library runs on holds the 1 MiB array until the process ends; its
+ *           address is looked up once per device, on the first call there
+ *   calls   allocates nothing, frees nothing, never synchronises. All calls on one GPU share that
+ *           GPU's array: two calls that may overlap in time (different streams) race; calls
+ *           on one stream are ordered and need nothing cleared between them
+ * Errors otherwise as for fspad_tree_accept_greedy; FSPAD_ERR_HIP if the array's address cannot
+ * be resolved.
+ */
+#define FSPAD_STATIC_SCRATCH_BYTES (1u << 20)
+fspad_status fspad_tree_accept_greedy_static(int32_t B, int32_t Nmax, int32_t V,
+                                             const float* logits, int64_t row_stride,
+                                             const int32_t* draft_tokens, const int32_t* parent,
+                                             const int32_t* n_nodes,
+                                             int32_t* path, int32_t* path_len,
+                                             int32_t* tokens, int32_t* n_tokens, void* hip_stream);
+
+/*
  * Sampling (temperature > 0) lossless acceptance: rejection sampling down the
  * tree against the residual distribution, with caller-supplied uniforms, so
  * that the emitted tokens are distributed exactly as the target's own samples

@@ -24,7 +24,8 @@ _STATUS_NAMES = {0: "FSPAD_OK", 1: "FSPAD_ERR_NULL", 2: "FSPAD_ERR_SHAPE", 3: "F
                  4: "FSPAD_ERR_DTYPE", 5: "FSPAD_ERR_WORKSPACE", 6: "FSPAD_ERR_TEMPERATURE", 7: "FSPAD_ERR_HIP"}
 
 EXPORTS = ("fspad_tree_attn_workspace_bytes", "fspad_tree_attn",
-           "fspad_tree_accept_workspace_bytes", "fspad_tree_accept_greedy", "fspad_tree_accept_sample",
+           "fspad_tree_accept_workspace_bytes", "fspad_tree_accept_greedy", "fspad_tree_accept_greedy_static",
+           "fspad_tree_accept_sample",
            "fspad_tree_accept_sample_draft_workspace_bytes", "fspad_tree_accept_sample_draft",
            "fspad_tree_accept_lm_head_workspace_bytes", "fspad_tree_accept_greedy_lm_head",
            "fspad_tree_accept_sample_lm_head",
@@ -81,6 +82,8 @@ def _lib():
         lib.fspad_tree_accept_workspace_bytes.argtypes = [i32, i32, i32]
         lib.fspad_tree_accept_greedy.restype = ctypes.c_int
         lib.fspad_tree_accept_greedy.argtypes = [i32, i32, i32, vp, i64, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        lib.fspad_tree_accept_greedy_static.restype = ctypes.c_int
+        lib.fspad_tree_accept_greedy_static.argtypes = [i32, i32, i32, vp, i64, vp, vp, vp, vp, vp, vp, vp, vp]
         lib.fspad_tree_accept_sample.restype = ctypes.c_int
         lib.fspad_tree_accept_sample.argtypes = [i32, i32, i32, vp, i64, vp, vp, vp, ctypes.c_float, vp,
                                                  vp, vp, vp, vp, vp, sz, vp]
@@ -293,6 +296,26 @@ def fspad_tree_accept_greedy(logits: torch.Tensor, draft_tokens: torch.Tensor, p
             workspace.numel() * workspace.element_size(), _stream_ptr(stream))
     keep = (logits, draft_tokens, parent, n_nodes, workspace)
     return _issue(_lib().fspad_tree_accept_greedy, "fspad_tree_accept_greedy", args, keep,
+                  (path, path_len, tokens, n_tokens), prepare)
+
+
+def fspad_tree_accept_greedy_static(logits: torch.Tensor, draft_tokens: torch.Tensor, parent: torch.Tensor,
+                                    n_nodes: torch.Tensor, outputs, stream=None, prepare: bool = False):
+    """fspad_tree_accept_greedy without a workspace (the library's own fixed device array holds the
+    chunk statistics) and without any allocation here either: the four output tensors are required."""
+    if logits.dim() != 3 or logits.stride(2) != 1 or logits.stride(0) != logits.shape[1] * logits.stride(1):
+        raise ValueError("logits must be [B,Nmax,V] with a uniform row stride")
+    B, Nmax, V = logits.shape
+    for name, t in (("draft_tokens", draft_tokens), ("parent", parent), ("n_nodes", n_nodes)):
+        if t.dtype != torch.int32 or not t.is_contiguous():
+            raise ValueError(f"{name} must be a contiguous int32 device tensor")
+    path, path_len, tokens, n_tokens = outputs
+    args = (B, Nmax, V, _dev_ptr(logits, "logits", torch.float32), logits.stride(1),
+            _dev_ptr(draft_tokens, "draft_tokens"), _dev_ptr(parent, "parent"), _dev_ptr(n_nodes, "n_nodes"),
+            _dev_ptr(path, "path"), _dev_ptr(path_len, "path_len"), _dev_ptr(tokens, "tokens"),
+            _dev_ptr(n_tokens, "n_tokens"), _stream_ptr(stream))
+    keep = (logits, draft_tokens, parent, n_nodes, outputs)
+    return _issue(_lib().fspad_tree_accept_greedy_static, "fspad_tree_accept_greedy_static", args, keep,
                   (path, path_len, tokens, n_tokens), prepare)
 
 

@@ -14,6 +14,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <mutex>
+
 #include "fspad.h"
 #include "exp_nonpos.h"
 #include "greedy_walk.h"
@@ -835,6 +837,52 @@ extern "C" fspad_status fspad_tree_accept_greedy(int32_t B, int32_t Nmax, int32_
   hipLaunchKernelGGL(accept_greedy_walk_kernel, dim3((unsigned)B), dim3(kThreads), 0, stream, p);
   if (hipGetLastError() != hipSuccess) return FSPAD_ERR_HIP;
   return FSPAD_OK;
+}
+
+// ------------------------------------------------------------------------------------------------
+// The greedy acceptance for callers that cannot allocate: the chunk statistics live in a fixed
+// device array of the library image. In host code the array's name is only a handle: its device
+// address is looked up once per device (with that device current) and kept; the kernels get that
+// address exactly as they get a caller's workspace.
+namespace {
+constexpr int kMaxDevices = 64;
+}  // namespace
+static __device__ __align__(256) unsigned char scratch[FSPAD_STATIC_SCRATCH_BYTES];
+namespace {
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices];   // device address of `scratch` on each device, nullptr until looked up
+
+// Device address of the static array on the current device, or nullptr.
+void* static_scratch() {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess) {
+      (void)hipGetLastError();
+      return nullptr;
+    }
+    g_scratch_ptr[dev] = ptr;
+  }
+  return g_scratch_ptr[dev];
+}
+}  // namespace
+
+extern "C" fspad_status fspad_tree_accept_greedy_static(int32_t B, int32_t Nmax, int32_t V, const float* logits,
+                                                        int64_t row_stride, const int32_t* draft_tokens,
+                                                        const int32_t* parent, const int32_t* n_nodes, int32_t* path,
+                                                        int32_t* path_len, int32_t* tokens, int32_t* n_tokens,
+                                                        void* hip_stream) {
+  if (!logits || !draft_tokens || !parent || !n_nodes || !path || !path_len || !tokens || !n_tokens) return FSPAD_ERR_NULL;
+  if (B < 1 || Nmax < 1 || Nmax > FSPAD_MAX_NODES || V < 1 || V > (1 << 30)) return FSPAD_ERR_SHAPE;
+  const size_t need = fspad_tree_accept_workspace_bytes(B, Nmax, V);
+  if (need == 0 || need > FSPAD_STATIC_SCRATCH_BYTES) return FSPAD_ERR_WORKSPACE;  // beyond the fixed array
+  void* ptr = static_scratch();
+  if (!ptr) return FSPAD_ERR_HIP;
+  // every slot the walk reads is written by the row pass of the same call: nothing to clear
+  return fspad_tree_accept_greedy(B, Nmax, V, logits, row_stride, draft_tokens, parent, n_nodes, path, path_len, tokens,
+                                  n_tokens, ptr, FSPAD_STATIC_SCRATCH_BYTES, hip_stream);
 }
 
 extern "C" fspad_status fspad_tree_accept_sample(int32_t B, int32_t Nmax, int32_t V, const float* logits,

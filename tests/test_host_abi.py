@@ -132,6 +132,19 @@ def test_accept_argument_checks_need_no_gpu(lib):
     assert greedy(wsb=need - 1) == 5
     assert greedy(ws=None) == 5
 
+    # the variant that keeps its scratch in the library's own fixed array: sizes beyond it are refused
+    # before anything touches the GPU
+    gs = lib.fspad_tree_accept_greedy_static
+
+    def greedy_static(B=1, N=26, V=32000, logits=fake, stride=32000):
+        return gs(i32(B), i32(N), i32(V), logits, i64(stride), fake, fake, fake, fake, fake, fake, fake, None)
+
+    assert greedy_static(logits=None) == 1
+    assert greedy_static(N=65) == 2
+    assert greedy_static(V=0) == 2
+    assert fspad.fspad_tree_accept_workspace_bytes(16, 64, 128256) > (1 << 20)
+    assert greedy_static(B=16, N=64, V=128256, stride=128256) == 5
+
     def sample(T, uni=fake):
         return s(i32(1), i32(26), i32(32000), fake, i64(32000), fake, fake, fake, ctypes.c_float(T), uni,
                  fake, fake, fake, fake, fake, sz(need), None)
