@@ -796,16 +796,26 @@ __global__ __launch_bounds__(64 * WAVES, (WAVES == 4 ? 2 : 1)) void tree_attn_gq
             for (int ks = 0; ks < KS; ++ks)
               kf[kt][ks] = *reinterpret_cast<const bf16x8*>(sbase + kt * 16 * (D * 2) + kfrag[ks]);
           if constexpr (D == 128) {
-            typedef __attribute__((ext_vector_type(4))) short s16x4;
-            typedef __attribute__((address_space(3))) s16x4* LdsS16x4;
+            // The transposing reads are written out as instructions: through the builtin the compiler
+            // cannot tell them from the stages that the copies requested above are still filling, and
+            // waits for every copy in flight (vmcnt(0)) before the first of them, which serialises the
+            // prefetch. This stage's copies have landed (the wait and the barrier above).
+            const unsigned sb = (unsigned)(uintptr_t)(LdsPtr)(sbase);
+            u32x2 tr[2 * DT];
+#pragma unroll
+            for (int e = 0; e < DT; ++e) {
+              const unsigned a0 = sb + (vtr_off ^ ((unsigned)e << 5));
+              asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(tr[2 * e]) : "v"(a0));
+              asm volatile("ds_read_b64_tr_b16 %0, %1 offset:4096" : "=v"(tr[2 * e + 1]) : "v"(a0));
+            }
+            static_assert(16 * (D * 2) == 4096, "second half of the keys: 16 rows further");
+            asm volatile("s_waitcnt lgkmcnt(0)"
+                         : "+v"(tr[0]), "+v"(tr[1]), "+v"(tr[2]), "+v"(tr[3]), "+v"(tr[4]), "+v"(tr[5]), "+v"(tr[6]), "+v"(tr[7]),
+                           "+v"(tr[8]), "+v"(tr[9]), "+v"(tr[10]), "+v"(tr[11]), "+v"(tr[12]), "+v"(tr[13]), "+v"(tr[14]), "+v"(tr[15]));
             unsigned* flat = &vr[0][0];
 #pragma unroll
             for (int e = 0; e < DT; ++e) {
-              const char* src = sbase + (vtr_off ^ ((unsigned)e << 5));
-              const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LdsS16x4)src);
-              const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LdsS16x4)(src + 16 * (D * 2)));
-              const u32x2 a = __builtin_bit_cast(u32x2, lo), b2 = __builtin_bit_cast(u32x2, hi);
-              flat[4 * e] = a[0]; flat[4 * e + 1] = a[1]; flat[4 * e + 2] = b2[0]; flat[4 * e + 3] = b2[1];
+              flat[4 * e] = tr[2 * e][0]; flat[4 * e + 1] = tr[2 * e][1]; flat[4 * e + 2] = tr[2 * e + 1][0]; flat[4 * e + 3] = tr[2 * e + 1][1];
             }
             process_block<QT, D, true>(st, kf, vr, q_frag, cur, mask_of_tile, c, g4, [] {}, [] {});
           } else {
