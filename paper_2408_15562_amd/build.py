@@ -21,8 +21,15 @@ _FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
           "-I", os.path.join(_ROOT, "include")]
 
 
+# per-source options. The attention kernels keep the results of their matrix instructions in ordinary
+# vector registers: left to itself the compiler puts the score tiles into accumulation registers and
+# copies every one of them out again for the softmax (a quarter of the instructions of a block).
+EXTRA_FLAGS = {"fspad_attn.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"]}
+
+
 def compile_command(src: str, obj: str, defines=()):
-    return ["hipcc", "-c"] + _FLAGS + [f"-D{d}" for d in defines] + ["-o", obj, os.path.join(CSRC, src)]
+    return (["hipcc", "-c"] + _FLAGS + EXTRA_FLAGS.get(src, []) + [f"-D{d}" for d in defines]
+            + ["-o", obj, os.path.join(CSRC, src)])
 
 
 def link_command(objs, out: str = LIB_PATH):
