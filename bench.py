@@ -84,6 +84,9 @@ def parse_args():
                     help="with --feature-sampler fused / --draft-layer fused / --lm-head fused: the weight matrices are repacked once into "
                          "the tile order of fspad_pack_weight (same results, faster streaming)")
     ap.add_argument("--hidden-dim", type=int, default=None, help="hidden size for --lm-head (default: the workload's model)")
+    ap.add_argument("--probe-overlap", action="store_true",
+                    help="instead of a workload: time what one SIMD runs at the same time (a matrix instruction and vector "
+                         "instructions of the same wavefront; a matrix wavefront next to a vector wavefront) and print it")
     ap.add_argument("--seed", type=int, default=2024)
     return ap.parse_args()
 
@@ -108,6 +111,10 @@ def main():
     only = args.only or extras or args.workload == "c0"
     # everything runs on one side stream: the prepared calls, the timing events and the captured graph share it
     side = torch.cuda.Stream()
+    if args.probe_overlap:
+        with torch.cuda.stream(side):
+            print(json.dumps(probe_overlap(torch, torch.cuda.current_stream().cuda_stream)))
+        return
     with torch.cuda.stream(side):
         result = run_workload(args, args.workload, args.steps, args.warmup, primary=True)
         if not only:
@@ -117,7 +124,7 @@ def main():
                     continue
                 rec = run_workload(args, name, None, None, primary=False)
                 others[name] = {k: rec[k] for k in ("value", "unit", "steps", "warmup", "ms_per_step", "config", "step_roofline",
-                                                    "roofline", "attn_call_us", "accept_call_us", "steps_per_s_graph_replay",
+                                                    "roofline", "accept_roofline", "attn_call_us", "accept_call_us", "steps_per_s_graph_replay",
                                                     "steps_per_s_one_buffer_set_cache_resident", "mean_tokens_per_step") if k in rec}
             result["other_workloads"] = others
             roofs = measure_roofs(torch, torch.cuda.current_stream().cuda_stream)
@@ -462,6 +469,19 @@ def run_workload(args, workload, steps_arg, warmup_arg, primary):
     step_roofline["frac"] = step_roofline["achieved"] / step_roofline["peak"]
     step_roofline.update(algorithmic_bytes=cfg.step_bytes(), algorithmic_flops=cfg.step_flops())
 
+    # the acceptance call (row pass + walk) against its own roofs: the logits are read once (HBM); the
+    # sampling form also evaluates one fp64 exponential per logit: cast, scale, range reduction, an
+    # 11-term polynomial, scaling and the sum: 27 fp64 vector operations of which 15 are fused
+    # multiply-adds, counted as 42 flops, against the fp64 vector peak of 256 CUs x 4 SIMDs x 16 lanes
+    # x 2 flops x 2.4 GHz = 78.6 TFLOP/s
+    accept_s = float(np.percentile(accept_ms, 50)) * 1e-3
+    accept_roofline = dict(bound="hbm", achieved=cfg.logit_bytes() / accept_s / 1e9, peak=HBM_PEAK_GBS, unit="GB/s")
+    accept_roofline["frac"] = accept_roofline["achieved"] / HBM_PEAK_GBS
+    if accept == "sample" and not args.lm_head:
+        fp64_tflops = B * N * V * 42 / accept_s / 1e12
+        accept_roofline.update(alu_fp64_tflops=fp64_tflops, alu_fp64_peak=78.6, alu_fp64_frac=fp64_tflops / 78.6)
+    accept_roofline.update(kernel="acceptance call (row pass + walk)", call_us_p50=accept_s * 1e6, algorithmic_bytes=cfg.logit_bytes())
+
     result = {
         "metric": "tree-verify steps/s", "value": 1e3 / ms_per_step, "unit": "steps/s", "n_gpus": 1, "steps": steps,
         "warmup": warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
@@ -486,6 +506,7 @@ def run_workload(args, workload, steps_arg, warmup_arg, primary):
                    "hbm_bytes": props.total_memory, "clocks": read_clock_levels()},
         "mean_tokens_per_step": n_tokens_mean,
         "roofline": roofline,
+        "accept_roofline": accept_roofline,
     }
 
     if args.feature_sampler:
@@ -538,6 +559,7 @@ def roofs_call(name, *call_args):
         lib.roofs_hbm_read.argtypes = [vp, sz, vp, i32, vp]
         lib.roofs_hbm_copy.argtypes = [vp, vp, sz, i32, vp]
         lib.roofs_mfma_bf16.argtypes = [i32, i32, i32, vp, vp]
+        lib.roofs_overlap.argtypes = [i32, i32, i32, i32, vp, vp]
         _ROOFS = lib
     rc = getattr(_ROOFS, name)(*call_args)
     if rc != 0:
@@ -581,6 +603,32 @@ def measure_roofs(torch, stream_handle):
             "hbm_read_bytes": nbytes, "mfma_bf16_tflops": max(mfma.values()),
             "mfma_bf16_frac_of_published": max(mfma.values()) / MFMA_BF16_PEAK_TFLOPS,
             "mfma_bf16_16x16x32_tflops": mfma[16], "mfma_bf16_32x32x16_tflops": mfma[32]}
+
+
+def probe_overlap(torch, stream_handle):
+    """Engine-clock cycles (at the nominal 2.4 GHz) per turn of the overlap kernels of libfspad_roofs.so: what a
+    SIMD runs at the same time. The attention kernels' wavefront shapes follow from these figures."""
+    sink = torch.zeros(64, dtype=torch.float32, device="cuda:0")
+    iters = 20000
+
+    def cycles(mode, nv, trans):
+        for n_it in (200, iters):
+            e0, e1 = TimingEvent(stream_handle), TimingEvent(stream_handle)
+            e0.record()
+            roofs_call("roofs_overlap", mode, nv, trans, n_it, sink.data_ptr(), stream_handle)
+            e1.record()
+            torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e-3 * 2.4e9 / iters
+
+    out = {"unit": "cycles per turn at 2.4 GHz", "same_wavefront_one_per_simd": {}, "two_wavefronts_per_simd": {}}
+    for trans, name in ((0, "fma"), (1, "exp")):
+        for nv in (0, 4, 8, 16):
+            # a turn = 2 x (one 32x32x16 matrix instruction + nv vector instructions)
+            out["same_wavefront_one_per_simd"][f"2x(mfma+{nv}{name})"] = cycles(0, nv, trans)
+        out["two_wavefronts_per_simd"][f"2mfma_wave_alone"] = cycles(2, 16, trans)
+        out["two_wavefronts_per_simd"][f"16{name}_wave_alone"] = cycles(3, 16, trans)
+        out["two_wavefronts_per_simd"][f"2mfma_wave_beside_16{name}_wave"] = cycles(1, 16, trans)
+    return out
 
 
 def read_profiled_traffic(workload):

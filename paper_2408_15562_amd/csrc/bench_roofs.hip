@@ -7,6 +7,9 @@
 //                    which the byte counters of the profiler are scaled
 //   roofs_mfma_bf16  a register-resident loop of v_mfma_f32_16x16x32_bf16 (or 32x32x16), eight independent
 //                    accumulator chains per wavefront, no memory access: what the matrix cores sustain
+//   roofs_overlap    what runs at the same time on one SIMD: a matrix instruction followed by vector
+//                    instructions in the same wavefront, or one wavefront of matrix instructions next to
+//                    one of vector instructions (the facts the attention kernels' wavefront shapes rest on)
 // Each returns 0 or a HIP error code; work is enqueued on the caller's stream, nothing is allocated.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -88,7 +91,83 @@ __global__ __launch_bounds__(kThreads) void roofs_mfma_kernel(int iters, float* 
   if (total == -1.0f) *sink = total;   // sums of non-negative products: never true
 }
 
+// mode 0: every wavefront alternates one 32x32x16 matrix instruction with `nv` vector instructions
+//         (one wavefront per SIMD: workgroups of 256 threads, one workgroup per compute unit)
+// mode 1: workgroups of 512 threads, two wavefronts per SIMD: wavefronts 0-3 issue two matrix
+//         instructions per turn, wavefronts 4-7 sixteen vector instructions per turn
+// mode 2 / 3: mode 1 with only the matrix / only the vector wavefronts doing work
+// trans: the vector instruction is v_exp_f32 instead of v_fma_f32
+template <int NV, bool TRANS>
+__device__ __forceinline__ void vector_ops(float (&x)[8]) {
+#pragma unroll
+  for (int i = 0; i < NV; ++i) {
+    if constexpr (TRANS) asm volatile("v_exp_f32 %0, %0" : "+v"(x[i % 8]));
+    else asm volatile("v_fma_f32 %0, %0, %1, %1" : "+v"(x[i % 8]) : "v"(x[(i + 3) % 8]));
+  }
+}
+
+template <int NV, bool TRANS>
+__global__ __launch_bounds__(512) void roofs_overlap_kernel(int mode, int iters, float* sink) {
+  bf16x8 a, b;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    a[j] = (__bf16)(float)((threadIdx.x + j) & 3);
+    b[j] = (__bf16)(float)((threadIdx.x * 3 + j) & 1);
+  }
+  f32x16 c0, c1;
+#pragma unroll
+  for (int e = 0; e < 16; ++e) { c0[e] = 0.f; c1[e] = 0.f; }
+  float x[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) x[i] = 0.001f * (float)(threadIdx.x + i);
+  const int role = threadIdx.x >> 8;
+  if (mode == 0) {
+    for (int it = 0; it < iters; ++it) {
+      asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(c0) : "v"(a), "v"(b));
+      vector_ops<NV, TRANS>(x);
+      asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(c1) : "v"(a), "v"(b));
+      vector_ops<NV, TRANS>(x);
+    }
+  } else if (role == 0 && mode != 3) {
+    for (int it = 0; it < iters; ++it) {
+      asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(c0) : "v"(a), "v"(b));
+      asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(c1) : "v"(a), "v"(b));
+    }
+  } else if (role == 1 && mode != 2) {
+    for (int it = 0; it < iters; ++it) vector_ops<16, TRANS>(x);
+  }
+  float total = 0.f;
+#pragma unroll
+  for (int e = 0; e < 16; ++e) total += c0[e] + c1[e];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) total += x[i];
+  if (total == -1.2345f) *sink = total;
+}
+
 }  // namespace
+
+// One launch on 256 workgroups (one per compute unit). mode 0: nv in {0, 4, 8, 16} vector instructions
+// after each matrix instruction; modes 1-3: see the kernel. The caller times it.
+extern "C" int roofs_overlap(int mode, int nv, int trans, int iters, void* sink, void* hip_stream) {
+  if (!sink || iters < 1 || mode < 0 || mode > 3) return -1;
+  hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
+  const dim3 grid(256), block(mode == 0 ? 256 : 512);
+  float* out = static_cast<float*>(sink);
+#define ROOFS_OVERLAP(NV)                                                                                              \
+  do {                                                                                                                 \
+    if (trans) hipLaunchKernelGGL((roofs_overlap_kernel<NV, true>), grid, block, 0, stream, mode, iters, out);         \
+    else hipLaunchKernelGGL((roofs_overlap_kernel<NV, false>), grid, block, 0, stream, mode, iters, out);              \
+  } while (0)
+  switch (nv) {
+    case 0: ROOFS_OVERLAP(0); break;
+    case 4: ROOFS_OVERLAP(4); break;
+    case 8: ROOFS_OVERLAP(8); break;
+    case 16: ROOFS_OVERLAP(16); break;
+    default: return -1;
+  }
+#undef ROOFS_OVERLAP
+  return (int)hipGetLastError();
+}
 
 extern "C" int roofs_hbm_read(const void* src, size_t bytes, void* sink, int workgroups, void* hip_stream) {
   if (!src || !sink || bytes < 16 || ((uintptr_t)src & 15) || workgroups < 1) return -1;
