@@ -590,17 +590,20 @@ __global__ __launch_bounds__(256, (QT <= 2 ? 2 : 1)) void tree_attn_bf16_kernel(
 }
 
 // ---------------------------------------------------------------------------------------------
-// GQA with many query rows per kv head and long streams: eight wavefronts per workgroup, 32 rows
-// each (256 rows of one kv head), two per SIMD so that the matrix work of one runs under the
-// vector work of the other. At 32 rows a wavefront cannot afford to fetch every K/V block for
-// itself (eight copies of each block through the texture path is what would bound the kernel):
-// the workgroup fetches each block once, every wavefront copying an eighth of it into an LDS
-// stage with the global-to-LDS load (row-contiguous requests, no registers), and all of them pick
-// their operands out of the stage. K is kept swizzled (16-byte chunk c of row r at slot c ^ f(r))
-// so that a fragment read, 16 rows by one chunk, touches 16 different bank groups; V (D = 128) is
-// read with the transposing LDS load of gfx950, which hands every lane the four keys of one dim --
-// the A operand of V^T P^T as it is, without byte permutes (its 32-byte pieces are swizzled too). Three stages of one block each (two blocks each in the
-// eight-wavefront form, which halves the barriers): stage i is read while i+1 and i+2 are in flight.
+// GQA with many query rows per kv head: four wavefronts per workgroup, 32 rows each (128 rows of
+// one kv head), two workgroups per compute unit, i.e. two wavefronts per SIMD, so that the matrix
+// work of one runs beside the vector work of the other (vector instructions behind a matrix
+// instruction of the same wavefront do not overlap it on this machine). At 32 rows a wavefront
+// cannot afford to fetch every K/V block for itself (four to eight copies of each block through the
+// texture path is what would bound the kernel): the workgroup fetches each block once, every
+// wavefront copying a quarter of it into an LDS stage with the global-to-LDS load (row-contiguous
+// requests, no registers), and all of them pick their operands out of the stage. K is kept swizzled
+// (16-byte chunk c of row r at slot c ^ f(r)) so that a fragment read, 16 rows by one chunk, touches
+// 16 different bank groups; V (D = 128) is read with the transposing LDS load of gfx950, which hands
+// every lane the four keys of one dim -- the A operand of V^T P^T as it is, without byte permutes
+// (its 32-byte pieces are swizzled too). Three stages of one block each: stage i is read while i+1
+// and i+2 are in flight. (WAVES and the blocks per stage are template parameters; only the
+// four-wavefront, one-block form is instantiated.)
 template <int D, int WAVES>
 struct Stage {
   static constexpr int kChunks = D / 8;                      // 16-byte chunks per row
