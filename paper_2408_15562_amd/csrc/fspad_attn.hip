@@ -621,17 +621,27 @@ struct Stage {
 typedef const __attribute__((address_space(1))) void* GlobalPtr;
 typedef __attribute__((address_space(3))) void* LdsPtr;
 
-template <int D, int WAVES>
-__global__ __launch_bounds__(64 * WAVES, (WAVES == 4 ? 2 : 1)) void tree_attn_gqa_kernel(const AttnParams p) {
+// KG key groups: with KG = 2 a workgroup is two such sets of four wavefronts on the same 128 rows;
+// the sets take alternate blocks of the workgroup's segment, each through three stages of its own,
+// and merge their states through LDS at the segment's end. One workgroup of eight wavefronts per
+// compute unit holds as many wavefronts as two of four, but a cut unit leaves one partial result
+// per workgroup: half as many partial bytes are written and read back.
+template <int D, int WAVES, int KG>
+__global__ __launch_bounds__(64 * WAVES * KG, (KG == 1 ? 2 : 1)) void tree_attn_gqa_kernel(const AttnParams p) {
   typedef Stage<D, WAVES> S;
   constexpr int QT = 2, KS = D / 32, DT = D / 16, ROWS = 32, kWaves = WAVES, kStages = 3;
-  // blocks per stage, one barrier per kGroup blocks: two where one workgroup fills the CU, one
-  // where two four-wavefront workgroups have to share its LDS
-  constexpr int kGroup = WAVES == 8 ? 2 : 1;
+  constexpr int kGroup = 1;   // blocks per stage
   constexpr int kStageBytes = kGroup * S::kBytes;
-  __shared__ __attribute__((aligned(16))) char stages[kStages * kStageBytes];
+  constexpr int kGroupBytes = kStages * kStageBytes;
+  // the merge of two key groups needs (DT + 1) 16-byte slots per lane, tile and wavefront of one group
+  constexpr int kMergeBytes = KG == 1 ? 0 : kWaves * QT * (DT + 1) * 64 * 16;
+  constexpr int kLdsBytes = KG * kGroupBytes > kMergeBytes ? KG * kGroupBytes : kMergeBytes;
+  __shared__ __attribute__((aligned(16))) char lds_all[kLdsBytes];
 
-  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63, wave_all = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int kg = KG == 1 ? 0 : wave_all / kWaves;          // key group of this wavefront
+  const int wave = KG == 1 ? wave_all : wave_all % kWaves; // its row slab within the workgroup
+  char* const stages = lds_all + kg * kGroupBytes;
   const int col = lane & 15, g4 = lane >> 4;
   const float c = p.scale * kLog2e;
   const unsigned tree_row_bytes = (unsigned)p.Hkv * D * 2u;
@@ -719,17 +729,15 @@ __global__ __launch_bounds__(64 * WAVES, (WAVES == 4 ? 2 : 1)) void tree_attn_gq
         __builtin_amdgcn_global_load_lds((GlobalPtr)src, (LdsPtr)(stages + stage * kStageBytes + u * S::kBytes + dma_dst[i]), 16, 0, 0);
       }
     };
-    const int blk_begin = seg_begin, blk_end = seg_begin + seg_count;
-    // a group = kGroup consecutive blocks (the last one may be short); returns how many blocks it requested
+    // key group kg takes blocks kg, kg + KG, ... of the segment
+    const int blk_begin = seg_begin + kg, blk_end = seg_begin + seg_count;
     auto request_group = [&](int first, int stage) {
-#pragma unroll
-      for (int u = 0; u < kGroup; ++u)
-        if (first + u < blk_end) request_block(locate(first + u), stage, u);
+      if (first < blk_end) request_block(locate(first), stage, 0);
     };
-    auto group_size = [&](int first) { return max(0, min(kGroup, blk_end - first)); };
+    auto group_size = [&](int first) { return first < blk_end ? 1 : 0; };
 
     request_group(blk_begin, 0);
-    request_group(blk_begin + kGroup, 1);
+    request_group(blk_begin + KG, 1);
 
     struct RowInfo { bool exists, valid; int node; int64_t out; };
     auto row_info = [&](int t) {
@@ -775,22 +783,22 @@ __global__ __launch_bounds__(64 * WAVES, (WAVES == 4 ? 2 : 1)) void tree_attn_gq
     }
 
     int stage = 0;
-    for (int first = blk_begin; first < blk_end; first += kGroup) {
-      // this group's copies have landed (the next group's, requested after them, may still be in
+    // every wavefront of the workgroup takes the same number of turns (the barriers are the whole
+    // workgroup's): as many as key group 0 has blocks; a group whose blocks have run out idles
+    const int n_turns = (seg_count + KG - 1) / KG;
+    for (int turn = 0, first = blk_begin; turn < n_turns; ++turn, first += KG) {
+      // this turn's copies have landed (the next turn's, requested after them, may still be in
       // flight); the barrier makes every wavefront's share visible and retires the stage that the
-      // group after the next is about to overwrite
-      const int next_size = group_size(first + kGroup);
-      if (next_size == kGroup) asm volatile("s_waitcnt vmcnt(%0)" : : "n"(kGroup * S::kPerWave) : "memory");
-      else if (next_size == 1) asm volatile("s_waitcnt vmcnt(%0)" : : "n"(S::kPerWave) : "memory");
+      // turn after the next is about to overwrite
+      const int next_size = group_size(first + KG);
+      if (next_size == 1) asm volatile("s_waitcnt vmcnt(%0)" : : "n"(S::kPerWave) : "memory");
       else asm volatile("s_waitcnt vmcnt(0)" : : : "memory");
       __syncthreads();
-      request_group(first + 2 * kGroup, stage == 0 ? 2 : stage - 1);
-      if (slab_live) {
-#pragma unroll
-        for (int u = 0; u < kGroup; ++u) {
-          if (first + u >= blk_end) break;
-          const BlockSrc cur = locate(first + u);
-          const char* sbase = stages + stage * kStageBytes + u * S::kBytes;
+      request_group(first + 2 * KG, stage == 0 ? 2 : stage - 1);
+      if (slab_live && first < blk_end) {
+        {
+          const BlockSrc cur = locate(first);
+          const char* sbase = stages + stage * kStageBytes;
           bf16x8 kf[2][KS];
           unsigned vr[8][D / 32];
 #pragma unroll
@@ -834,8 +842,37 @@ __global__ __launch_bounds__(64 * WAVES, (WAVES == 4 ? 2 : 1)) void tree_attn_gq
       stage = stage == 2 ? 0 : stage + 1;
     }
 
-    // no merge: every wavefront owns its rows; final rows or a partial slot, straight from registers
-    if (slab_live) {
+    if constexpr (KG == 2) {
+      // the second key group hands its states over in lane-private LDS slots (the stages are free
+      // once every wavefront has left the loop); wavefront w of the first group and wavefront w of the
+      // second hold the same rows in the same lanes, so the merge is lane by lane and in a fixed order
+      __syncthreads();
+      f32x4* mbuf = reinterpret_cast<f32x4*>(lds_all) + (wave * QT * (DT + 1)) * 64 + lane;
+      if (kg == 1 && slab_live) {
+#pragma unroll
+        for (int t = 0; t < QT; ++t) {
+#pragma unroll
+          for (int e = 0; e < DT; ++e) mbuf[(t * (DT + 1) + e) * 64] = st.o[t][e];
+          mbuf[(t * (DT + 1) + DT) * 64] = f32x4{st.m[t], st.l[t][0], 0.f, 0.f};
+        }
+      }
+      __syncthreads();
+      if (kg == 0 && slab_live) {
+#pragma unroll
+        for (int t = 0; t < QT; ++t) {
+          const f32x4 ml = mbuf[(t * (DT + 1) + DT) * 64];
+          const float mm = fmaxf(st.m[t], ml[0]);
+          const float a0 = __builtin_amdgcn_exp2f(st.m[t] - mm), a1 = __builtin_amdgcn_exp2f(ml[0] - mm);
+          st.m[t] = mm;
+          st.l[t] = st.l[t] * a0 + ml[1] * a1;
+#pragma unroll
+          for (int e = 0; e < DT; ++e) st.o[t][e] = st.o[t][e] * a0 + mbuf[(t * (DT + 1) + e) * 64] * a1;
+        }
+      }
+    }
+
+    // every wavefront (of the first key group) owns its rows: final rows or a partial slot, straight from registers
+    if (slab_live && kg == 0) {
 #pragma unroll
       for (int t = 0; t < QT; ++t) {
         const RowInfo ri = row_info(t);
@@ -1126,9 +1163,11 @@ int blocks_of(int kv_len, int n_nodes) {
 // straddles two units (a second segment costs a short-lived workgroup as much as its blocks do).
 // With one piece per unit nothing is cut and nothing is merged.
 int plan_wgs(const Plan& pl, int64_t total_blocks, int64_t units, bool uniform, int forced) {
-  const int KW = pl.WS >= 4 ? 1 : 4 / pl.WS;
-  // (eight wavefronts of 256 registers fill a compute unit by themselves)
-  const int64_t resident = (pl.QT <= 2 && pl.WS < 8 && !pl.short_stream) ? 512 : 256;
+  // wavefront sets that split a workgroup's keys: the two key groups of the shared-stage kernel, or
+  // the wavefronts that do not take a row slab of their own
+  const int KW = pl.shared_stage ? 2 : (pl.WS >= 4 ? 1 : 4 / pl.WS);
+  // (the shared-stage kernel's eight wavefronts of up to 256 registers fill a compute unit by themselves)
+  const int64_t resident = (pl.QT <= 2 && !pl.shared_stage) ? 512 : 256;
   int64_t wgs = resident;
   const int64_t cap = total_blocks / (2 * KW);
   if (wgs > cap) wgs = cap;
@@ -1315,8 +1354,8 @@ extern "C" fspad_status fspad_tree_attn(const fspad_attn_desc* desc, const void*
       const size_t need = (size_t)slots * slot_bytes(d, pl);
       if (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 15)) return FSPAD_ERR_WORKSPACE;
       if (pl.shared_stage) {
-        if (d.head_dim == 128) hipLaunchKernelGGL((tree_attn_gqa_kernel<128, 4>), dim3((unsigned)sl.n_wgs), dim3(256), 0, stream, sl);
-        else hipLaunchKernelGGL((tree_attn_gqa_kernel<64, 4>), dim3((unsigned)sl.n_wgs), dim3(256), 0, stream, sl);
+        if (d.head_dim == 128) hipLaunchKernelGGL((tree_attn_gqa_kernel<128, 4, 2>), dim3((unsigned)sl.n_wgs), dim3(512), 0, stream, sl);
+        else hipLaunchKernelGGL((tree_attn_gqa_kernel<64, 4, 2>), dim3((unsigned)sl.n_wgs), dim3(512), 0, stream, sl);
       } else if (d.head_dim == 128) {
         launch_bf16<128>(pl, sl, stream);
       } else {
