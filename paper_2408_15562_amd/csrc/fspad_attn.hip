@@ -17,6 +17,7 @@
 // fp32 path: plain VALU kernel, one wavefront per query row, used for the small
 // fp32 parity configuration.
 #include <hip/hip_runtime.h>
+#include <stddef.h>
 #include <stdint.h>
 
 #include "fspad.h"
@@ -55,10 +56,86 @@ struct AttnParams {
   uint32_t g_magic, gy_magic;  // ceil(2^32 / G), ceil(2^32 / GY): division by multiplication (unused when the divisor is 1)
   int32_t out_bf16;
   float scale;      // softmax scale
+  // when every sequence of the launch has the same prefix length and node count: the flat blocks of
+  // one sequence (0 otherwise) and those two numbers, so that a workgroup finds its sequence and its
+  // lengths by arithmetic instead of dependent loads from the arrays below
+  int32_t seq_blocks, same_len, same_nodes;
   int32_t kv_len[kMaxBatchPerLaunch];
   int32_t bstart[kMaxBatchPerLaunch + 1];  // first flat block of each sequence; bstart[B] = total_blocks
   int32_t n_nodes[kMaxBatchPerLaunch];
 };
+
+// The scalar part of AttnParams as the kernels use it, fetched from the kernel-argument segment in
+// ONE batch of scalar loads at the top of a kernel. Left to the compiler, the arguments are loaded
+// where they are first needed: eight dependent round trips stood between a wavefront's start and
+// its first K/V request (a kernel that lives for ten to a hundred microseconds notices each of
+// them). The per-sequence arrays stay in the argument segment and are read from there.
+typedef const __attribute__((address_space(4))) int32_t* KernargI32;
+typedef const __attribute__((address_space(4))) char* KernargPtr;
+struct AttnArgs {
+  const void* q;
+  const void* k_tree;
+  const void* v_tree;
+  const void* k_cache;
+  const void* v_cache;
+  const uint64_t* anc_mask;
+  void* out;
+  float* part;
+  int64_t stride_batch, stride_head, stride_token;
+  int32_t B, Nmax, Hq, Hkv, G, WS, ws_shift, NS, GY, n_wgs, total_blocks, wg_quot, wg_rem;
+  uint32_t g_magic, gy_magic;
+  int32_t out_bf16;
+  float scale;
+  int32_t seq_blocks, same_len, same_nodes;
+  KernargI32 kv_len, bstart, n_nodes;
+};
+static_assert(offsetof(AttnParams, stride_batch) == 64 && offsetof(AttnParams, B) == 88 && offsetof(AttnParams, total_blocks) == 128 &&
+              offsetof(AttnParams, scale) == 152 && offsetof(AttnParams, same_nodes) == 164 && offsetof(AttnParams, kv_len) == 168,
+              "fetch_args reads the scalars by their offsets");
+
+__device__ __forceinline__ AttnArgs fetch_args() {
+  typedef int v16i __attribute__((ext_vector_type(16)));
+  KernargPtr ka = (KernargPtr)__builtin_amdgcn_kernarg_segment_ptr();   // AttnParams is the first argument
+  v16i a, b, c;
+  asm volatile("s_load_dwordx16 %0, %3, 0x0\n\ts_load_dwordx16 %1, %3, 0x40\n\ts_load_dwordx16 %2, %3, 0x80\n\ts_waitcnt lgkmcnt(0)"
+               : "=&s"(a), "=&s"(b), "=&s"(c) : "s"(ka));
+  auto u64 = [](int lo, int hi) { return ((uint64_t)(uint32_t)hi << 32) | (uint32_t)lo; };
+  AttnArgs r;
+  r.q = reinterpret_cast<const void*>(u64(a[0], a[1]));
+  r.k_tree = reinterpret_cast<const void*>(u64(a[2], a[3]));
+  r.v_tree = reinterpret_cast<const void*>(u64(a[4], a[5]));
+  r.k_cache = reinterpret_cast<const void*>(u64(a[6], a[7]));
+  r.v_cache = reinterpret_cast<const void*>(u64(a[8], a[9]));
+  r.anc_mask = reinterpret_cast<const uint64_t*>(u64(a[10], a[11]));
+  r.out = reinterpret_cast<void*>(u64(a[12], a[13]));
+  r.part = reinterpret_cast<float*>(u64(a[14], a[15]));
+  r.stride_batch = (int64_t)u64(b[0], b[1]);
+  r.stride_head = (int64_t)u64(b[2], b[3]);
+  r.stride_token = (int64_t)u64(b[4], b[5]);
+  r.B = b[6]; r.Nmax = b[7]; r.Hq = b[8]; r.Hkv = b[9]; r.G = b[10]; r.WS = b[11]; r.ws_shift = b[12]; r.NS = b[13];
+  r.GY = b[14]; r.n_wgs = b[15];
+  r.total_blocks = c[0]; r.wg_quot = c[1]; r.wg_rem = c[2]; r.g_magic = (uint32_t)c[3]; r.gy_magic = (uint32_t)c[4];
+  r.out_bf16 = c[5];
+  const int scale_bits = c[6];   // (a bit cast straight from the vector element reads element 0)
+  r.scale = __builtin_bit_cast(float, scale_bits);
+  r.seq_blocks = c[7]; r.same_len = c[8]; r.same_nodes = c[9];
+  r.kv_len = (KernargI32)(ka + offsetof(AttnParams, kv_len));
+  r.bstart = (KernargI32)(ka + offsetof(AttnParams, bstart));
+  r.n_nodes = (KernargI32)(ka + offsetof(AttnParams, n_nodes));
+  return r;
+}
+// sequence that flat block r0 belongs to, and the first flat block / lengths of a sequence
+__device__ __forceinline__ int seq_of_block(const AttnArgs& p, unsigned r0) {
+  if (p.seq_blocks > 0) return (int)(r0 / (unsigned)p.seq_blocks);
+  int b = 0;
+  while (b + 1 < p.B && r0 >= (unsigned)p.bstart[b + 1]) ++b;
+  return b;
+}
+__device__ __forceinline__ unsigned seq_first_block(const AttnArgs& p, int b) {
+  return p.seq_blocks > 0 ? (unsigned)b * (unsigned)p.seq_blocks : (unsigned)p.bstart[b];
+}
+__device__ __forceinline__ int seq_nodes(const AttnArgs& p, int b) { return p.seq_blocks > 0 ? p.same_nodes : p.n_nodes[b]; }
+__device__ __forceinline__ int seq_len(const AttnArgs& p, int b) { return p.seq_blocks > 0 ? p.same_len : p.kv_len[b]; }
 
 // x / d for x*d < 2^32, with magic = ceil(2^32 / d) (d >= 2) from the host
 __device__ __forceinline__ unsigned div_magic(unsigned x, int d, unsigned magic) {
@@ -67,7 +144,7 @@ __device__ __forceinline__ unsigned div_magic(unsigned x, int d, unsigned magic)
 
 // First flat block of workgroup w under the even split: floor(w * T / W), in 32-bit arithmetic
 // (w * wg_rem < 2^30 because both stay below the 32768 workgroups a launch may have).
-__device__ __forceinline__ unsigned wg_first_block(const AttnParams& p, unsigned w) {
+__device__ __forceinline__ unsigned wg_first_block(const AttnArgs& p, unsigned w) {
   return w * (unsigned)p.wg_quot + (w * (unsigned)p.wg_rem) / (unsigned)p.n_wgs;
 }
 
@@ -273,7 +350,8 @@ __device__ __forceinline__ void process_block(RowState<QT, D>& st, const bf16x8 
 // to `out` directly; otherwise its un-normalised (O, max, sum) goes to partial slot unit+w and the
 // merge kernel finishes the unit.
 template <int QT, int D>
-__global__ __launch_bounds__(256, (QT <= 2 ? 2 : 1)) void tree_attn_bf16_kernel(const AttnParams p) {
+__global__ __launch_bounds__(256, (QT <= 2 ? 2 : 1)) void tree_attn_bf16_kernel(const AttnParams) {
+  const AttnArgs p = fetch_args();
   constexpr int KS = D / 32;
   constexpr int DT = D / 16;
   constexpr int ROWS = 16 * QT;
@@ -312,15 +390,14 @@ __global__ __launch_bounds__(256, (QT <= 2 ? 2 : 1)) void tree_attn_bf16_kernel(
   const unsigned wr = w * (unsigned)p.wg_rem, wq = wr / (unsigned)p.n_wgs;
   const unsigned r0 = w * (unsigned)p.wg_quot + wq;
   const unsigned r1 = r0 + (unsigned)p.wg_quot + ((wr - wq * (unsigned)p.n_wgs) + (unsigned)p.wg_rem >= (unsigned)p.n_wgs ? 1u : 0u);
-  int b = 0;
-  while (b + 1 < p.B && r0 >= (unsigned)p.bstart[b + 1]) ++b;
+  int b = seq_of_block(p, r0);
 
   for (unsigned r = r0; r < r1;) {
-    const int n = p.n_nodes[b];
-    const int L = p.kv_len[b];
+    const int n = seq_nodes(p, b);
+    const int L = seq_len(p, b);
     const int n_prefix_blocks = (L + kBlockKeys - 1) / kBlockKeys;
     const int n_blocks = n_prefix_blocks + (n + kBlockKeys - 1) / kBlockKeys;
-    const unsigned rel = r - (unsigned)p.bstart[b];
+    const unsigned rel = r - seq_first_block(p, b);
     const int ub = (int)(rel / (unsigned)n_blocks);              // unit within the sequence: (g, y)
     const int seg_begin = (int)(rel - (unsigned)ub * (unsigned)n_blocks);
     const int seg_count = min(n_blocks - seg_begin, (int)(r1 - r));
@@ -584,7 +661,7 @@ __global__ __launch_bounds__(256, (QT <= 2 ? 2 : 1)) void tree_attn_bf16_kernel(
         }
     }
     r += (unsigned)seg_count;
-    if (b + 1 < p.B && r >= (unsigned)p.bstart[b + 1]) ++b;
+    if (b + 1 < p.B && r >= seq_first_block(p, b + 1)) ++b;
     if ((KW > 1 || kQInLds) && r < r1) __syncthreads();  // the LDS buffers are reused by the next segment
   }
 }
@@ -627,7 +704,8 @@ typedef __attribute__((address_space(3))) void* LdsPtr;
 // compute unit holds as many wavefronts as two of four, but a cut unit leaves one partial result
 // per workgroup: half as many partial bytes are written and read back.
 template <int D, int WAVES, int KG>
-__global__ __launch_bounds__(64 * WAVES * KG, (KG == 1 ? 2 : 1)) void tree_attn_gqa_kernel(const AttnParams p) {
+__global__ __launch_bounds__(64 * WAVES * KG, (KG == 1 ? 2 : 1)) void tree_attn_gqa_kernel(const AttnParams) {
+  const AttnArgs p = fetch_args();
   typedef Stage<D, WAVES> S;
   constexpr int QT = 2, KS = D / 32, DT = D / 16, ROWS = 32, kWaves = WAVES, kStages = 3;
   constexpr int kGroup = 1;   // blocks per stage
@@ -675,15 +753,14 @@ __global__ __launch_bounds__(64 * WAVES * KG, (KG == 1 ? 2 : 1)) void tree_attn_
   const unsigned wr = w * (unsigned)p.wg_rem, wq = wr / (unsigned)p.n_wgs;
   const unsigned r0 = w * (unsigned)p.wg_quot + wq;
   const unsigned r1 = r0 + (unsigned)p.wg_quot + ((wr - wq * (unsigned)p.n_wgs) + (unsigned)p.wg_rem >= (unsigned)p.n_wgs ? 1u : 0u);
-  int b = 0;
-  while (b + 1 < p.B && r0 >= (unsigned)p.bstart[b + 1]) ++b;
+  int b = seq_of_block(p, r0);
 
   for (unsigned r = r0; r < r1;) {
-    const int n = p.n_nodes[b];
-    const int L = p.kv_len[b];
+    const int n = seq_nodes(p, b);
+    const int L = seq_len(p, b);
     const int n_prefix_blocks = (L + kBlockKeys - 1) / kBlockKeys;
     const int n_blocks = n_prefix_blocks + (n + kBlockKeys - 1) / kBlockKeys;
-    const unsigned rel = r - (unsigned)p.bstart[b];
+    const unsigned rel = r - seq_first_block(p, b);
     const int ub = (int)(rel / (unsigned)n_blocks);
     const int seg_begin = (int)(rel - (unsigned)ub * (unsigned)n_blocks);
     const int seg_count = min(n_blocks - seg_begin, (int)(r1 - r));
@@ -942,14 +1019,14 @@ __global__ __launch_bounds__(64 * WAVES * KG, (KG == 1 ? 2 : 1)) void tree_attn_
       }
     }
     r += (unsigned)seg_count;
-    if (b + 1 < p.B && r >= (unsigned)p.bstart[b + 1]) ++b;
+    if (b + 1 < p.B && r >= seq_first_block(p, b + 1)) ++b;
     __syncthreads();  // every wavefront is done with the stages before the next segment refills them
   }
 }
 
 // Workgroup that owns flat block x under the even split: the w with first(w) <= x < first(w+1).
 // A float estimate (off by one at most for the sizes a launch can have) and a correction.
-__device__ __forceinline__ int owner_of(const AttnParams& p, unsigned x) {
+__device__ __forceinline__ int owner_of(const AttnArgs& p, unsigned x) {
   int w = (int)((float)x * ((float)p.n_wgs / (float)p.total_blocks));
   w = min(w, p.n_wgs - 1);
   while (w > 0 && wg_first_block(p, (unsigned)w) > x) --w;
@@ -961,14 +1038,15 @@ __device__ __forceinline__ int owner_of(const AttnParams& p, unsigned x) {
 // out = sum_s 2^(m_s - M) O_s / sum_s 2^(m_s - M) l_s over the unit's partial slots.
 // One thread per 4 output dims; rows of nodes past n_nodes are written as zeros.
 template <int D>
-__global__ __launch_bounds__(256) void tree_attn_combine_kernel(const AttnParams p, int rows_per_slab) {
+__global__ __launch_bounds__(256) void tree_attn_combine_kernel(const AttnParams, int rows_per_slab) {
+  const AttnArgs p = fetch_args();
   constexpr int TPR = D / 4;  // threads per row
   const int unit = blockIdx.y;
   const int units_per_seq = p.Hkv * p.GY;
   const int b = unit / units_per_seq, ub = unit - b * units_per_seq;
   const int g = (int)div_magic((unsigned)ub, p.GY, p.gy_magic), y = ub - g * p.GY;
-  const int n_blocks = (p.kv_len[b] + kBlockKeys - 1) / kBlockKeys + (p.n_nodes[b] + kBlockKeys - 1) / kBlockKeys;
-  const unsigned fs = (unsigned)p.bstart[b] + (unsigned)ub * (unsigned)n_blocks;
+  const int n_blocks = (seq_len(p, b) + kBlockKeys - 1) / kBlockKeys + (seq_nodes(p, b) + kBlockKeys - 1) / kBlockKeys;
+  const unsigned fs = seq_first_block(p, b) + (unsigned)ub * (unsigned)n_blocks;
   const int w0 = owner_of(p, fs), w1 = owner_of(p, fs + (unsigned)n_blocks - 1u);
   if (w0 == w1) return;  // written directly by the one workgroup that held the whole unit
   const int rows_per_unit = p.WS * rows_per_slab;
@@ -981,7 +1059,7 @@ __global__ __launch_bounds__(256) void tree_attn_combine_kernel(const AttnParams
   const int node = (int)div_magic((unsigned)rr, p.G, p.g_magic), hl = rr - node * p.G;
   const int64_t row = ((int64_t)b * p.Nmax + node) * p.Hq + g * p.G + hl;
   f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-  if (node < p.n_nodes[b]) {
+  if (node < seq_nodes(p, b)) {
     const int64_t slot_floats = (int64_t)rows_per_unit * (D + 2);
     const float* o_base = p.part + (int64_t)(unit + w0) * slot_floats + (int64_t)lr * D + d0;
     const float* ml_base = p.part + (int64_t)(unit + w0) * slot_floats + (int64_t)rows_per_unit * D + 2 * lr;
@@ -1346,6 +1424,11 @@ extern "C" fspad_status fspad_tree_attn(const fspad_attn_desc* desc, const void*
       }
       sl.bstart[nb] = (int32_t)total;
       sl.total_blocks = (int32_t)total;
+      bool same = true;
+      for (int i = 1; i < nb; ++i) same = same && sl.kv_len[i] == sl.kv_len[0] && sl.n_nodes[i] == sl.n_nodes[0];
+      sl.seq_blocks = same ? (int32_t)(units_per_seq * blocks_of(sl.kv_len[0], sl.n_nodes[0])) : 0;
+      sl.same_len = sl.kv_len[0];
+      sl.same_nodes = sl.n_nodes[0];
       const int64_t units = (int64_t)nb * units_per_seq;
       sl.n_wgs = plan_wgs(pl, total, units, uniform, d.workgroups);
       sl.wg_quot = (int32_t)(total / sl.n_wgs);
