@@ -245,6 +245,32 @@ def test_config4_one_layer_long_context_sampled_heads(H):
     assert torch.isfinite(out).all()
 
 
+def test_very_long_prefix(H):
+    """150 000 prefix keys of one kv head under two query heads (4 689 blocks per unit, cut over every
+    compute unit): the flat block arithmetic and the merge at the far end of their ranges."""
+    case = H.AttnCase(505, 1, 64, 2, 1, 128, 150_000, "bf16")
+    _check(H, case, H.TOL["bf16"])
+
+
+def test_token_stride_of_two_megabytes(H):
+    """A cache whose tokens lie 2^20 elements apart (the largest strides the descriptor accepts are of
+    that order): byte offsets inside one sequence pass 4 GB, so every address has to be formed in 64
+    bits. The keys and values themselves are the usual ones, viewed through the wide stride."""
+    L, stride = 2100, 1 << 20
+    case = H.AttnCase(506, 1, 40, 4, 2, 128, L, "bf16")
+    wide = []
+    for t in (case.k_cache, case.v_cache):          # [1, 2, L, 128] contiguous
+        buf = torch.empty((2 * L * stride,), dtype=torch.bfloat16, device=H.DEV)
+        view = buf.as_strided((1, 2, L, 128), (2 * L * stride, L * stride, stride, 1))
+        view.copy_(t)
+        wide.append(view)
+    case.k_cache, case.v_cache = wide
+    assert case.k_cache.stride(2) == stride and (L - 1) * stride * 2 > 4 * 2 ** 30
+    _check(H, case, H.TOL["bf16"])
+    del wide, case
+    torch.cuda.empty_cache()
+
+
 def test_missing_workspace_is_an_error_not_a_crash(H):
     import paper_2408_15562_amd as fspad
     case = H.AttnCase(504, 1, 26, 32, 32, 128, 2048, "bf16")
