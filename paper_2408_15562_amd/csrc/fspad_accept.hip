@@ -195,8 +195,14 @@ __global__ __launch_bounds__(kThreads) void accept_greedy_walk_kernel(const Acce
 }
 
 // ------------------------------------------------------------------------------------------------
+// The sampling walk runs with 1024 threads: its code runs once per call, so what it costs is the
+// longest chain of dependent fp64 instructions in any one thread and the number of instruction lines
+// fetched (cold at every launch), and both shrink when the same arithmetic is spread over more lanes.
+constexpr int kWalkThreads = 1024;
+constexpr int kWalkWaves = kWalkThreads / 64;
+
 // Last step of the sampling pass: the workgroup draws the token at which the running sum of the
-// residual weights of one chunk crosses `target`. Thread k owns PT consecutive entries; their
+// residual weights of one chunk crosses `target`. Thread k owns E consecutive entries; their
 // weights are formed once and stay in registers, so the thread that owns the crossing finds it
 // without touching memory again. If rounding leaves no crossing, the last entry with mass is taken.
 struct DrawArgs {
@@ -205,38 +211,43 @@ struct DrawArgs {
   double M, target, inv_temperature;
   const int* rej_tok;       // tokens rejected at this node: zero weight
   int nrej;
-  double* scan_part;        // LDS scratch: 4 doubles
-  int* sh_i;                // LDS scratch: entries 5 and 6 are used
+  double* scan_part;        // LDS scratch: kWalkWaves doubles
+  int* sh_wave;             // LDS scratch: 2 * kWalkWaves ints
   int32_t* out;
   bool vec;                 // rows are 16-byte aligned
 };
 
-template <int PT>
+template <int E>
 __device__ __forceinline__ void draw_in_chunk(const DrawArgs& a) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int e0 = a.first + tid * PT;
-  float lx[PT];
+  const int e0 = a.first + tid * E;
+  float lx[E];
+  if constexpr (E % 4 == 0) {
 #pragma unroll
-  for (int k = 0; k < PT / 4; ++k) {
-    const int e = e0 + 4 * k;
-    if (a.vec && e + 3 < a.V) {
-      const f32x4 v = *reinterpret_cast<const f32x4*>(a.rp + e);
-      lx[4 * k] = v[0]; lx[4 * k + 1] = v[1]; lx[4 * k + 2] = v[2]; lx[4 * k + 3] = v[3];
-    } else {
+    for (int k = 0; k < E / 4; ++k) {
+      const int e = e0 + 4 * k;
+      if (a.vec && e + 3 < a.V) {
+        const f32x4 v = *reinterpret_cast<const f32x4*>(a.rp + e);
+        lx[4 * k] = v[0]; lx[4 * k + 1] = v[1]; lx[4 * k + 2] = v[2]; lx[4 * k + 3] = v[3];
+      } else {
 #pragma unroll
-      for (int j = 0; j < 4; ++j) lx[4 * k + j] = (e + j < a.V) ? a.rp[e + j] : NAN;
+        for (int j = 0; j < 4; ++j) lx[4 * k + j] = (e + j < a.V) ? a.rp[e + j] : NAN;
+      }
     }
+  } else {
+#pragma unroll
+    for (int j = 0; j < E; ++j) lx[j] = (e0 + j < a.V) ? a.rp[e0 + j] : NAN;
   }
   unsigned gone = 0u;   // bit j: entry e0 + j was rejected at this node and has left the residual
   for (int k = 0; k < a.nrej; ++k) {
     const unsigned r = (unsigned)(a.rej_tok[k] - e0);
-    if (r < (unsigned)PT) gone |= 1u << r;
+    if (r < (unsigned)E) gone |= 1u << r;
   }
-  double w[PT];
+  double w[E];
   double local = 0.0;
   int last_here = -1;
 #pragma unroll
-  for (int j = 0; j < PT; ++j) {
+  for (int j = 0; j < E; ++j) {
     double wj = 0.0;
     if (lx[j] == lx[j] && !((gone >> j) & 1u))   // not NaN (entries past the vocabulary were loaded as NaN)
       wj = exp_nonpos(((double)lx[j] - a.M) * a.inv_temperature);
@@ -251,25 +262,41 @@ __device__ __forceinline__ void draw_in_chunk(const DrawArgs& a) {
     if (lane >= off) incl += up;
   }
   if (lane == 63) a.scan_part[wave] = incl;
-  if (tid == 0) { a.sh_i[5] = kNone; a.sh_i[6] = -1; }
   __syncthreads();
-  double wave_base = 0.0;
-  for (int v = 0; v < wave; ++v) wave_base += a.scan_part[v];
-  // the owner is the first thread whose inclusive running sum exceeds the target
+  double wave_base = 0.0;   // the wavefronts before this one, in order (every partial is read: the loads go out together)
+#pragma unroll
+  for (int v = 0; v < kWalkWaves; ++v) {
+    const double part = a.scan_part[v];
+    if (v < wave) wave_base += part;
+  }
+  // the owner is the first thread whose inclusive running sum exceeds the target: first lane of a
+  // wavefront by ballot, first wavefront through LDS (one slot each: no two lanes meet on an address)
   const double inclusive = wave_base + incl;
-  if (inclusive > a.target && local > 0.0) atomicMin(&a.sh_i[5], tid);
-  if (last_here >= 0) atomicMax(&a.sh_i[6], last_here);
+  const unsigned long long hits = __ballot(inclusive > a.target && local > 0.0);
+  int last_wave = last_here;
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) last_wave = max(last_wave, __shfl_xor(last_wave, off));
+  if (lane == 0) {
+    a.sh_wave[wave] = hits ? wave * 64 + (__ffsll(hits) - 1) : kNone;
+    a.sh_wave[kWalkWaves + wave] = last_wave;
+  }
   __syncthreads();
-  if (a.sh_i[5] == kNone) {  // rounding left no crossing: the last entry with mass
-    if (tid == 0) *a.out = a.sh_i[6] < 0 ? 0 : a.sh_i[6];
+  int owner = kNone, last_any = -1;
+#pragma unroll
+  for (int v = 0; v < kWalkWaves; ++v) {
+    owner = min(owner, a.sh_wave[v]);
+    last_any = max(last_any, a.sh_wave[kWalkWaves + v]);
+  }
+  if (owner == kNone) {  // rounding left no crossing: the last entry with mass
+    if (tid == 0) *a.out = last_any < 0 ? 0 : last_any;
     return;
   }
-  if (tid == a.sh_i[5]) {
+  if (tid == owner) {
     double run = inclusive - local;
     int pick = last_here;  // if rounding hides the crossing inside the segment: its last entry with mass
     bool done = false;
 #pragma unroll
-    for (int j = 0; j < PT; ++j) {
+    for (int j = 0; j < E; ++j) {
       run += w[j];
       if (!done && run > a.target) { pick = e0 + j; done = true; }
     }
@@ -284,12 +311,13 @@ __device__ __forceinline__ void draw_in_chunk(const DrawArgs& a) {
 // already proposed weighs nothing, because it has left the residual by the time it is tested);
 // (3) wavefront 0 walks the tree out of LDS, testing the children of the current node in index
 // order against the running residual; (4) the workgroup draws the last token.
-__global__ __launch_bounds__(kThreads) void accept_sample_walk_kernel(const AcceptParams p) {
+__global__ __launch_bounds__(kWalkThreads) void accept_sample_walk_kernel(const AcceptParams p) {
   __shared__ int rej_tok[FSPAD_MAX_NODES];
   __shared__ double rej_w[FSPAD_MAX_NODES];
   __shared__ double sh_d[8];
   __shared__ int sh_i[8];
-  __shared__ double scan_part[4];
+  __shared__ double scan_part[kWalkWaves];
+  __shared__ int sh_wave[2 * kWalkWaves];
   __shared__ double row_M[FSPAD_MAX_NODES], row_Z[FSPAD_MAX_NODES], node_w[FSPAD_MAX_NODES];
   __shared__ int node_par[FSPAD_MAX_NODES], node_tok[FSPAD_MAX_NODES];
   __shared__ float node_u[2][FSPAD_MAX_NODES];
@@ -297,44 +325,43 @@ __global__ __launch_bounds__(kThreads) void accept_sample_walk_kernel(const Acce
   const int64_t o = (int64_t)b * p.Nmax;
   const float* u_acc = p.uniforms + (int64_t)b * 2 * p.Nmax;
 
-  // (1) row statistics: thread (row = tid / 4, quarter = tid % 4) scans every 4th chunk of its row,
-  // eight chunks in flight at a time, keeping a running (max, sum); the four quarters of a row are
-  // then merged. Nothing here waits for the tree size: rows past it hold unused numbers.
+  // (1) row statistics: thread (row = tid / 16, part = tid % 16) takes every 16th chunk of its row,
+  // two chunks in flight at a time, keeping a running (max, sum); the sixteen parts of a row are then
+  // merged with lane exchanges. Nothing here waits for the tree size: rows past it hold unused numbers.
   const int n_raw = p.n_nodes[b];
   {
-    const int row = tid >> 2, q = tid & 3;
+    const int row = tid >> 4, q = tid & 15;
     const bool in_range = row < p.Nmax;
     const float* pm = p.part_max + (o + (in_range ? row : 0)) * p.n_chunks;
     const double* ps = p.part_sum + (o + (in_range ? row : 0)) * p.n_chunks;
     float m_run = -INFINITY;
     double z_run = 0.0;
     for (int c0 = q; c0 < p.n_chunks; c0 += 32) {
-      float m_c[8];
-      double s_c[8];
+      float m_c[2];
+      double s_c[2];
 #pragma unroll
-      for (int k = 0; k < 8; ++k) {
-        const int c = c0 + 4 * k;
+      for (int k = 0; k < 2; ++k) {
+        const int c = c0 + 16 * k;
         const bool ok = in_range && c < p.n_chunks;
         m_c[k] = ok ? pm[c] : -INFINITY;
         s_c[k] = ok ? ps[c] : 0.0;
       }
-      float m_new = m_run;
-#pragma unroll
-      for (int k = 0; k < 8; ++k) m_new = fmaxf(m_new, m_c[k]);
+      const float m_new = fmaxf(m_run, fmaxf(m_c[0], m_c[1]));
       if (m_new > -INFINITY) {
         double z = m_run > -INFINITY ? z_run * exp_nonpos(((double)m_run - (double)m_new) * p.inv_temperature) : 0.0;
 #pragma unroll
-        for (int k = 0; k < 8; ++k)
+        for (int k = 0; k < 2; ++k)
           if (m_c[k] > -INFINITY) z += s_c[k] * exp_nonpos(((double)m_c[k] - (double)m_new) * p.inv_temperature);
         z_run = z;
         m_run = m_new;
       }
     }
-    float mx = fmaxf(m_run, __shfl_xor(m_run, 1));
-    mx = fmaxf(mx, __shfl_xor(mx, 2));
+    float mx = m_run;
+#pragma unroll
+    for (int off = 1; off < 16; off <<= 1) mx = fmaxf(mx, __shfl_xor(mx, off));
     double z = m_run > -INFINITY ? z_run * exp_nonpos(((double)m_run - (double)mx) * p.inv_temperature) : 0.0;
-    z += __shfl_xor(z, 1);
-    z += __shfl_xor(z, 2);
+#pragma unroll
+    for (int off = 1; off < 16; off <<= 1) z += __shfl_xor(z, off);
     if (in_range && q == 0) { row_M[row] = (double)mx; row_Z[row] = z; }
     if (tid < FSPAD_MAX_NODES) {
       const bool ok = tid < p.Nmax;
@@ -454,7 +481,7 @@ __global__ __launch_bounds__(kThreads) void accept_sample_walk_kernel(const Acce
   }
   __syncthreads();
 
-  // bonus, stage 2: inside the chunk, thread k owns chunk/256 consecutive entries
+  // bonus, stage 2: inside the chunk, thread k owns chunk/1024 consecutive entries
   const int cur = sh_i[0], len = sh_i[1], nrej = sh_i[2], chunk = sh_i[3];
   if (chunk < 0) {  // no mass anywhere (cannot happen with finite logits): token 0
     if (tid == 0) p.tokens[o + len - 1] = 0;
@@ -470,14 +497,14 @@ __global__ __launch_bounds__(kThreads) void accept_sample_walk_kernel(const Acce
   a.rej_tok = rej_tok;
   a.nrej = nrej;
   a.scan_part = scan_part;
-  a.sh_i = sh_i;
+  a.sh_wave = sh_wave;
   a.out = p.tokens + o + len - 1;
   a.vec = (((uintptr_t)p.logits) & 15) == 0 && (p.row_stride % 4) == 0;
-  switch (p.chunk / kThreads) {
+  switch (p.chunk / kWalkThreads) {
+    case 1: draw_in_chunk<1>(a); break;
+    case 2: draw_in_chunk<2>(a); break;
     case 4: draw_in_chunk<4>(a); break;
-    case 8: draw_in_chunk<8>(a); break;
-    case 16: draw_in_chunk<16>(a); break;
-    default: draw_in_chunk<32>(a); break;
+    default: draw_in_chunk<8>(a); break;
   }
 }
 
@@ -799,7 +826,9 @@ __global__ __launch_bounds__(kDraftThreads) void accept_sample_draft_kernel(cons
         if (c0 + lane < w1 && wp[c0 + lane] > 0.0) last = c0 + lane;
       if (tid == 0) sh_last = -1;
       __syncthreads();
-      if (last >= 0) atomicMax(&sh_last, last);   // the highest such entry over the workgroup
+#pragma unroll
+      for (int off = 32; off > 0; off >>= 1) last = max(last, __shfl_xor(last, off));
+      if (lane == 0 && last >= 0) atomicMax(&sh_last, last);   // the highest such entry over the workgroup (one lane a wavefront)
       __syncthreads();
       if (tid == 0) sh_tok = sh_last < 0 ? 0 : sh_last;
       __syncthreads();
@@ -903,7 +932,7 @@ extern "C" fspad_status fspad_tree_accept_sample(int32_t B, int32_t Nmax, int32_
   hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
   launch_rows<1>(p, rows_vectorisable(logits, row_stride), stream);
   if (hipGetLastError() != hipSuccess) return FSPAD_ERR_HIP;
-  hipLaunchKernelGGL(accept_sample_walk_kernel, dim3((unsigned)B), dim3(kThreads), 0, stream, p);
+  hipLaunchKernelGGL(accept_sample_walk_kernel, dim3((unsigned)B), dim3(kWalkThreads), 0, stream, p);
   if (hipGetLastError() != hipSuccess) return FSPAD_ERR_HIP;
   return FSPAD_OK;
 }

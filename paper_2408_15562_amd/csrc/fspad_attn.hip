@@ -279,35 +279,44 @@ __device__ __forceinline__ void process_block(RowState<QT, D>& st, const bf16x8 
           for (int i = 0; i < 4; ++i) s[tt][kt][i] = ((vis >> (16 * kt + i)) & 1u) ? s[tt][kt][i] : -INFINITY;
       }
     }
-    float mx[TP];
+    // exponents of the weights under the shift in use: t = s*c - m. Their maximum decides whether
+    // the shift has to move (results of an fma are canonical numbers: the maximum needs no
+    // quieting of its inputs, unlike one over the raw outputs of the matrix instructions)
+    float tv[TP][8];
     bool grow = false;
 #pragma unroll
     for (int tt = 0; tt < TP; ++tt) {
       if (t0 + tt >= QT) continue;
-      mx[tt] = fmaxf(fmaxf(fmaxf(s[tt][0][0], s[tt][0][1]), fmaxf(s[tt][0][2], s[tt][0][3])),
-                     fmaxf(fmaxf(s[tt][1][0], s[tt][1][1]), fmaxf(s[tt][1][2], s[tt][1][3])));
-      grow = grow || (mx[tt] * c > st.m[t0 + tt] + kLazyLog2);
+      const float m = st.m[t0 + tt];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) tv[tt][j] = fmaf(s[tt][j >> 2][j & 3], c, -m);
+      const float mt = fmaxf(fmaxf(fmaxf(tv[tt][0], tv[tt][1]), fmaxf(tv[tt][2], tv[tt][3])),
+                             fmaxf(fmaxf(tv[tt][4], tv[tt][5]), fmaxf(tv[tt][6], tv[tt][7])));
+      grow = grow || (mt > kLazyLog2);
     }
     if (__any(grow)) {  // wavefront-uniform and rare: move these rows' shifts to their running maxima
 #pragma unroll
       for (int tt = 0; tt < TP; ++tt) {
         if (t0 + tt >= QT) continue;
         const int t = t0 + tt;
-        const float mnew = fmaxf(st.m[t], wave_xor_max_16_32(mx[tt]) * c);
+        const float mx = fmaxf(fmaxf(fmaxf(s[tt][0][0], s[tt][0][1]), fmaxf(s[tt][0][2], s[tt][0][3])),
+                               fmaxf(fmaxf(s[tt][1][0], s[tt][1][1]), fmaxf(s[tt][1][2], s[tt][1][3])));
+        const float mnew = fmaxf(st.m[t], wave_xor_max_16_32(mx) * c);
         const float alpha = __builtin_amdgcn_exp2f(st.m[t] - mnew);
         st.m[t] = mnew;
         st.l[t] *= alpha;
 #pragma unroll
         for (int e = 0; e < DT; ++e) st.o[t][e] *= alpha;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) tv[tt][j] = fmaf(s[tt][j >> 2][j & 3], c, -mnew);
       }
     }
     bf16x8 pf[TP];
 #pragma unroll
     for (int tt = 0; tt < TP; ++tt) {
       if (t0 + tt >= QT) continue;
-      const float m = st.m[t0 + tt];
 #pragma unroll
-      for (int j = 0; j < 8; ++j) pf[tt][j] = (__bf16)__builtin_amdgcn_exp2f(fmaf(s[tt][j >> 2][j & 3], c, -m));
+      for (int j = 0; j < 8; ++j) pf[tt][j] = (__bf16)__builtin_amdgcn_exp2f(tv[tt][j]);
     }
     auto transposed = [&](int e) {  // A operand of d-tile e from the lane's 8 x DT slice of V
       if constexpr (kVReady) {

@@ -363,6 +363,7 @@ __global__ __launch_bounds__(kWalkThreads) void lm_head_sample_walk_kernel(const
   __shared__ float node_u[2][FSPAD_MAX_NODES];
   __shared__ float slice_logit[16];
   __shared__ double wave_sum[kWalkThreads / 64];
+  __shared__ int wave_first[kWalkThreads / 64], wave_last[kWalkThreads / 64];
   const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int64_t o = (int64_t)b * p.Nmax;
   const float* u_acc = p.uniforms + (int64_t)b * 2 * p.Nmax;
@@ -462,6 +463,7 @@ __global__ __launch_bounds__(kWalkThreads) void lm_head_sample_walk_kernel(const
     const float* pm = p.part_max + row * p.n_slices;
     const double* ps = p.part_sum + row * p.n_slices;
     double carry = 0.0;
+    int last_mass = -1;
     for (int c0 = 0; c0 < p.n_slices; c0 += kWalkThreads) {
       const int c = c0 + tid;
       double r = 0.0;
@@ -486,21 +488,32 @@ __global__ __launch_bounds__(kWalkThreads) void lm_head_sample_walk_kernel(const
       double total = carry;
       for (int w2 = 0; w2 < kWalkThreads / 64; ++w2) total += wave_sum[w2];
       const double inclusive = base + incl;
-      if (c < p.n_slices && r > 0.0) {
-        atomicMax(&sh_i[4], c);                              // the last slice with mass (rounding fallback)
-        if (inclusive > t) atomicMin(&sh_i[3], c);
+      // first slice above t and last slice with mass (the rounding fallback): by ballot inside a
+      // wavefront, one LDS slot per wavefront across them (no two lanes meet on an address)
+      const bool has_mass = c < p.n_slices && r > 0.0;
+      const unsigned long long mass = __ballot(has_mass), hit = __ballot(has_mass && inclusive > t);
+      if (lane == 0) {
+        wave_first[wave] = hit ? c0 + wave * 64 + (__ffsll(hit) - 1) : kNone;
+        wave_last[wave] = mass ? c0 + wave * 64 + (63 - __clzll(mass)) : -1;
       }
       __syncthreads();
-      const int found = sh_i[3];
+      int found = kNone;
+#pragma unroll
+      for (int w2 = 0; w2 < kWalkThreads / 64; ++w2) {
+        found = min(found, wave_first[w2]);
+        last_mass = max(last_mass, wave_last[w2]);
+      }
       if (found != kNone) {
         if (c == found) sh_d[2] = t - (inclusive - r);       // what is left of t inside the slice
+        if (tid == 0) sh_i[3] = found;
         break;
       }
       carry = total;
+      __syncthreads();   // the slots are rewritten in the next turn
     }
     __syncthreads();
     if (tid == 0) {
-      if (sh_i[3] == kNone) { sh_i[3] = sh_i[4]; sh_d[2] = INFINITY; }   // no crossing: the last slice with mass, to its end
+      if (sh_i[3] == kNone) { sh_i[3] = last_mass; sh_d[2] = INFINITY; }   // no crossing: the last slice with mass, to its end
       sh_d[1] = sh_d[2];
     }
   }
@@ -581,8 +594,11 @@ __global__ __launch_bounds__(kWalkThreads) void lm_head_sample_walk_kernel(const
       const double up = __shfl_up(incl, off);
       if (lane >= off) incl += up;
     }
-    if (incl > sh_d[3] && w > 0.0) atomicMin(&sh_i[5], tid);
-    if (w > 0.0) atomicMax(&sh_i[6], e);
+    const unsigned long long hit = __ballot(incl > sh_d[3] && w > 0.0), mass = __ballot(w > 0.0);
+    if (tid == 0) {
+      sh_i[5] = hit ? __ffsll(hit) - 1 : kNone;
+      sh_i[6] = mass ? e0 + (63 - __clzll(mass)) : -1;
+    }
   }
   __syncthreads();
   if (tid == 0) {
