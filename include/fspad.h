@@ -235,8 +235,16 @@ fspad_status fspad_tree_accept_sample(int32_t B, int32_t Nmax, int32_t V,
  *   workspace    dev, 16-byte aligned, >= fspad_tree_accept_sample_draft_workspace_bytes(B,Nmax,V)
  *                (3 V fp64 entries per sequence and the chunk statistics of both logit arrays); two
  *                calls that may overlap need different ones
- * All arithmetic that takes a decision is fp64. One workgroup walks each sequence: the cost is a
- * few passes over the two rows of every node on the accepted path (not over all B*Nmax rows).
+ * All arithmetic that takes a decision is fp64. With at most 256 sequences and a vocabulary of at
+ * most 524288 entries a sequence is walked by up to 64 workgroups that keep their shares of the
+ * node's two rows in registers and meet after every rejection (a cooperative launch: all of them
+ * resident; every wait is bounded all the same); otherwise, or where the device refuses such a
+ * launch, by one workgroup. Either way the cost is a few passes over the two rows of every node on
+ * the accepted path (not over all B*Nmax rows).
+ * Error reporting on the device: path_len[b] = n_tokens[b] = -1 says that the workgroups of
+ * sequence b stopped waiting for one another (they could not run side by side); the other outputs
+ * of that sequence are then undefined. It cannot happen while the launch itself succeeds as a
+ * cooperative one, which the runtime only grants when the whole grid fits.
  */
 size_t fspad_tree_accept_sample_draft_workspace_bytes(int32_t B, int32_t Nmax, int32_t V);
 fspad_status fspad_tree_accept_sample_draft(int32_t B, int32_t Nmax, int32_t V,

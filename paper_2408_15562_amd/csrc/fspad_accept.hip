@@ -12,6 +12,7 @@
 // out of LDS and, for sampling, draws the last token by an inverse-CDF search that
 // descends chunk -> thread segment -> element.
 #include <hip/hip_runtime.h>
+#include <algorithm>
 #include <stdint.h>
 
 #include <mutex>
@@ -48,6 +49,8 @@ struct AcceptParams {
   double inv_temperature;
   int32_t B, Nmax, V, n_chunks;
   int32_t chunk;       // logits per (row, chunk) workgroup: 256 * PT
+  uint32_t* clear_words;   // words this launch sets to zero for the kernel behind it (may be null)
+  int32_t clear_count;
 };
 
 __device__ __forceinline__ float clean(float x) { return (x != x) ? -INFINITY : x; }  // NaN ranks lowest
@@ -69,6 +72,8 @@ __global__ __launch_bounds__(kThreads) void accept_rows_kernel(const AcceptParam
   __shared__ double sh_sum[4];
   const int row = blockIdx.y, chunk = blockIdx.x;
   const int b = row / p.Nmax, node = row - b * p.Nmax;
+  if (row == 0 && chunk == 0)
+    for (int i = threadIdx.x; i < p.clear_count; i += kThreads) p.clear_words[i] = 0u;
   if (node >= p.n_nodes[b]) return;  // rows of unused tree slots are never read
   const float* rp = p.logits + (int64_t)row * p.row_stride;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -842,6 +847,344 @@ __global__ __launch_bounds__(kDraftThreads) void accept_sample_draft_kernel(cons
   }
 }
 
+
+// ------------------------------------------------------------------------------------------------
+// The same acceptance spread over the chip. With one workgroup per sequence every rejection is a
+// pass over two rows of V fp64 entries at the rate of one compute unit. Here G workgroups share a
+// sequence: each thread keeps E consecutive entries of the unnormalised p and q of the current node
+// in registers, a rejection is arithmetic on registers plus one barrier across the G workgroups
+// (partial sums and the two entries the next test needs go through memory), and the draw is located
+// from the workgroups' totals. Every workgroup takes every decision from the same published numbers,
+// summed in the same order, so the control flow is the same in all of them.
+//
+// The barrier counts arrivals in a word that the streaming pass of the same call has set to zero;
+// the kernel is launched as a cooperative grid (all workgroups resident). A wait is bounded all the
+// same: a workgroup that sees no progress for kSpinLimit polls raises the sequence's failure word,
+// reports path_len = n_tokens = -1 and leaves, and so does every other workgroup at its next wait.
+constexpr int kGridThreads = 256;
+constexpr int kGridWaves = kGridThreads / 64;
+constexpr int kGridMaxWgs = 64;          // workgroups per sequence, at most
+constexpr unsigned kSpinLimit = 1u << 20;
+
+struct DraftGridParams {
+  const float* logits;
+  const float* draft_logits;
+  int64_t row_stride;
+  const int32_t* draft_tokens;
+  const int32_t* parent;
+  const int32_t* n_nodes;
+  const float* uniforms;
+  int32_t* path;
+  int32_t* path_len;
+  int32_t* tokens;
+  int32_t* n_tokens;
+  const float* part_max_p;
+  const double* part_sum_p;
+  const float* part_max_q;
+  const double* part_sum_q;
+  uint32_t* sync;      // [B][2]: arrivals, failure word
+  double* slots;       // [B][2][G][4]: per round parity and workgroup: sum of the new p, of what q keeps, of the old p
+  double* pubs;        // [B][2][4]: the next test's entry of the new p, of the old p, of q
+  double inv_temperature;
+  int32_t B, Nmax, V, n_chunks, G;
+};
+
+__device__ __forceinline__ double grid_wg_sum(double v, double* sh) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
+  __syncthreads();                  // sh may still be read from the previous reduction
+  if (lane == 0) sh[wave] = v;
+  __syncthreads();
+  return (sh[0] + sh[1]) + (sh[2] + sh[3]);
+}
+
+__device__ __forceinline__ float grid_wg_max(float v, float* sh) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off));
+  __syncthreads();
+  if (lane == 0) sh[wave] = v;
+  __syncthreads();
+  return fmaxf(fmaxf(sh[0], sh[1]), fmaxf(sh[2], sh[3]));
+}
+
+// All G workgroups of a sequence meet; what each wrote before is visible to all after. False: the wait ran out.
+__device__ __forceinline__ bool grid_barrier(uint32_t* sync, unsigned target, int* sh_ok) {
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    __threadfence();
+    __hip_atomic_fetch_add(&sync[0], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    unsigned polls = 0;
+    int ok = 1;
+    while (__hip_atomic_load(&sync[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target) {
+      if (__hip_atomic_load(&sync[1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u || ++polls > kSpinLimit) {
+        __hip_atomic_store(&sync[1], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        ok = 0;
+        break;
+      }
+      __builtin_amdgcn_s_sleep(4);
+    }
+    __threadfence();
+    *sh_ok = ok;
+  }
+  __syncthreads();
+  return *sh_ok != 0;
+}
+
+template <int E>
+__global__ __launch_bounds__(kGridThreads) void accept_sample_draft_grid_kernel(const DraftGridParams p) {
+  __shared__ double sh_d[kGridWaves];
+  __shared__ float sh_f[kGridWaves];
+  __shared__ int sh_ok;
+  __shared__ int sh_w[2 * kGridWaves];
+  __shared__ double sh_tot[kGridMaxWgs];
+  const int g = blockIdx.x, b = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int G = p.G, V = p.V;
+  const int64_t o = (int64_t)b * p.Nmax;
+  const int n = p.n_nodes[b];
+  const float* u_acc = p.uniforms + (int64_t)b * 2 * p.Nmax;
+  const float* u_draw = u_acc + p.Nmax;
+  uint32_t* sync = p.sync + 2 * b;
+  double* slots = p.slots + (int64_t)b * 2 * G * 4;
+  double* pubs = p.pubs + (int64_t)b * 2 * 4;
+  const int e0 = (g * kGridThreads + tid) * E;   // this thread's E consecutive entries
+
+  if (g == 0)
+    for (int i = tid; i < p.Nmax; i += kGridThreads) { p.path[o + i] = i == 0 ? 0 : -1; p.tokens[o + i] = -1; }
+
+  double rp[E], rq[E];   // unnormalised p and q of the current node, once a rejection or the draw has formed them
+  unsigned round = 0;
+  auto meet = [&]() {
+    ++round;
+    if (grid_barrier(sync, round * (unsigned)G, &sh_ok)) return true;
+    if (tid == 0) { p.path_len[b] = -1; p.n_tokens[b] = -1; }
+    return false;
+  };
+  // sum over the workgroups of entry `what` of this round's slots: the same order in every workgroup
+  auto over_workgroups = [&](int what) {
+    const double* sl = slots + (int64_t)(round & 1u) * G * 4;
+    return grid_wg_sum(tid < G ? sl[tid * 4 + what] : 0.0, sh_d);
+  };
+
+  int cur = 0, len = 1;
+  for (;;) {
+    const float* lrow = p.logits + (o + cur) * p.row_stride;
+    const float* qrow = p.draft_logits + (o + cur) * p.row_stride;
+    const int64_t srow = (o + cur) * p.n_chunks;
+    float mp = -INFINITY, mq = -INFINITY;
+    for (int c = tid; c < p.n_chunks; c += kGridThreads) {
+      mp = fmaxf(mp, p.part_max_p[srow + c]);
+      mq = fmaxf(mq, p.part_max_q[srow + c]);
+    }
+    mp = grid_wg_max(mp, sh_f);
+    mq = grid_wg_max(mq, sh_f);
+    double zp = 0.0, zq = 0.0;
+    for (int c = tid; c < p.n_chunks; c += kGridThreads) {
+      const float cp = p.part_max_p[srow + c], cq = p.part_max_q[srow + c];
+      if (cp > -INFINITY) zp += p.part_sum_p[srow + c] * exp_nonpos(((double)cp - (double)mp) * p.inv_temperature);
+      if (cq > -INFINITY) zq += p.part_sum_q[srow + c] * exp_nonpos(((double)cq - (double)mq) * p.inv_temperature);
+    }
+    zp = grid_wg_sum(zp, sh_d);
+    zq = grid_wg_sum(zq, sh_d);
+    double sp = zp > 0.0 ? 1.0 / zp : 0.0, sq = zq > 0.0 ? 1.0 / zq : 0.0;
+    auto weight_p = [&](int v) {
+      const float a = lrow[v];
+      return (a == a && mp > -INFINITY) ? exp_nonpos(((double)a - (double)mp) * p.inv_temperature) : 0.0;
+    };
+    auto weight_q = [&](int v) {
+      const float c = qrow[v];
+      return (c == c && mq > -INFINITY) ? exp_nonpos(((double)c - (double)mq) * p.inv_temperature) : 0.0;
+    };
+
+    bool filled = false;
+    int total_at = 2;             // which slot entry holds the workgroups' totals of the p in the registers
+    double pub_p = 0.0, pub_q = 0.0;   // the entries of p and q for the child under test, once filled
+    int next = -1;
+    for (int c = cur + 1; c < n && len < p.Nmax; ++c) {
+      if (p.parent[o + c] != cur) continue;
+      const int x = p.draft_tokens[o + c];
+      const bool valid = x >= 0 && x < V;
+      double px = 0.0, qx = 0.0;
+      if (valid && filled) {
+        px = pub_p * sp; qx = pub_q * sq;
+      } else if (valid) {
+        const float a = lrow[x], d = qrow[x];
+        px = (a == a && mp > -INFINITY) ? exp_nonpos(((double)a - (double)mp) * p.inv_temperature) * sp : 0.0;
+        qx = (d == d && mq > -INFINITY) ? exp_nonpos(((double)d - (double)mq) * p.inv_temperature) * sq : 0.0;
+      }
+      if ((double)u_acc[c] * qx < px) { next = c; break; }
+      // rejected: p <- max(p - q, 0), renormalised; q loses x and is renormalised. The sibling tested
+      // next (if any) needs its entries of the new p and q: their owner publishes them in the same round.
+      int x2 = -1;
+      for (int c2 = c + 1; c2 < n; ++c2)
+        if (p.parent[o + c2] == cur) { x2 = p.draft_tokens[o + c2]; break; }
+      const unsigned buf = (round + 1u) & 1u;
+      double rn[E];
+      double z = 0.0, s = 0.0, told = 0.0;
+#pragma unroll
+      for (int j = 0; j < E; ++j) {
+        const int v = e0 + j;
+        double qv, pold, r;
+        if (!filled) {
+          qv = v < V ? weight_q(v) : 0.0;
+          pold = v < V ? weight_p(v) : 0.0;
+        } else {
+          qv = rq[j];
+          pold = rp[j];
+        }
+        r = fmax(pold * sp - qv * sq, 0.0);
+        const double keep = (valid && v == x) ? 0.0 : qv;
+        rn[j] = r; rp[j] = pold; rq[j] = keep;
+        z += r; s += keep; told += pold;
+        if (v == x2 && v < V) { pubs[buf * 4 + 0] = r; pubs[buf * 4 + 1] = pold; pubs[buf * 4 + 2] = keep; }
+      }
+      z = grid_wg_sum(z, sh_d);
+      s = grid_wg_sum(s, sh_d);
+      told = grid_wg_sum(told, sh_d);
+      if (tid == 0) {
+        double* mine = slots + ((int64_t)buf * G + g) * 4;
+        mine[0] = z; mine[1] = s; mine[2] = told;
+      }
+      if (!meet()) return;
+      const double Z = over_workgroups(0), S = over_workgroups(1);
+      const bool moved = Z > 0.0;            // else p = q exactly: p is kept
+      if (moved) {
+#pragma unroll
+        for (int j = 0; j < E; ++j) rp[j] = rn[j];
+        sp = 1.0 / Z;
+      }
+      total_at = moved ? 0 : 2;
+      sq = S > 0.0 ? 1.0 / S : sq;
+      filled = true;
+      pub_p = pubs[(round & 1u) * 4 + (moved ? 0 : 1)];
+      pub_q = pubs[(round & 1u) * 4 + 2];
+    }
+    if (next >= 0) {
+      if (g == 0 && tid == 0) { p.tokens[o + len - 1] = p.draft_tokens[o + next]; p.path[o + len] = next; }
+      ++len;
+      cur = next;
+      continue;
+    }
+
+    // no child accepted: inverse-CDF draw from the current p, located from the workgroups' totals
+    if (!filled) {
+      double told = 0.0;
+#pragma unroll
+      for (int j = 0; j < E; ++j) {
+        rp[j] = e0 + j < V ? weight_p(e0 + j) : 0.0;
+        told += rp[j];
+      }
+      told = grid_wg_sum(told, sh_d);
+      if (tid == 0) slots[((int64_t)((round + 1u) & 1u) * G + g) * 4 + 2] = told;
+      if (!meet()) return;
+      total_at = 2;
+    }
+    if (tid < G) sh_tot[tid] = slots[((int64_t)(round & 1u) * G + tid) * 4 + total_at];
+    __syncthreads();
+    double total = 0.0;
+    for (int w = 0; w < G; ++w) total += sh_tot[w];
+    const double t = (double)u_draw[cur] * total;
+    int owner = -1, last_mass = -1;
+    double before = 0.0;
+    {
+      double run = 0.0;
+      for (int w = 0; w < G; ++w) {
+        if (sh_tot[w] > 0.0) last_mass = w;
+        if (owner < 0 && run + sh_tot[w] > t && sh_tot[w] > 0.0) { owner = w; before = run; }
+        run += sh_tot[w];
+      }
+    }
+    double target = t - before;
+    if (owner < 0) { owner = last_mass; target = INFINITY; }   // rounding left no crossing: the last entry with mass
+    if (owner < 0) {                                            // no mass at all: token 0
+      if (g == 0 && tid == 0) { p.tokens[o + len - 1] = 0; p.path_len[b] = len; p.n_tokens[b] = len; }
+      return;
+    }
+    if (g != owner) return;
+    double local = 0.0;
+    int last_here = -1;
+#pragma unroll
+    for (int j = 0; j < E; ++j) {
+      local += rp[j];
+      if (rp[j] > 0.0) last_here = e0 + j;
+    }
+    double incl = local;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+      const double up = __shfl_up(incl, off);
+      if (lane >= off) incl += up;
+    }
+    __syncthreads();
+    if (lane == 63) sh_d[wave] = incl;
+    __syncthreads();
+    double wave_base = 0.0;
+#pragma unroll
+    for (int w = 0; w < kGridWaves; ++w) {
+      const double part = sh_d[w];
+      if (w < wave) wave_base += part;
+    }
+    const double inclusive = wave_base + incl;
+    const unsigned long long hits = __ballot(inclusive > target && local > 0.0);
+    int last_wave = last_here;
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) last_wave = max(last_wave, __shfl_xor(last_wave, off));
+    if (lane == 0) {
+      sh_w[wave] = hits ? wave * 64 + (__ffsll(hits) - 1) : kNone;
+      sh_w[kGridWaves + wave] = last_wave;
+    }
+    __syncthreads();
+    int first_thread = kNone, last_any = -1;
+#pragma unroll
+    for (int w = 0; w < kGridWaves; ++w) {
+      first_thread = min(first_thread, sh_w[w]);
+      last_any = max(last_any, sh_w[kGridWaves + w]);
+    }
+    if (first_thread == kNone) {
+      if (tid == 0) { p.tokens[o + len - 1] = last_any < 0 ? 0 : last_any; p.path_len[b] = len; p.n_tokens[b] = len; }
+      return;
+    }
+    if (tid == first_thread) {
+      double run = inclusive - local;
+      int pick = last_here;
+      bool done = false;
+#pragma unroll
+      for (int j = 0; j < E; ++j) {
+        run += rp[j];
+        if (!done && run > target && rp[j] > 0.0) { pick = e0 + j; done = true; }
+      }
+      p.tokens[o + len - 1] = pick;
+      p.path_len[b] = len;
+      p.n_tokens[b] = len;
+    }
+    return;
+  }
+}
+
+struct GridPlan { int G, E; size_t slots_at, pubs_at; };
+// E = 0: the chip-wide form does not apply (too many sequences, a vocabulary beyond 64 x 256 x 32 entries or too
+// small to hold the exchange area in the workspace's row buffers, or no cooperative launch on this device).
+GridPlan plan_draft_grid(int32_t B, int32_t V) {
+  GridPlan pl{0, 0, 0, 0};
+  if (B > 256) return pl;
+  int dev = 0, coop = 0;
+  if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&coop, hipDeviceAttributeCooperativeLaunch, dev) != hipSuccess || !coop) {
+    (void)hipGetLastError();
+    return pl;
+  }
+  const int max_g = std::min(kGridMaxWgs, 256 / B);
+  const int64_t per = ((int64_t)V + (int64_t)max_g * kGridThreads - 1) / ((int64_t)max_g * kGridThreads);
+  const int E = per <= 4 ? 4 : per <= 8 ? 8 : per <= 16 ? 16 : per <= 32 ? 32 : 0;
+  if (E == 0) return pl;
+  const int G = (int)(((int64_t)V + (int64_t)kGridThreads * E - 1) / ((int64_t)kGridThreads * E));
+  const size_t slots_at = ((size_t)B * 2 * sizeof(uint32_t) + 255) & ~(size_t)255;
+  const size_t pubs_at = slots_at + (size_t)B * 2 * G * 4 * sizeof(double);
+  const size_t end = pubs_at + (size_t)B * 2 * 4 * sizeof(double);
+  if (end > (size_t)B * 3 * (size_t)V * 8) return pl;
+  pl.G = G; pl.E = E; pl.slots_at = slots_at; pl.pubs_at = pubs_at;
+  return pl;
+}
+
 }  // namespace
 
 extern "C" size_t fspad_tree_accept_workspace_bytes(int32_t B, int32_t Nmax, int32_t V) {
@@ -965,10 +1308,41 @@ extern "C" fspad_status fspad_tree_accept_sample_draft(int32_t B, int32_t Nmax, 
   fill_params(pb, B, Nmax, V, draft_logits, row_stride, draft_tokens, parent, n_nodes, path, path_len, tokens, n_tokens,
               ws + region);
   pa.inv_temperature = pb.inv_temperature = 1.0 / (double)temperature;
+  // Chip-wide form: G workgroups a sequence, E entries a thread, if the shape allows it and the device
+  // runs cooperative grids; else one workgroup a sequence.
+  const GridPlan plan = plan_draft_grid(B, V);
+  char* const work = ws + 2 * region;
+  if (plan.E != 0) {
+    pb.clear_words = reinterpret_cast<uint32_t*>(work);
+    pb.clear_count = 2 * B;
+  }
   launch_rows<1>(pa, rows_vectorisable(logits, row_stride), stream);
   if (hipGetLastError() != hipSuccess) return FSPAD_ERR_HIP;
   launch_rows<1>(pb, rows_vectorisable(draft_logits, row_stride), stream);
   if (hipGetLastError() != hipSuccess) return FSPAD_ERR_HIP;
+  if (plan.E != 0) {
+    DraftGridParams gp{};
+    gp.logits = logits; gp.draft_logits = draft_logits; gp.row_stride = row_stride;
+    gp.draft_tokens = draft_tokens; gp.parent = parent; gp.n_nodes = n_nodes; gp.uniforms = uniforms;
+    gp.path = path; gp.path_len = path_len; gp.tokens = tokens; gp.n_tokens = n_tokens;
+    gp.part_max_p = pa.part_max; gp.part_sum_p = pa.part_sum; gp.part_max_q = pb.part_max; gp.part_sum_q = pb.part_sum;
+    gp.sync = reinterpret_cast<uint32_t*>(work);
+    gp.slots = reinterpret_cast<double*>(work + plan.slots_at);
+    gp.pubs = reinterpret_cast<double*>(work + plan.pubs_at);
+    gp.inv_temperature = pa.inv_temperature;
+    gp.B = B; gp.Nmax = Nmax; gp.V = V; gp.n_chunks = pa.n_chunks; gp.G = plan.G;
+    void* args[] = {&gp};
+    const dim3 grid((unsigned)plan.G, (unsigned)B), block(kGridThreads);
+    hipError_t err = hipErrorInvalidValue;
+    switch (plan.E) {
+      case 4: err = hipLaunchCooperativeKernel(reinterpret_cast<const void*>(&accept_sample_draft_grid_kernel<4>), grid, block, args, 0, stream); break;
+      case 8: err = hipLaunchCooperativeKernel(reinterpret_cast<const void*>(&accept_sample_draft_grid_kernel<8>), grid, block, args, 0, stream); break;
+      case 16: err = hipLaunchCooperativeKernel(reinterpret_cast<const void*>(&accept_sample_draft_grid_kernel<16>), grid, block, args, 0, stream); break;
+      case 32: err = hipLaunchCooperativeKernel(reinterpret_cast<const void*>(&accept_sample_draft_grid_kernel<32>), grid, block, args, 0, stream); break;
+    }
+    if (err == hipSuccess) return FSPAD_OK;
+    (void)hipGetLastError();   // the launch was refused (a capture in progress, say): the one-workgroup form below
+  }
   DraftAcceptParams p{};
   p.logits = logits; p.draft_logits = draft_logits; p.row_stride = row_stride;
   p.draft_tokens = draft_tokens; p.parent = parent; p.n_nodes = n_nodes; p.uniforms = uniforms;

@@ -59,6 +59,14 @@ def test_matches_oracle(B, N, V, peak, noise, T):
     _run(5000 + B + N + V, B, N, V, T, peak=peak, noise=noise)
 
 
+@pytest.mark.parametrize("B,N,V", [(260, 4, 600), (1, 6, 200000), (1, 5, 300001), (40, 8, 5000), (256, 3, 700)])
+def test_both_launch_forms(B, N, V):
+    """The library spreads a sequence over several workgroups when the shape allows it and keeps one
+    workgroup a sequence otherwise: more sequences than the chip-wide form takes; vocabularies that
+    put 16 and 32 entries into a thread; batches that leave a sequence five workgroups, or one."""
+    _run(6100 + B + V, B, N, V, 0.9, peak=2.0, noise=0.5, min_compared=B - max(1, B // 40))
+
+
 def test_walks_accept_reject_and_draw():
     """A drafter close to a peaked target: accepted chains several levels deep, rejections with
     siblings left (the residual max(p - q, 0) applied more than once at a node), draws at inner
