@@ -961,11 +961,6 @@ __global__ __launch_bounds__(kGridThreads) void accept_sample_draft_grid_kernel(
     if (tid == 0) { p.path_len[b] = -1; p.n_tokens[b] = -1; }
     return false;
   };
-  // sum over the workgroups of entry `what` of this round's slots: the same order in every workgroup
-  auto over_workgroups = [&](int what) {
-    const double* sl = slots + (int64_t)(round & 1u) * G * 4;
-    return grid_wg_sum(tid < G ? sl[tid * 4 + what] : 0.0, sh_d);
-  };
 
   int cur = 0, len = 1;
   for (;;) {
@@ -1047,7 +1042,11 @@ __global__ __launch_bounds__(kGridThreads) void accept_sample_draft_grid_kernel(
         mine[0] = z; mine[1] = s; mine[2] = told;
       }
       if (!meet()) return;
-      const double Z = over_workgroups(0), S = over_workgroups(1);
+      // (every load of the round goes out before the first is used: one trip to memory, not three)
+      const double* sl = slots + (int64_t)(round & 1u) * G * 4;
+      const double part_z = tid < G ? sl[tid * 4] : 0.0, part_s = tid < G ? sl[tid * 4 + 1] : 0.0;
+      const double pub_new = pubs[(round & 1u) * 4], pub_old = pubs[(round & 1u) * 4 + 1], pub_keep = pubs[(round & 1u) * 4 + 2];
+      const double Z = grid_wg_sum(part_z, sh_d), S = grid_wg_sum(part_s, sh_d);
       const bool moved = Z > 0.0;            // else p = q exactly: p is kept
       if (moved) {
 #pragma unroll
@@ -1057,8 +1056,8 @@ __global__ __launch_bounds__(kGridThreads) void accept_sample_draft_grid_kernel(
       total_at = moved ? 0 : 2;
       sq = S > 0.0 ? 1.0 / S : sq;
       filled = true;
-      pub_p = pubs[(round & 1u) * 4 + (moved ? 0 : 1)];
-      pub_q = pubs[(round & 1u) * 4 + 2];
+      pub_p = moved ? pub_new : pub_old;
+      pub_q = pub_keep;
     }
     if (next >= 0) {
       if (g == 0 && tid == 0) { p.tokens[o + len - 1] = p.draft_tokens[o + next]; p.path[o + len] = next; }
