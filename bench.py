@@ -626,8 +626,9 @@ def probe_overlap(torch, stream_handle):
             # a turn = 2 x (one 32x32x16 matrix instruction + nv vector instructions)
             out["same_wavefront_one_per_simd"][f"2x(mfma+{nv}{name})"] = cycles(0, nv, trans)
         out["two_wavefronts_per_simd"][f"2mfma_wave_alone"] = cycles(2, 16, trans)
-        out["two_wavefronts_per_simd"][f"16{name}_wave_alone"] = cycles(3, 16, trans)
-        out["two_wavefronts_per_simd"][f"2mfma_wave_beside_16{name}_wave"] = cycles(1, 16, trans)
+        for nv in (4, 8, 16):   # wavefront B's vector instructions per turn
+            out["two_wavefronts_per_simd"][f"{nv}{name}_wave_alone"] = cycles(3, nv, trans)
+            out["two_wavefronts_per_simd"][f"2mfma_wave_beside_{nv}{name}_wave"] = cycles(1, nv, trans)
     return out
 
 

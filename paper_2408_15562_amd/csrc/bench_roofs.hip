@@ -94,7 +94,7 @@ __global__ __launch_bounds__(kThreads) void roofs_mfma_kernel(int iters, float* 
 // mode 0: every wavefront alternates one 32x32x16 matrix instruction with `nv` vector instructions
 //         (one wavefront per SIMD: workgroups of 256 threads, one workgroup per compute unit)
 // mode 1: workgroups of 512 threads, two wavefronts per SIMD: wavefronts 0-3 issue two matrix
-//         instructions per turn, wavefronts 4-7 sixteen vector instructions per turn
+//         instructions per turn, wavefronts 4-7 `nv` vector instructions per turn (sixteen for nv = 0)
 // mode 2 / 3: mode 1 with only the matrix / only the vector wavefronts doing work
 // trans: the vector instruction is v_exp_f32 instead of v_fma_f32
 template <int NV, bool TRANS>
@@ -134,7 +134,7 @@ __global__ __launch_bounds__(512) void roofs_overlap_kernel(int mode, int iters,
       asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(c1) : "v"(a), "v"(b));
     }
   } else if (role == 1 && mode != 2) {
-    for (int it = 0; it < iters; ++it) vector_ops<16, TRANS>(x);
+    for (int it = 0; it < iters; ++it) vector_ops<(NV == 0 ? 16 : NV), TRANS>(x);
   }
   float total = 0.f;
 #pragma unroll

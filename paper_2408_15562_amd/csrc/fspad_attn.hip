@@ -677,9 +677,9 @@ __global__ __launch_bounds__(256, (QT <= 2 ? 2 : 1)) void tree_attn_bf16_kernel(
 
 // ---------------------------------------------------------------------------------------------
 // GQA with many query rows per kv head: four wavefronts per workgroup, 32 rows each (128 rows of
-// one kv head), two such sets per compute unit, i.e. two wavefronts per SIMD, so that one computes
-// while the other waits for LDS, the barrier or its scalar work (matrix and vector instructions of a
-// SIMD take turns on this machine, whichever wavefront they come from). At 32 rows a wavefront
+// one kv head), two such sets per compute unit, i.e. two wavefronts per SIMD, so that the matrix
+// work of one can run beside the vector work and the waits of the other (vector instructions behind a
+// matrix instruction of the same wavefront do not overlap it on this machine). At 32 rows a wavefront
 // cannot afford to fetch every K/V block for itself (four to eight copies of each block through the
 // texture path is what would bound the kernel): the workgroup fetches each block once, every
 // wavefront copying a quarter of it into an LDS stage with the global-to-LDS load (row-contiguous
