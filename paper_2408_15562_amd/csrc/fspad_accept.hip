@@ -13,6 +13,7 @@
 // descends chunk -> thread segment -> element.
 #include <hip/hip_runtime.h>
 #include <algorithm>
+#include <atomic>
 #include <stdint.h>
 
 #include <mutex>
@@ -1166,11 +1167,23 @@ struct GridPlan { int G, E; size_t slots_at, pubs_at; };
 GridPlan plan_draft_grid(int32_t B, int32_t V) {
   GridPlan pl{0, 0, 0, 0};
   if (B > 256) return pl;
-  int dev = 0, coop = 0;
-  if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&coop, hipDeviceAttributeCooperativeLaunch, dev) != hipSuccess || !coop) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) {
     (void)hipGetLastError();
     return pl;
   }
+  static std::atomic<int> coop_known[64];   // 0: not asked yet, 1: no, 2: yes (asked once per device)
+  int known = coop_known[dev].load(std::memory_order_relaxed);
+  if (known == 0) {
+    int coop = 0;
+    if (hipDeviceGetAttribute(&coop, hipDeviceAttributeCooperativeLaunch, dev) != hipSuccess) {
+      (void)hipGetLastError();
+      coop = 0;
+    }
+    known = coop ? 2 : 1;
+    coop_known[dev].store(known, std::memory_order_relaxed);
+  }
+  if (known != 2) return pl;
   const int max_g = std::min(kGridMaxWgs, 256 / B);
   const int64_t per = ((int64_t)V + (int64_t)max_g * kGridThreads - 1) / ((int64_t)max_g * kGridThreads);
   const int E = per <= 4 ? 4 : per <= 8 ? 8 : per <= 16 ? 16 : per <= 32 ? 32 : 0;
