@@ -54,6 +54,26 @@ struct AcceptParams {
   int32_t clear_count;
 };
 
+// Inclusive running sum over the 64 lanes of a wavefront, lane order, with data-parallel-primitive moves
+// (no LDS round trips): four shifts inside each row of 16 lanes (a lane without a source adds 0), then the
+// last lane of row 0 / 2 onto rows 1 / 3 and lane 31 onto rows 2 and 3.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ double dpp_take(double v) {
+  const unsigned long long bits = __builtin_bit_cast(unsigned long long, v);
+  const int lo = __builtin_amdgcn_update_dpp(0, (int)(unsigned)bits, CTRL, ROW_MASK, 0xf, true);
+  const int hi = __builtin_amdgcn_update_dpp(0, (int)(unsigned)(bits >> 32), CTRL, ROW_MASK, 0xf, true);
+  return __builtin_bit_cast(double, ((unsigned long long)(unsigned)hi << 32) | (unsigned)lo);
+}
+__device__ __forceinline__ double wave_running_sum(double v) {
+  v += dpp_take<0x111, 0xf>(v);   // row_shr:1
+  v += dpp_take<0x112, 0xf>(v);   // row_shr:2
+  v += dpp_take<0x114, 0xf>(v);   // row_shr:4
+  v += dpp_take<0x118, 0xf>(v);   // row_shr:8
+  v += dpp_take<0x142, 0xa>(v);   // row_bcast:15 onto rows 1 and 3
+  v += dpp_take<0x143, 0xc>(v);   // row_bcast:31 onto rows 2 and 3
+  return v;
+}
+
 __device__ __forceinline__ float clean(float x) { return (x != x) ? -INFINITY : x; }  // NaN ranks lowest
 
 // (value, index) with "larger value, then lower index" order
@@ -261,12 +281,7 @@ __device__ __forceinline__ void draw_in_chunk(const DrawArgs& a) {
     local += wj;
     if (wj > 0.0) last_here = e0 + j;
   }
-  double incl = local;
-#pragma unroll
-  for (int off = 1; off < 64; off <<= 1) {
-    const double up = __shfl_up(incl, off);
-    if (lane >= off) incl += up;
-  }
+  const double incl = wave_running_sum(local);
   if (lane == 63) a.scan_part[wave] = incl;
   __syncthreads();
   double wave_base = 0.0;   // the wavefronts before this one, in order (every partial is read: the loads go out together)
@@ -461,12 +476,7 @@ __global__ __launch_bounds__(kWalkThreads) void accept_sample_walk_kernel(const 
         for (int k = 0; k < nrej; ++k)
           if (rej_tok[k] >= c * p.chunk && rej_tok[k] < (c + 1) * p.chunk && rej_tok[k] < p.V) r -= rej_w[k];
       }
-      double incl = r;
-#pragma unroll
-      for (int off = 1; off < 64; off <<= 1) {
-        const double up = __shfl_up(incl, off);
-        if (lane >= off) incl += up;
-      }
+      const double incl = wave_running_sum(r);
       const unsigned long long pos = __ballot(r > 0.0);
       if (pos) last_pos = c0 + 63 - __clzll(pos);
       const unsigned long long hit = __ballot(c < p.n_chunks && carry + incl > t);
@@ -1109,12 +1119,7 @@ __global__ __launch_bounds__(kGridThreads) void accept_sample_draft_grid_kernel(
       local += rp[j];
       if (rp[j] > 0.0) last_here = e0 + j;
     }
-    double incl = local;
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-      const double up = __shfl_up(incl, off);
-      if (lane >= off) incl += up;
-    }
+    const double incl = wave_running_sum(local);
     __syncthreads();
     if (lane == 63) sh_d[wave] = incl;
     __syncthreads();
