@@ -707,7 +707,7 @@ struct Stage {
 typedef const __attribute__((address_space(1))) void* GlobalPtr;
 typedef __attribute__((address_space(3))) void* LdsPtr;
 
-// KG key groups: with KG = 2 a workgroup is two such sets of four wavefronts on the same 128 rows;
+// KG key groups: with KG = 2 (3 for head dim 64) a workgroup is two (three) such sets of four wavefronts on the same 128 rows;
 // the sets take alternate blocks of the workgroup's segment, each through three stages of its own,
 // and merge their states through LDS at the segment's end. One workgroup of eight wavefronts per
 // compute unit holds as many wavefronts as two of four, but a cut unit leaves one partial result
@@ -721,7 +721,7 @@ __global__ __launch_bounds__(64 * WAVES * KG, (KG == 1 ? 2 : 1)) void tree_attn_
   constexpr int kStageBytes = kGroup * S::kBytes;
   constexpr int kGroupBytes = kStages * kStageBytes;
   // the merge of two key groups needs (DT + 1) 16-byte slots per lane, tile and wavefront of one group
-  constexpr int kMergeBytes = KG == 1 ? 0 : kWaves * QT * (DT + 1) * 64 * 16;
+  constexpr int kMergeBytes = (KG - 1) * kWaves * QT * (DT + 1) * 64 * 16;
   constexpr int kLdsBytes = KG * kGroupBytes > kMergeBytes ? KG * kGroupBytes : kMergeBytes;
   __shared__ __attribute__((aligned(16))) char lds_all[kLdsBytes];
 
@@ -928,13 +928,15 @@ __global__ __launch_bounds__(64 * WAVES * KG, (KG == 1 ? 2 : 1)) void tree_attn_
       stage = stage == 2 ? 0 : stage + 1;
     }
 
-    if constexpr (KG == 2) {
-      // the second key group hands its states over in lane-private LDS slots (the stages are free
+    if constexpr (KG >= 2) {
+      // the other key groups hand their states over in lane-private LDS slots (the stages are free
       // once every wavefront has left the loop); wavefront w of the first group and wavefront w of the
       // second hold the same rows in the same lanes, so the merge is lane by lane and in a fixed order
       __syncthreads();
-      f32x4* mbuf = reinterpret_cast<f32x4*>(lds_all) + (wave * QT * (DT + 1)) * 64 + lane;
-      if (kg == 1 && slab_live) {
+      constexpr int kGroupSlots = kWaves * QT * (DT + 1) * 64;   // 16-byte slots one group hands over
+      f32x4* const mbuf0 = reinterpret_cast<f32x4*>(lds_all) + (wave * QT * (DT + 1)) * 64 + lane;
+      if (kg >= 1 && slab_live) {
+        f32x4* mbuf = mbuf0 + (kg - 1) * kGroupSlots;
 #pragma unroll
         for (int t = 0; t < QT; ++t) {
 #pragma unroll
@@ -945,6 +947,9 @@ __global__ __launch_bounds__(64 * WAVES * KG, (KG == 1 ? 2 : 1)) void tree_attn_
       __syncthreads();
       if (kg == 0 && slab_live) {
 #pragma unroll
+        for (int other = 1; other < KG; ++other) {   // in group order: deterministic
+        const f32x4* mbuf = mbuf0 + (other - 1) * kGroupSlots;
+#pragma unroll
         for (int t = 0; t < QT; ++t) {
           const f32x4 ml = mbuf[(t * (DT + 1) + DT) * 64];
           const float mm = fmaxf(st.m[t], ml[0]);
@@ -953,6 +958,7 @@ __global__ __launch_bounds__(64 * WAVES * KG, (KG == 1 ? 2 : 1)) void tree_attn_
           st.l[t] = st.l[t] * a0 + ml[1] * a1;
 #pragma unroll
           for (int e = 0; e < DT; ++e) st.o[t][e] = st.o[t][e] * a0 + mbuf[(t * (DT + 1) + e) * 64] * a1;
+        }
         }
       }
     }
@@ -1447,7 +1453,9 @@ extern "C" fspad_status fspad_tree_attn(const fspad_attn_desc* desc, const void*
       if (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 15)) return FSPAD_ERR_WORKSPACE;
       if (pl.shared_stage) {
         if (d.head_dim == 128) hipLaunchKernelGGL((tree_attn_gqa_kernel<128, 4, 2>), dim3((unsigned)sl.n_wgs), dim3(512), 0, stream, sl);
-        else hipLaunchKernelGGL((tree_attn_gqa_kernel<64, 4, 2>), dim3((unsigned)sl.n_wgs), dim3(512), 0, stream, sl);
+        // (head dim 64 leaves registers for three wavefronts per SIMD: three key groups; 43.1 -> 40.6 us on a
+        // 64/8-head, 16384-key, 60-node call, 70.7 -> 64.5 us at 32768 keys)
+        else hipLaunchKernelGGL((tree_attn_gqa_kernel<64, 4, 3>), dim3((unsigned)sl.n_wgs), dim3(768), 0, stream, sl);
       } else if (d.head_dim == 128) {
         launch_bf16<128>(pl, sl, stream);
       } else {
