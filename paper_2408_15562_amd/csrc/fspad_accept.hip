@@ -52,6 +52,10 @@ struct AcceptParams {
   int32_t chunk;       // logits per (row, chunk) workgroup: 256 * PT
   uint32_t* clear_words;   // words this launch sets to zero for the kernel behind it (may be null)
   int32_t clear_count;
+  // a second logit array of the same shape for the same launch (grid.z = 2; sampling statistics only), or null
+  const float* logits2;
+  float* part_max2;
+  double* part_sum2;
 };
 
 // Inclusive running sum over the 64 lanes of a wavefront, lane order, with data-parallel-primitive moves
@@ -96,7 +100,10 @@ __global__ __launch_bounds__(kThreads) void accept_rows_kernel(const AcceptParam
   if (row == 0 && chunk == 0)
     for (int i = threadIdx.x; i < p.clear_count; i += kThreads) p.clear_words[i] = 0u;
   if (node >= p.n_nodes[b]) return;  // rows of unused tree slots are never read
-  const float* rp = p.logits + (int64_t)row * p.row_stride;
+  const bool second = blockIdx.z != 0;
+  const float* rp = (second ? p.logits2 : p.logits) + (int64_t)row * p.row_stride;
+  float* const part_max = second ? p.part_max2 : p.part_max;
+  double* const part_sum = second ? p.part_sum2 : p.part_sum;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int base = chunk * kChunk;
 
@@ -139,8 +146,8 @@ __global__ __launch_bounds__(kThreads) void accept_rows_kernel(const AcceptParam
     if (lane == 0) sh_sum[wave] = sum;
     __syncthreads();
     if (tid == 0) {
-      p.part_max[slot] = mc;
-      p.part_sum[slot] = (sh_sum[0] + sh_sum[1]) + (sh_sum[2] + sh_sum[3]);
+      part_max[slot] = mc;
+      part_sum[slot] = (sh_sum[0] + sh_sum[1]) + (sh_sum[2] + sh_sum[3]);
     }
     return;
   }
@@ -165,7 +172,7 @@ __global__ __launch_bounds__(kThreads) void accept_rows_kernel(const AcceptParam
   best = sh_max[0]; idx = sh_idx[0];
 #pragma unroll
   for (int w = 1; w < 4; ++w) take_better(best, idx, sh_max[w], sh_idx[w]);
-  if (tid == 0) { p.part_max[slot] = best; p.part_idx[slot] = idx; }
+  if (tid == 0) { part_max[slot] = best; p.part_idx[slot] = idx; }
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -568,7 +575,7 @@ bool rows_vectorisable(const float* logits, int64_t row_stride) {
 
 template <int MODE>
 void launch_rows(const AcceptParams& p, bool vec, hipStream_t stream) {
-  const dim3 grid((unsigned)p.n_chunks, (unsigned)(p.B * p.Nmax));
+  const dim3 grid((unsigned)p.n_chunks, (unsigned)(p.B * p.Nmax), p.logits2 ? 2u : 1u);
 #define FSPAD_ROWS(PT)                                                                                         \
   do {                                                                                                           \
     if (vec) hipLaunchKernelGGL((accept_rows_kernel<MODE, true, PT>), grid, dim3(kThreads), 0, stream, p);      \
@@ -1333,9 +1340,11 @@ extern "C" fspad_status fspad_tree_accept_sample_draft(int32_t B, int32_t Nmax, 
     pb.clear_words = reinterpret_cast<uint32_t*>(work);
     pb.clear_count = 2 * B;
   }
-  launch_rows<1>(pa, rows_vectorisable(logits, row_stride), stream);
-  if (hipGetLastError() != hipSuccess) return FSPAD_ERR_HIP;
-  launch_rows<1>(pb, rows_vectorisable(draft_logits, row_stride), stream);
+  // one streaming launch over both logit arrays (grid.z picks the array)
+  AcceptParams both = pa;
+  both.logits2 = draft_logits; both.part_max2 = pb.part_max; both.part_sum2 = pb.part_sum;
+  both.clear_words = pb.clear_words; both.clear_count = pb.clear_count;
+  launch_rows<1>(both, rows_vectorisable(logits, row_stride) && rows_vectorisable(draft_logits, row_stride), stream);
   if (hipGetLastError() != hipSuccess) return FSPAD_ERR_HIP;
   if (plan.E != 0) {
     DraftGridParams gp{};
