@@ -67,6 +67,28 @@ def test_both_launch_forms(B, N, V):
     _run(6100 + B + V, B, N, V, 0.9, peak=2.0, noise=0.5, min_compared=B - max(1, B // 40))
 
 
+def test_one_workspace_call_after_call():
+    """The chip-wide form keeps its arrival counts in the workspace and has the streaming pass of every
+    call set them to zero: calls that follow one another through one workspace (a larger problem, then a
+    smaller one, then the first again) each match the oracle."""
+    import paper_2408_15562_amd as fspad
+    shapes = [(2, 40, 20000), (1, 12, 3000), (2, 40, 20000)]
+    ws = torch.empty(max(fspad.fspad_tree_accept_sample_draft_workspace_bytes(*sh) for sh in shapes), dtype=torch.uint8, device=DEV)
+    ws.fill_(0xAB)   # nothing in it is assumed to be zero
+    for i, (B, N, V) in enumerate(shapes):
+        parent, n_nodes, logits, draft_logits, tokens = _case(6400 + i, B, N, V, 0.8, peak=2.0, noise=0.5)
+        uni = gen_uniforms(i, B, N)
+        out = fspad.fspad_tree_accept_sample_draft(torch.from_numpy(logits).to(DEV), torch.from_numpy(draft_logits).to(DEV),
+                                                   torch.from_numpy(tokens).to(DEV), torch.from_numpy(parent).to(DEV),
+                                                   torch.from_numpy(n_nodes).to(DEV), 0.8, torch.from_numpy(uni).to(DEV), workspace=ws)
+        torch.cuda.synchronize()
+        ref = oracle.accept_sample_draft(logits, draft_logits, tokens, parent, n_nodes, 0.8, uni)
+        keep = ref[4] >= MARGIN
+        assert keep.sum() >= 1
+        for name, g, c in zip(("path", "path_len", "tokens", "n_tokens"), out, ref[:4]):
+            np.testing.assert_array_equal(g.cpu().numpy()[keep], c[keep], err_msg=f"call {i}: {name}")
+
+
 def test_walks_accept_reject_and_draw():
     """A drafter close to a peaked target: accepted chains several levels deep, rejections with
     siblings left (the residual max(p - q, 0) applied more than once at a node), draws at inner
