@@ -917,6 +917,25 @@ __device__ __forceinline__ double grid_wg_sum(double v, double* sh) {
   return (sh[0] + sh[1]) + (sh[2] + sh[3]);
 }
 
+// K sums over the workgroup at once: running sums inside the wavefronts (no LDS), the four totals of each
+// through LDS, one barrier. `sh` holds two sets of K x 4 doubles used in turn, so that a wavefront that
+// runs ahead into the next call writes the other set.
+template <int K>
+__device__ __forceinline__ void grid_wg_sums(double (&v)[K], double* sh, int& flip) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  double* const buf = sh + flip * (K * kGridWaves);
+  flip ^= 1;
+#pragma unroll
+  for (int k = 0; k < K; ++k) {
+    const double run = wave_running_sum(v[k]);
+    if (lane == 63) buf[k * kGridWaves + wave] = run;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int k = 0; k < K; ++k)
+    v[k] = (buf[k * kGridWaves] + buf[k * kGridWaves + 1]) + (buf[k * kGridWaves + 2] + buf[k * kGridWaves + 3]);
+}
+
 __device__ __forceinline__ float grid_wg_max(float v, float* sh) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
 #pragma unroll
@@ -953,10 +972,12 @@ __device__ __forceinline__ bool grid_barrier(uint32_t* sync, unsigned target, in
 template <int E>
 __global__ __launch_bounds__(kGridThreads) void accept_sample_draft_grid_kernel(const DraftGridParams p) {
   __shared__ double sh_d[kGridWaves];
+  __shared__ double sh_sums[2 * 3 * kGridWaves];
   __shared__ float sh_f[kGridWaves];
   __shared__ int sh_ok;
   __shared__ int sh_w[2 * kGridWaves];
   __shared__ double sh_tot[kGridMaxWgs];
+  int flip = 0;
   const int g = blockIdx.x, b = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int G = p.G, V = p.V;
   const int64_t o = (int64_t)b * p.Nmax;
@@ -998,8 +1019,11 @@ __global__ __launch_bounds__(kGridThreads) void accept_sample_draft_grid_kernel(
       if (cp > -INFINITY) zp += p.part_sum_p[srow + c] * exp_nonpos(((double)cp - (double)mp) * p.inv_temperature);
       if (cq > -INFINITY) zq += p.part_sum_q[srow + c] * exp_nonpos(((double)cq - (double)mq) * p.inv_temperature);
     }
-    zp = grid_wg_sum(zp, sh_d);
-    zq = grid_wg_sum(zq, sh_d);
+    {
+      double zz[2] = {zp, zq};
+      grid_wg_sums<2>(zz, sh_sums, flip);
+      zp = zz[0]; zq = zz[1];
+    }
     double sp = zp > 0.0 ? 1.0 / zp : 0.0, sq = zq > 0.0 ? 1.0 / zq : 0.0;
     auto weight_p = [&](int v) {
       const float a = lrow[v];
@@ -1052,9 +1076,11 @@ __global__ __launch_bounds__(kGridThreads) void accept_sample_draft_grid_kernel(
         z += r; s += keep; told += pold;
         if (v == x2 && v < V) { pubs[buf * 4 + 0] = r; pubs[buf * 4 + 1] = pold; pubs[buf * 4 + 2] = keep; }
       }
-      z = grid_wg_sum(z, sh_d);
-      s = grid_wg_sum(s, sh_d);
-      told = grid_wg_sum(told, sh_d);
+      {
+        double three[3] = {z, s, told};
+        grid_wg_sums<3>(three, sh_sums, flip);
+        z = three[0]; s = three[1]; told = three[2];
+      }
       if (tid == 0) {
         double* mine = slots + ((int64_t)buf * G + g) * 4;
         mine[0] = z; mine[1] = s; mine[2] = told;
@@ -1064,7 +1090,9 @@ __global__ __launch_bounds__(kGridThreads) void accept_sample_draft_grid_kernel(
       const double* sl = slots + (int64_t)(round & 1u) * G * 4;
       const double part_z = tid < G ? sl[tid * 4] : 0.0, part_s = tid < G ? sl[tid * 4 + 1] : 0.0;
       const double pub_new = pubs[(round & 1u) * 4], pub_old = pubs[(round & 1u) * 4 + 1], pub_keep = pubs[(round & 1u) * 4 + 2];
-      const double Z = grid_wg_sum(part_z, sh_d), S = grid_wg_sum(part_s, sh_d);
+      double both[2] = {part_z, part_s};
+      grid_wg_sums<2>(both, sh_sums, flip);
+      const double Z = both[0], S = both[1];
       const bool moved = Z > 0.0;            // else p = q exactly: p is kept
       if (moved) {
 #pragma unroll
