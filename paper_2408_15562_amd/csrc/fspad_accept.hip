@@ -976,7 +976,7 @@ __global__ __launch_bounds__(kGridThreads) void accept_sample_draft_grid_kernel(
   __shared__ float sh_f[kGridWaves];
   __shared__ int sh_ok;
   __shared__ int sh_w[2 * kGridWaves];
-  __shared__ double sh_tot[kGridMaxWgs];
+  __shared__ double sh_tot[2];
   int flip = 0;
   const int g = blockIdx.x, b = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int G = p.G, V = p.V;
@@ -1125,23 +1125,23 @@ __global__ __launch_bounds__(kGridThreads) void accept_sample_draft_grid_kernel(
       if (!meet()) return;
       total_at = 2;
     }
-    if (tid < G) sh_tot[tid] = slots[((int64_t)(round & 1u) * G + tid) * 4 + total_at];
-    __syncthreads();
-    double total = 0.0;
-    for (int w = 0; w < G; ++w) total += sh_tot[w];
-    const double t = (double)u_draw[cur] * total;
-    int owner = -1, last_mass = -1;
-    double before = 0.0;
-    {
-      double run = 0.0;
-      for (int w = 0; w < G; ++w) {
-        if (sh_tot[w] > 0.0) last_mass = w;
-        if (owner < 0 && run + sh_tot[w] > t && sh_tot[w] > 0.0) { owner = w; before = run; }
-        run += sh_tot[w];
-      }
+    // wavefront 0, one lane per workgroup (G <= 64): running sum of the totals, first workgroup above t
+    static_assert(kGridMaxWgs <= 64, "one lane per workgroup");
+    if (wave == 0) {
+      const double mine = lane < G ? slots[((int64_t)(round & 1u) * G + lane) * 4 + total_at] : 0.0;
+      const double incl = wave_running_sum(mine);
+      const double total = __shfl(incl, 63);
+      const double t = (double)u_draw[cur] * total;
+      const unsigned long long mass = __ballot(mine > 0.0), hit = __ballot(mine > 0.0 && incl > t);
+      const int first = hit ? __ffsll(hit) - 1 : (mass ? 63 - __clzll(mass) : -1);
+      // (no crossing by rounding: the last workgroup with mass, to its last entry with mass)
+      const double left = hit ? t - (__shfl(incl, first < 0 ? 0 : first) - __shfl(mine, first < 0 ? 0 : first)) : INFINITY;
+      if (lane == 0) { sh_w[0] = first; sh_tot[0] = left; }
     }
-    double target = t - before;
-    if (owner < 0) { owner = last_mass; target = INFINITY; }   // rounding left no crossing: the last entry with mass
+    __syncthreads();
+    const int owner = sh_w[0];
+    const double target = sh_tot[0];
+    __syncthreads();   // sh_w is written again below
     if (owner < 0) {                                            // no mass at all: token 0
       if (g == 0 && tid == 0) { p.tokens[o + len - 1] = 0; p.path_len[b] = len; p.n_tokens[b] = len; }
       return;
