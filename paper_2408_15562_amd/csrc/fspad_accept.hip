@@ -981,7 +981,7 @@ __global__ __launch_bounds__(kGridThreads) void accept_sample_draft_grid_kernel(
   const int g = blockIdx.x, b = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int G = p.G, V = p.V;
   const int64_t o = (int64_t)b * p.Nmax;
-  const int n = p.n_nodes[b];
+  const int n = min(p.n_nodes[b], p.Nmax);
   const float* u_acc = p.uniforms + (int64_t)b * 2 * p.Nmax;
   const float* u_draw = u_acc + p.Nmax;
   uint32_t* sync = p.sync + 2 * b;
@@ -991,6 +991,17 @@ __global__ __launch_bounds__(kGridThreads) void accept_sample_draft_grid_kernel(
 
   if (g == 0)
     for (int i = tid; i < p.Nmax; i += kGridThreads) { p.path[o + i] = i == 0 ? 0 : -1; p.tokens[o + i] = -1; }
+  // the tree and the uniforms go to LDS once: the walk reads them in loops
+  __shared__ int t_par[FSPAD_MAX_NODES], t_tok[FSPAD_MAX_NODES];
+  __shared__ float t_ua[FSPAD_MAX_NODES], t_ud[FSPAD_MAX_NODES];
+  if (tid < FSPAD_MAX_NODES) {
+    const bool ok = tid < p.Nmax;
+    t_par[tid] = ok ? p.parent[o + tid] : -2;
+    t_tok[tid] = ok ? p.draft_tokens[o + tid] : -1;
+    t_ua[tid] = ok ? u_acc[tid] : 0.f;
+    t_ud[tid] = ok ? u_draw[tid] : 0.f;
+  }
+  __syncthreads();
 
   double rp[E], rq[E];   // unnormalised p and q of the current node, once a rejection or the draw has formed them
   unsigned round = 0;
@@ -1039,8 +1050,8 @@ __global__ __launch_bounds__(kGridThreads) void accept_sample_draft_grid_kernel(
     double pub_p = 0.0, pub_q = 0.0;   // the entries of p and q for the child under test, once filled
     int next = -1;
     for (int c = cur + 1; c < n && len < p.Nmax; ++c) {
-      if (p.parent[o + c] != cur) continue;
-      const int x = p.draft_tokens[o + c];
+      if (t_par[c] != cur) continue;
+      const int x = t_tok[c];
       const bool valid = x >= 0 && x < V;
       double px = 0.0, qx = 0.0;
       if (valid && filled) {
@@ -1050,12 +1061,12 @@ __global__ __launch_bounds__(kGridThreads) void accept_sample_draft_grid_kernel(
         px = (a == a && mp > -INFINITY) ? exp_nonpos(((double)a - (double)mp) * p.inv_temperature) * sp : 0.0;
         qx = (d == d && mq > -INFINITY) ? exp_nonpos(((double)d - (double)mq) * p.inv_temperature) * sq : 0.0;
       }
-      if ((double)u_acc[c] * qx < px) { next = c; break; }
+      if ((double)t_ua[c] * qx < px) { next = c; break; }
       // rejected: p <- max(p - q, 0), renormalised; q loses x and is renormalised. The sibling tested
       // next (if any) needs its entries of the new p and q: their owner publishes them in the same round.
       int x2 = -1;
       for (int c2 = c + 1; c2 < n; ++c2)
-        if (p.parent[o + c2] == cur) { x2 = p.draft_tokens[o + c2]; break; }
+        if (t_par[c2] == cur) { x2 = t_tok[c2]; break; }
       const unsigned buf = (round + 1u) & 1u;
       double rn[E];
       double z = 0.0, s = 0.0, told = 0.0;
@@ -1106,7 +1117,7 @@ __global__ __launch_bounds__(kGridThreads) void accept_sample_draft_grid_kernel(
       pub_q = pub_keep;
     }
     if (next >= 0) {
-      if (g == 0 && tid == 0) { p.tokens[o + len - 1] = p.draft_tokens[o + next]; p.path[o + len] = next; }
+      if (g == 0 && tid == 0) { p.tokens[o + len - 1] = t_tok[next]; p.path[o + len] = next; }
       ++len;
       cur = next;
       continue;
@@ -1131,7 +1142,7 @@ __global__ __launch_bounds__(kGridThreads) void accept_sample_draft_grid_kernel(
       const double mine = lane < G ? slots[((int64_t)(round & 1u) * G + lane) * 4 + total_at] : 0.0;
       const double incl = wave_running_sum(mine);
       const double total = __shfl(incl, 63);
-      const double t = (double)u_draw[cur] * total;
+      const double t = (double)t_ud[cur] * total;
       const unsigned long long mass = __ballot(mine > 0.0), hit = __ballot(mine > 0.0 && incl > t);
       const int first = hit ? __ffsll(hit) - 1 : (mass ? 63 - __clzll(mass) : -1);
       // (no crossing by rounding: the last workgroup with mass, to its last entry with mass)
