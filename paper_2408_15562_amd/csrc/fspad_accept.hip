@@ -903,6 +903,7 @@ struct DraftGridParams {
   uint32_t* sync;      // [B][2]: arrivals, failure word
   double* slots;       // [B][2][G][4]: per round parity and workgroup: sum of the new p, of what q keeps, of the old p
   double* pubs;        // [B][2][4]: the next test's entry of the new p, of the old p, of q
+  double* row_stats;   // [2][B*Nmax][2]: (max, sum of exponentials) of every row of logits, then of draft_logits
   double inv_temperature;
   int32_t B, Nmax, V, n_chunks, G;
 };
@@ -969,6 +970,34 @@ __device__ __forceinline__ bool grid_barrier(uint32_t* sync, unsigned target, in
   return *sh_ok != 0;
 }
 
+// Row statistics of both logit arrays from the chunk statistics of the streaming pass, for every row at once
+// (one workgroup per row and array): the walk then finds a node's (max, sum) ready instead of merging them,
+// node after node, on its critical path.
+__global__ __launch_bounds__(kGridThreads) void accept_row_merge_kernel(const DraftGridParams p) {
+  __shared__ double sh_sums[2 * kGridWaves];
+  __shared__ float sh_f[kGridWaves];
+  const int row = blockIdx.x, arr = blockIdx.y, tid = threadIdx.x;
+  const int b = row / p.Nmax, node = row - b * p.Nmax;
+  if (node >= p.n_nodes[b]) return;   // rows of unused tree slots have no chunk statistics
+  const float* pm = (arr ? p.part_max_q : p.part_max_p) + (int64_t)row * p.n_chunks;
+  const double* ps = (arr ? p.part_sum_q : p.part_sum_p) + (int64_t)row * p.n_chunks;
+  float m = -INFINITY;
+  for (int c = tid; c < p.n_chunks; c += kGridThreads) m = fmaxf(m, pm[c]);
+  m = grid_wg_max(m, sh_f);
+  double z[1] = {0.0};
+  for (int c = tid; c < p.n_chunks; c += kGridThreads) {
+    const float mc = pm[c];
+    if (mc > -INFINITY) z[0] += ps[c] * exp_nonpos(((double)mc - (double)m) * p.inv_temperature);
+  }
+  int flip = 0;
+  grid_wg_sums<1>(z, sh_sums, flip);
+  if (tid == 0) {
+    double* out = p.row_stats + ((int64_t)arr * p.B * p.Nmax + row) * 2;
+    out[0] = (double)m;
+    out[1] = z[0];
+  }
+}
+
 template <int E>
 __global__ __launch_bounds__(kGridThreads) void accept_sample_draft_grid_kernel(const DraftGridParams p) {
   __shared__ double sh_d[kGridWaves];
@@ -994,6 +1023,11 @@ __global__ __launch_bounds__(kGridThreads) void accept_sample_draft_grid_kernel(
   // the tree and the uniforms go to LDS once: the walk reads them in loops
   __shared__ int t_par[FSPAD_MAX_NODES], t_tok[FSPAD_MAX_NODES];
   __shared__ float t_ua[FSPAD_MAX_NODES], t_ud[FSPAD_MAX_NODES];
+  __shared__ double t_stats[2][FSPAD_MAX_NODES][2];   // (max, sum) of every row of this sequence: logits, draft logits
+  for (int i = tid; i < 4 * p.Nmax; i += kGridThreads) {
+    const int arr = i / (2 * p.Nmax), rest = i - arr * 2 * p.Nmax;
+    t_stats[arr][rest >> 1][rest & 1] = p.row_stats[((int64_t)arr * p.B * p.Nmax + o) * 2 + rest];
+  }
   if (tid < FSPAD_MAX_NODES) {
     const bool ok = tid < p.Nmax;
     t_par[tid] = ok ? p.parent[o + tid] : -2;
@@ -1016,25 +1050,8 @@ __global__ __launch_bounds__(kGridThreads) void accept_sample_draft_grid_kernel(
   for (;;) {
     const float* lrow = p.logits + (o + cur) * p.row_stride;
     const float* qrow = p.draft_logits + (o + cur) * p.row_stride;
-    const int64_t srow = (o + cur) * p.n_chunks;
-    float mp = -INFINITY, mq = -INFINITY;
-    for (int c = tid; c < p.n_chunks; c += kGridThreads) {
-      mp = fmaxf(mp, p.part_max_p[srow + c]);
-      mq = fmaxf(mq, p.part_max_q[srow + c]);
-    }
-    mp = grid_wg_max(mp, sh_f);
-    mq = grid_wg_max(mq, sh_f);
-    double zp = 0.0, zq = 0.0;
-    for (int c = tid; c < p.n_chunks; c += kGridThreads) {
-      const float cp = p.part_max_p[srow + c], cq = p.part_max_q[srow + c];
-      if (cp > -INFINITY) zp += p.part_sum_p[srow + c] * exp_nonpos(((double)cp - (double)mp) * p.inv_temperature);
-      if (cq > -INFINITY) zq += p.part_sum_q[srow + c] * exp_nonpos(((double)cq - (double)mq) * p.inv_temperature);
-    }
-    {
-      double zz[2] = {zp, zq};
-      grid_wg_sums<2>(zz, sh_sums, flip);
-      zp = zz[0]; zq = zz[1];
-    }
+    // (rows of nodes beyond the tree are never walked: their entries hold no statistics)
+    const double mp = t_stats[0][cur][0], zp = t_stats[0][cur][1], mq = t_stats[1][cur][0], zq = t_stats[1][cur][1];
     double sp = zp > 0.0 ? 1.0 / zp : 0.0, sq = zq > 0.0 ? 1.0 / zq : 0.0;
     auto weight_p = [&](int v) {
       const float a = lrow[v];
@@ -1212,11 +1229,11 @@ __global__ __launch_bounds__(kGridThreads) void accept_sample_draft_grid_kernel(
   }
 }
 
-struct GridPlan { int G, E; size_t slots_at, pubs_at; };
+struct GridPlan { int G, E; size_t slots_at, pubs_at, stats_at; };
 // E = 0: the chip-wide form does not apply (too many sequences, a vocabulary beyond 64 x 256 x 32 entries or too
 // small to hold the exchange area in the workspace's row buffers, or no cooperative launch on this device).
-GridPlan plan_draft_grid(int32_t B, int32_t V) {
-  GridPlan pl{0, 0, 0, 0};
+GridPlan plan_draft_grid(int32_t B, int32_t Nmax, int32_t V) {
+  GridPlan pl{0, 0, 0, 0, 0};
   if (B > 256) return pl;
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) {
@@ -1242,9 +1259,10 @@ GridPlan plan_draft_grid(int32_t B, int32_t V) {
   const int G = (int)(((int64_t)V + (int64_t)kGridThreads * E - 1) / ((int64_t)kGridThreads * E));
   const size_t slots_at = ((size_t)B * 2 * sizeof(uint32_t) + 255) & ~(size_t)255;
   const size_t pubs_at = slots_at + (size_t)B * 2 * G * 4 * sizeof(double);
-  const size_t end = pubs_at + (size_t)B * 2 * 4 * sizeof(double);
+  const size_t stats_at = pubs_at + (size_t)B * 2 * 4 * sizeof(double);
+  const size_t end = stats_at + (size_t)2 * B * Nmax * 2 * sizeof(double);
   if (end > (size_t)B * 3 * (size_t)V * 8) return pl;
-  pl.G = G; pl.E = E; pl.slots_at = slots_at; pl.pubs_at = pubs_at;
+  pl.G = G; pl.E = E; pl.slots_at = slots_at; pl.pubs_at = pubs_at; pl.stats_at = stats_at;
   return pl;
 }
 
@@ -1373,7 +1391,7 @@ extern "C" fspad_status fspad_tree_accept_sample_draft(int32_t B, int32_t Nmax, 
   pa.inv_temperature = pb.inv_temperature = 1.0 / (double)temperature;
   // Chip-wide form: G workgroups a sequence, E entries a thread, if the shape allows it and the device
   // runs cooperative grids; else one workgroup a sequence.
-  const GridPlan plan = plan_draft_grid(B, V);
+  const GridPlan plan = plan_draft_grid(B, Nmax, V);
   char* const work = ws + 2 * region;
   if (plan.E != 0) {
     pb.clear_words = reinterpret_cast<uint32_t*>(work);
@@ -1394,8 +1412,11 @@ extern "C" fspad_status fspad_tree_accept_sample_draft(int32_t B, int32_t Nmax, 
     gp.sync = reinterpret_cast<uint32_t*>(work);
     gp.slots = reinterpret_cast<double*>(work + plan.slots_at);
     gp.pubs = reinterpret_cast<double*>(work + plan.pubs_at);
+    gp.row_stats = reinterpret_cast<double*>(work + plan.stats_at);
     gp.inv_temperature = pa.inv_temperature;
     gp.B = B; gp.Nmax = Nmax; gp.V = V; gp.n_chunks = pa.n_chunks; gp.G = plan.G;
+    hipLaunchKernelGGL(accept_row_merge_kernel, dim3((unsigned)(B * Nmax), 2u), dim3(kGridThreads), 0, stream, gp);
+    if (hipGetLastError() != hipSuccess) return FSPAD_ERR_HIP;
     void* args[] = {&gp};
     const dim3 grid((unsigned)plan.G, (unsigned)B), block(kGridThreads);
     hipError_t err = hipErrorInvalidValue;
