@@ -129,3 +129,59 @@ def test_deterministic_and_reusable_workspace(H):
     for x, y in zip(a, b):
         assert torch.equal(x, y)
     H.assert_accept_equal([t.cpu().numpy() for t in g], case.cpu_greedy())
+
+
+@pytest.mark.parametrize("V", [1024, 5000, 128256])
+def test_draw_finds_a_point_mass_at_lane_wavefront_and_chunk_edges(V):
+    """A root without children draws its token from the target's distribution. With all the mass on one
+    entry the draw must return that entry whatever the uniform is (closed form); the entries sit on both
+    sides of the borders of the draw's running sums: lanes 15|16, 31|32, 63|64, thread, wavefront and
+    chunk edges, the first and the last entry of the vocabulary. The same through the sampled-draft entry point."""
+    import paper_2408_15562_amd as fspad
+    from workloads import gen_uniforms
+    spots = sorted({i for i in (0, 1, 15, 16, 31, 32, 63, 64, 255, 256, 1023, 1024, 4095, 4096, 8191, 8192, 65535, 65536,
+                                V // 2, V - 2, V - 1) if i < V})
+    B = len(spots)
+    logits = np.full((B, 1, V), -30000.0, np.float32)
+    for b, i in enumerate(spots):
+        logits[b, 0, i] = 3.0
+    tokens = np.zeros((B, 1), np.int32)
+    parent = np.full((B, 1), -1, np.int32)
+    n_nodes = np.ones(B, np.int32)
+    dev = "cuda:0"
+    for useed in range(3):
+        uni = torch.from_numpy(gen_uniforms(useed, B, 1)).to(dev)
+        args = [torch.from_numpy(a).to(dev) for a in (tokens, parent, n_nodes)]
+        lg = torch.from_numpy(logits).to(dev)
+        out = fspad.fspad_tree_accept_sample(lg, *args, 0.8, uni)
+        out2 = fspad.fspad_tree_accept_sample_draft(lg, lg.clone(), *args, 0.8, uni)
+        torch.cuda.synchronize()
+        for o in (out, out2):
+            assert o[1].cpu().tolist() == [1] * B and o[3].cpu().tolist() == [1] * B
+            assert o[2].cpu().numpy()[:, 0].tolist() == spots
+
+
+@pytest.mark.parametrize("V", [5000, 128256])
+def test_draw_splits_two_equal_masses_at_every_border(V):
+    """Two neighbouring entries with half of the mass each, on the two sides of a border of the draw's running
+    sums: a uniform of 0.25 must give the first, 0.75 the second (closed form), through both sampling entry points."""
+    import paper_2408_15562_amd as fspad
+    firsts = sorted({i for i in (0, 15, 31, 63, 255, 1023, 4095, 8191, 65535, V // 2, V - 2) if i + 1 < V})
+    B = 2 * len(firsts)
+    logits = np.full((B, 1, V), -30000.0, np.float32)
+    uni = np.zeros((B, 2, 1), np.float32)
+    want = []
+    for k, i in enumerate(firsts):
+        for half in (0, 1):
+            b = 2 * k + half
+            logits[b, 0, i] = logits[b, 0, i + 1] = -1.5
+            uni[b, 1, 0] = 0.25 + 0.5 * half
+            want.append(i + half)
+    dev = "cuda:0"
+    args = [torch.from_numpy(a).to(dev) for a in (np.zeros((B, 1), np.int32), np.full((B, 1), -1, np.int32), np.ones(B, np.int32))]
+    lg, u = torch.from_numpy(logits).to(dev), torch.from_numpy(uni).to(dev)
+    out = fspad.fspad_tree_accept_sample(lg, *args, 1.3, u)
+    out2 = fspad.fspad_tree_accept_sample_draft(lg, lg.clone(), *args, 1.3, u)
+    torch.cuda.synchronize()
+    assert out[2].cpu().numpy()[:, 0].tolist() == want
+    assert out2[2].cpu().numpy()[:, 0].tolist() == want
